@@ -1,0 +1,133 @@
+/* C ABI of the MI355X (gfx950) library for one training step of the CNN of
+ * arXiv 1912.05234 ("Array Languages Make Neural Networks Fast"), Section 3.
+ *
+ * Network (listing `forward`): image I[28,28] -> C1 = sigmoid(mconv(I, k1[6,5,5], b1[6]))
+ * [6,24,24] -> S1 = avgpool [6,12,12] -> C2 = sigmoid(mconv(S1, k2[12,6,5,5], b2[12]))
+ * [12,8,8] -> S2 = avgpool [12,4,4] -> yhat = sigmoid(mconv(S2, fc[10,12,1,4,4], b[10])) [10].
+ * Loss of one image: 1/2 * sum_o (yhat_o - t_o)^2 with t the one-hot label
+ * (paragraph "Backpropagating Convolution").
+ *
+ * General rules for every entry point
+ *  - All data pointers are DEVICE pointers (HIP global memory on the current
+ *    device), fp32 / int32 / int64 as typed, contiguous, row-major, and at
+ *    least 16-byte aligned.  The library never allocates, frees or keeps
+ *    caller memory except the workspace handed to cnn_init.
+ *  - Work is enqueued on the given HIP stream (a hipStream_t passed as void*;
+ *    NULL = the default stream) and the call returns without waiting.
+ *    Results, including scalars, are written to device memory.
+ *  - Return value: CNN_OK (0) or a negative CNN_E* code; nothing is enqueued
+ *    when an argument check fails.  cnn_strerror names a code.
+ *  - Labels must lie in 0..9; this is a precondition, not checked on the device.
+ *  - Parameter layout is the paper's: k1[i][u][v], k2[j][c][u][v],
+ *    fc[o][c][y][x] (flat input index c*16 + y*4 + x), biases one per map.
+ */
+#ifndef PAPER_1912_05234_CNN_H
+#define PAPER_1912_05234_CNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CNN_OK 0
+#define CNN_EINVAL (-1)     /* null / misaligned pointer, size out of range, odd pooling extent */
+#define CNN_EWORKSPACE (-2) /* workspace too small for max_batch */
+#define CNN_EHIP (-3)       /* a HIP call or kernel launch failed */
+
+#define CNN_NPARAM 3898     /* 150 + 6 + 1800 + 12 + 1920 + 10 */
+
+typedef struct cnn_ctx cnn_ctx; /* opaque, host memory owned by the library */
+
+const char* cnn_strerror(int code);
+
+/* Device bytes cnn_init needs for batches of up to max_batch images
+ * (weights, per-workgroup gradient partials, reduction scratch).  0 if max_batch < 1. */
+size_t cnn_workspace_bytes(int max_batch);
+
+/* Creates a context over caller-owned device `workspace` (>= cnn_workspace_bytes(max_batch),
+ * 256-byte aligned; must outlive the context) and copies the six parameter
+ * arrays into it (device pointers; a NULL array means zeros, the usual start
+ * for the biases).  All later calls on the context run on `hip_stream`. */
+int cnn_init(cnn_ctx** out, void* workspace, size_t workspace_bytes, int max_batch,
+             const float* k1, const float* b1, const float* k2, const float* b2,
+             const float* fc, const float* b, void* hip_stream);
+
+/* Frees the host-side context (not the workspace).  NULL is allowed. */
+void cnn_destroy(cnn_ctx* ctx);
+
+/* Copy the current parameters out to / in from device arrays; NULL skips an array. */
+int cnn_get_weights(cnn_ctx* ctx, float* k1, float* b1, float* k2, float* b2, float* fc, float* b);
+int cnn_set_weights(cnn_ctx* ctx, const float* k1, const float* b1, const float* k2,
+                    const float* b2, const float* fc, const float* b);
+
+/* Listing `forward` over a batch: images[B,28,28] -> yhat[B,10].  1 <= B <= max_batch. */
+int cnn_forward(cnn_ctx* ctx, const float* images, int B, float* yhat);
+
+/* As cnn_forward, also storing every layer's activations (any may be NULL):
+ * c1[B,6,24,24], s1[B,6,12,12], c2[B,12,8,8], s2[B,12,4,4], yhat[B,10]. */
+int cnn_forward_activations(cnn_ctx* ctx, const float* images, int B, float* c1, float* s1,
+                            float* c2, float* s2, float* yhat);
+
+/* Sum over the batch of the loss gradient with respect to all parameters
+ * (order k1,b1,k2,b2,fc,b; grad[3898]) without touching the weights: the
+ * backweights / backbias / backin / backavgpool chain of Section 3 applied per
+ * image and summed (Section 2: F = sum_i F_i).  loss_sum (nullable) receives
+ * sum_n L_n. */
+int cnn_gradient(cnn_ctx* ctx, const float* images, const int32_t* labels, int B, float* grad,
+                 float* loss_sum);
+
+/* One SGD step: the gradient above, then w <- w - (lr / B) * grad for every
+ * parameter, all gradients taken at the weights from before the step
+ * (listing `weights = weights - rate*backweights(d_out,in)`; batch mean).
+ * loss_sum (nullable, device) receives sum_n L_n at the old weights.
+ * Bitwise reproducible for equal inputs and equal B. */
+int cnn_train_batch(cnn_ctx* ctx, const float* images, const int32_t* labels, int B, float lr,
+                    float* loss_sum);
+
+/* Forward-only classification of N images (1 <= N <= max_batch): n_correct
+ * (device int64) = number of images whose largest output (lowest index on ties)
+ * equals the label; loss_sum (nullable) = sum_n L_n. */
+int cnn_evaluate(cnn_ctx* ctx, const float* images, const int32_t* labels, int N,
+                 int64_t* n_correct, float* loss_sum);
+
+/* ---- Stateless per-operation entry points (batch axis first, NCHW). ----------
+ * conv = valid cross-correlation, no kernel flip (listing `conv`), over all Cin
+ * input maps per output map plus bias (listing `mconv`), no activation:
+ *   out[b,co,y,x] = bias[co] + sum_{ci,u,v} in[b,ci,y+u,x+v] * k[co,ci,u,v]
+ * with Ho = H-KH+1, Wo = W-KW+1 (both must be >= 1).  bias may be NULL. */
+int cnn_conv_fwd(const float* in, const float* k, const float* bias, float* out, int B, int Cin,
+                 int H, int W, int Cout, int KH, int KW, void* hip_stream);
+/* `backin` summed over output maps: d_in[b,ci,p,q] = sum_co sum_{u,v : 0<=p-u<Ho, 0<=q-v<Wo}
+ * k[co,ci,u,v] * d_out[b,co,p-u,q-v]. */
+int cnn_conv_bwd_input(const float* d_out, const float* k, float* d_in, int B, int Cin, int H,
+                       int W, int Cout, int KH, int KW, void* hip_stream);
+/* `backweights` and `backbias`, summed over the batch:
+ *   d_k[co,ci,u,v] = sum_{b,y,x} in[b,ci,y+u,x+v] * d_out[b,co,y,x];  d_bias[co] = sum d_out[:,co].
+ * d_bias may be NULL.  Deterministic summation order. */
+int cnn_conv_bwd_weight(const float* in, const float* d_out, float* d_k, float* d_bias, int B,
+                        int Cin, int H, int W, int Cout, int KH, int KW, void* hip_stream);
+/* Listing `avgpool` over [B,C,H,W] (H, W even) -> [B,C,H/2,W/2]. */
+int cnn_avgpool_fwd(const float* in, float* out, int B, int C, int H, int W, void* hip_stream);
+/* Listing `backavgpool`: d_out[B,C,Ho,Wo] -> d_in[B,C,2Ho,2Wo] = d_out[..,y/2,x/2] / 4. */
+int cnn_avgpool_bwd(const float* d_out, float* d_in, int B, int C, int Ho, int Wo, void* hip_stream);
+/* Fully connected layer (mconv with kernel shape = input shape):
+ *   out[b,o] = bias[o] + sum_i in[b,i] * w[o,i];  bias may be NULL. */
+int cnn_fc_fwd(const float* in, const float* w, const float* bias, float* out, int B, int I, int O,
+               void* hip_stream);
+/* d_in[b,i] = sum_o w[o,i] * d_out[b,o]. */
+int cnn_fc_bwd_input(const float* d_out, const float* w, float* d_in, int B, int I, int O,
+                     void* hip_stream);
+/* d_w[o,i] = sum_b d_out[b,o] * in[b,i];  d_bias[o] = sum_b d_out[b,o] (nullable). */
+int cnn_fc_bwd_weight(const float* in, const float* d_out, float* d_w, float* d_bias, int B, int I,
+                      int O, void* hip_stream);
+/* Listing `sigmoid`: y = 1 / (1 + exp(-x)), n elements. */
+int cnn_logistic_fwd(const float* x, float* y, size_t n, void* hip_stream);
+/* Its derivative through the stored output: d_x = d_y * y * (1 - y). */
+int cnn_logistic_bwd(const float* y, const float* d_y, float* d_x, size_t n, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

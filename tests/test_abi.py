@@ -1,0 +1,75 @@
+"""CPU-side checks of the C ABI: the built library loads without a GPU, exports every
+function include/cnn.h declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1912_05234_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "cnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cnn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_binding_list_the_same_functions():
+    names = declared_functions()
+    assert len(names) >= 20
+    assert names == sorted(binding.SIGNATURES)
+
+
+def test_library_exports_every_declared_symbol():
+    handle = binding.lib()
+    for name in declared_functions():
+        assert hasattr(handle, name), name
+
+
+def test_error_strings_and_workspace_size():
+    L = binding.lib()
+    assert L.cnn_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -99):
+        assert len(L.cnn_strerror(code)) > 0
+    assert L.cnn_workspace_bytes(0) == 0 and L.cnn_workspace_bytes(-5) == 0
+    small, big = L.cnn_workspace_bytes(1), L.cnn_workspace_bytes(60000)
+    assert 0 < small <= big
+    assert L.cnn_workspace_bytes(10 ** 6) == L.cnn_workspace_bytes(10 ** 7)  # partial count is capped
+
+
+def test_bad_arguments_are_rejected_on_the_host():
+    L = binding.lib()
+    ctx = ctypes.c_void_p()
+    nul = ctypes.c_void_p(None)
+    fake = ctypes.c_void_p(0x1000)       # never dereferenced: the checks below fail first
+    odd = ctypes.c_void_p(0x1004)
+    EINVAL, EWS = -1, -2
+    assert L.cnn_init(None, fake, 1 << 30, 10, nul, nul, nul, nul, nul, nul, nul) == EINVAL
+    assert L.cnn_init(ctypes.byref(ctx), nul, 1 << 30, 10, nul, nul, nul, nul, nul, nul, nul) == EINVAL
+    assert L.cnn_init(ctypes.byref(ctx), odd, 1 << 30, 10, nul, nul, nul, nul, nul, nul, nul) == EINVAL
+    assert L.cnn_init(ctypes.byref(ctx), fake, 1 << 30, 0, nul, nul, nul, nul, nul, nul, nul) == EINVAL
+    assert L.cnn_init(ctypes.byref(ctx), fake, 16, 10, nul, nul, nul, nul, nul, nul, nul) == EWS
+    assert not ctx.value
+    assert L.cnn_forward(nul, fake, 1, fake) == EINVAL
+    assert L.cnn_train_batch(nul, fake, fake, 1, 0.05, nul) == EINVAL
+    assert L.cnn_evaluate(nul, fake, fake, 1, fake, nul) == EINVAL
+    assert L.cnn_gradient(nul, fake, fake, 1, fake, nul) == EINVAL
+    assert L.cnn_get_weights(nul, nul, nul, nul, nul, nul, nul) == EINVAL
+    L.cnn_destroy(nul)
+    # per-op: null, misaligned, bad shapes
+    assert L.cnn_conv_fwd(nul, fake, nul, fake, 1, 1, 8, 8, 1, 3, 3, nul) == EINVAL
+    assert L.cnn_conv_fwd(odd, fake, nul, fake, 1, 1, 8, 8, 1, 3, 3, nul) == EINVAL
+    assert L.cnn_conv_fwd(fake, fake, nul, fake, 1, 1, 2, 8, 1, 3, 3, nul) == EINVAL   # H < KH
+    assert L.cnn_conv_fwd(fake, fake, nul, fake, 0, 1, 8, 8, 1, 3, 3, nul) == EINVAL   # B < 1
+    assert L.cnn_conv_bwd_input(fake, nul, fake, 1, 1, 8, 8, 1, 3, 3, nul) == EINVAL
+    assert L.cnn_conv_bwd_weight(fake, fake, nul, nul, 1, 1, 8, 8, 1, 3, 3, nul) == EINVAL
+    assert L.cnn_avgpool_fwd(fake, fake, 1, 1, 7, 8, nul) == EINVAL                     # odd extent
+    assert L.cnn_avgpool_bwd(fake, nul, 1, 1, 4, 4, nul) == EINVAL
+    assert L.cnn_fc_fwd(fake, fake, nul, fake, 1, 0, 10, nul) == EINVAL
+    assert L.cnn_fc_bwd_input(nul, fake, fake, 1, 4, 4, nul) == EINVAL
+    assert L.cnn_fc_bwd_weight(fake, fake, fake, odd, 1, 4, 4, nul) == EINVAL
+    assert L.cnn_logistic_fwd(fake, fake, 0, nul) == EINVAL
+    assert L.cnn_logistic_bwd(fake, nul, fake, 4, nul) == EINVAL

@@ -1,0 +1,189 @@
+"""GPU parity of the fused forward / backward / SGD path against the CPU oracle (through the
+C ABI): activations, per-batch gradients, the small training configuration, evaluation,
+reproducibility and edge cases."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1912_05234_amd import binding, inputs
+from parity import RTOL_ACT, RTOL_W, assert_close, assert_close_elementwise
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+LR = 0.05
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def weights(seed=inputs.DEFAULT_SEED, biases=False):
+    w = inputs.make_weights(seed)
+    return inputs.make_random_biases(w, seed + 1) if biases else w
+
+
+def oracle_grad(images, labels, wflat):
+    w = wflat.copy()
+    loss, g = oracle.train_batch(images, labels, 0.0, w, want_grad=True)
+    return loss, g
+
+
+@pytest.mark.parametrize("B", [1, 7, 64])
+def test_forward_activations(B):
+    images, _ = inputs.make_batch(B, 21)
+    w = weights(biases=True)
+    net = binding.CNN(w, max_batch=B)
+    acts = {k: host(v) for k, v in net.forward_activations(dev(images)).items()}
+    yhat = host(net.forward(dev(images)))
+    wflat = inputs.flatten(w)
+    for n in range(B):
+        ref = oracle.forward(images[n], wflat)
+        for name in ("c1", "s1", "c2", "s2", "y"):
+            assert_close(acts[name][n], ref[name], RTOL_ACT, "%s[%d]" % (name, n))
+            assert_close_elementwise(acts[name][n], ref[name], RTOL_ACT, "%s[%d]" % (name, n))
+        np.testing.assert_array_equal(yhat[n], acts["y"][n])
+
+
+@pytest.mark.parametrize("B", [1, 3, 100, 257])
+def test_batch_gradient(B):
+    images, labels = inputs.make_batch(B, 22)
+    w = weights(biases=True)
+    net = binding.CNN(w, max_batch=B)
+    grad, loss = net.gradient(dev(images), dev(labels))
+    ref_loss, ref_g = oracle_grad(images, labels, inputs.flatten(w))
+    g = inputs.unflatten(host(grad))
+    r = inputs.unflatten(ref_g)
+    for name in ("k1", "b1", "k2", "b2", "fc", "b"):
+        assert_close(g[name], r[name], 2e-5, "grad %s (B=%d)" % (name, B))
+    assert abs(host(loss)[0] - ref_loss) <= 1e-5 * ref_loss
+    # the weights were not touched
+    np.testing.assert_array_equal(host(net.get_weights_flat()), inputs.flatten(w))
+
+
+def test_zero_weights_closed_form():
+    # all activations 1/2, loss 1.25 per image, only fc and b receive gradient
+    B = 10
+    images, labels = inputs.make_batch(B, 23)
+    net = binding.CNN({}, max_batch=B)
+    yhat = host(net.forward(dev(images)))
+    assert np.all(yhat == 0.5)
+    grad, loss = net.gradient(dev(images), dev(labels))
+    g = inputs.unflatten(host(grad))
+    assert host(loss)[0] == 1.25 * B
+    delta = np.full((B, 10), 0.125, np.float32)
+    delta[np.arange(B), labels] = -0.125
+    np.testing.assert_array_equal(g["b"], delta.sum(0))
+    np.testing.assert_array_equal(g["fc"].reshape(10, 192), np.repeat(delta.sum(0)[:, None] * 0.5, 192, 1))
+    for name in ("k1", "b1", "k2", "b2"):
+        assert np.all(g[name] == 0)
+
+
+def run_training(net, images, labels, batch, lr):
+    img_d, lab_d = dev(images), dev(labels)
+    losses = torch.zeros(len(images) // batch, dtype=torch.float32, device=DEV)
+    for s in range(len(images) // batch):
+        sl = slice(s * batch, (s + 1) * batch)
+        net.train_batch(img_d[sl], lab_d[sl], lr, losses[s:s + 1])
+    return host(net.get_weights_flat()), host(losses)
+
+
+def test_small_training_configuration():
+    """1000 images, batch 100, rate 0.05, one epoch: every weight within 1e-4 of the oracle."""
+    images, labels = inputs.make_batch(1000, 24)
+    w = weights()
+    net = binding.CNN(w, max_batch=100)
+    w_gpu, losses = run_training(net, images, labels, 100, LR)
+    w_ref = inputs.flatten(w)
+    ref_losses = []
+    for s in range(10):
+        sl = slice(s * 100, (s + 1) * 100)
+        ref_losses.append(oracle.train_batch(images[sl], labels[sl], float(np.float32(LR)), w_ref))
+    g, r = inputs.unflatten(w_gpu), inputs.unflatten(w_ref)
+    for name in g:
+        assert_close(g[name], r[name], RTOL_W, "weights %s after the epoch" % name)
+    assert_close_elementwise(w_gpu[np.abs(w_ref) > 1e-3], w_ref[np.abs(w_ref) > 1e-3], RTOL_W, "weights")
+    np.testing.assert_allclose(losses, ref_losses, rtol=1e-5)
+    # the update moved the weights by far more than the tolerance (the test can fail)
+    assert np.abs(w_ref - inputs.flatten(w)).max() > 100 * RTOL_W * np.abs(w_ref).max()
+    # evaluation on fresh images with the trained weights
+    ev_images, ev_labels = inputs.make_batch(500, 25)
+    net_e = binding.CNN(inputs.unflatten(w_ref), max_batch=500)
+    n_ok, loss = net_e.evaluate(dev(ev_images), dev(ev_labels))
+    yhat = host(net_e.forward(dev(ev_images)))
+    ref_y, ref_ok, ref_loss = oracle.evaluate(ev_images, ev_labels, w_ref)
+    assert_close(yhat, ref_y, RTOL_ACT, "yhat")
+    # the count may differ only on images whose two largest outputs tie to within the tolerance
+    top2 = np.sort(ref_y, axis=1)[:, -2:]
+    near_ties = int((top2[:, 1] - top2[:, 0] <= 2 * RTOL_ACT).sum())
+    assert abs(int(host(n_ok)[0]) - ref_ok) <= near_ties
+    assert int(host(n_ok)[0]) == int((yhat.argmax(1) == ev_labels).sum())
+    assert abs(host(loss)[0] - ref_loss) <= 1e-5 * ref_loss
+
+
+def test_step_is_bitwise_reproducible_and_zero_rate_is_identity():
+    images, labels = inputs.make_batch(300, 26)
+    w = weights(biases=True)
+    runs = []
+    for _ in range(2):
+        net = binding.CNN(w, max_batch=300)
+        runs.append(run_training(net, images, labels, 150, LR)[0])
+    np.testing.assert_array_equal(runs[0], runs[1])
+    net = binding.CNN(w, max_batch=300)
+    net.train_batch(dev(images), dev(labels), 0.0)
+    np.testing.assert_array_equal(host(net.get_weights_flat()), inputs.flatten(w))
+
+
+def test_batch_invariants_on_gpu():
+    images, labels = inputs.make_batch(6, 27)
+    w = weights(biases=True)
+    net = binding.CNN(w, max_batch=64)
+    g_all, _ = net.gradient(dev(images), dev(labels))
+    g_sum = np.zeros(oracle.NPARAM)
+    for n in range(6):
+        g_n, _ = net.gradient(dev(images[n:n + 1]), dev(labels[n:n + 1]))
+        g_sum += host(g_n)
+    assert_close(host(g_all), g_sum, 1e-6, "sum of single-image gradients")
+    # B copies of one image: B times its gradient
+    g_rep, _ = net.gradient(dev(np.repeat(images[:1], 5, 0)), dev(np.repeat(labels[:1], 5)))
+    g_one, _ = net.gradient(dev(images[:1]), dev(labels[:1]))
+    assert_close(host(g_rep), 5 * host(g_one), 1e-6, "repeated image")
+
+
+def test_ragged_batch_beyond_the_workgroup_cap():
+    """More images than gradient partials: workgroups loop, the last round is ragged."""
+    B = 2 * 1024 + 37
+    images, labels = inputs.make_batch(B, 28)
+    w = weights(biases=True)
+    net = binding.CNN(w, max_batch=B)
+    wflat = inputs.flatten(w)
+    yhat = host(net.forward(dev(images)))
+    for n in (0, 1023, 1024, 2047, 2048, B - 1):
+        assert_close(yhat[n], oracle.forward(images[n], wflat)["y"], RTOL_ACT, "yhat[%d]" % n)
+    grad, loss = net.gradient(dev(images), dev(labels))
+    ref_loss, ref_g = oracle_grad(images, labels, wflat)
+    assert_close(host(grad), ref_g, 2e-5, "gradient")
+    assert abs(host(loss)[0] - ref_loss) <= 1e-5 * ref_loss
+    n_ok, _ = net.evaluate(dev(images), dev(labels))
+    assert int(host(n_ok)[0]) == int((yhat.argmax(1) == labels).sum())
+
+
+def test_context_errors():
+    net = binding.CNN(weights(), max_batch=8)
+    images, labels = inputs.make_batch(9, 29)
+    with pytest.raises(binding.CnnError) as e:
+        net.forward(dev(images))             # B > max_batch
+    assert e.value.code == -1
+    with pytest.raises(binding.CnnError):
+        net.train_batch(dev(images), dev(labels), LR)
+    with pytest.raises(binding.CnnError):
+        net.forward(dev(images[:0]))         # empty batch
+    # weights round trip
+    w2 = weights(seed=5, biases=True)
+    net.set_weights(w2)
+    np.testing.assert_array_equal(host(net.get_weights_flat()), inputs.flatten(w2))

@@ -1,0 +1,118 @@
+"""GPU parity of the per-operation entry points against the CPU oracle (through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1912_05234_amd import binding, inputs
+from parity import RTOL_ACT, assert_close, assert_close_elementwise
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+# (B, Cin, H, W, Cout, KH, KW): the network's two layers, ragged shapes, 1x1 and full-size kernels
+CONV_CASES = [(3, 1, 28, 28, 6, 5, 5), (5, 6, 12, 12, 12, 5, 5), (2, 3, 9, 7, 4, 3, 2), (1, 2, 5, 5, 3, 1, 1),
+              (4, 12, 4, 4, 10, 4, 4), (1, 1, 6, 5, 1, 6, 5), (37, 2, 11, 13, 5, 4, 6)]
+
+
+def oracle_conv_fwd(x, k, b):
+    return np.stack([oracle.mconv(x[n], k, b).reshape(k.shape[0], x.shape[2] - k.shape[2] + 1, -1)
+                     for n in range(x.shape[0])])
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_fwd(case):
+    B, Cin, H, W, Cout, KH, KW = case
+    x = inputs.make_signed((B, Cin, H, W), 1)
+    k = inputs.make_signed((Cout, Cin, KH, KW), 2)
+    b = inputs.make_signed((Cout,), 3)
+    ref = oracle_conv_fwd(x, k, b)
+    assert_close(host(binding.conv_fwd(dev(x), dev(k), dev(b))), ref, RTOL_ACT, "conv_fwd")
+    ref0 = oracle_conv_fwd(x, k, np.zeros(Cout, np.float32))
+    assert_close(host(binding.conv_fwd(dev(x), dev(k), None)), ref0, RTOL_ACT, "conv_fwd no bias")
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_bwd_input(case):
+    B, Cin, H, W, Cout, KH, KW = case
+    Ho, Wo = H - KH + 1, W - KW + 1
+    d = inputs.make_signed((B, Cout, Ho, Wo), 4)
+    k = inputs.make_signed((Cout, Cin, KH, KW), 5)
+    ref = np.zeros((B, Cin, H, W), np.float64)
+    for n in range(B):
+        for co in range(Cout):
+            ref[n] += oracle.backin(d[n, co][None].astype(np.float64), k[co].astype(np.float64), (Cin, H, W))
+    assert_close(host(binding.conv_bwd_input(dev(d), dev(k), H, W)), ref, RTOL_ACT, "conv_bwd_input")
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_bwd_weight(case):
+    B, Cin, H, W, Cout, KH, KW = case
+    Ho, Wo = H - KH + 1, W - KW + 1
+    x = inputs.make_signed((B, Cin, H, W), 6)
+    d = inputs.make_signed((B, Cout, Ho, Wo), 7)
+    ref_k = np.zeros((Cout, Cin, KH, KW), np.float64)
+    ref_b = np.zeros(Cout, np.float64)
+    for n in range(B):
+        for co in range(Cout):
+            ref_k[co] += oracle.backweights(d[n, co][None].astype(np.float64), x[n].astype(np.float64))
+            ref_b[co] += oracle.backbias(d[n, co].astype(np.float64))
+    d_k, d_b = binding.conv_bwd_weight(dev(x), dev(d))
+    assert_close(host(d_k), ref_k, RTOL_ACT, "conv_bwd_weight")
+    assert_close(host(d_b), ref_b, RTOL_ACT, "conv_bwd_bias")
+    d_k2, none = binding.conv_bwd_weight(dev(x), dev(d), want_bias=False)
+    assert none is None and torch.equal(d_k2, d_k)   # deterministic order
+
+
+@pytest.mark.parametrize("shape", [(2, 6, 24, 24), (3, 12, 8, 8), (1, 1, 2, 2), (5, 3, 6, 10)])
+def test_avgpool_fwd_bwd(shape):
+    x = inputs.make_signed(shape, 8)
+    assert_close(host(binding.avgpool_fwd(dev(x))), oracle.avgpool(x), 1e-6, "avgpool_fwd")
+    d = inputs.make_signed(shape[:2] + (shape[2] // 2, shape[3] // 2), 9)
+    up = host(binding.avgpool_bwd(dev(d)))
+    np.testing.assert_array_equal(up, oracle.backavgpool(d))   # d/4 is exact
+    assert abs(up.astype(np.float64).sum() - d.astype(np.float64).sum()) <= 1e-6 * np.abs(d).sum()
+
+
+@pytest.mark.parametrize("B,I,O", [(7, 192, 10), (1, 1, 1), (300, 33, 5)])
+def test_fc(B, I, O):
+    x, w, b = inputs.make_signed((B, I), 10), inputs.make_signed((O, I), 11), inputs.make_signed((O,), 12)
+    d = inputs.make_signed((B, O), 13)
+    x64, w64, d64 = x.astype(np.float64), w.astype(np.float64), d.astype(np.float64)
+    # FC is mconv with kernel shape == input shape (Section 3): check one row through the oracle's mconv
+    np.testing.assert_allclose(oracle.mconv(x64[0], w64, b.astype(np.float64)).ravel(), x64[0] @ w64.T + b,
+                               rtol=0, atol=1e-12)
+    assert_close(host(binding.fc_fwd(dev(x), dev(w), dev(b))), x64 @ w64.T + b, RTOL_ACT, "fc_fwd")
+    assert_close(host(binding.fc_fwd(dev(x), dev(w), None)), x64 @ w64.T, RTOL_ACT, "fc_fwd no bias")
+    assert_close(host(binding.fc_bwd_input(dev(d), dev(w))), d64 @ w64, RTOL_ACT, "fc_bwd_input")
+    d_w, d_b = binding.fc_bwd_weight(dev(x), dev(d))
+    assert_close(host(d_w), d64.T @ x64, RTOL_ACT, "fc_bwd_weight")
+    assert_close(host(d_b), d64.sum(0), RTOL_ACT, "fc_bwd_bias")
+
+
+def test_logistic():
+    x = np.concatenate([np.linspace(-20, 20, 4001), [0.0, -100.0, 100.0, -1e4, 1e4, 88.0, -88.0, 104.0]])
+    x = x.astype(np.float32)
+    y = host(binding.logistic_fwd(dev(x)))
+    ref = oracle.sigmoid(x)
+    assert np.all(np.isfinite(y))
+    assert_close(y, ref, RTOL_ACT, "logistic_fwd")
+    inner = np.abs(x) <= 12
+    assert_close_elementwise(y[inner], ref[inner], 1e-5, "logistic_fwd element-wise")
+    assert y[x == 0][0] == 0.5 and y[x == -1e4][0] == 0.0 and y[x == 1e4][0] == 1.0
+    d = inputs.make_signed(x.shape, 14)
+    assert_close(host(binding.logistic_bwd(dev(ref), dev(d))), oracle.sigmoid_back(ref, d), 1e-6, "logistic_bwd")
+    # ragged sizes around the workgroup size
+    for n in (1, 255, 257, 1000003):
+        xs = inputs.make_signed((n,), 15) * 8
+        assert_close(host(binding.logistic_fwd(dev(xs))), oracle.sigmoid(xs), RTOL_ACT, "logistic n=%d" % n)
