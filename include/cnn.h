@@ -92,6 +92,16 @@ int cnn_train_batch(cnn_ctx* ctx, const float* images, const int32_t* labels, in
 int cnn_evaluate(cnn_ctx* ctx, const float* images, const int32_t* labels, int N,
                  int64_t* n_correct, float* loss_sum);
 
+/* Timing aid for callers that cannot see inside a step.  After cnn_profile_begin(ctx, capacity)
+ * each cnn_train_batch / cnn_gradient call records one pair of HIP events around its fused
+ * forward+backward kernel (the first `capacity` calls; later ones are not recorded).
+ * cnn_profile_read waits for the context's stream, writes the elapsed milliseconds of each
+ * recorded kernel to ms (a HOST array of at least `capacity` floats) and the number of recorded
+ * steps to *n_recorded (HOST), and restarts recording from zero.  capacity == 0 stops recording
+ * and frees the events.  No device memory is involved. */
+int cnn_profile_begin(cnn_ctx* ctx, int capacity);
+int cnn_profile_read(cnn_ctx* ctx, float* ms, int capacity, int* n_recorded);
+
 /* ---- Stateless per-operation entry points (batch axis first, NCHW). ----------
  * conv = valid cross-correlation, no kernel flip (listing `conv`), over all Cin
  * input maps per output map plus bias (listing `mconv`), no activation:

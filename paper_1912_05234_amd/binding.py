@@ -31,6 +31,8 @@ SIGNATURES = {
     "cnn_gradient": (_i, [_vp, _vp, _vp, _i, _vp, _vp]),
     "cnn_train_batch": (_i, [_vp, _vp, _vp, _i, _f, _vp]),
     "cnn_evaluate": (_i, [_vp, _vp, _vp, _i, _vp, _vp]),
+    "cnn_profile_begin": (_i, [_vp, _i]),
+    "cnn_profile_read": (_i, [_vp, _vp, _i, ctypes.POINTER(_i)]),
     "cnn_conv_fwd": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp]),
     "cnn_conv_bwd_input": (_i, [_vp, _vp, _vp] + [_i] * 7 + [_vp]),
     "cnn_conv_bwd_weight": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp]),
@@ -173,6 +175,18 @@ class CNN:
         _check(lib().cnn_evaluate(self._ctx, _ptr(images), _ptr(labels), images.shape[0], _ptr(n_ok),
                                   _ptr(loss)), "cnn_evaluate")
         return n_ok, loss
+
+
+    def profile_begin(self, capacity):
+        _check(lib().cnn_profile_begin(self._ctx, int(capacity)), "cnn_profile_begin")
+
+    def profile_read(self, capacity):
+        """Per-step milliseconds of the fused forward+backward kernel (host list)."""
+        buf = (ctypes.c_float * max(1, capacity))()
+        n = ctypes.c_int(0)
+        _check(lib().cnn_profile_read(self._ctx, ctypes.cast(buf, _vp), int(capacity), ctypes.byref(n)),
+               "cnn_profile_read")
+        return [buf[i] for i in range(n.value)]
 
 
 # ---- per-operation entry points -------------------------------------------------

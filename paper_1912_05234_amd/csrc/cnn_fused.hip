@@ -14,6 +14,7 @@
 // scheduling.  A second kernel adds the G partials in a fixed order and applies
 // the update.
 #include <new>
+#include <vector>
 
 #include "cnn_common.h"
 
@@ -403,6 +404,8 @@ struct cnn_ctx {
   float* w;             // [PSTRIDE]
   float* partial;       // [gcap][PSTRIDE]
   float* eval_partial;  // [gcap][2]
+  std::vector<hipEvent_t> ev;  // 2 per recorded step (before, after the fused kernel)
+  int ev_used = 0;             // recorded steps
 };
 
 namespace {
@@ -444,8 +447,14 @@ int run_forward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B,
 int run_backward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B, float scale,
                  float* grad_out, float* loss_sum) {
   const int G = grid_for(ctx, B);
+  const bool timed = (size_t)(2 * ctx->ev_used + 1) < ctx->ev.size();
+  if (timed) CNN_HIP_TRY(hipEventRecord(ctx->ev[2 * ctx->ev_used], ctx->stream));
   train_kernel<<<G, TPB, 0, ctx->stream>>>(images, labels, B, ctx->w, ctx->partial);
   if (hipGetLastError() != hipSuccess) return CNN_EHIP;
+  if (timed) {
+    CNN_HIP_TRY(hipEventRecord(ctx->ev[2 * ctx->ev_used + 1], ctx->stream));
+    ++ctx->ev_used;
+  }
   reduce_update_kernel<<<PSTRIDE / 64, TPB, 0, ctx->stream>>>(ctx->partial, G, scale, ctx->w, grad_out,
                                                               loss_sum);
   if (hipGetLastError() != hipSuccess) return CNN_EHIP;
@@ -520,7 +529,39 @@ int cnn_init(cnn_ctx** out, void* workspace, size_t workspace_bytes, int max_bat
   return CNN_OK;
 }
 
-void cnn_destroy(cnn_ctx* ctx) { delete ctx; }
+int cnn_profile_begin(cnn_ctx* ctx, int capacity) {
+  if (!ctx || capacity < 0 || capacity > (1 << 20)) return CNN_EINVAL;
+  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+  ctx->ev.clear();
+  ctx->ev_used = 0;
+  for (int i = 0; i < 2 * capacity; ++i) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) {
+      (void)hipGetLastError();
+      for (hipEvent_t d : ctx->ev) (void)hipEventDestroy(d);
+      ctx->ev.clear();
+      return CNN_EHIP;
+    }
+    ctx->ev.push_back(e);
+  }
+  return CNN_OK;
+}
+
+int cnn_profile_read(cnn_ctx* ctx, float* ms, int capacity, int* n_recorded) {
+  if (!ctx || !ms || !n_recorded || capacity < 0) return CNN_EINVAL;
+  CNN_HIP_TRY(hipStreamSynchronize(ctx->stream));
+  const int n = ctx->ev_used < capacity ? ctx->ev_used : capacity;
+  for (int i = 0; i < n; ++i) CNN_HIP_TRY(hipEventElapsedTime(&ms[i], ctx->ev[2 * i], ctx->ev[2 * i + 1]));
+  *n_recorded = n;
+  ctx->ev_used = 0;
+  return CNN_OK;
+}
+
+void cnn_destroy(cnn_ctx* ctx) {
+  if (!ctx) return;
+  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+  delete ctx;
+}
 
 int cnn_forward(cnn_ctx* ctx, const float* images, int B, float* yhat) {
   if (!batch_ok(ctx, B) || !images || !yhat || !aligned16(images) || !aligned16(yhat)) return CNN_EINVAL;
