@@ -1,0 +1,605 @@
+// Device code of the fused step: ONE WAVEFRONT (64 lanes) OWNS ONE IMAGE from the
+// pixel load to the last gradient term.  Definitions: arXiv 1912.05234, Section 3
+// (forward, conv, mconv, sigmoid, avgpool, backweights, backbias, backin,
+// backavgpool); the backward driver is the chain rule over those.
+//
+// Where the arithmetic runs
+//   C1 forward            fp32 VALU, weights wave-uniform (scalar registers)
+//   C2 forward            v_mfma_f32_16x16x4_f32: M = 16 pixels, N = 12(16) maps, K = 150(152) taps
+//   C2 weight gradient    v_mfma_f32_16x16x4_f32: M = 12(16) maps, N = 16 taps, K = 64 pixels
+//   C2 input error        v_mfma_f32_16x16x4_f32: T[tap,pixel] = k2^T * d_c2 (K = 12 maps), then T is
+//                         added into d_s1 at (y+u, x+v) (the col2im form of `backin`: no zero padding)
+//                         in rounds of plain LDS read-add-write whose targets cannot collide
+//   C1 weight gradient    v_mfma_f32_4x4x1_f32: 16 blocks = 16 pixels, each a 4 maps x 4 taps outer product
+//   FC, pooling, sigmoid  fp32 VALU
+//
+// A workgroup is four such waves.  They share nothing but a read-only table of MFMA operands in
+// LDS (the C2 and FC weights, laid out [entry][lane] exactly as the instructions consume them),
+// built once per kernel; after that single workgroup barrier the waves never synchronise with
+// each other, only with themselves.
+//
+// Pixel order.  A lane quad (4 consecutive lanes) is one 2x2 pooling window, so
+// avgpool is a sum inside the quad (C1) or inside a lane's four MFMA result
+// registers (C2) and never needs an LDS round trip.
+//   C1: group g < 9, lane l: window w = 16 g + l/4 of the 12x12 windows, sub-pixel l%4.
+//   C2: pixel index p = 4 w + sub, w = 4 wy + wx over the 4x4 windows; tile mt covers p in [16mt, 16mt+16).
+// MFMA operand layouts (64 lanes, q = lane/16, n16 = lane%16):
+//   16x16x4: A[i=n16][k=q], B[k=q][j=n16], D[i=4q+r][j=n16] in result register r.
+//   4x4x1  : D_r(lane) += A(4*(lane/4)+r) * B(lane).
+#pragma once
+
+#include "cnn_common.h"
+
+// Hook for a cycle-counter probe at phase boundaries; empty in the library build.
+#ifndef CNN_PHASE
+#define CNN_PHASE_DECL
+#define CNN_PHASE(k)
+#define CNN_PHASE_FLUSH
+#endif
+
+namespace cnn {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr int WAVES = 4;  // waves (= images in flight) per workgroup
+constexpr int D2S = 68;   // row stride of the C2 error array in LDS (floats)
+
+// Per-wave LDS of the forward pass.  Padded K steps of the C2 forward read up to 1152 floats
+// past the start of s1; those cells are zero or finite and meet zero weights.
+struct __align__(16) FwdLds {
+  float img[NI];
+  float s1[NS1 + 288];
+  float s2[NS2];
+};
+// Per-wave LDS of the training step.  d_s1 comes first: the col2im rows of the two padding maps
+// (c = 6, 7) add 0.0 at offsets up to 1152 floats past its start, which stays inside the struct.
+struct __align__(16) TrainLds {
+  float d_s1[NS1];      // error at S1 (col2im target)
+  float img[NI];
+  float s1[NS1 + 288];
+  float s2[NS2];
+  float d_s2[NS2 + 64]; // rows of the four padding maps of the C2 tiles read up to index 255
+  float d2[16 * D2S];   // error at C2's pre-activation, [map][pixel p]
+  float stage[2][512];  // C1 error of a pair of pixel groups: [lane][8 maps] (maps 6,7 stay zero)
+};
+
+// Shared operand table, [entry][lane].
+constexpr int TAB_BF = 0;          // 38: C2 forward B operand, k2[j = n16][tap(s, q)]
+constexpr int TAB_FCW = 38;        // 30: fc[o][lane + 64 k] at entry 3 o + k
+constexpr int TAB_FWD_ENTRIES = 68;
+constexpr int TAB_AB = 68;         // 42: C2 input-error A operand, entry (cg*7 + tile)*3 + s
+constexpr int TAB_TRAIN_ENTRIES = 110;
+
+enum Mode { kForward = 0, kForwardDump = 1, kTrain = 2 };
+template <int MODE>
+struct LdsOf {
+  typedef FwdLds type;
+  static constexpr int entries = TAB_FWD_ENTRIES;
+};
+template <>
+struct LdsOf<kTrain> {
+  typedef TrainLds type;
+  static constexpr int entries = TAB_TRAIN_ENTRIES;
+};
+
+__device__ __forceinline__ float quad_xor1(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float quad_xor2(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float dpp_row_half_mirror(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float dpp_row_mirror(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));
+}
+// Sum over the 64 lanes in a fixed order, same value in every lane: quad, 8, 16 lanes by DPP,
+// then the four rows of 16 through scalar registers.
+__device__ __forceinline__ float wave_sum(float v) {
+  v += quad_xor1(v);
+  v += quad_xor2(v);
+  v += dpp_row_half_mirror(v);
+  v += dpp_row_mirror(v);
+  const int iv = __builtin_bit_cast(int, v);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
+  return (r0 + r1) + (r2 + r3);
+}
+__device__ __forceinline__ f4 mfma16(float a, float b, f4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f4 mfma4(float a, float b, f4 c) {
+  return __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, 0, 0, 0);
+}
+// Ordering point inside ONE wave: LDS writes issued before it by any lane are seen by LDS reads
+// issued after it by any lane of the same wave.  The LDS unit executes one wave's instructions in
+// order, so nothing has to be waited for; the fences only stop the compiler from moving LDS
+// accesses across this point.  No other wave is involved.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ---- K order of the C2 forward GEMM: step s < 38, lane quarter q -> tap (c,u,v) -------------
+// steps 0..29: (c = s/5, v = s%5), u = q            LDS offset c*144 + v      + 12 q
+// steps 30..35: c = s-30, u = 4, v = q               LDS offset c*144 + 48     + q
+// steps 36,37: u = v = 4, c = 4(s-36) + q (c < 6)    LDS offset 576(s-36) + 52 + 144 q
+__host__ __device__ constexpr int fwd_tap(int s, int q) {
+  return s < 30 ? (s / 5) * 25 + q * 5 + (s % 5)
+                : s < 36 ? (s - 30) * 25 + 20 + q : (4 * (s - 36) + q < 6 ? (4 * (s - 36) + q) * 25 + 24 : -1);
+}
+__host__ __device__ constexpr int fwd_imm(int s) {
+  return s < 30 ? (s / 5) * 144 + (s % 5) : s < 36 ? (s - 30) * 144 + 48 : 576 * (s - 36) + 52;
+}
+// ---- M tiles of the C2 input-error GEMM.  Row i = 4 qi + ri of every tile belongs to input map
+// c = 4 cg + qi (cg = 0, 1; maps 6, 7 are zero padding) and to the tap
+//   tile V(v), v < 5 : (u = ri, v)        tile U4 : (u = 4, v = ri)        tile C : (4, 4) in ri = 0 only.
+// A lane's result register r of tile (cg, .) therefore lands in d_s1[c = 4 cg + q] at row y+u, column x+v.
+enum BwdTile { kTileV0 = 0, kTileU4 = 5, kTileC = 6 };  // V(v) = kTileV0 + v
+__host__ __device__ constexpr int bwd_tap(int tile, int ri) {
+  return tile < 5 ? 5 * ri + tile : tile == kTileU4 ? 20 + ri : (ri == 0 ? 24 : -1);
+}
+// ---- N order of the C1 weight-gradient outer products: tile nt < 7, column = lane%4 -> tap ----
+// nt 0..4: u = nt, v = sub (v < 4); nt 5: v = 4, u = sub (u < 4); nt 6: (4,4) in column 0 only.
+__host__ __device__ constexpr int k1_tap(int nt, int sub) {
+  return nt < 5 ? nt * 5 + sub : nt == 5 ? sub * 5 + 4 : (sub == 0 ? 24 : -1);
+}
+
+// Fills the shared operand table from the flat parameter vector; all 256 threads take part and
+// the caller follows with a workgroup barrier.
+template <int MODE>
+__device__ __forceinline__ void build_tables(float* __restrict__ tab, const float* __restrict__ w) {
+  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
+  for (int e = wave; e < LdsOf<MODE>::entries; e += WAVES) {
+    float v;
+    if (e < TAB_FCW) {
+      const int tap = fwd_tap(e, q);
+      v = (n16 < 12 && tap >= 0) ? w[OFF_K2 + n16 * 150 + tap] : 0.0f;
+    } else if (e < TAB_AB) {
+      const int o = (e - TAB_FCW) / 3, k = (e - TAB_FCW) % 3;
+      v = w[OFF_FC + o * NS2 + l + 64 * k];
+    } else {
+      const int idx = e - TAB_AB, sidx = idx % 3, tile = (idx / 3) % 7, cg = idx / 21;
+      const int c = 4 * cg + (n16 >> 2), tap = bwd_tap(tile, n16 & 3);
+      v = (c < 6 && tap >= 0) ? w[OFF_K2 + (4 * sidx + q) * 150 + c * 25 + tap] : 0.0f;
+    }
+    tab[e * 64 + l] = v;
+  }
+}
+
+// Everything a wave keeps in registers across its images.
+template <int MODE>
+struct WaveState {
+  int pix0[9];    // LDS offset of the origin of this lane's pooling window in pixel group g
+  float bias2;    // b2[n16]
+  // training only
+  int toffb[10];  // C2 weight-gradient B operand: s1 offset of tap 16 nt + n16
+  f4 acc_k2[10];  // sum over images of d_c2 (x) s1 patches, D[j = 4q+r][tap = 16 nt + n16]
+  f4 acc_k1[2][7];  // per 4-lane block partial of d_c1 (x) image patches
+  float g_b1[6], g_b2, g_fc[10][3], g_b[10], loss;
+};
+
+template <int MODE>
+__device__ __forceinline__ void wave_init(WaveState<MODE>& st, typename LdsOf<MODE>::type& s,
+                                          const float* __restrict__ w) {
+  const int l = threadIdx.x & 63, n16 = l & 15, b = l >> 2;
+  // all of this wave's LDS starts finite: padded GEMM steps multiply it by zero weights
+  float* raw = reinterpret_cast<float*>(&s);
+  for (int e = l; e < (int)(sizeof(s) / 4); e += 64) raw[e] = 0.0f;
+#pragma unroll
+  for (int g = 0; g < 9; ++g) {
+    const int win = 16 * g + b;
+    st.pix0[g] = 2 * (win / 12) * 28 + 2 * (win % 12);
+  }
+  st.bias2 = n16 < 12 ? w[OFF_B2 + n16] : 0.0f;
+  if (MODE == kTrain) {
+#pragma unroll
+    for (int nt = 0; nt < 10; ++nt) {
+      const int tap = 16 * nt + n16;
+      const int c = tap / 25, u = (tap % 25) / 5, v = tap % 5;
+      st.toffb[nt] = tap < 150 ? c * 144 + u * 12 + v : 0;
+      st.acc_k2[nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 7; ++nt) st.acc_k1[mt][nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int i = 0; i < 6; ++i) st.g_b1[i] = 0.0f;
+    st.g_b2 = 0.0f;
+    st.loss = 0.0f;
+#pragma unroll
+    for (int o = 0; o < 10; ++o) {
+      st.g_b[o] = 0.0f;
+#pragma unroll
+      for (int k = 0; k < 3; ++k) st.g_fc[o][k] = 0.0f;
+    }
+  }
+}
+
+// Optional per-image outputs of the forward pass.
+struct DumpPtrs {
+  float *c1, *s1, *c2, *s2;
+};
+
+// The 196 16-byte pieces of one image as four registers per lane (the fourth only in lanes 0..3).
+struct Pixels {
+  float4 v[4];
+};
+__device__ __forceinline__ void load_pixels(Pixels& px, const float* __restrict__ image) {
+  const float4* src = reinterpret_cast<const float4*>(image);
+  const int l = threadIdx.x & 63;
+#pragma unroll
+  for (int k = 0; k < 3; ++k) px.v[k] = src[l + 64 * k];  // consecutive lanes -> consecutive 16 bytes
+  if (l < 4) px.v[3] = src[l + 192];
+}
+
+// One image through forward (and, when MODE == kTrain, backward).  `px` holds this image's pixels on
+// entry; if `next_image` is not null its pixels are loaded into `px` while this image is still being
+// worked on, so the HBM latency of the only per-image global read is hidden.  Returns yhat in y[10]
+// (wave-uniform).  `label` is only read when training.
+template <int MODE>
+__device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<MODE>::type& s,
+                                           const float* __restrict__ tab, Pixels& px,
+                                           const float* __restrict__ next_image, int label,
+                                           const float* __restrict__ w, float (&y)[10], const DumpPtrs& dump,
+                                           size_t n) {
+  const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15, b = l >> 2, sub = l & 3;
+  const int pp = 12 * ((n16 & 3) >> 1) + 2 * (n16 >> 2) + (n16 & 1);
+  const float* tl = tab + l;  // this lane's column of the operand table
+
+  CNN_PHASE_DECL;
+  CNN_PHASE(0);
+  {
+    float4* dst = reinterpret_cast<float4*>(s.img);
+#pragma unroll
+    for (int k = 0; k < 3; ++k) dst[l + 64 * k] = px.v[k];
+    if (l < 4) dst[l + 192] = px.v[3];
+  }
+  wave_sync();
+  if (MODE != kTrain && next_image) load_pixels(px, next_image);
+
+  CNN_PHASE(1);
+  // ---- C1 = sigmoid(mconv(I, k1, b1)), S1 = avgpool(C1).  Tap-outer: the six weights of a tap are
+  //      wave-uniform scalars, every lane holds its nine pixels' accumulators for all six maps. ----
+  float c1[9][6];
+  {
+    const float* ip[9];
+#pragma unroll
+    for (int g = 0; g < 9; ++g) {
+      ip[g] = s.img + st.pix0[g] + (sub >> 1) * 28 + (sub & 1);
+#pragma unroll
+      for (int i = 0; i < 6; ++i) c1[g][i] = w[OFF_B1 + i];
+    }
+    // The loop over kernel rows is a real loop: its body holds 45 pixel reads, 30 scalar weight
+    // loads and 270 multiply-adds, and the 54 accumulators are carried around it, which keeps the
+    // compiler from hoisting all 225 reads (and their registers) or serialising the sums.
+#pragma unroll 1
+    for (int u = 0; u < 5; ++u) {
+      const float* ku = w + OFF_K1 + u * 5;  // wave-uniform: scalar loads
+#pragma unroll
+      for (int v = 0; v < 5; ++v) {
+        float x[9];
+#pragma unroll
+        for (int g = 0; g < 9; ++g) x[g] = ip[g][u * 28 + v];
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+          const float wt = ku[i * 25 + v];
+#pragma unroll
+          for (int g = 0; g < 9; ++g) c1[g][i] = fmaf(wt, x[g], c1[g][i]);
+        }
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < 9; ++g)
+#pragma unroll
+      for (int i = 0; i < 6; ++i) {
+        const float c = logistic(c1[g][i]);
+        c1[g][i] = c;
+        float t = c + quad_xor1(c);
+        t += quad_xor2(t);
+        if (sub == 0) s.s1[i * 144 + 16 * g + b] = 0.25f * t;
+        if (MODE == kForwardDump && dump.c1) {
+          const int win = 16 * g + b;
+          dump.c1[n * NC1 + i * 576 + (2 * (win / 12) + (sub >> 1)) * 24 + 2 * (win % 12) + (sub & 1)] = c;
+        }
+      }
+  }
+  wave_sync();
+  if (MODE == kForwardDump && dump.s1)
+    for (int e = l; e < NS1; e += 64) dump.s1[n * NS1 + e] = s.s1[e];
+
+  CNN_PHASE(2);
+  // ---- C2 = sigmoid(mconv(S1, k2, b2)) as a 64 x 16 x 152 GEMM, S2 = avgpool(C2) ------------------
+  f4 c2v[4];
+  {
+    const float* a12 = s.s1 + pp + 12 * q;
+    const float* a1 = s.s1 + pp + q;
+    const float* a144 = s.s1 + pp + 144 * q;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) c2v[mt] = f4{st.bias2, st.bias2, st.bias2, st.bias2};
+#pragma unroll
+    for (int sidx = 0; sidx < 38; ++sidx) {
+      const float* base = sidx < 30 ? a12 : sidx < 36 ? a1 : a144;
+      const float bw = tl[(TAB_BF + sidx) * 64];
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) c2v[mt] = mfma16(base[fwd_imm(sidx) + 24 * mt], bw, c2v[mt]);
+    }
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) c2v[mt][r] = logistic(c2v[mt][r]);
+      if (n16 < 12) s.s2[n16 * 16 + 4 * mt + q] = 0.25f * ((c2v[mt][0] + c2v[mt][1]) + (c2v[mt][2] + c2v[mt][3]));
+      if (MODE == kForwardDump && dump.c2 && n16 < 12)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          dump.c2[n * NC2 + n16 * 64 + (2 * mt + (r >> 1)) * 8 + 2 * q + (r & 1)] = c2v[mt][r];
+    }
+  }
+  wave_sync();
+  if (MODE == kForwardDump && dump.s2)
+    for (int e = l; e < NS2; e += 64) dump.s2[n * NS2 + e] = s.s2[e];
+
+  CNN_PHASE(3);
+  // ---- output = sigmoid(mconv(S2, fc, b)): lane owns inputs lane, lane+64, lane+128 ----------------
+  float sv[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) sv[k] = s.s2[l + 64 * k];
+#pragma unroll
+  for (int o = 0; o < 10; ++o) {
+    float p = tl[(TAB_FCW + 3 * o) * 64] * sv[0];
+    p = fmaf(tl[(TAB_FCW + 3 * o + 1) * 64], sv[1], p);
+    p = fmaf(tl[(TAB_FCW + 3 * o + 2) * 64], sv[2], p);
+    y[o] = logistic(wave_sum(p) + w[OFF_B + o]);
+  }
+  if constexpr (MODE == kTrain) {
+    // ---- output error, FC backweights / backbias / backin ------------------------------------------
+    float delta[10];
+    {
+      float lsum = 0.0f;
+#pragma unroll
+      for (int o = 0; o < 10; ++o) {
+        const float e = y[o] - (o == label ? 1.0f : 0.0f);
+        lsum = fmaf(e, e, lsum);
+        delta[o] = e * y[o] * (1.0f - y[o]);
+        st.g_b[o] += delta[o];
+      }
+      st.loss = fmaf(0.5f, lsum, st.loss);
+    }
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      float d = 0.0f;
+#pragma unroll
+      for (int o = 0; o < 10; ++o) {
+        st.g_fc[o][k] = fmaf(delta[o], sv[k], st.g_fc[o][k]);
+        d = fmaf(tl[(TAB_FCW + 3 * o + k) * 64], delta[o], d);
+      }
+      s.d_s2[l + 64 * k] = d;
+    }
+    // clear the col2im target of the C2 input error
+    for (int e = l; e < NS1 / 4; e += 64) reinterpret_cast<f4*>(s.d_s1)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    wave_sync();
+
+    CNN_PHASE(4);
+    // ---- backavgpool through S2 and the derivative of C2's sigmoid; d_c2 stays in the MFMA result
+    //      layout, which is exactly the A-operand layout of the weight-gradient GEMM -------------------
+    f4 d2v[4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+      const float up = s.d_s2[n16 * 16 + 4 * mt + q] * 0.25f;  // rows n16 >= 12 read finite filler
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float c = c2v[mt][r];
+        d2v[mt][r] = up * c * (1.0f - c);
+      }
+      *reinterpret_cast<f4*>(&s.d2[n16 * D2S + 16 * mt + 4 * q]) = d2v[mt];
+      st.g_b2 += (d2v[mt][0] + d2v[mt][1]) + (d2v[mt][2] + d2v[mt][3]);
+    }
+    wave_sync();
+
+    CNN_PHASE(5);
+    // ---- C2 backweights: G[j, tap] += sum_p d_c2[j, p] * s1[c, y(p)+u, x(p)+v];  K step = (S, r):
+    //      the four pixels 16 S + 4 q + r of lane quarter q ------------------------------------------
+#pragma unroll
+    for (int S = 0; S < 4; ++S)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int imm = 24 * S + 12 * (r >> 1) + (r & 1);
+#pragma unroll
+        for (int nt = 0; nt < 10; ++nt)
+          st.acc_k2[nt] = mfma16(d2v[S][r], s.s1[st.toffb[nt] + 2 * q + imm], st.acc_k2[nt]);
+      }
+
+    CNN_PHASE(6);
+    // ---- C2 backin summed over the twelve maps, col2im form:
+    //        T[(c,u,v), p] = sum_j k2[j,c,u,v] * d_c2[j,p];   d_s1[c, y(p)+u, x(p)+v] += T[(c,u,v), p].
+    //      With level = 2 nt + u (nt = pixel tile = row pair of p), two terms of one map touch the
+    //      same cells only if their levels differ by at most 1; equal level and equal v means the very
+    //      same cells.  So for each v: terms of equal level are added in registers, then all even
+    //      levels go to LDS in one round of read-add-write, then all odd levels.  Within a round no two
+    //      lanes share an address (maps are 144 floats apart, levels 24, pixels of a tile distinct).
+    {
+      float bd[3][4];
+#pragma unroll
+      for (int sidx = 0; sidx < 3; ++sidx)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) bd[sidx][nt] = s.d2[(4 * sidx + q) * D2S + 16 * nt + n16];
+      f4 t4[2][4];      // taps (4, v), v < 4, in register v
+      float t44[2][4];  // tap (4, 4)
+#pragma unroll
+      for (int cg = 0; cg < 2; ++cg) {
+        float au[3], ac[3];
+#pragma unroll
+        for (int sidx = 0; sidx < 3; ++sidx) {
+          au[sidx] = tl[(TAB_AB + (cg * 7 + kTileU4) * 3 + sidx) * 64];
+          ac[sidx] = tl[(TAB_AB + (cg * 7 + kTileC) * 3 + sidx) * 64];
+        }
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+          f4 a = f4{0.0f, 0.0f, 0.0f, 0.0f}, c = a;
+#pragma unroll
+          for (int sidx = 0; sidx < 3; ++sidx) {
+            a = mfma16(au[sidx], bd[sidx][nt], a);
+            c = mfma16(ac[sidx], bd[sidx][nt], c);
+          }
+          t4[cg][nt] = a;
+          t44[cg][nt] = c[0];
+        }
+      }
+      float* tgt = s.d_s1 + 144 * q + pp;
+#pragma unroll
+      for (int v = 0; v < 5; ++v) {
+        f4 tv[2][4];  // taps (u, v), u < 4, in register u
+#pragma unroll
+        for (int cg = 0; cg < 2; ++cg) {
+          float av[3];
+#pragma unroll
+          for (int sidx = 0; sidx < 3; ++sidx) av[sidx] = tl[(TAB_AB + (cg * 7 + kTileV0 + v) * 3 + sidx) * 64];
+#pragma unroll
+          for (int nt = 0; nt < 4; ++nt) {
+            f4 a = f4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int sidx = 0; sidx < 3; ++sidx) a = mfma16(av[sidx], bd[sidx][nt], a);
+            tv[cg][nt] = a;
+          }
+        }
+        // even levels 2m, m < 6: (nt = m, u = 0) + (m-1, 2) + (m-2, 4)
+        {
+          float e[2][6], old[2][6];
+#pragma unroll
+          for (int cg = 0; cg < 2; ++cg)
+#pragma unroll
+            for (int m = 0; m < 6; ++m) {
+              float acc = 0.0f;
+              if (m < 4) acc = tv[cg][m < 4 ? m : 0][0];
+              if (m >= 1 && m <= 4) acc += tv[cg][m >= 1 ? m - 1 : 0][2];
+              if (m >= 2) acc += v < 4 ? t4[cg][m >= 2 ? m - 2 : 0][v < 4 ? v : 0] : t44[cg][m >= 2 ? m - 2 : 0];
+              e[cg][m] = acc;
+              old[cg][m] = tgt[576 * cg + 24 * m + v];
+            }
+#pragma unroll
+          for (int cg = 0; cg < 2; ++cg)
+#pragma unroll
+            for (int m = 0; m < 6; ++m) tgt[576 * cg + 24 * m + v] = old[cg][m] + e[cg][m];
+        }
+        wave_sync();
+        // odd levels 2m+1, m < 5: (nt = m, u = 1) + (m-1, 3)
+        {
+          float e[2][5], old[2][5];
+#pragma unroll
+          for (int cg = 0; cg < 2; ++cg)
+#pragma unroll
+            for (int m = 0; m < 5; ++m) {
+              float acc = 0.0f;
+              if (m < 4) acc = tv[cg][m < 4 ? m : 0][1];
+              if (m >= 1) acc += tv[cg][m >= 1 ? m - 1 : 0][3];
+              e[cg][m] = acc;
+              old[cg][m] = tgt[576 * cg + 24 * m + 12 + v];
+            }
+#pragma unroll
+          for (int cg = 0; cg < 2; ++cg)
+#pragma unroll
+            for (int m = 0; m < 5; ++m) tgt[576 * cg + 24 * m + 12 + v] = old[cg][m] + e[cg][m];
+        }
+        wave_sync();
+      }
+    }
+
+    CNN_PHASE(7);
+    if (next_image) load_pixels(px, next_image);
+    // ---- backavgpool through S1, derivative of C1's sigmoid, C1 backweights / backbias: per pixel
+    //      (= 4-lane block) the outer product of 6(8) map errors and 25(28) image taps -------------------
+#pragma unroll
+    for (int gp = 0; gp < 5; ++gp) {
+      float* buf = &s.stage[0][0];
+      if (gp > 0) wave_sync();  // the previous pair's operands have been read
+#pragma unroll
+      for (int k = 0; k < (gp < 4 ? 2 : 1); ++k) {
+        const int g = 2 * gp + k;
+        float d1[6];
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+          const float c = c1[g][i];
+          d1[i] = s.d_s1[i * 144 + 16 * g + b] * 0.25f * c * (1.0f - c);
+          st.g_b1[i] += d1[i];
+        }
+        *reinterpret_cast<f4*>(&buf[512 * k + l * 8]) = f4{d1[0], d1[1], d1[2], d1[3]};
+        *reinterpret_cast<float2*>(&buf[512 * k + l * 8 + 4]) = float2{d1[4], d1[5]};
+      }
+      wave_sync();
+#pragma unroll
+      for (int k = 0; k < (gp < 4 ? 2 : 1); ++k) {
+        const int g = 2 * gp + k;
+        const float* pa = s.img + st.pix0[g] + sub;       // taps (u = nt, v = sub) and (4,4)
+        const float* pb = s.img + st.pix0[g] + 28 * sub;  // taps (u = sub, v = 4)
+        const float* sa = buf + 512 * k + 32 * b + sub;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int pt = (t >> 1) * 28 + (t & 1);  // sub-pixel t of the window
+          const float a0 = sa[8 * t], a1 = sa[8 * t + 4];
+#pragma unroll
+          for (int nt = 0; nt < 7; ++nt) {
+            const float bv = nt < 5 ? pa[28 * nt + pt] : nt == 5 ? pb[4 + pt] : pa[116 + pt];
+            st.acc_k1[0][nt] = mfma4(a0, bv, st.acc_k1[0][nt]);
+            st.acc_k1[1][nt] = mfma4(a1, bv, st.acc_k1[1][nt]);
+          }
+        }
+      }
+    }
+    wave_sync();
+    CNN_PHASE(8);
+  }
+}
+
+// Writes the wave's gradient sums to its partial row (every slot has exactly one writer).
+__device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, float* __restrict__ out) {
+  const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15, b = l >> 2, sub = l & 3;
+#pragma unroll
+  for (int o = 0; o < 10; ++o)
+#pragma unroll
+    for (int k = 0; k < 3; ++k) out[OFF_FC + o * NS2 + l + 64 * k] = st.g_fc[o][k];
+  if (l == 0) {
+#pragma unroll
+    for (int o = 0; o < 10; ++o) out[OFF_B + o] = st.g_b[o];
+    out[LOSS_SLOT] = st.loss;
+  }
+#pragma unroll
+  for (int nt = 0; nt < 10; ++nt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int j = 4 * q + r, tap = 16 * nt + n16;
+      if (j < 12 && tap < 150) out[OFF_K2 + j * 150 + tap] = st.acc_k2[nt][r];
+    }
+  {
+    float v = st.g_b2;  // lane (q, j): sum over the four lane quarters
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    if (q == 0 && n16 < 12) out[OFF_B2 + n16] = v;
+  }
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 7; ++nt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float v = st.acc_k1[mt][nt][r];  // sum over the sixteen 4-lane blocks
+        v += __shfl_xor(v, 4);
+        v += __shfl_xor(v, 8);
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 32);
+        const int map = 4 * mt + r;
+        const int tap = k1_tap(nt, sub);
+        if (b == 0 && map < 6 && tap >= 0) out[OFF_K1 + map * 25 + tap] = v;
+      }
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    const float v = wave_sum(st.g_b1[i]);
+    if (l == 0) out[OFF_B1 + i] = v;
+  }
+}
+
+}  // namespace cnn
