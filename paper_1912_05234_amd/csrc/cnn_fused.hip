@@ -31,7 +31,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void forward_kernel(const float* __r
                                                             const float* __restrict__ w,
                                                             float* __restrict__ yhat, DumpPtrs dump,
                                                             float* __restrict__ eval_partial) {
-  __shared__ float tab[TAB_FWD_ENTRIES * 64];
+  __shared__ OperandTable<TAB_FWD_ENTRIES> tab;
   __shared__ FwdLds lds[WAVES];
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
   FwdLds& s = lds[wave];
@@ -41,8 +41,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void forward_kernel(const float* __r
   __syncthreads();  // the only workgroup-wide barrier: the operand table is complete
   const size_t gw = (size_t)blockIdx.x * WAVES + wave, G = (size_t)gridDim.x * WAVES;
   float n_ok = 0.0f, loss = 0.0f;
-  Pixels px;
-  if (gw < (size_t)B) load_pixels(px, images + gw * NI);
+  Pixels px = load_pixels(images + (gw < (size_t)B ? gw : 0) * NI);
   for (size_t n = gw; n < (size_t)B; n += G) {
     float y[10];
     const size_t nn = n + G;
@@ -99,7 +98,7 @@ __global__ __launch_bounds__(64 * WAVES) void train_kernel(const float* __restri
                                                           const int32_t* __restrict__ labels, int B,
                                                           const float* __restrict__ w,
                                                           float* __restrict__ partial) {
-  __shared__ float tab[TAB_TRAIN_ENTRIES * 64];
+  __shared__ OperandTable<TAB_TRAIN_ENTRIES> tab;
   __shared__ TrainLds lds[WAVES];
   const int wave = threadIdx.x >> 6;
   TrainLds& s = lds[wave];
@@ -109,8 +108,7 @@ __global__ __launch_bounds__(64 * WAVES) void train_kernel(const float* __restri
   __syncthreads();  // the only workgroup-wide barrier: the operand table is complete
   const size_t gw = (size_t)blockIdx.x * WAVES + wave, G = (size_t)gridDim.x * WAVES;
   const DumpPtrs none = {nullptr, nullptr, nullptr, nullptr};
-  Pixels px;
-  if (gw < (size_t)B) load_pixels(px, images + gw * NI);
+  Pixels px = load_pixels(images + (gw < (size_t)B ? gw : 0) * NI);
   for (size_t n = gw; n < (size_t)B; n += G) {
     float y[10];
     const size_t nn = n + G;

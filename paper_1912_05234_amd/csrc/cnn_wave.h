@@ -4,7 +4,7 @@
 // backavgpool); the backward driver is the chain rule over those.
 //
 // Where the arithmetic runs
-//   C1 forward            fp32 VALU, weights wave-uniform (scalar registers)
+//   C1 forward            fp32 VALU, weights broadcast from LDS
 //   C2 forward            v_mfma_f32_16x16x4_f32: M = 16 pixels, N = 12(16) maps, K = 150(152) taps
 //   C2 weight gradient    v_mfma_f32_16x16x4_f32: M = 12(16) maps, N = 16 taps, K = 64 pixels
 //   C2 input error        v_mfma_f32_16x16x4_f32: T[tap,pixel] = k2^T * d_c2 (K = 12 maps), then T is
@@ -48,27 +48,39 @@ constexpr int D2S = 68;   // row stride of the C2 error array in LDS (floats)
 // past the start of s1; those cells are zero or finite and meet zero weights.
 struct __align__(16) FwdLds {
   float img[NI];
-  float s1[NS1 + 288];
-  float s2[NS2];
+  float pool[NS1 + 288 + NS2];  // s1 at P_S1, s2 at P_S2
 };
 // Per-wave LDS of the training step.  d_s1 comes first: the col2im rows of the two padding maps
 // (c = 6, 7) add 0.0 at offsets up to 1152 floats past its start, which stays inside the struct.
+// `pool` holds, at the P_* offsets, the arrays that are dead by the time the C1 weight gradient
+// runs; that phase reuses the whole pool as its staging area.
+constexpr int P_S1 = 0;                 // s1[6][12][12] + 288 (padded K steps of the C2 forward read them)
+constexpr int P_S2 = P_S1 + NS1 + 288;  // s2[192]
+constexpr int P_DS2 = P_S2 + NS2;       // d_s2[192] + 64 (rows of the padding maps of the C2 tiles)
+constexpr int P_D2 = P_DS2 + NS2 + 64;  // d2[16][D2S]: error at C2's pre-activation, [map][pixel p]
+constexpr int P_END = P_D2 + 16 * D2S;
+constexpr int STG = 6;                  // floats per lane in the C1 error staging, [g][lane][6]
+constexpr int POOL_FLOATS = 9 * 64 * STG + 32;  // + the over-read of the last lane's padding rows
+static_assert(POOL_FLOATS >= P_END, "pool holds the forward/C2 arrays");
 struct __align__(16) TrainLds {
-  float d_s1[NS1];      // error at S1 (col2im target)
+  float d_s1[NS1];  // error at S1 (col2im target)
   float img[NI];
-  float s1[NS1 + 288];
-  float s2[NS2];
-  float d_s2[NS2 + 64]; // rows of the four padding maps of the C2 tiles read up to index 255
-  float d2[16 * D2S];   // error at C2's pre-activation, [map][pixel p]
-  float stage[2][512];  // C1 error of a pair of pixel groups: [lane][8 maps] (maps 6,7 stay zero)
+  float pool[POOL_FLOATS];
 };
-
 // Shared operand table, [entry][lane].
 constexpr int TAB_BF = 0;          // 38: C2 forward B operand, k2[j = n16][tap(s, q)]
 constexpr int TAB_FCW = 38;        // 30: fc[o][lane + 64 k] at entry 3 o + k
 constexpr int TAB_FWD_ENTRIES = 68;
 constexpr int TAB_AB = 68;         // 42: C2 input-error A operand, entry (cg*7 + tile)*3 + s
 constexpr int TAB_TRAIN_ENTRIES = 110;
+// After the [entry][lane] part: C1 weights by tap, k1t[tap][8] = k1[0..5][tap], 0, 0 for tap < 25 and
+// the biases b1 in row 25; every lane reads the same row (an LDS broadcast).
+constexpr int K1T_FLOATS = 26 * 8;
+template <int ENTRIES>
+struct __align__(16) OperandTable {
+  float e[ENTRIES * 64];
+  float k1t[K1T_FLOATS];
+};
 
 enum Mode { kForward = 0, kForwardDump = 1, kTrain = 2 };
 template <int MODE>
@@ -150,24 +162,39 @@ __host__ __device__ constexpr int k1_tap(int nt, int sub) {
 }
 
 // Fills the shared operand table from the flat parameter vector; all 256 threads take part and
-// the caller follows with a workgroup barrier.
+// the caller follows with a workgroup barrier.  The loop is unrolled so that a thread's gathers
+// are all in flight together instead of one memory round trip per entry.
 template <int MODE>
-__device__ __forceinline__ void build_tables(float* __restrict__ tab, const float* __restrict__ w) {
+__device__ __forceinline__ void build_tables(OperandTable<LdsOf<MODE>::entries>& tab,
+                                             const float* __restrict__ w) {
+  constexpr int ENTRIES = LdsOf<MODE>::entries;
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
-  for (int e = wave; e < LdsOf<MODE>::entries; e += WAVES) {
-    float v;
+  float v[(ENTRIES + WAVES - 1) / WAVES];
+#pragma unroll
+  for (int it = 0; it < (ENTRIES + WAVES - 1) / WAVES; ++it) {
+    const int e = it * WAVES + wave;
+    int idx = -1;
     if (e < TAB_FCW) {
       const int tap = fwd_tap(e, q);
-      v = (n16 < 12 && tap >= 0) ? w[OFF_K2 + n16 * 150 + tap] : 0.0f;
+      if (n16 < 12 && tap >= 0) idx = OFF_K2 + n16 * 150 + tap;
     } else if (e < TAB_AB) {
       const int o = (e - TAB_FCW) / 3, k = (e - TAB_FCW) % 3;
-      v = w[OFF_FC + o * NS2 + l + 64 * k];
-    } else {
-      const int idx = e - TAB_AB, sidx = idx % 3, tile = (idx / 3) % 7, cg = idx / 21;
+      idx = OFF_FC + o * NS2 + l + 64 * k;
+    } else if (e < ENTRIES) {
+      const int t = e - TAB_AB, sidx = t % 3, tile = (t / 3) % 7, cg = t / 21;
       const int c = 4 * cg + (n16 >> 2), tap = bwd_tap(tile, n16 & 3);
-      v = (c < 6 && tap >= 0) ? w[OFF_K2 + (4 * sidx + q) * 150 + c * 25 + tap] : 0.0f;
+      if (c < 6 && tap >= 0) idx = OFF_K2 + (4 * sidx + q) * 150 + c * 25 + tap;
     }
-    tab[e * 64 + l] = v;
+    v[it] = idx >= 0 ? w[idx] : 0.0f;
+  }
+#pragma unroll
+  for (int it = 0; it < (ENTRIES + WAVES - 1) / WAVES; ++it) {
+    const int e = it * WAVES + wave;
+    if (e < ENTRIES) tab.e[e * 64 + l] = v[it];
+  }
+  if (threadIdx.x < K1T_FLOATS) {
+    const int tap = threadIdx.x >> 3, i = threadIdx.x & 7;
+    tab.k1t[threadIdx.x] = i < 6 ? (tap < 25 ? w[OFF_K1 + i * 25 + tap] : w[OFF_B1 + i]) : 0.0f;
   }
 }
 
@@ -177,10 +204,11 @@ struct WaveState {
   int pix0[9];    // LDS offset of the origin of this lane's pooling window in pixel group g
   float bias2;    // b2[n16]
   // training only
-  int toffb[10];  // C2 weight-gradient B operand: s1 offset of tap 16 nt + n16
   f4 acc_k2[10];  // sum over images of d_c2 (x) s1 patches, D[j = 4q+r][tap = 16 nt + n16]
   f4 acc_k1[2][7];  // per 4-lane block partial of d_c1 (x) image patches
-  float g_b1[6], g_b2, g_fc[10][3], g_b[10], loss;
+  f4 acc_fc[3][3];  // FC weight gradient, D_r(lane) = g_fc[o = 4 mt + r][i = lane + 64 k]
+  float g_bq[3];    // FC bias gradient: lane l holds b[4 mt + l % 4] (the same in every quad)
+  float g_b1[6], g_b2, loss;
 };
 
 template <int MODE>
@@ -188,8 +216,9 @@ __device__ __forceinline__ void wave_init(WaveState<MODE>& st, typename LdsOf<MO
                                           const float* __restrict__ w) {
   const int l = threadIdx.x & 63, n16 = l & 15, b = l >> 2;
   // all of this wave's LDS starts finite: padded GEMM steps multiply it by zero weights
-  float* raw = reinterpret_cast<float*>(&s);
-  for (int e = l; e < (int)(sizeof(s) / 4); e += 64) raw[e] = 0.0f;
+  static_assert(sizeof(s) % 16 == 0, "LDS struct is a whole number of 16-byte pieces");
+  f4* raw = reinterpret_cast<f4*>(&s);
+  for (int e = l; e < (int)(sizeof(s) / 16); e += 64) raw[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
   for (int g = 0; g < 9; ++g) {
     const int win = 16 * g + b;
@@ -198,12 +227,7 @@ __device__ __forceinline__ void wave_init(WaveState<MODE>& st, typename LdsOf<MO
   st.bias2 = n16 < 12 ? w[OFF_B2 + n16] : 0.0f;
   if (MODE == kTrain) {
 #pragma unroll
-    for (int nt = 0; nt < 10; ++nt) {
-      const int tap = 16 * nt + n16;
-      const int c = tap / 25, u = (tap % 25) / 5, v = tap % 5;
-      st.toffb[nt] = tap < 150 ? c * 144 + u * 12 + v : 0;
-      st.acc_k2[nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-    }
+    for (int nt = 0; nt < 10; ++nt) st.acc_k2[nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -213,10 +237,10 @@ __device__ __forceinline__ void wave_init(WaveState<MODE>& st, typename LdsOf<MO
     st.g_b2 = 0.0f;
     st.loss = 0.0f;
 #pragma unroll
-    for (int o = 0; o < 10; ++o) {
-      st.g_b[o] = 0.0f;
+    for (int mt = 0; mt < 3; ++mt) {
+      st.g_bq[mt] = 0.0f;
 #pragma unroll
-      for (int k = 0; k < 3; ++k) st.g_fc[o][k] = 0.0f;
+      for (int k = 0; k < 3; ++k) st.acc_fc[mt][k] = f4{0.0f, 0.0f, 0.0f, 0.0f};
     }
   }
 }
@@ -226,16 +250,20 @@ struct DumpPtrs {
   float *c1, *s1, *c2, *s2;
 };
 
-// The 196 16-byte pieces of one image as four registers per lane (the fourth only in lanes 0..3).
+// The 196 16-byte pieces of one image as four float4 registers per lane (the fourth only in lanes
+// 0..3).  Kept as separate values so that they stay in registers.
 struct Pixels {
-  float4 v[4];
+  f4 a, b, c, d;
 };
-__device__ __forceinline__ void load_pixels(Pixels& px, const float* __restrict__ image) {
-  const float4* src = reinterpret_cast<const float4*>(image);
+__device__ __forceinline__ Pixels load_pixels(const float* __restrict__ image) {
+  const f4* src = reinterpret_cast<const f4*>(image);
   const int l = threadIdx.x & 63;
-#pragma unroll
-  for (int k = 0; k < 3; ++k) px.v[k] = src[l + 64 * k];  // consecutive lanes -> consecutive 16 bytes
-  if (l < 4) px.v[3] = src[l + 192];
+  Pixels px;
+  px.a = src[l];  // consecutive lanes -> consecutive 16 bytes
+  px.b = src[l + 64];
+  px.c = src[l + 128];
+  px.d = src[l < 4 ? l + 192 : l];  // lanes >= 4 re-read a piece they already have (no divergence)
+  return px;
 }
 
 // One image through forward (and, when MODE == kTrain, backward).  `px` holds this image's pixels on
@@ -244,24 +272,25 @@ __device__ __forceinline__ void load_pixels(Pixels& px, const float* __restrict_
 // (wave-uniform).  `label` is only read when training.
 template <int MODE>
 __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<MODE>::type& s,
-                                           const float* __restrict__ tab, Pixels& px,
+                                           const OperandTable<LdsOf<MODE>::entries>& tab, Pixels& px,
                                            const float* __restrict__ next_image, int label,
                                            const float* __restrict__ w, float (&y)[10], const DumpPtrs& dump,
                                            size_t n) {
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15, b = l >> 2, sub = l & 3;
   const int pp = 12 * ((n16 & 3) >> 1) + 2 * (n16 >> 2) + (n16 & 1);
-  const float* tl = tab + l;  // this lane's column of the operand table
+  const float* tl = tab.e + l;  // this lane's column of the operand table
 
   CNN_PHASE_DECL;
   CNN_PHASE(0);
   {
-    float4* dst = reinterpret_cast<float4*>(s.img);
-#pragma unroll
-    for (int k = 0; k < 3; ++k) dst[l + 64 * k] = px.v[k];
-    if (l < 4) dst[l + 192] = px.v[3];
+    f4* dst = reinterpret_cast<f4*>(s.img);
+    dst[l] = px.a;
+    dst[l + 64] = px.b;
+    dst[l + 128] = px.c;
+    if (l < 4) dst[l + 192] = px.d;
   }
   wave_sync();
-  if (MODE != kTrain && next_image) load_pixels(px, next_image);
+  if (MODE != kTrain && next_image) px = load_pixels(next_image);
 
   CNN_PHASE(1);
   // ---- C1 = sigmoid(mconv(I, k1, b1)), S1 = avgpool(C1).  Tap-outer: the six weights of a tap are
@@ -269,57 +298,76 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
   float c1[9][6];
   {
     const float* ip[9];
+    {
+      const f4 ba = *reinterpret_cast<const f4*>(&tab.k1t[25 * 8]);
+      const float2 bb = *reinterpret_cast<const float2*>(&tab.k1t[25 * 8 + 4]);
 #pragma unroll
-    for (int g = 0; g < 9; ++g) {
-      ip[g] = s.img + st.pix0[g] + (sub >> 1) * 28 + (sub & 1);
-#pragma unroll
-      for (int i = 0; i < 6; ++i) c1[g][i] = w[OFF_B1 + i];
+      for (int g = 0; g < 9; ++g) {
+        ip[g] = s.img + st.pix0[g] + (sub >> 1) * 28 + (sub & 1);
+        c1[g][0] = ba[0]; c1[g][1] = ba[1]; c1[g][2] = ba[2]; c1[g][3] = ba[3];
+        c1[g][4] = bb.x;  c1[g][5] = bb.y;
+      }
     }
-    // The loop over kernel rows is a real loop: its body holds 45 pixel reads, 30 scalar weight
-    // loads and 270 multiply-adds, and the 54 accumulators are carried around it, which keeps the
+    // The loop over kernel rows is a real loop: its body holds 45 pixel reads, 10 broadcast weight
+    // reads and 270 multiply-adds, and the 54 accumulators are carried around it, which keeps the
     // compiler from hoisting all 225 reads (and their registers) or serialising the sums.
 #pragma unroll 1
     for (int u = 0; u < 5; ++u) {
-      const float* ku = w + OFF_K1 + u * 5;  // wave-uniform: scalar loads
+      const float* ku = tab.k1t + u * 40;
 #pragma unroll
       for (int v = 0; v < 5; ++v) {
+        const f4 wa = *reinterpret_cast<const f4*>(&ku[v * 8]);
+        const float2 wb = *reinterpret_cast<const float2*>(&ku[v * 8 + 4]);
+        const float wt[6] = {wa[0], wa[1], wa[2], wa[3], wb.x, wb.y};
         float x[9];
 #pragma unroll
         for (int g = 0; g < 9; ++g) x[g] = ip[g][u * 28 + v];
 #pragma unroll
-        for (int i = 0; i < 6; ++i) {
-          const float wt = ku[i * 25 + v];
+        for (int i = 0; i < 6; ++i)
 #pragma unroll
-          for (int g = 0; g < 9; ++g) c1[g][i] = fmaf(wt, x[g], c1[g][i]);
-        }
+          for (int g = 0; g < 9; ++g) c1[g][i] = fmaf(wt[i], x[g], c1[g][i]);
       }
     }
+    // sigmoid, then S1 = avgpool(C1): the four lanes of a quad are the four pixels of one window.
+    // A butterfly with selects leaves the window sum of map `sub` in lane `sub`, so one unmasked
+    // store per group writes four maps (no divergent store, nothing for the scheduler to trip on).
+    const bool odd = sub & 1, hi = sub & 2;
 #pragma unroll
-    for (int g = 0; g < 9; ++g)
+    for (int g = 0; g < 9; ++g) {
 #pragma unroll
       for (int i = 0; i < 6; ++i) {
-        const float c = logistic(c1[g][i]);
-        c1[g][i] = c;
-        float t = c + quad_xor1(c);
-        t += quad_xor2(t);
-        if (sub == 0) s.s1[i * 144 + 16 * g + b] = 0.25f * t;
+        c1[g][i] = logistic(c1[g][i]);
         if (MODE == kForwardDump && dump.c1) {
           const int win = 16 * g + b;
-          dump.c1[n * NC1 + i * 576 + (2 * (win / 12) + (sub >> 1)) * 24 + 2 * (win % 12) + (sub & 1)] = c;
+          dump.c1[n * NC1 + i * 576 + (2 * (win / 12) + (sub >> 1)) * 24 + 2 * (win % 12) + (sub & 1)] = c1[g][i];
         }
       }
+      const float s01 = (odd ? c1[g][1] : c1[g][0]) + quad_xor1(odd ? c1[g][0] : c1[g][1]);
+      const float s23 = (odd ? c1[g][3] : c1[g][2]) + quad_xor1(odd ? c1[g][2] : c1[g][3]);
+      const float tot = (hi ? s23 : s01) + quad_xor2(hi ? s01 : s23);
+      s.pool[P_S1 + sub * 144 + 16 * g + b] = 0.25f * tot;
+    }
+    // maps 4 and 5 of two groups at a time: lane sub -> map 4 + (sub & 1) of group (sub & 2 ? g1 : g0)
+#pragma unroll
+    for (int gp = 0; gp < 5; ++gp) {
+      const int g0 = 2 * gp, g1 = gp < 4 ? 2 * gp + 1 : 8;
+      const float sa = (odd ? c1[g0][5] : c1[g0][4]) + quad_xor1(odd ? c1[g0][4] : c1[g0][5]);
+      const float sb = (odd ? c1[g1][5] : c1[g1][4]) + quad_xor1(odd ? c1[g1][4] : c1[g1][5]);
+      const float tot = (hi ? sb : sa) + quad_xor2(hi ? sa : sb);
+      s.pool[P_S1 + (4 + (sub & 1)) * 144 + 16 * (hi ? g1 : g0) + b] = 0.25f * tot;
+    }
   }
   wave_sync();
   if (MODE == kForwardDump && dump.s1)
-    for (int e = l; e < NS1; e += 64) dump.s1[n * NS1 + e] = s.s1[e];
+    for (int e = l; e < NS1; e += 64) dump.s1[n * NS1 + e] = s.pool[P_S1 + e];
 
   CNN_PHASE(2);
   // ---- C2 = sigmoid(mconv(S1, k2, b2)) as a 64 x 16 x 152 GEMM, S2 = avgpool(C2) ------------------
   f4 c2v[4];
   {
-    const float* a12 = s.s1 + pp + 12 * q;
-    const float* a1 = s.s1 + pp + q;
-    const float* a144 = s.s1 + pp + 144 * q;
+    const float* a12 = s.pool + P_S1 + pp + 12 * q;
+    const float* a1 = s.pool + P_S1 + pp + q;
+    const float* a144 = s.pool + P_S1 + pp + 144 * q;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) c2v[mt] = f4{st.bias2, st.bias2, st.bias2, st.bias2};
 #pragma unroll
@@ -333,7 +381,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
     for (int mt = 0; mt < 4; ++mt) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) c2v[mt][r] = logistic(c2v[mt][r]);
-      if (n16 < 12) s.s2[n16 * 16 + 4 * mt + q] = 0.25f * ((c2v[mt][0] + c2v[mt][1]) + (c2v[mt][2] + c2v[mt][3]));
+      if (n16 < 12) s.pool[P_S2 + n16 * 16 + 4 * mt + q] = 0.25f * ((c2v[mt][0] + c2v[mt][1]) + (c2v[mt][2] + c2v[mt][3]));
       if (MODE == kForwardDump && dump.c2 && n16 < 12)
 #pragma unroll
         for (int r = 0; r < 4; ++r)
@@ -342,13 +390,13 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
   }
   wave_sync();
   if (MODE == kForwardDump && dump.s2)
-    for (int e = l; e < NS2; e += 64) dump.s2[n * NS2 + e] = s.s2[e];
+    for (int e = l; e < NS2; e += 64) dump.s2[n * NS2 + e] = s.pool[P_S2 + e];
 
   CNN_PHASE(3);
   // ---- output = sigmoid(mconv(S2, fc, b)): lane owns inputs lane, lane+64, lane+128 ----------------
   float sv[3];
 #pragma unroll
-  for (int k = 0; k < 3; ++k) sv[k] = s.s2[l + 64 * k];
+  for (int k = 0; k < 3; ++k) sv[k] = s.pool[P_S2 + l + 64 * k];
 #pragma unroll
   for (int o = 0; o < 10; ++o) {
     float p = tl[(TAB_FCW + 3 * o) * 64] * sv[0];
@@ -366,19 +414,26 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
         const float e = y[o] - (o == label ? 1.0f : 0.0f);
         lsum = fmaf(e, e, lsum);
         delta[o] = e * y[o] * (1.0f - y[o]);
-        st.g_b[o] += delta[o];
       }
       st.loss = fmaf(0.5f, lsum, st.loss);
+    }
+    // backweights as rank-1 updates on the 4x4 MFMA: A(lane) = delta[4 mt + lane%4] (delta is
+    // wave-uniform, so every quad holds the same four values), B(lane) = s2[lane + 64 k].
+#pragma unroll
+    for (int mt = 0; mt < 3; ++mt) {
+      const float d0 = delta[4 * mt], d1 = delta[4 * mt + 1];
+      const float d2 = mt < 2 ? delta[4 * mt + 2] : 0.0f, d3 = mt < 2 ? delta[4 * mt + 3] : 0.0f;
+      const float aq = (sub & 2) ? ((sub & 1) ? d3 : d2) : ((sub & 1) ? d1 : d0);
+      st.g_bq[mt] += aq;  // backbias
+#pragma unroll
+      for (int k = 0; k < 3; ++k) st.acc_fc[mt][k] = mfma4(aq, sv[k], st.acc_fc[mt][k]);
     }
 #pragma unroll
     for (int k = 0; k < 3; ++k) {
       float d = 0.0f;
 #pragma unroll
-      for (int o = 0; o < 10; ++o) {
-        st.g_fc[o][k] = fmaf(delta[o], sv[k], st.g_fc[o][k]);
-        d = fmaf(tl[(TAB_FCW + 3 * o + k) * 64], delta[o], d);
-      }
-      s.d_s2[l + 64 * k] = d;
+      for (int o = 0; o < 10; ++o) d = fmaf(tl[(TAB_FCW + 3 * o + k) * 64], delta[o], d);
+      s.pool[P_DS2 + l + 64 * k] = d;
     }
     // clear the col2im target of the C2 input error
     for (int e = l; e < NS1 / 4; e += 64) reinterpret_cast<f4*>(s.d_s1)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
@@ -390,13 +445,13 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
     f4 d2v[4];
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
-      const float up = s.d_s2[n16 * 16 + 4 * mt + q] * 0.25f;  // rows n16 >= 12 read finite filler
+      const float up = s.pool[P_DS2 + n16 * 16 + 4 * mt + q] * 0.25f;  // rows n16 >= 12 read finite filler
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const float c = c2v[mt][r];
         d2v[mt][r] = up * c * (1.0f - c);
       }
-      *reinterpret_cast<f4*>(&s.d2[n16 * D2S + 16 * mt + 4 * q]) = d2v[mt];
+      *reinterpret_cast<f4*>(&s.pool[P_D2 + n16 * D2S + 16 * mt + 4 * q]) = d2v[mt];
       st.g_b2 += (d2v[mt][0] + d2v[mt][1]) + (d2v[mt][2] + d2v[mt][3]);
     }
     wave_sync();
@@ -404,15 +459,23 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
     CNN_PHASE(5);
     // ---- C2 backweights: G[j, tap] += sum_p d_c2[j, p] * s1[c, y(p)+u, x(p)+v];  K step = (S, r):
     //      the four pixels 16 S + 4 q + r of lane quarter q ------------------------------------------
+    {
+      const float* bsrc[10];  // s1 patch element of tap 16 nt + n16 for pixel quarter q
 #pragma unroll
-    for (int S = 0; S < 4; ++S)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int imm = 24 * S + 12 * (r >> 1) + (r & 1);
-#pragma unroll
-        for (int nt = 0; nt < 10; ++nt)
-          st.acc_k2[nt] = mfma16(d2v[S][r], s.s1[st.toffb[nt] + 2 * q + imm], st.acc_k2[nt]);
+      for (int nt = 0; nt < 10; ++nt) {
+        const int tap = 16 * nt + n16;
+        const int c = tap / 25, rem = tap - 25 * c, u = rem / 5, v = rem - 5 * u;
+        bsrc[nt] = s.pool + P_S1 + (tap < 150 ? c * 144 + u * 12 + v : 0) + 2 * q;
       }
+#pragma unroll
+      for (int S = 0; S < 4; ++S)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int imm = 24 * S + 12 * (r >> 1) + (r & 1);
+#pragma unroll
+          for (int nt = 0; nt < 10; ++nt) st.acc_k2[nt] = mfma16(d2v[S][r], bsrc[nt][imm], st.acc_k2[nt]);
+        }
+    }
 
     CNN_PHASE(6);
     // ---- C2 backin summed over the twelve maps, col2im form:
@@ -427,7 +490,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
 #pragma unroll
       for (int sidx = 0; sidx < 3; ++sidx)
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) bd[sidx][nt] = s.d2[(4 * sidx + q) * D2S + 16 * nt + n16];
+        for (int nt = 0; nt < 4; ++nt) bd[sidx][nt] = s.pool[P_D2 + (4 * sidx + q) * D2S + 16 * nt + n16];
       f4 t4[2][4];      // taps (4, v), v < 4, in register v
       float t44[2][4];  // tap (4, 4)
 #pragma unroll
@@ -451,9 +514,9 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
         }
       }
       float* tgt = s.d_s1 + 144 * q + pp;
-#pragma unroll
-      for (int v = 0; v < 5; ++v) {
-        f4 tv[2][4];  // taps (u, v), u < 4, in register u
+      // tile V(v+1) is issued before the rounds of V(v), so its MFMAs run under the LDS round trips
+      f4 tv[2][4], tn[2][4];  // taps (u, v), u < 4, in register u
+      auto v_tiles = [&](int v, f4 (&out)[2][4]) {
 #pragma unroll
         for (int cg = 0; cg < 2; ++cg) {
           float av[3];
@@ -464,9 +527,14 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
             f4 a = f4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int sidx = 0; sidx < 3; ++sidx) a = mfma16(av[sidx], bd[sidx][nt], a);
-            tv[cg][nt] = a;
+            out[cg][nt] = a;
           }
         }
+      };
+      v_tiles(0, tv);
+#pragma unroll
+      for (int v = 0; v < 5; ++v) {
+        if (v < 4) v_tiles(v + 1, tn);
         // even levels 2m, m < 6: (nt = m, u = 0) + (m-1, 2) + (m-2, 4)
         {
           float e[2][6], old[2][6];
@@ -506,52 +574,74 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
             for (int m = 0; m < 5; ++m) tgt[576 * cg + 24 * m + 12 + v] = old[cg][m] + e[cg][m];
         }
         wave_sync();
+        if (v < 4) {
+#pragma unroll
+          for (int cg = 0; cg < 2; ++cg)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) tv[cg][nt] = tn[cg][nt];
+        }
       }
     }
 
     CNN_PHASE(7);
-    if (next_image) load_pixels(px, next_image);
-    // ---- backavgpool through S1, derivative of C1's sigmoid, C1 backweights / backbias: per pixel
-    //      (= 4-lane block) the outer product of 6(8) map errors and 25(28) image taps -------------------
+    if (next_image) px = load_pixels(next_image);
+    // ---- backavgpool through S1 and the derivative of C1's sigmoid for all nine pixel groups, staged
+    //      in LDS as [g][lane][6 maps] over the pool (s1, s2, d_s2, d2 are dead by now) ------------------
 #pragma unroll
-    for (int gp = 0; gp < 5; ++gp) {
-      float* buf = &s.stage[0][0];
-      if (gp > 0) wave_sync();  // the previous pair's operands have been read
+    for (int gp = 0; gp < 3; ++gp) {
+      float up[3][6];
 #pragma unroll
-      for (int k = 0; k < (gp < 4 ? 2 : 1); ++k) {
-        const int g = 2 * gp + k;
+      for (int k = 0; k < 3; ++k)
+#pragma unroll
+        for (int i = 0; i < 6; ++i) up[k][i] = s.d_s1[i * 144 + 16 * (3 * gp + k) + b];
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        const int g = 3 * gp + k;
         float d1[6];
 #pragma unroll
         for (int i = 0; i < 6; ++i) {
           const float c = c1[g][i];
-          d1[i] = s.d_s1[i * 144 + 16 * g + b] * 0.25f * c * (1.0f - c);
+          d1[i] = up[k][i] * 0.25f * c * (1.0f - c);
           st.g_b1[i] += d1[i];
         }
-        *reinterpret_cast<f4*>(&buf[512 * k + l * 8]) = f4{d1[0], d1[1], d1[2], d1[3]};
-        *reinterpret_cast<float2*>(&buf[512 * k + l * 8 + 4]) = float2{d1[4], d1[5]};
-      }
-      wave_sync();
-#pragma unroll
-      for (int k = 0; k < (gp < 4 ? 2 : 1); ++k) {
-        const int g = 2 * gp + k;
-        const float* pa = s.img + st.pix0[g] + sub;       // taps (u = nt, v = sub) and (4,4)
-        const float* pb = s.img + st.pix0[g] + 28 * sub;  // taps (u = sub, v = 4)
-        const float* sa = buf + 512 * k + 32 * b + sub;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int pt = (t >> 1) * 28 + (t & 1);  // sub-pixel t of the window
-          const float a0 = sa[8 * t], a1 = sa[8 * t + 4];
-#pragma unroll
-          for (int nt = 0; nt < 7; ++nt) {
-            const float bv = nt < 5 ? pa[28 * nt + pt] : nt == 5 ? pb[4 + pt] : pa[116 + pt];
-            st.acc_k1[0][nt] = mfma4(a0, bv, st.acc_k1[0][nt]);
-            st.acc_k1[1][nt] = mfma4(a1, bv, st.acc_k1[1][nt]);
-          }
-        }
+        float2* dst = reinterpret_cast<float2*>(&s.pool[(g * 64 + l) * STG]);
+        dst[0] = float2{d1[0], d1[1]};
+        dst[1] = float2{d1[2], d1[3]};
+        dst[2] = float2{d1[4], d1[5]};
       }
     }
     wave_sync();
     CNN_PHASE(8);
+    // ---- C1 backweights: per pixel (= 4-lane block) the outer product of 6(8) map errors and
+    //      25(28) image taps; 36 steps of 16 pixels, no synchronisation between them.  Rows of the
+    //      padding maps 6, 7 read the next lane's staging cells: finite, and their results are dropped.
+    {
+      // operands of step k+1 are read while the 14 MFMAs of step k issue (explicit double buffer)
+      float opa[2][2], opb[2][7];
+      auto load_step = [&](int k, float (&oa)[2], float (&ob)[7]) {
+        const int g = k >> 2, t = k & 3;
+        const int pt = (t >> 1) * 28 + (t & 1);                // sub-pixel t of the window
+        const float* pa = s.img + st.pix0[g] + sub;            // taps (u = nt, v = sub) and (4,4)
+        const float* pb = s.img + st.pix0[g] + 28 * sub;       // taps (u = sub, v = 4)
+        const float* sa = s.pool + (g * 64 + 4 * b) * STG + sub;
+        oa[0] = sa[STG * t];
+        oa[1] = sa[STG * t + 4];
+#pragma unroll
+        for (int nt = 0; nt < 7; ++nt) ob[nt] = nt < 5 ? pa[28 * nt + pt] : nt == 5 ? pb[4 + pt] : pa[116 + pt];
+      };
+      load_step(0, opa[0], opb[0]);
+#pragma unroll
+      for (int k = 0; k < 36; ++k) {
+        if (k + 1 < 36) load_step(k + 1, opa[(k + 1) & 1], opb[(k + 1) & 1]);
+#pragma unroll
+        for (int nt = 0; nt < 7; ++nt) {
+          st.acc_k1[0][nt] = mfma4(opa[k & 1][0], opb[k & 1][nt], st.acc_k1[0][nt]);
+          st.acc_k1[1][nt] = mfma4(opa[k & 1][1], opb[k & 1][nt], st.acc_k1[1][nt]);
+        }
+      }
+    }
+    wave_sync();
+    CNN_PHASE(9);
   }
 }
 
@@ -559,14 +649,17 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
 __device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, float* __restrict__ out) {
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15, b = l >> 2, sub = l & 3;
 #pragma unroll
-  for (int o = 0; o < 10; ++o)
+  for (int mt = 0; mt < 3; ++mt) {
 #pragma unroll
-    for (int k = 0; k < 3; ++k) out[OFF_FC + o * NS2 + l + 64 * k] = st.g_fc[o][k];
-  if (l == 0) {
+    for (int k = 0; k < 3; ++k)
 #pragma unroll
-    for (int o = 0; o < 10; ++o) out[OFF_B + o] = st.g_b[o];
-    out[LOSS_SLOT] = st.loss;
+      for (int r = 0; r < 4; ++r) {
+        const int o = 4 * mt + r;
+        if (o < 10) out[OFF_FC + o * NS2 + l + 64 * k] = st.acc_fc[mt][k][r];
+      }
+    if (l < 4 && 4 * mt + l < 10) out[OFF_B + 4 * mt + l] = st.g_bq[mt];
   }
+  if (l == 0) out[LOSS_SLOT] = st.loss;
 #pragma unroll
   for (int nt = 0; nt < 10; ++nt)
 #pragma unroll
