@@ -20,7 +20,6 @@ namespace {
 
 using namespace cnn;
 
-constexpr int TPB = 256;      // reduction kernel
 constexpr int GCAP = 1024;    // most waves (= gradient partials) per step: one per SIMD of 256 CUs
 
 // Forward-only: yhat[B,10], optional activation dump, optional (count, loss) per wave.
@@ -36,12 +35,12 @@ __global__ __launch_bounds__(64 * WAVES, 2) void forward_kernel(const float* __r
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
   FwdLds& s = lds[wave];
   WaveState<MODE> st;
+  const size_t gw = (size_t)blockIdx.x * WAVES + wave, G = (size_t)gridDim.x * WAVES;
+  Pixels px = load_pixels(images + (gw < (size_t)B ? gw : 0) * NI);  // in flight during the set-up
   build_tables<MODE>(tab, w);
   wave_init(st, s, w);
   __syncthreads();  // the only workgroup-wide barrier: the operand table is complete
-  const size_t gw = (size_t)blockIdx.x * WAVES + wave, G = (size_t)gridDim.x * WAVES;
   float n_ok = 0.0f, loss = 0.0f;
-  Pixels px = load_pixels(images + (gw < (size_t)B ? gw : 0) * NI);
   for (size_t n = gw; n < (size_t)B; n += G) {
     float y[10];
     const size_t nn = n + G;
@@ -103,12 +102,12 @@ __global__ __launch_bounds__(64 * WAVES) void train_kernel(const float* __restri
   const int wave = threadIdx.x >> 6;
   TrainLds& s = lds[wave];
   WaveState<kTrain> st;
+  const size_t gw = (size_t)blockIdx.x * WAVES + wave, G = (size_t)gridDim.x * WAVES;
+  Pixels px = load_pixels(images + (gw < (size_t)B ? gw : 0) * NI);  // in flight during the set-up
   build_tables<kTrain>(tab, w);
   wave_init(st, s, w);
   __syncthreads();  // the only workgroup-wide barrier: the operand table is complete
-  const size_t gw = (size_t)blockIdx.x * WAVES + wave, G = (size_t)gridDim.x * WAVES;
   const DumpPtrs none = {nullptr, nullptr, nullptr, nullptr};
-  Pixels px = load_pixels(images + (gw < (size_t)B ? gw : 0) * NI);
   for (size_t n = gw; n < (size_t)B; n += G) {
     float y[10];
     const size_t nn = n + G;
@@ -118,23 +117,39 @@ __global__ __launch_bounds__(64 * WAVES) void train_kernel(const float* __restri
   CNN_PHASE_FLUSH;
 }
 
-// Adds the G partial rows in a fixed order (four interleaved strands, then a
-// fixed tree over the strands) and either applies  w <- w - scale * g  (grad_out
-// == nullptr) or stores g.  One workgroup per 64 parameters; lanes of a wave
-// read 64 consecutive floats of a row.
-__global__ __launch_bounds__(TPB) void reduce_update_kernel(const float* __restrict__ partial, int G,
-                                                            float scale, float* __restrict__ w,
-                                                            float* __restrict__ grad_out,
-                                                            float* __restrict__ loss_sum) {
-  __shared__ float red[4][64];
+// Adds the G partial rows in a fixed order (sixteen interleaved strands, each summed in row
+// order, then a fixed tree over the strands) and either applies  w <- w - scale * g  (grad_out ==
+// nullptr) or stores g.  One workgroup per 64 parameters; the lanes of a wave read 64 consecutive
+// floats of a row, and a strand keeps four row reads in flight.
+constexpr int RSTRANDS = 16;
+__global__ __launch_bounds__(64 * RSTRANDS) void reduce_update_kernel(const float* __restrict__ partial, int G,
+                                                                     float scale, float* __restrict__ w,
+                                                                     float* __restrict__ grad_out,
+                                                                     float* __restrict__ loss_sum) {
+  __shared__ float red[RSTRANDS][64];
   const int lane = threadIdx.x & 63, strand = threadIdx.x >> 6;
   const int p = blockIdx.x * 64 + lane;
-  float acc = 0.0f;
-  for (int g = strand; g < G; g += 4) acc += partial[(size_t)g * PSTRIDE + p];
-  red[strand][lane] = acc;
+  const float* src = partial + p;
+  float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+  int g = strand;
+  for (; g + 3 * RSTRANDS < G; g += 4 * RSTRANDS) {
+    a0 += src[(size_t)g * PSTRIDE];
+    a1 += src[(size_t)(g + RSTRANDS) * PSTRIDE];
+    a2 += src[(size_t)(g + 2 * RSTRANDS) * PSTRIDE];
+    a3 += src[(size_t)(g + 3 * RSTRANDS) * PSTRIDE];
+  }
+  for (; g < G; g += RSTRANDS) a0 += src[(size_t)g * PSTRIDE];
+  red[strand][lane] = (a0 + a1) + (a2 + a3);
   __syncthreads();
   if (strand == 0) {
-    const float total = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+    float t[RSTRANDS];
+#pragma unroll
+    for (int k = 0; k < RSTRANDS; ++k) t[k] = red[k][lane];
+#pragma unroll
+    for (int step = 1; step < RSTRANDS; step *= 2)
+#pragma unroll
+      for (int k = 0; k < RSTRANDS; k += 2 * step) t[k] += t[k + step];
+    const float total = t[0];
     if (p < NPARAM) {
       if (grad_out)
         grad_out[p] = total;
@@ -220,7 +235,7 @@ int run_backward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B
     CNN_HIP_TRY(hipEventRecord(ctx->ev[2 * ctx->ev_used + 1], ctx->stream));
     ++ctx->ev_used;
   }
-  reduce_update_kernel<<<PSTRIDE / 64, TPB, 0, ctx->stream>>>(ctx->partial, G, scale, ctx->w, grad_out,
+  reduce_update_kernel<<<PSTRIDE / 64, 64 * RSTRANDS, 0, ctx->stream>>>(ctx->partial, G, scale, ctx->w, grad_out,
                                                               loss_sum);
   if (hipGetLastError() != hipSuccess) return CNN_EHIP;
   return CNN_OK;
