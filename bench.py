@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--batch", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (a dispatch of known HBM traffic for "
+                         "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build is a single-GPU kernel study; run it with --gpus 1 "
@@ -86,6 +89,13 @@ def main():
         assert bool(torch.isfinite(loss).item())
         net.close()
         return batch * steps / dt, 1e3 * dt / steps, float(np.mean(ms))
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)   # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     value, ms_per_step, kernel_ms = measure(args.batch, args.steps, args.warmup)
     achieved_tflops = FLOP_PER_IMAGE_TRAIN * args.batch / (kernel_ms * 1e-3) / 1e12

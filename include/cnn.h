@@ -96,7 +96,7 @@ int cnn_evaluate(cnn_ctx* ctx, const float* images, const int32_t* labels, int N
  * each cnn_train_batch / cnn_gradient call records one pair of HIP events around its fused
  * forward+backward kernel (the first `capacity` calls; later ones are not recorded).
  * cnn_profile_read waits for the context's stream, writes the elapsed milliseconds of each
- * recorded kernel to ms (a HOST array of at least `capacity` floats) and the number of recorded
+ * recorded kernel (less the reading of an empty event pair, measured in the same call) to ms (a HOST array of at least `capacity` floats) and the number of recorded
  * steps to *n_recorded (HOST), and restarts recording from zero.  capacity == 0 stops recording
  * and frees the events.  No device memory is involved. */
 int cnn_profile_begin(cnn_ctx* ctx, int capacity);
