@@ -20,7 +20,8 @@ namespace {
 
 using namespace cnn;
 
-constexpr int GCAP = 1024;    // most waves (= gradient partials) per step: one per SIMD of 256 CUs
+constexpr int GCAP = 1024;      // most training waves (= gradient partials) per step: one per SIMD of 256 CUs
+constexpr int FWD_GCAP = 3072;  // most forward-only waves: three per SIMD
 
 // Forward-only: yhat[B,10], optional activation dump, optional (count, loss) per wave.
 // Wave gw = 4 * blockIdx.x + wave walks the images gw, gw + G, gw + 2G, ... (G = waves in the grid).
@@ -102,18 +103,22 @@ __global__ __launch_bounds__(64 * WAVES) void train_kernel(const float* __restri
   const int wave = threadIdx.x >> 6;
   TrainLds& s = lds[wave];
   WaveState<kTrain> st;
+  CNN_KERNEL_MARK(0);
   const size_t gw = (size_t)blockIdx.x * WAVES + wave, G = (size_t)gridDim.x * WAVES;
   Pixels px = load_pixels(images + (gw < (size_t)B ? gw : 0) * NI);  // in flight during the set-up
   build_tables<kTrain>(tab, w);
   wave_init(st, s, w);
   __syncthreads();  // the only workgroup-wide barrier: the operand table is complete
   const DumpPtrs none = {nullptr, nullptr, nullptr, nullptr};
+  CNN_KERNEL_MARK(1);
   for (size_t n = gw; n < (size_t)B; n += G) {
     float y[10];
     const size_t nn = n + G;
     wave_image<kTrain>(st, s, tab, px, nn < (size_t)B ? images + nn * NI : nullptr, labels[n], w, y, none, n);
   }
+  CNN_KERNEL_MARK(2);
   wave_flush(st, partial + gw * PSTRIDE);
+  CNN_KERNEL_MARK(3);
   CNN_PHASE_FLUSH;
 }
 
@@ -167,7 +172,8 @@ __global__ __launch_bounds__(64 * RSTRANDS) void reduce_update_kernel(const floa
 struct cnn_ctx {
   hipStream_t stream;
   int max_batch;
-  int gcap;
+  int gcap;      // cap on training waves
+  int fwd_gcap;  // cap on forward-only waves
   float* w;             // [PSTRIDE]
   float* partial;       // [gcap][PSTRIDE]
   float* eval_partial;  // [gcap][2]
@@ -180,8 +186,8 @@ namespace {
 constexpr size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Cap on waves, rounded up to whole workgroups.
-inline int gcap_for(int max_batch) {
-  const int g = max_batch < GCAP ? max_batch : GCAP;
+inline int gcap_for(int max_batch, int cap = GCAP) {
+  const int g = max_batch < cap ? max_batch : cap;
   return (g + WAVES - 1) / WAVES * WAVES;
 }
 
@@ -195,7 +201,7 @@ inline Layout layout_for(int max_batch) {
   l.w = 0;
   l.partial = align_up(l.w + sizeof(float) * PSTRIDE, 256);
   l.eval_partial = align_up(l.partial + sizeof(float) * PSTRIDE * g, 256);
-  l.total = align_up(l.eval_partial + sizeof(float) * 2 * g, 256);
+  l.total = align_up(l.eval_partial + sizeof(float) * 2 * (size_t)gcap_for(max_batch, FWD_GCAP), 256);
   return l;
 }
 
@@ -205,14 +211,15 @@ const int kParamLen[6] = {150, 6, 1800, 12, 1920, 10};
 inline bool batch_ok(const cnn_ctx* ctx, int B) { return ctx && B >= 1 && B <= ctx->max_batch; }
 
 // Workgroups to launch for B images: one wave per image up to the cap on waves.
-inline int blocks_for(const cnn_ctx* ctx, int B) {
-  const int waves = B < ctx->gcap ? B : ctx->gcap;
+inline int blocks_for(const cnn_ctx* ctx, int B, bool forward_only) {
+  const int cap = forward_only ? ctx->fwd_gcap : ctx->gcap;
+  const int waves = B < cap ? B : cap;
   return (waves + WAVES - 1) / WAVES;
 }
 
 int run_forward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B, float* yhat, float* c1,
                 float* s1, float* c2, float* s2, bool eval) {
-  const int blocks = blocks_for(ctx, B);
+  const int blocks = blocks_for(ctx, B, true);
   const DumpPtrs dump = {c1, s1, c2, s2};
   if (c1 || s1 || c2 || s2)
     forward_kernel<kForwardDump><<<blocks, 64 * WAVES, 0, ctx->stream>>>(images, labels, B, ctx->w, yhat,
@@ -226,7 +233,7 @@ int run_forward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B,
 
 int run_backward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B, float scale,
                  float* grad_out, float* loss_sum) {
-  const int blocks = blocks_for(ctx, B), G = blocks * WAVES;
+  const int blocks = blocks_for(ctx, B, false), G = blocks * WAVES;
   const bool timed = (size_t)(2 * ctx->ev_used + 3) < ctx->ev.size();
   if (timed) CNN_HIP_TRY(hipEventRecord(ctx->ev[2 * ctx->ev_used], ctx->stream));
   train_kernel<<<blocks, 64 * WAVES, 0, ctx->stream>>>(images, labels, B, ctx->w, ctx->partial);
@@ -292,6 +299,7 @@ int cnn_init(cnn_ctx** out, void* workspace, size_t workspace_bytes, int max_bat
   ctx->stream = (hipStream_t)hip_stream;
   ctx->max_batch = max_batch;
   ctx->gcap = gcap_for(max_batch);
+  ctx->fwd_gcap = gcap_for(max_batch, FWD_GCAP);
   ctx->w = reinterpret_cast<float*>(base + l.w);
   ctx->partial = reinterpret_cast<float*>(base + l.partial);
   ctx->eval_partial = reinterpret_cast<float*>(base + l.eval_partial);

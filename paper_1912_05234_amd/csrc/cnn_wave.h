@@ -35,6 +35,7 @@
 #define CNN_PHASE_DECL
 #define CNN_PHASE(k)
 #define CNN_PHASE_FLUSH
+#define CNN_KERNEL_MARK(k)
 #endif
 
 namespace cnn {
@@ -105,6 +106,13 @@ __device__ __forceinline__ float dpp_row_half_mirror(float v) {
 }
 __device__ __forceinline__ float dpp_row_mirror(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));
+}
+// rotate right by 4 / by 8 lanes inside each row of 16 lanes
+__device__ __forceinline__ float dpp_row_ror4(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x124, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float dpp_row_ror8(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x128, 0xF, 0xF, true));
 }
 // Sum over the 64 lanes in a fixed order, same value in every lane: quad, 8, 16 lanes by DPP,
 // then the four rows of 16 through scalar registers.
@@ -673,21 +681,38 @@ __device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, float* __restr
     v += __shfl_xor(v, 32);
     if (q == 0 && n16 < 12) out[OFF_B2 + n16] = v;
   }
+  // C1 weights: sum over the sixteen 4-lane blocks.  Inside a row of 16 lanes the four blocks are
+  // joined by two DPP rotations; the four rows are joined through lane exchanges, all values of a
+  // stage issued together.  The order of the additions is fixed.
+  {
 #pragma unroll
-  for (int mt = 0; mt < 2; ++mt)
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < 7; ++nt)
+      for (int nt = 0; nt < 7; ++nt)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        float v = st.acc_k1[mt][nt][r];  // sum over the sixteen 4-lane blocks
-        v += __shfl_xor(v, 4);
-        v += __shfl_xor(v, 8);
-        v += __shfl_xor(v, 16);
-        v += __shfl_xor(v, 32);
-        const int map = 4 * mt + r;
-        const int tap = k1_tap(nt, sub);
-        if (b == 0 && map < 6 && tap >= 0) out[OFF_K1 + map * 25 + tap] = v;
-      }
+        for (int r = 0; r < (mt == 0 ? 4 : 2); ++r) {
+          float x = st.acc_k1[mt][nt][r];
+          x += dpp_row_ror8(x);
+          x += dpp_row_ror4(x);
+          st.acc_k1[mt][nt][r] = x;
+        }
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 7; ++nt)
+#pragma unroll
+        for (int r = 0; r < (mt == 0 ? 4 : 2); ++r) st.acc_k1[mt][nt][r] += __shfl_xor(st.acc_k1[mt][nt][r], 16);
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 7; ++nt)
+#pragma unroll
+        for (int r = 0; r < (mt == 0 ? 4 : 2); ++r) {
+          const float x = st.acc_k1[mt][nt][r] + __shfl_xor(st.acc_k1[mt][nt][r], 32);
+          const int map = 4 * mt + r, tap = k1_tap(nt, sub);
+          if (b == 0 && tap >= 0) out[OFF_K1 + map * 25 + tap] = x;
+        }
+  }
 #pragma unroll
   for (int i = 0; i < 6; ++i) {
     const float v = wave_sum(st.g_b1[i]);
