@@ -378,12 +378,24 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
     const float* a144 = s.pool + P_S1 + pp + 144 * q;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) c2v[mt] = f4{st.bias2, st.bias2, st.bias2, st.bias2};
+    // operands of K step s+2 are read while the MFMAs of step s issue (three rotating buffers);
+    // the scheduling groups pin that order, which the compiler would otherwise collapse
+    float opa[3][4], opw[3];
+    auto load_step = [&](int sidx, float (&oa)[4], float& ow) {
+      const float* base = sidx < 30 ? a12 : sidx < 36 ? a1 : a144;
+      ow = tl[(TAB_BF + sidx) * 64];
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) oa[mt] = base[fwd_imm(sidx) + 24 * mt];
+    };
+    load_step(0, opa[0], opw[0]);
+    load_step(1, opa[1], opw[1]);
 #pragma unroll
     for (int sidx = 0; sidx < 38; ++sidx) {
-      const float* base = sidx < 30 ? a12 : sidx < 36 ? a1 : a144;
-      const float bw = tl[(TAB_BF + sidx) * 64];
+      if (sidx + 2 < 38) load_step(sidx + 2, opa[(sidx + 2) % 3], opw[(sidx + 2) % 3]);
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) c2v[mt] = mfma16(base[fwd_imm(sidx) + 24 * mt], bw, c2v[mt]);
+      for (int mt = 0; mt < 4; ++mt) c2v[mt] = mfma16(opa[sidx % 3][mt], opw[sidx % 3], c2v[mt]);
+      if (sidx + 2 < 38) __builtin_amdgcn_sched_group_barrier(0x100, 5, 0);  // 5 LDS reads of step s+2
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);                     // 4 MFMAs of step s
     }
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {

@@ -1,0 +1,144 @@
+"""GPU parity at the full-size configurations, in the launch configuration the benchmark times:
+60000 resident synthetic images, batch 100 (one and ten epochs), the full-batch steps at 1000 /
+10000 / 60000 images, the 10000-image evaluation pass, and the C2-shaped per-layer kernels at
+10000 images.  Expected values come from tests/golden/training_golden.npz, written by
+tests/golden/make_training_golden.py, which calls only the CPU oracle."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1912_05234_amd import binding, inputs
+from parity import RTOL_ACT, RTOL_W, assert_close
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+LR = 0.05
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "training_golden.npz")
+
+
+@pytest.fixture(scope="module")
+def golden():
+    return np.load(GOLDEN)
+
+
+@pytest.fixture(scope="module")
+def train_set():
+    images, labels = inputs.make_batch(60000, 1001)
+    return torch.from_numpy(images).to(DEV), torch.from_numpy(labels).to(DEV)
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+@pytest.mark.parametrize("B", [1000, 10000, 60000])
+def test_full_batch_step(B, golden, train_set):
+    """One full-batch step (batch sweep): gradient, loss and the updated weights."""
+    images, labels = train_set
+    w0 = inputs.make_weights()
+    net = binding.CNN(w0, max_batch=B)
+    grad, loss = net.gradient(images[:B], labels[:B])
+    g_ref = golden["grad_%d" % B]
+    g, r = inputs.unflatten(host(grad)), inputs.unflatten(g_ref)
+    for name in g:
+        assert_close(g[name], r[name], 2e-5, "grad %s at B=%d" % (name, B))
+    assert abs(host(loss)[0] - float(golden["loss_%d" % B])) <= 2e-5 * float(golden["loss_%d" % B])
+    # the step itself: w0 - (lr/B) * g, and bitwise the same when run twice
+    net.train_batch(images[:B], labels[:B], LR)
+    w1 = host(net.get_weights_flat())
+    expect = inputs.flatten(w0).astype(np.float64) - float(np.float32(LR)) / B * g_ref
+    assert_close(w1, expect, 1e-6, "weights after one step at B=%d" % B)
+    net2 = binding.CNN(w0, max_batch=B)
+    net2.train_batch(images[:B], labels[:B], LR)
+    np.testing.assert_array_equal(host(net2.get_weights_flat()), w1)
+
+
+def run_epochs(net, images, labels, epochs, losses=None):
+    for e in range(epochs):
+        for s in range(600):
+            net.train_batch(images[s * 100:(s + 1) * 100], labels[s * 100:(s + 1) * 100], LR,
+                            None if losses is None else losses[e * 600 + s:e * 600 + s + 1])
+
+
+def test_one_epoch_then_evaluation(golden, train_set):
+    """600 steps of batch 100 over the 60000 images, then forward-only over 10000 more."""
+    images, labels = train_set
+    net = binding.CNN(inputs.make_weights(), max_batch=10000)
+    losses = torch.zeros(600, dtype=torch.float32, device=DEV)
+    run_epochs(net, images, labels, 1, losses)
+    w = host(net.get_weights_flat())
+    g, r = inputs.unflatten(w), inputs.unflatten(golden["w_epoch1"])
+    for name in g:
+        assert_close(g[name], r[name], RTOL_W, "weights %s after one epoch" % name)
+    assert abs(host(losses).astype(np.float64).sum() - golden["loss_epoch"][0]) <= 1e-5 * golden["loss_epoch"][0]
+    # the training moved the weights far beyond the tolerance
+    assert np.abs(golden["w_epoch1"] - inputs.flatten(inputs.make_weights())).max() > 1e3 * RTOL_W * np.abs(w).max()
+
+    ev_images, ev_labels = inputs.make_batch(10000, 1002)
+    ev_i, ev_l = torch.from_numpy(ev_images).to(DEV), torch.from_numpy(ev_labels).to(DEV)
+    net.set_weights(inputs.unflatten(golden["w_epoch1"].astype(np.float32)))   # the oracle's weights
+    n_ok, loss = net.evaluate(ev_i, ev_l)
+    yhat = host(net.forward(ev_i))
+    assert_close(yhat[:64], golden["eval1_yhat_head"], RTOL_ACT, "yhat of the first 64 evaluation images")
+    for n in (5000, 9999):   # sampled rows computed one by one
+        ref = oracle.forward(ev_images[n], golden["w_epoch1"].astype(np.float32))["y"]
+        assert_close(yhat[n], ref, RTOL_ACT, "yhat[%d]" % n)
+    top2 = np.sort(yhat, axis=1)[:, -2:]
+    near_ties = int((top2[:, 1] - top2[:, 0] <= 4 * RTOL_ACT * np.abs(yhat).max()).sum())
+    assert abs(int(host(n_ok)[0]) - int(golden["eval1_correct"])) <= near_ties
+    assert int(host(n_ok)[0]) == int((yhat.argmax(1) == ev_labels).sum())
+    assert abs(host(loss)[0] - float(golden["eval1_loss"])) <= 2e-5 * float(golden["eval1_loss"])
+
+
+def test_ten_epochs(golden, train_set):
+    """The paper-shaped run: ten epochs of 600 steps; final weights against the oracle's."""
+    if "w_epoch10" not in golden.files:
+        pytest.skip("golden file holds fewer than ten epochs")
+    images, labels = train_set
+    net = binding.CNN(inputs.make_weights(), max_batch=100)
+    run_epochs(net, images, labels, 10)
+    w = host(net.get_weights_flat())
+    g, r = inputs.unflatten(w), inputs.unflatten(golden["w_epoch10"])
+    for name in g:
+        assert_close(g[name], r[name], RTOL_W, "weights %s after ten epochs" % name)
+
+
+def test_c2_layer_kernels_at_10000_images():
+    """Per-layer kernels on the C2 shape (input [B,6,12,12], twelve 6x5x5 kernels), uniform [-1,1):
+    sampled images against the oracle one by one, and additivity of the batch-summed weight
+    gradient over chunks."""
+    B = 10000
+    x = inputs.make_signed((B, 6, 12, 12), 31)
+    k = inputs.make_signed((12, 6, 5, 5), 32)
+    bias = inputs.make_signed((12,), 33)
+    d = inputs.make_signed((B, 12, 8, 8), 34)
+    xd, kd, bd, dd = (torch.from_numpy(a).to(DEV) for a in (x, k, bias, d))
+    out = host(binding.conv_fwd(xd, kd, bd))
+    d_in = host(binding.conv_bwd_input(dd, kd, 12, 12))
+    for n in (0, 4097, B - 1):
+        ref = oracle.mconv(x[n], k, bias).reshape(12, 8, 8)
+        assert_close(out[n], ref, RTOL_ACT, "conv_fwd[%d]" % n)
+        ref_in = np.zeros((6, 12, 12))
+        for j in range(12):
+            ref_in += oracle.backin(d[n, j][None].astype(np.float64), k[j].astype(np.float64), (6, 12, 12))
+        assert_close(d_in[n], ref_in, RTOL_ACT, "conv_bwd_input[%d]" % n)
+    d_k, d_b = binding.conv_bwd_weight(xd, dd)
+    # chunk of 64 images against the oracle
+    d_k64, d_b64 = binding.conv_bwd_weight(xd[:64].contiguous(), dd[:64].contiguous())
+    ref_k = np.zeros((12, 6, 5, 5))
+    for n in range(64):
+        for j in range(12):
+            ref_k[j] += oracle.backweights(d[n, j][None].astype(np.float64), x[n].astype(np.float64))
+    assert_close(host(d_k64), ref_k, RTOL_ACT, "conv_bwd_weight on 64 images")
+    assert_close(host(d_b64), d[:64].astype(np.float64).sum(axis=(0, 2, 3)), RTOL_ACT, "bias gradient")
+    # the full batch is the sum of its chunks
+    acc_k = np.zeros((12, 6, 5, 5))
+    for c in range(0, B, 2500):
+        dk_c, _ = binding.conv_bwd_weight(xd[c:c + 2500].contiguous(), dd[c:c + 2500].contiguous())
+        acc_k += host(dk_c).astype(np.float64)
+    assert_close(host(d_k), acc_k, RTOL_ACT, "conv_bwd_weight additivity over chunks")
+    assert_close(host(d_b), d.astype(np.float64).sum(axis=(0, 2, 3)), RTOL_ACT, "bias gradient at 10000")
