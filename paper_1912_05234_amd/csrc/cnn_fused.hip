@@ -15,6 +15,7 @@
 #include <vector>
 
 #include "cnn_wave.h"
+#include "cnn_group.h"
 
 namespace {
 
@@ -22,13 +23,16 @@ using namespace cnn;
 
 constexpr int GCAP = 1024;      // most training waves (= gradient partials) per step: one per SIMD of 256 CUs
 constexpr int FWD_GCAP = 3072;  // most forward-only waves: three per SIMD
+// Batches up to this size give each image to a workgroup of four waves (lower latency per image);
+// larger ones give each image to a single wave (more images in flight, no barriers).
+constexpr int GROUP_MAX_BATCH = 256;
 
 // Forward-only: yhat[B,10], optional activation dump, optional (count, loss) per wave.
 // Wave gw = 4 * blockIdx.x + wave walks the images gw, gw + G, gw + 2G, ... (G = waves in the grid).
 template <int MODE>
 __global__ __launch_bounds__(64 * WAVES, 2) void forward_kernel(const float* __restrict__ images,
                                                             const int32_t* __restrict__ labels, int B,
-                                                            const float* __restrict__ w,
+                                                            const float* __restrict__ tabg,
                                                             float* __restrict__ yhat, DumpPtrs dump,
                                                             float* __restrict__ eval_partial) {
   __shared__ OperandTable<TAB_FWD_ENTRIES> tab;
@@ -38,14 +42,15 @@ __global__ __launch_bounds__(64 * WAVES, 2) void forward_kernel(const float* __r
   WaveState<MODE> st;
   const size_t gw = (size_t)blockIdx.x * WAVES + wave, G = (size_t)gridDim.x * WAVES;
   Pixels px = load_pixels(images + (gw < (size_t)B ? gw : 0) * NI);  // in flight during the set-up
-  build_tables<MODE>(tab, w);
-  wave_init(st, s, w);
+  load_tables<MODE>(tab, tabg);
+  wave_init(st, s);
   __syncthreads();  // the only workgroup-wide barrier: the operand table is complete
+  st.bias2 = tab.bias[l & 15];
   float n_ok = 0.0f, loss = 0.0f;
   for (size_t n = gw; n < (size_t)B; n += G) {
     float y[10];
     const size_t nn = n + G;
-    wave_image<MODE>(st, s, tab, px, nn < (size_t)B ? images + nn * NI : nullptr, 0, w, y, dump, n);
+    wave_image<MODE>(st, s, tab, px, nn < (size_t)B ? images + nn * NI : nullptr, 0, y, dump, n);
     if (yhat) {
 #pragma unroll
       for (int o = 0; o < NY; ++o)
@@ -96,7 +101,7 @@ __global__ __launch_bounds__(64) void eval_reduce_kernel(const float* __restrict
 // without images writes zeros).
 __global__ __launch_bounds__(64 * WAVES) void train_kernel(const float* __restrict__ images,
                                                           const int32_t* __restrict__ labels, int B,
-                                                          const float* __restrict__ w,
+                                                          const float* __restrict__ tabg,
                                                           float* __restrict__ partial) {
   __shared__ OperandTable<TAB_TRAIN_ENTRIES> tab;
   __shared__ TrainLds lds[WAVES];
@@ -106,29 +111,53 @@ __global__ __launch_bounds__(64 * WAVES) void train_kernel(const float* __restri
   CNN_KERNEL_MARK(0);
   const size_t gw = (size_t)blockIdx.x * WAVES + wave, G = (size_t)gridDim.x * WAVES;
   Pixels px = load_pixels(images + (gw < (size_t)B ? gw : 0) * NI);  // in flight during the set-up
-  build_tables<kTrain>(tab, w);
-  wave_init(st, s, w);
+  load_tables<kTrain>(tab, tabg);
+  wave_init(st, s);
   __syncthreads();  // the only workgroup-wide barrier: the operand table is complete
+  st.bias2 = tab.bias[threadIdx.x & 15];
   const DumpPtrs none = {nullptr, nullptr, nullptr, nullptr};
   CNN_KERNEL_MARK(1);
   for (size_t n = gw; n < (size_t)B; n += G) {
     float y[10];
     const size_t nn = n + G;
-    wave_image<kTrain>(st, s, tab, px, nn < (size_t)B ? images + nn * NI : nullptr, labels[n], w, y, none, n);
+    wave_image<kTrain>(st, s, tab, px, nn < (size_t)B ? images + nn * NI : nullptr, labels[n], y, none, n);
   }
   CNN_KERNEL_MARK(2);
-  wave_flush(st, partial + gw * PSTRIDE);
+  wave_flush(st, s, partial + gw * PSTRIDE);
   CNN_KERNEL_MARK(3);
   CNN_PHASE_FLUSH;
 }
 
+// Small batches: four waves share one image (cnn_group.h); one partial row per workgroup.
+__global__ __launch_bounds__(64 * WAVES) void train_group_kernel(const float* __restrict__ images,
+                                                                const int32_t* __restrict__ labels, int B,
+                                                                const float* __restrict__ tabg,
+                                                                float* __restrict__ partial) {
+  __shared__ OperandTable<TAB_TRAIN_ENTRIES> tab;
+  __shared__ TrainLds s;
+  __shared__ float ybuf[16];
+  group_train(images, labels, B, tabg, partial + (size_t)blockIdx.x * PSTRIDE, tab, s, ybuf);
+}
+
+// Expanded operand table from the flat parameter vector: tabg[i] = w[table_source(i)] or 0.
+__global__ __launch_bounds__(256) void expand_kernel(const float* __restrict__ w, float* __restrict__ tabg) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < TABG_FLOATS) {
+    const int p = table_source(i);
+    tabg[i] = p >= 0 ? w[p] : 0.0f;
+  }
+}
+
 // Adds the G partial rows in a fixed order (sixteen interleaved strands, each summed in row
 // order, then a fixed tree over the strands) and either applies  w <- w - scale * g  (grad_out ==
-// nullptr) or stores g.  One workgroup per 64 parameters; the lanes of a wave read 64 consecutive
-// floats of a row, and a strand keeps four row reads in flight.
+// nullptr) or stores g.  An updated parameter is also written to its slots of the expanded operand
+// table, dest[p][0..1] (-1 = none).  One workgroup per 64 parameters; the lanes of a wave read 64
+// consecutive floats of a row, and a strand keeps four row reads in flight.
 constexpr int RSTRANDS = 16;
 __global__ __launch_bounds__(64 * RSTRANDS) void reduce_update_kernel(const float* __restrict__ partial, int G,
                                                                      float scale, float* __restrict__ w,
+                                                                     const int32_t* __restrict__ dest,
+                                                                     float* __restrict__ tabg,
                                                                      float* __restrict__ grad_out,
                                                                      float* __restrict__ loss_sum) {
   __shared__ float red[RSTRANDS][64];
@@ -156,10 +185,15 @@ __global__ __launch_bounds__(64 * RSTRANDS) void reduce_update_kernel(const floa
       for (int k = 0; k < RSTRANDS; k += 2 * step) t[k] += t[k + step];
     const float total = t[0];
     if (p < NPARAM) {
-      if (grad_out)
+      if (grad_out) {
         grad_out[p] = total;
-      else
-        w[p] = fmaf(-scale, total, w[p]);
+      } else {
+        const float wn = fmaf(-scale, total, w[p]);
+        w[p] = wn;
+        const int d0 = dest[2 * p], d1 = dest[2 * p + 1];
+        if (d0 >= 0) tabg[d0] = wn;
+        if (d1 >= 0) tabg[d1] = wn;
+      }
     } else if (p == LOSS_SLOT && loss_sum) {
       *loss_sum = total;
     }
@@ -175,6 +209,8 @@ struct cnn_ctx {
   int gcap;      // cap on training waves
   int fwd_gcap;  // cap on forward-only waves
   float* w;             // [PSTRIDE]
+  float* tabg;          // [TABG_FLOATS]: the operand table expanded from w, kept in step with it
+  int32_t* dest;        // [PSTRIDE][2]: slots of tabg that hold parameter p
   float* partial;       // [gcap][PSTRIDE]
   float* eval_partial;  // [gcap][2]
   std::vector<hipEvent_t> ev;  // 2 per recorded step (before, after the fused kernel)
@@ -192,14 +228,16 @@ inline int gcap_for(int max_batch, int cap = GCAP) {
 }
 
 struct Layout {
-  size_t w, partial, eval_partial, total;
+  size_t w, tabg, dest, partial, eval_partial, total;
 };
 
 inline Layout layout_for(int max_batch) {
   Layout l;
   const size_t g = (size_t)gcap_for(max_batch);
   l.w = 0;
-  l.partial = align_up(l.w + sizeof(float) * PSTRIDE, 256);
+  l.tabg = align_up(l.w + sizeof(float) * PSTRIDE, 256);
+  l.dest = align_up(l.tabg + sizeof(float) * TABG_FLOATS, 256);
+  l.partial = align_up(l.dest + sizeof(int32_t) * 2 * PSTRIDE, 256);
   l.eval_partial = align_up(l.partial + sizeof(float) * PSTRIDE * g, 256);
   l.total = align_up(l.eval_partial + sizeof(float) * 2 * (size_t)gcap_for(max_batch, FWD_GCAP), 256);
   return l;
@@ -222,10 +260,10 @@ int run_forward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B,
   const int blocks = blocks_for(ctx, B, true);
   const DumpPtrs dump = {c1, s1, c2, s2};
   if (c1 || s1 || c2 || s2)
-    forward_kernel<kForwardDump><<<blocks, 64 * WAVES, 0, ctx->stream>>>(images, labels, B, ctx->w, yhat,
+    forward_kernel<kForwardDump><<<blocks, 64 * WAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, yhat,
                                                                           dump, nullptr);
   else
-    forward_kernel<kForward><<<blocks, 64 * WAVES, 0, ctx->stream>>>(images, labels, B, ctx->w, yhat, dump,
+    forward_kernel<kForward><<<blocks, 64 * WAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, yhat, dump,
                                                                       eval ? ctx->eval_partial : nullptr);
   if (hipGetLastError() != hipSuccess) return CNN_EHIP;
   return blocks * WAVES;
@@ -233,17 +271,22 @@ int run_forward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B,
 
 int run_backward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B, float scale,
                  float* grad_out, float* loss_sum) {
-  const int blocks = blocks_for(ctx, B, false), G = blocks * WAVES;
+  const bool grouped = B <= GROUP_MAX_BATCH;
+  const int blocks = grouped ? (B < ctx->gcap ? B : ctx->gcap) : blocks_for(ctx, B, false);
+  const int G = grouped ? blocks : blocks * WAVES;
   const bool timed = (size_t)(2 * ctx->ev_used + 3) < ctx->ev.size();
   if (timed) CNN_HIP_TRY(hipEventRecord(ctx->ev[2 * ctx->ev_used], ctx->stream));
-  train_kernel<<<blocks, 64 * WAVES, 0, ctx->stream>>>(images, labels, B, ctx->w, ctx->partial);
+  if (grouped)
+    train_group_kernel<<<blocks, 64 * WAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, ctx->partial);
+  else
+    train_kernel<<<blocks, 64 * WAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, ctx->partial);
   if (hipGetLastError() != hipSuccess) return CNN_EHIP;
   if (timed) {
     CNN_HIP_TRY(hipEventRecord(ctx->ev[2 * ctx->ev_used + 1], ctx->stream));
     ++ctx->ev_used;
   }
-  reduce_update_kernel<<<PSTRIDE / 64, 64 * RSTRANDS, 0, ctx->stream>>>(ctx->partial, G, scale, ctx->w, grad_out,
-                                                              loss_sum);
+  reduce_update_kernel<<<PSTRIDE / 64, 64 * RSTRANDS, 0, ctx->stream>>>(ctx->partial, G, scale, ctx->w, ctx->dest,
+                                                              ctx->tabg, grad_out, loss_sum);
   if (hipGetLastError() != hipSuccess) return CNN_EHIP;
   return CNN_OK;
 }
@@ -272,7 +315,8 @@ int cnn_set_weights(cnn_ctx* ctx, const float* k1, const float* b1, const float*
     if (src[a])
       CNN_HIP_TRY(hipMemcpyAsync(ctx->w + kParamOff[a], src[a], sizeof(float) * kParamLen[a],
                                  hipMemcpyDeviceToDevice, ctx->stream));
-  return CNN_OK;
+  expand_kernel<<<(TABG_FLOATS + 255) / 256, 256, 0, ctx->stream>>>(ctx->w, ctx->tabg);
+  return hipGetLastError() == hipSuccess ? CNN_OK : CNN_EHIP;
 }
 
 int cnn_get_weights(cnn_ctx* ctx, float* k1, float* b1, float* k2, float* b2, float* fc, float* b) {
@@ -301,12 +345,25 @@ int cnn_init(cnn_ctx** out, void* workspace, size_t workspace_bytes, int max_bat
   ctx->gcap = gcap_for(max_batch);
   ctx->fwd_gcap = gcap_for(max_batch, FWD_GCAP);
   ctx->w = reinterpret_cast<float*>(base + l.w);
+  ctx->tabg = reinterpret_cast<float*>(base + l.tabg);
+  ctx->dest = reinterpret_cast<int32_t*>(base + l.dest);
   ctx->partial = reinterpret_cast<float*>(base + l.partial);
   ctx->eval_partial = reinterpret_cast<float*>(base + l.eval_partial);
-  if (hipMemsetAsync(ctx->w, 0, sizeof(float) * PSTRIDE, ctx->stream) != hipSuccess) {
-    (void)hipGetLastError();
-    delete ctx;
-    return CNN_EHIP;
+  {
+    // inverse of table_source: where each parameter sits in the expanded table
+    static_assert(table_max_multiplicity() <= TABLE_MAX_DEST, "a parameter has at most two table slots");
+    std::vector<int32_t> dest(2 * PSTRIDE, -1);
+    for (int i = 0; i < TABG_FLOATS; ++i) {
+      const int p = table_source(i);
+      if (p >= 0) dest[2 * p + (dest[2 * p] < 0 ? 0 : 1)] = i;
+    }
+    // synchronous copy: the host vector may go away as soon as the call returns
+    if (hipMemcpy(ctx->dest, dest.data(), sizeof(int32_t) * dest.size(), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemsetAsync(ctx->w, 0, sizeof(float) * PSTRIDE, ctx->stream) != hipSuccess) {
+      (void)hipGetLastError();
+      delete ctx;
+      return CNN_EHIP;
+    }
   }
   const int rc = cnn_set_weights(ctx, k1, b1, k2, b2, fc, b);
   if (rc != CNN_OK) {

@@ -1,0 +1,474 @@
+// Small-batch form of the fused step: FOUR WAVEFRONTS SHARE ONE IMAGE.  Same arithmetic, same
+// operand table, same LDS arrays and the same MFMA formulations as cnn_wave.h (arXiv 1912.05234,
+// Section 3); only the division of labour differs, to cut the latency of a single image when there
+// are too few images to give every SIMD its own:
+//
+//   C1 forward, C1 error and C1 weight gradient   pixel groups g = wave + 4 k (wave 0 takes three)
+//   C2 forward, C2 error                          pixel tile mt = wave
+//   output layer                                  outputs o = wave, wave + 4, wave + 8
+//   FC weight gradient                            waves 0..2 take the three 4-output row tiles
+//   C2 input error (col2im)                       wave 0: input maps 0..3, wave 1: maps 4, 5
+//   C2 weight gradient                            wave 2: pixels 0..31, wave 3: pixels 32..63
+//
+// Phases that hand data between waves are separated by workgroup barriers (seven per image); the
+// two col2im waves never touch the same input map, so their read-add-write rounds need no barrier.
+#pragma once
+
+#include "cnn_wave.h"
+
+namespace cnn {
+
+struct GroupState {
+  int pix0[3];      // window origin of this lane in the wave's pixel groups g = wave + 4 k
+  float bias2;      // b2[n16]
+  f4 acc_k2[10];    // waves 2, 3: C2 weight gradient over their half of the pixels
+  f4 acc_k1[2][7];  // C1 weight gradient over this wave's pixel groups, per 4-lane block
+  f4 acc_fc[3];     // waves 0..2: FC weight gradient rows o = 4 wave + r, columns lane + 64 k
+  float g_bq;       // waves 0..2: FC bias gradient b[4 wave + lane % 4]
+  float g_b1[6], g_b2, loss;
+};
+
+// C1 forward for NS pixel groups of this wave: returns the activations in c1[k][map].
+template <int NS>
+__device__ __forceinline__ void group_c1_forward(const GroupState& st, TrainLds& s,
+                                                 const OperandTable<TAB_TRAIN_ENTRIES>& tab, int wave,
+                                                 float (&c1)[3][6]) {
+  const int l = threadIdx.x & 63, b = l >> 2, sub = l & 3;
+  const float* ip[NS];
+  {
+    const f4 ba = *reinterpret_cast<const f4*>(&tab.k1t[25 * 8]);
+    const float2 bb = *reinterpret_cast<const float2*>(&tab.k1t[25 * 8 + 4]);
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+      ip[k] = s.img + st.pix0[k] + (sub >> 1) * 28 + (sub & 1);
+      c1[k][0] = ba[0]; c1[k][1] = ba[1]; c1[k][2] = ba[2]; c1[k][3] = ba[3];
+      c1[k][4] = bb.x;  c1[k][5] = bb.y;
+    }
+  }
+#pragma unroll 1
+  for (int u = 0; u < 5; ++u) {
+    const float* ku = tab.k1t + u * 40;
+#pragma unroll
+    for (int v = 0; v < 5; ++v) {
+      const f4 wa = *reinterpret_cast<const f4*>(&ku[v * 8]);
+      const float2 wb = *reinterpret_cast<const float2*>(&ku[v * 8 + 4]);
+      const float wt[6] = {wa[0], wa[1], wa[2], wa[3], wb.x, wb.y};
+      float x[NS];
+#pragma unroll
+      for (int k = 0; k < NS; ++k) x[k] = ip[k][u * 28 + v];
+#pragma unroll
+      for (int i = 0; i < 6; ++i)
+#pragma unroll
+        for (int k = 0; k < NS; ++k) c1[k][i] = fmaf(wt[i], x[k], c1[k][i]);
+    }
+  }
+  // sigmoid and S1 = avgpool(C1) by the quad butterfly of cnn_wave.h
+  const bool odd = sub & 1, hi = sub & 2;
+#pragma unroll
+  for (int k = 0; k < NS; ++k) {
+    const int g = wave + 4 * k;
+#pragma unroll
+    for (int i = 0; i < 6; ++i) c1[k][i] = logistic(c1[k][i]);
+    const float s01 = (odd ? c1[k][1] : c1[k][0]) + quad_xor1(odd ? c1[k][0] : c1[k][1]);
+    const float s23 = (odd ? c1[k][3] : c1[k][2]) + quad_xor1(odd ? c1[k][2] : c1[k][3]);
+    const float tot = (hi ? s23 : s01) + quad_xor2(hi ? s01 : s23);
+    s.pool[P_S1 + sub * 144 + 16 * g + b] = 0.25f * tot;
+  }
+  // maps 4, 5: slots 0 and 1 together, slot 2 (wave 0 only) with itself
+#pragma unroll
+  for (int kp = 0; kp < (NS + 1) / 2; ++kp) {
+    const int k0 = 2 * kp, k1 = 2 * kp + 1 < NS ? 2 * kp + 1 : 2 * kp;
+    const float sa = (odd ? c1[k0][5] : c1[k0][4]) + quad_xor1(odd ? c1[k0][4] : c1[k0][5]);
+    const float sb = (odd ? c1[k1][5] : c1[k1][4]) + quad_xor1(odd ? c1[k1][4] : c1[k1][5]);
+    const float tot = (hi ? sb : sa) + quad_xor2(hi ? sa : sb);
+    s.pool[P_S1 + (4 + (sub & 1)) * 144 + 16 * (wave + 4 * (hi ? k1 : k0)) + b] = 0.25f * tot;
+  }
+}
+
+// C1 error of NS pixel groups into the staging area, then their share of the C1 weight gradient.
+template <int NS>
+__device__ __forceinline__ void group_c1_backward(GroupState& st, TrainLds& s, int wave,
+                                                  const float (&c1)[3][6]) {
+  const int l = threadIdx.x & 63, b = l >> 2, sub = l & 3;
+#pragma unroll
+  for (int k = 0; k < NS; ++k) {
+    const int g = wave + 4 * k;
+    float d1[6];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+      const float c = c1[k][i];
+      d1[i] = s.d_s1[i * 144 + 16 * g + b] * 0.25f * c * (1.0f - c);
+      st.g_b1[i] += d1[i];
+    }
+    float2* dst = reinterpret_cast<float2*>(&s.pool[(g * 64 + l) * STG]);
+    dst[0] = float2{d1[0], d1[1]};
+    dst[1] = float2{d1[2], d1[3]};
+    dst[2] = float2{d1[4], d1[5]};
+  }
+  wave_sync();  // a wave reads only the staging cells it wrote itself
+#pragma unroll
+  for (int k = 0; k < NS; ++k) {
+    const int g = wave + 4 * k;
+    const float* pa = s.img + st.pix0[k] + sub;
+    const float* pb = s.img + st.pix0[k] + 28 * sub;
+    const float* sa = s.pool + (g * 64 + 4 * b) * STG + sub;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int pt = (t >> 1) * 28 + (t & 1);
+      const float a0 = sa[STG * t], a1 = sa[STG * t + 4];
+#pragma unroll
+      for (int nt = 0; nt < 7; ++nt) {
+        const float bv = nt < 5 ? pa[28 * nt + pt] : nt == 5 ? pb[4 + pt] : pa[116 + pt];
+        st.acc_k1[0][nt] = mfma4(a0, bv, st.acc_k1[0][nt]);
+        st.acc_k1[1][nt] = mfma4(a1, bv, st.acc_k1[1][nt]);
+      }
+    }
+  }
+}
+
+// The whole step for the workgroup's images n = blockIdx.x, blockIdx.x + gridDim.x, ...; one
+// partial row per workgroup.  `ybuf` is 16 floats of LDS for the network output.
+__device__ __forceinline__ void group_train(const float* __restrict__ images,
+                                            const int32_t* __restrict__ labels, int B,
+                                            const float* __restrict__ tabg, float* __restrict__ out,
+                                            OperandTable<TAB_TRAIN_ENTRIES>& tab, TrainLds& s, float* ybuf) {
+  const int t = threadIdx.x, wave = t >> 6, l = t & 63, q = l >> 4, n16 = l & 15, b = l >> 2, sub = l & 3;
+  const int pp = 12 * ((n16 & 3) >> 1) + 2 * (n16 >> 2) + (n16 & 1);
+  const float* tl = tab.e + l;
+  const int pix = t < NI / 4 ? t : 0;  // the 16-byte piece of the image this thread moves
+  CNN_GROUP_MARK(0);
+
+  f4 px = reinterpret_cast<const f4*>(images + (size_t)(blockIdx.x < (unsigned)B ? blockIdx.x : 0) * NI)[pix];
+  int label_next = labels[blockIdx.x < (unsigned)B ? blockIdx.x : 0];  // in flight during the set-up too
+  load_tables<kTrain>(tab, tabg);
+  {
+    f4* raw = reinterpret_cast<f4*>(&s);
+    for (int e = t; e < (int)(sizeof(TrainLds) / 16); e += 64 * WAVES) raw[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+  }
+  GroupState st;
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    const int g = wave + 4 * k < 9 ? wave + 4 * k : 8, win = 16 * g + b;
+    st.pix0[k] = 2 * (win / 12) * 28 + 2 * (win % 12);
+  }
+#pragma unroll
+  for (int nt = 0; nt < 10; ++nt) st.acc_k2[nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 7; ++nt) st.acc_k1[mt][nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int k = 0; k < 3; ++k) st.acc_fc[k] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+  st.g_bq = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 6; ++i) st.g_b1[i] = 0.0f;
+  st.g_b2 = 0.0f;
+  st.loss = 0.0f;
+  CNN_GROUP_MARK(1);
+  __syncthreads();
+  st.bias2 = tab.bias[n16];
+
+  for (size_t n = blockIdx.x; n < (size_t)B; n += gridDim.x) {
+    const int label = label_next;
+    if (t < NI / 4) reinterpret_cast<f4*>(s.img)[t] = px;
+    CNN_GROUP_MARK(2);
+    __syncthreads();  // (1) image in LDS
+    if (n + gridDim.x < (size_t)B) {
+      px = reinterpret_cast<const f4*>(images + (n + gridDim.x) * NI)[pix];
+      label_next = labels[n + gridDim.x];
+    }
+
+    // ---- C1 forward + S1 for this wave's pixel groups --------------------------------------------
+    float c1[3][6];
+    if (wave == 0)
+      group_c1_forward<3>(st, s, tab, wave, c1);
+    else
+      group_c1_forward<2>(st, s, tab, wave, c1);
+    CNN_GROUP_MARK(3);
+    __syncthreads();  // (2) S1 complete
+
+    // ---- C2 forward for pixel tile mt = wave, S2 ---------------------------------------------------
+    f4 c2v = f4{st.bias2, st.bias2, st.bias2, st.bias2};
+    {
+      const float* a12 = s.pool + P_S1 + pp + 12 * q + 24 * wave;
+      const float* a1 = s.pool + P_S1 + pp + q + 24 * wave;
+      const float* a144 = s.pool + P_S1 + pp + 144 * q + 24 * wave;
+      float opa[3], opw[3];
+      auto load_step = [&](int sidx, float& oa, float& ow) {
+        const float* base = sidx < 30 ? a12 : sidx < 36 ? a1 : a144;
+        ow = tl[(TAB_BF + sidx) * 64];
+        oa = base[fwd_imm(sidx)];
+      };
+      load_step(0, opa[0], opw[0]);
+      load_step(1, opa[1], opw[1]);
+#pragma unroll
+      for (int sidx = 0; sidx < 38; ++sidx) {
+        if (sidx + 2 < 38) load_step(sidx + 2, opa[(sidx + 2) % 3], opw[(sidx + 2) % 3]);
+        c2v = mfma16(opa[sidx % 3], opw[sidx % 3], c2v);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) c2v[r] = logistic(c2v[r]);
+      if (n16 < 12) s.pool[P_S2 + n16 * 16 + 4 * wave + q] = 0.25f * ((c2v[0] + c2v[1]) + (c2v[2] + c2v[3]));
+    }
+    CNN_GROUP_MARK(4);
+    __syncthreads();  // (3) S2 complete
+
+    // ---- output layer: this wave's outputs; then everybody reads all ten -----------------------------
+    float sv[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) sv[k] = s.pool[P_S2 + l + 64 * k];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const int o = wave + 4 * j;  // wave-uniform
+      if (o < NY) {
+        float p = tl[(TAB_FCW + 3 * o) * 64] * sv[0];
+        p = fmaf(tl[(TAB_FCW + 3 * o + 1) * 64], sv[1], p);
+        p = fmaf(tl[(TAB_FCW + 3 * o + 2) * 64], sv[2], p);
+        const float yo = logistic(wave_sum(p) + tab.bias[16 + o]);
+        if (l == 0) ybuf[o] = yo;
+      }
+    }
+    // wave 3 clears the col2im target while the others finish
+    if (wave == 3)
+      for (int e = l; e < NS1 / 4; e += 64) reinterpret_cast<f4*>(s.d_s1)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    CNN_GROUP_MARK(5);
+    __syncthreads();  // (4) yhat complete
+    float delta[10];
+    {
+      float lsum = 0.0f;
+#pragma unroll
+      for (int o = 0; o < 10; ++o) {
+        const float yo = ybuf[o];
+        const float e = yo - (o == label ? 1.0f : 0.0f);
+        lsum = fmaf(e, e, lsum);
+        delta[o] = e * yo * (1.0f - yo);
+      }
+      if (wave == 0) st.loss = fmaf(0.5f, lsum, st.loss);
+    }
+    if (wave < 3) {  // FC backweights / backbias, row tile mt = wave
+      float d[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float v = 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < 3; ++mt)
+          if (4 * mt + r < 10) v = wave == mt ? delta[4 * mt + r] : v;
+        d[r] = v;
+      }
+      const float aq = (sub & 2) ? ((sub & 1) ? d[3] : d[2]) : ((sub & 1) ? d[1] : d[0]);
+      st.g_bq += aq;
+#pragma unroll
+      for (int k = 0; k < 3; ++k) st.acc_fc[k] = mfma4(aq, sv[k], st.acc_fc[k]);
+    }
+    // error at S2 (every wave computes and writes all of it: identical values, no barrier needed)
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      float d = 0.0f;
+#pragma unroll
+      for (int o = 0; o < 10; ++o) d = fmaf(tl[(TAB_FCW + 3 * o + k) * 64], delta[o], d);
+      s.pool[P_DS2 + l + 64 * k] = d;
+    }
+    wave_sync();
+    // ---- error at C2 for this wave's tile -----------------------------------------------------------
+    {
+      const float up = s.pool[P_DS2 + n16 * 16 + 4 * wave + q] * 0.25f;
+      f4 d2v;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) d2v[r] = up * c2v[r] * (1.0f - c2v[r]);
+      *reinterpret_cast<f4*>(&s.pool[P_D2 + n16 * D2S + 16 * wave + 4 * q]) = d2v;
+      st.g_b2 += (d2v[0] + d2v[1]) + (d2v[2] + d2v[3]);
+    }
+    CNN_GROUP_MARK(6);
+    __syncthreads();  // (5) d_c2 complete, d_s1 cleared
+
+    if (wave < 2) {
+      // ---- C2 input error for input maps 4 wave .. 4 wave + 3 (col2im rounds of cnn_wave.h) ---------
+      const int cg = wave;
+      float bd[3][4];
+#pragma unroll
+      for (int sidx = 0; sidx < 3; ++sidx)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) bd[sidx][nt] = s.pool[P_D2 + (4 * sidx + q) * D2S + 16 * nt + n16];
+      const float* ta = tl + (TAB_AB + cg * 21) * 64;
+      f4 t4[4];
+      float t44[4];
+      {
+        float au[3], ac[3];
+#pragma unroll
+        for (int sidx = 0; sidx < 3; ++sidx) {
+          au[sidx] = ta[(kTileU4 * 3 + sidx) * 64];
+          ac[sidx] = ta[(kTileC * 3 + sidx) * 64];
+        }
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+          f4 a = f4{0.0f, 0.0f, 0.0f, 0.0f}, c = a;
+#pragma unroll
+          for (int sidx = 0; sidx < 3; ++sidx) {
+            a = mfma16(au[sidx], bd[sidx][nt], a);
+            c = mfma16(ac[sidx], bd[sidx][nt], c);
+          }
+          t4[nt] = a;
+          t44[nt] = c[0];
+        }
+      }
+      float* tgt = s.d_s1 + 144 * q + pp + 576 * cg;
+#pragma unroll
+      for (int v = 0; v < 5; ++v) {
+        f4 tv[4];
+        {
+          float av[3];
+#pragma unroll
+          for (int sidx = 0; sidx < 3; ++sidx) av[sidx] = ta[((kTileV0 + v) * 3 + sidx) * 64];
+#pragma unroll
+          for (int nt = 0; nt < 4; ++nt) {
+            f4 a = f4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int sidx = 0; sidx < 3; ++sidx) a = mfma16(av[sidx], bd[sidx][nt], a);
+            tv[nt] = a;
+          }
+        }
+        {
+          float e[6], old[6];
+#pragma unroll
+          for (int m = 0; m < 6; ++m) {
+            float acc = 0.0f;
+            if (m < 4) acc = tv[m < 4 ? m : 0][0];
+            if (m >= 1 && m <= 4) acc += tv[m >= 1 ? m - 1 : 0][2];
+            if (m >= 2) acc += v < 4 ? t4[m >= 2 ? m - 2 : 0][v < 4 ? v : 0] : t44[m >= 2 ? m - 2 : 0];
+            e[m] = acc;
+            old[m] = tgt[24 * m + v];
+          }
+#pragma unroll
+          for (int m = 0; m < 6; ++m) tgt[24 * m + v] = old[m] + e[m];
+        }
+        wave_sync();
+        {
+          float e[5], old[5];
+#pragma unroll
+          for (int m = 0; m < 5; ++m) {
+            float acc = 0.0f;
+            if (m < 4) acc = tv[m < 4 ? m : 0][1];
+            if (m >= 1) acc += tv[m >= 1 ? m - 1 : 0][3];
+            e[m] = acc;
+            old[m] = tgt[24 * m + 12 + v];
+          }
+#pragma unroll
+          for (int m = 0; m < 5; ++m) tgt[24 * m + 12 + v] = old[m] + e[m];
+        }
+        wave_sync();
+      }
+    } else {
+      // ---- C2 weight gradient over pixel tiles S = 2 (wave - 2), 2 (wave - 2) + 1 ---------------------
+      const float* bsrc[10];
+#pragma unroll
+      for (int nt = 0; nt < 10; ++nt) {
+        const int tap = 16 * nt + n16;
+        const int c = tap / 25, rem = tap - 25 * c, u = rem / 5, v = rem - 5 * u;
+        bsrc[nt] = s.pool + P_S1 + (tap < 150 ? c * 144 + u * 12 + v : 0) + 2 * q;
+      }
+#pragma unroll
+      for (int ss = 0; ss < 2; ++ss) {
+        const int S = 2 * (wave - 2) + ss;  // wave-uniform
+        const f4 a = *reinterpret_cast<const f4*>(&s.pool[P_D2 + n16 * D2S + 16 * S + 4 * q]);
+        const float* bs0 = nullptr;
+        (void)bs0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int imm = 12 * (r >> 1) + (r & 1);
+#pragma unroll
+          for (int nt = 0; nt < 10; ++nt) st.acc_k2[nt] = mfma16(a[r], bsrc[nt][24 * S + imm], st.acc_k2[nt]);
+        }
+      }
+    }
+    CNN_GROUP_MARK(7);
+    __syncthreads();  // (6) d_s1 complete; s1, d_c2 no longer needed
+
+    // ---- C1 error and C1 weight gradient for this wave's pixel groups --------------------------------
+    if (wave == 0)
+      group_c1_backward<3>(st, s, wave, c1);
+    else
+      group_c1_backward<2>(st, s, wave, c1);
+    CNN_GROUP_MARK(8);
+    __syncthreads();  // (7) the image and the staging area are free again
+  }
+
+  // ---- one partial row per workgroup: cross-wave sums through LDS in a fixed order -------------------
+  // The operand table is dead after the last image; its storage takes the parked values.
+  float* k1s = tab.e;                               // [4 waves][4 rows][42][4]: C1 weight row sums
+  float* b1s = tab.e + 16 * 4 * K1_VALUES;          // [4 waves][4 rows][8]: C1 bias row sums
+  float* b2s = b1s + 128;                           // [4 waves][64]: per-lane C2 bias sums
+  float* scr = b2s + 256;                           // [64 lanes][20]: half of a wave's C2 gradient tiles
+  k1_park_row_sums(st.acc_k1, k1s + wave * 16 * K1_VALUES);
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    float v = st.g_b1[i];
+    v += quad_xor1(v);
+    v += quad_xor2(v);
+    v += dpp_row_half_mirror(v);
+    v += dpp_row_mirror(v);
+    if (n16 == 0) b1s[(wave * 4 + q) * 8 + i] = v;
+  }
+  b2s[wave * 64 + l] = st.g_b2;  // lane (q, j) of this wave's pixel tile
+  // waves 2 and 3 each hold half of the C2 weight gradient: wave 3 hands over tiles 0..4, wave 2 tiles 5..9
+  if (wave >= 2) {
+#pragma unroll
+    for (int k = 0; k < 5; ++k)
+      *reinterpret_cast<f4*>(&scr[(wave - 2) * 1280 + l * 20 + 4 * k]) = st.acc_k2[wave == 3 ? k : 5 + k];
+  }
+  CNN_GROUP_MARK(9);
+  __syncthreads();
+  if (wave >= 2) {
+#pragma unroll
+    for (int k = 0; k < 5; ++k) {
+      const int nt = wave == 2 ? k : 5 + k;
+      const f4 mine = st.acc_k2[wave == 2 ? k : 5 + k];
+      const f4 other = *reinterpret_cast<const f4*>(&scr[(3 - wave) * 1280 + l * 20 + 4 * k]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int j = 4 * q + r, tap = 16 * nt + n16;
+        // wave 2's share is always the left operand, so the sum does not depend on who adds
+        const float v = wave == 2 ? mine[r] + other[r] : other[r] + mine[r];
+        if (j < 12 && tap < 150) out[OFF_K2 + j * 150 + tap] = v;
+      }
+    }
+  }
+  if (wave < 3) {
+#pragma unroll
+    for (int k = 0; k < 3; ++k)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int o = 4 * wave + r;
+        if (o < 10) out[OFF_FC + o * NS2 + l + 64 * k] = st.acc_fc[k][r];
+      }
+    if (l < 4 && 4 * wave + l < 10) out[OFF_B + 4 * wave + l] = st.g_bq;
+  }
+  if (t < 4 * K1_VALUES) {  // one thread per parked C1 weight slot: sixteen row sums
+    float x[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) x[k] = k1s[k * 4 * K1_VALUES + t];
+#pragma unroll
+    for (int k = 0; k < 16; k += 4) x[k] = (x[k] + x[k + 1]) + (x[k + 2] + x[k + 3]);
+    const int idx = k1_slot_param(t);
+    if (idx >= 0) out[idx] = (x[0] + x[4]) + (x[8] + x[12]);
+  } else if (t < 4 * K1_VALUES + 6) {
+    const int i = t - 4 * K1_VALUES;
+    float x[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) x[k] = b1s[k * 8 + i];
+#pragma unroll
+    for (int k = 0; k < 16; k += 4) x[k] = (x[k] + x[k + 1]) + (x[k + 2] + x[k + 3]);
+    out[OFF_B1 + i] = (x[0] + x[4]) + (x[8] + x[12]);
+  } else if (t >= 192 && t < 204) {
+    const int j = t - 192;
+    float x[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) x[k] = b2s[k * 16 + j];
+#pragma unroll
+    for (int k = 0; k < 16; k += 4) x[k] = (x[k] + x[k + 1]) + (x[k + 2] + x[k + 3]);
+    out[OFF_B2 + j] = (x[0] + x[4]) + (x[8] + x[12]);
+  }
+  if (t == 0) out[LOSS_SLOT] = st.loss;
+  CNN_GROUP_MARK(10);
+}
+
+}  // namespace cnn

@@ -37,6 +37,9 @@
 #define CNN_PHASE_FLUSH
 #define CNN_KERNEL_MARK(k)
 #endif
+#ifndef CNN_GROUP_MARK
+#define CNN_GROUP_MARK(k)
+#endif
 
 namespace cnn {
 
@@ -77,11 +80,20 @@ constexpr int TAB_TRAIN_ENTRIES = 110;
 // After the [entry][lane] part: C1 weights by tap, k1t[tap][8] = k1[0..5][tap], 0, 0 for tap < 25 and
 // the biases b1 in row 25; every lane reads the same row (an LDS broadcast).
 constexpr int K1T_FLOATS = 26 * 8;
+// Last: the biases read per image, bias[0..11] = b2, bias[16..25] = b, zeros elsewhere.
+constexpr int TAB_BIAS_FLOATS = 32;
 template <int ENTRIES>
 struct __align__(16) OperandTable {
   float e[ENTRIES * 64];
   float k1t[K1T_FLOATS];
+  float bias[TAB_BIAS_FLOATS];
 };
+// The table is kept expanded in global memory next to the flat parameter vector (all 110 entries,
+// then k1t, then bias); a kernel copies the part it needs into LDS with 16-byte loads.
+constexpr int TABG_K1T = TAB_TRAIN_ENTRIES * 64;
+constexpr int TABG_BIAS = TABG_K1T + K1T_FLOATS;
+constexpr int TABG_FLOATS = TABG_BIAS + TAB_BIAS_FLOATS;
+static_assert(TABG_K1T % 4 == 0 && K1T_FLOATS % 4 == 0, "16-byte pieces");
 
 enum Mode { kForward = 0, kForwardDump = 1, kTrain = 2 };
 template <int MODE>
@@ -169,41 +181,97 @@ __host__ __device__ constexpr int k1_tap(int nt, int sub) {
   return nt < 5 ? nt * 5 + sub : nt == 5 ? sub * 5 + 4 : (sub == 0 ? 24 : -1);
 }
 
-// Fills the shared operand table from the flat parameter vector; all 256 threads take part and
-// the caller follows with a workgroup barrier.  The loop is unrolled so that a thread's gathers
-// are all in flight together instead of one memory round trip per entry.
-template <int MODE>
-__device__ __forceinline__ void build_tables(OperandTable<LdsOf<MODE>::entries>& tab,
-                                             const float* __restrict__ w) {
-  constexpr int ENTRIES = LdsOf<MODE>::entries;
-  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
-  float v[(ENTRIES + WAVES - 1) / WAVES];
-#pragma unroll
-  for (int it = 0; it < (ENTRIES + WAVES - 1) / WAVES; ++it) {
-    const int e = it * WAVES + wave;
-    int idx = -1;
+// Flat parameter index whose value slot i of the expanded table holds, or -1 for a zero.
+__host__ __device__ constexpr int table_source(int i) {
+  if (i < TABG_K1T) {
+    const int e = i >> 6, l = i & 63, q = l >> 4, n16 = l & 15;
     if (e < TAB_FCW) {
       const int tap = fwd_tap(e, q);
-      if (n16 < 12 && tap >= 0) idx = OFF_K2 + n16 * 150 + tap;
-    } else if (e < TAB_AB) {
-      const int o = (e - TAB_FCW) / 3, k = (e - TAB_FCW) % 3;
-      idx = OFF_FC + o * NS2 + l + 64 * k;
-    } else if (e < ENTRIES) {
-      const int t = e - TAB_AB, sidx = t % 3, tile = (t / 3) % 7, cg = t / 21;
-      const int c = 4 * cg + (n16 >> 2), tap = bwd_tap(tile, n16 & 3);
-      if (c < 6 && tap >= 0) idx = OFF_K2 + (4 * sidx + q) * 150 + c * 25 + tap;
+      return n16 < 12 && tap >= 0 ? OFF_K2 + n16 * 150 + tap : -1;
     }
-    v[it] = idx >= 0 ? w[idx] : 0.0f;
+    if (e < TAB_AB) {
+      const int o = (e - TAB_FCW) / 3, k = (e - TAB_FCW) % 3;
+      return OFF_FC + o * NS2 + l + 64 * k;
+    }
+    const int t = e - TAB_AB, sidx = t % 3, tile = (t / 3) % 7, cg = t / 21;
+    const int c = 4 * cg + (n16 >> 2), tap = bwd_tap(tile, n16 & 3);
+    return c < 6 && tap >= 0 ? OFF_K2 + (4 * sidx + q) * 150 + c * 25 + tap : -1;
   }
+  if (i < TABG_BIAS) {
+    const int tap = (i - TABG_K1T) >> 3, m = (i - TABG_K1T) & 7;
+    return m < 6 ? (tap < 25 ? OFF_K1 + m * 25 + tap : OFF_B1 + m) : -1;
+  }
+  const int k = i - TABG_BIAS;
+  return k < 12 ? OFF_B2 + k : (k >= 16 && k < 16 + NY ? OFF_B + (k - 16) : -1);
+}
+// No parameter sits in more than two slots: the SGD kernel refreshes the expanded table by writing
+// every updated parameter to (at most) two recorded places.
+constexpr int TABLE_MAX_DEST = 2;
+constexpr int table_max_multiplicity() {
+  int count[NPARAM] = {};
+  int most = 0;
+  for (int i = 0; i < TABG_FLOATS; ++i) {
+    const int p = table_source(i);
+    if (p >= 0 && ++count[p] > most) most = count[p];
+  }
+  return most;
+}
+
+// Copies the expanded table from global memory into the workgroup's LDS; all 256 threads take part
+// and the caller follows with a workgroup barrier.  All of a thread's loads are in flight together.
+template <int MODE>
+__device__ __forceinline__ void load_tables(OperandTable<LdsOf<MODE>::entries>& tab,
+                                            const float* __restrict__ tabg) {
+  constexpr int PIECES = LdsOf<MODE>::entries * 16, ROUNDS = (PIECES + 64 * WAVES - 1) / (64 * WAVES);
+  constexpr int TAIL = (K1T_FLOATS + TAB_BIAS_FLOATS) / 4;
+  static_assert(offsetof(OperandTable<LdsOf<MODE>::entries>, bias) ==
+                    offsetof(OperandTable<LdsOf<MODE>::entries>, k1t) + sizeof(float) * K1T_FLOATS,
+                "k1t and bias are copied as one run");
+  const int t = threadIdx.x;
+  const f4* src = reinterpret_cast<const f4*>(tabg);
+  f4 v[ROUNDS], tail;
 #pragma unroll
-  for (int it = 0; it < (ENTRIES + WAVES - 1) / WAVES; ++it) {
-    const int e = it * WAVES + wave;
-    if (e < ENTRIES) tab.e[e * 64 + l] = v[it];
+  for (int r = 0; r < ROUNDS; ++r) {
+    const int i = r * 64 * WAVES + t;
+    v[r] = src[i < PIECES ? i : 0];
   }
-  if (threadIdx.x < K1T_FLOATS) {
-    const int tap = threadIdx.x >> 3, i = threadIdx.x & 7;
-    tab.k1t[threadIdx.x] = i < 6 ? (tap < 25 ? w[OFF_K1 + i * 25 + tap] : w[OFF_B1 + i]) : 0.0f;
+  tail = src[TABG_K1T / 4 + (t < TAIL ? t : 0)];
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    const int i = r * 64 * WAVES + t;
+    if (i < PIECES) reinterpret_cast<f4*>(tab.e)[i] = v[r];
   }
+  if (t < TAIL) reinterpret_cast<f4*>(tab.k1t)[t] = tail;
+}
+
+// ---- cross-lane sum of the C1 weight gradient ----------------------------------------------------
+// acc_k1 holds, per 4-lane block, 42 used result registers: value v = 4 nt + r for maps 0..3 and
+// 28 + 2 nt + r for maps 4, 5 (tile nt < 7, column = lane % 4).  k1_park_row_sums folds the four
+// blocks of every 16-lane row with two DPP rotations and parks the row sums at
+// dst[(q * 42 + v) * 4 + sub] (q = lane / 16; conflict-free: rows are 168 floats = 8 banks apart).
+constexpr int K1_VALUES = 42;
+__device__ __forceinline__ void k1_park_row_sums(const f4 (&acc)[2][7], float* dst) {
+  const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 7; ++nt)
+#pragma unroll
+      for (int r = 0; r < (mt == 0 ? 4 : 2); ++r) {
+        float x = acc[mt][nt][r];
+        x += dpp_row_ror8(x);
+        x += dpp_row_ror4(x);
+        const int v = mt == 0 ? 4 * nt + r : 28 + 2 * nt + r;
+        if (n16 < 4) dst[(q * K1_VALUES + v) * 4 + n16] = x;
+      }
+}
+// Flat parameter index of parked slot t = 4 v + sub, or -1 for the unused columns of tile 6.
+__device__ __forceinline__ int k1_slot_param(int t) {
+  const int v = t >> 2, sub = t & 3;
+  const int mt = v >= 28 ? 1 : 0, vv = v - 28 * mt;
+  const int nt = mt ? vv >> 1 : vv >> 2, r = mt ? vv & 1 : vv & 3;
+  const int tap = k1_tap(nt, sub);
+  return tap >= 0 ? OFF_K1 + (4 * mt + r) * 25 + tap : -1;
 }
 
 // Everything a wave keeps in registers across its images.
@@ -220,9 +288,8 @@ struct WaveState {
 };
 
 template <int MODE>
-__device__ __forceinline__ void wave_init(WaveState<MODE>& st, typename LdsOf<MODE>::type& s,
-                                          const float* __restrict__ w) {
-  const int l = threadIdx.x & 63, n16 = l & 15, b = l >> 2;
+__device__ __forceinline__ void wave_init(WaveState<MODE>& st, typename LdsOf<MODE>::type& s) {
+  const int l = threadIdx.x & 63, b = l >> 2;
   // all of this wave's LDS starts finite: padded GEMM steps multiply it by zero weights
   static_assert(sizeof(s) % 16 == 0, "LDS struct is a whole number of 16-byte pieces");
   f4* raw = reinterpret_cast<f4*>(&s);
@@ -232,7 +299,7 @@ __device__ __forceinline__ void wave_init(WaveState<MODE>& st, typename LdsOf<MO
     const int win = 16 * g + b;
     st.pix0[g] = 2 * (win / 12) * 28 + 2 * (win % 12);
   }
-  st.bias2 = n16 < 12 ? w[OFF_B2 + n16] : 0.0f;
+  st.bias2 = 0.0f;  // read from the operand table once it is complete
   if (MODE == kTrain) {
 #pragma unroll
     for (int nt = 0; nt < 10; ++nt) st.acc_k2[nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
@@ -282,7 +349,7 @@ template <int MODE>
 __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<MODE>::type& s,
                                            const OperandTable<LdsOf<MODE>::entries>& tab, Pixels& px,
                                            const float* __restrict__ next_image, int label,
-                                           const float* __restrict__ w, float (&y)[10], const DumpPtrs& dump,
+                                           float (&y)[10], const DumpPtrs& dump,
                                            size_t n) {
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15, b = l >> 2, sub = l & 3;
   const int pp = 12 * ((n16 & 3) >> 1) + 2 * (n16 >> 2) + (n16 & 1);
@@ -422,7 +489,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
     float p = tl[(TAB_FCW + 3 * o) * 64] * sv[0];
     p = fmaf(tl[(TAB_FCW + 3 * o + 1) * 64], sv[1], p);
     p = fmaf(tl[(TAB_FCW + 3 * o + 2) * 64], sv[2], p);
-    y[o] = logistic(wave_sum(p) + w[OFF_B + o]);
+    y[o] = logistic(wave_sum(p) + tab.bias[16 + o]);
   }
   if constexpr (MODE == kTrain) {
     // ---- output error, FC backweights / backbias / backin ------------------------------------------
@@ -666,8 +733,8 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
 }
 
 // Writes the wave's gradient sums to its partial row (every slot has exactly one writer).
-__device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, float* __restrict__ out) {
-  const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15, b = l >> 2, sub = l & 3;
+__device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, TrainLds& s, float* __restrict__ out) {
+  const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
 #pragma unroll
   for (int mt = 0; mt < 3; ++mt) {
 #pragma unroll
@@ -693,37 +760,18 @@ __device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, float* __restr
     v += __shfl_xor(v, 32);
     if (q == 0 && n16 < 12) out[OFF_B2 + n16] = v;
   }
-  // C1 weights: sum over the sixteen 4-lane blocks.  Inside a row of 16 lanes the four blocks are
-  // joined by two DPP rotations; the four rows are joined through lane exchanges, all values of a
-  // stage issued together.  The order of the additions is fixed.
-  {
+  // C1 weights: sum over the sixteen 4-lane blocks, in a fixed order: row sums parked in the wave's
+  // own LDS, then one lane per weight adds the four rows.
+  k1_park_row_sums(st.acc_k1, s.pool);
+  wave_sync();
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < 7; ++nt)
-#pragma unroll
-        for (int r = 0; r < (mt == 0 ? 4 : 2); ++r) {
-          float x = st.acc_k1[mt][nt][r];
-          x += dpp_row_ror8(x);
-          x += dpp_row_ror4(x);
-          st.acc_k1[mt][nt][r] = x;
-        }
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < 7; ++nt)
-#pragma unroll
-        for (int r = 0; r < (mt == 0 ? 4 : 2); ++r) st.acc_k1[mt][nt][r] += __shfl_xor(st.acc_k1[mt][nt][r], 16);
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < 7; ++nt)
-#pragma unroll
-        for (int r = 0; r < (mt == 0 ? 4 : 2); ++r) {
-          const float x = st.acc_k1[mt][nt][r] + __shfl_xor(st.acc_k1[mt][nt][r], 32);
-          const int map = 4 * mt + r, tap = k1_tap(nt, sub);
-          if (b == 0 && tap >= 0) out[OFF_K1 + map * 25 + tap] = x;
-        }
+  for (int round = 0; round < 3; ++round) {
+    const int t = l + 64 * round;
+    if (t < 4 * K1_VALUES) {
+      const float x = (s.pool[t] + s.pool[4 * K1_VALUES + t]) + (s.pool[8 * K1_VALUES + t] + s.pool[12 * K1_VALUES + t]);
+      const int idx = k1_slot_param(t);
+      if (idx >= 0) out[idx] = x;
+    }
   }
 #pragma unroll
   for (int i = 0; i < 6; ++i) {
