@@ -30,6 +30,12 @@ PEAK_FP32_TFLOPS = 157.3              # MI355X vector / matrix fp32
 PEAK_HBM_GBS = 8000.0
 LR = 0.05
 N_TRAIN, N_EVAL = 60000, 10000
+GROUP_MAX_BATCH = 256                 # batches up to this size run train_group_kernel, larger ones train_kernel
+# HBM bytes per launch of the fused kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same
+# command (profiles/train_group_kernel_batch100.md, profiles/train_kernel_batch60000.md), scaled by
+# what the counters read for a plain 256 MiB copy (FETCH x2.0, WRITE x1.0).  Only for the batch
+# sizes that were profiled; other sizes report null.
+MEASURED_TRAFFIC_BYTES = {100: 2568397, 60000: 206920499}
 
 
 def main():
@@ -117,13 +123,16 @@ def main():
                                "SGD lr 0.05 (steps cycle over the epoch's batches)" % args.batch,
                    "batch": args.batch, "images_resident": N_TRAIN, "lr": LR},
         "roofline": {
-            "kernel": "train_kernel (fused forward+backward of one batch)",
+            "kernel": "%s (fused forward+backward of one batch)"
+                      % ("train_group_kernel" if args.batch <= GROUP_MAX_BATCH else "train_kernel"),
             "bound": "alu",
             "achieved": achieved_tflops,
             "peak": PEAK_FP32_TFLOPS,
             "unit": "TFLOP/s",
             "frac": achieved_tflops / PEAK_FP32_TFLOPS,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.batch),
+            "traffic_unit": "HBM bytes per launch (algorithmic: %d image bytes + %d partial-row bytes)"
+                            % (args.batch * BYTES_PER_IMAGE, min(args.batch, 1024) * 15616),
             "kernel_ms": kernel_ms,
             "flop_per_launch": FLOP_PER_IMAGE_TRAIN * args.batch,
             "hbm_frac_whole_step": value * BYTES_PER_IMAGE / 1e9 / PEAK_HBM_GBS,

@@ -94,9 +94,11 @@ int cnn_evaluate(cnn_ctx* ctx, const float* images, const int32_t* labels, int N
 
 /* Timing aid for callers that cannot see inside a step.  After cnn_profile_begin(ctx, capacity)
  * each cnn_train_batch / cnn_gradient call records one pair of HIP events around its fused
- * forward+backward kernel (the first `capacity` calls; later ones are not recorded).
+ * forward+backward kernel on the context's stream (the first `capacity` calls; later ones are
+ * not recorded).  A pair's reading is the kernel's duration plus the dispatch latency between
+ * the two records (about a microsecond), so it is an upper bound on the kernel time.
  * cnn_profile_read waits for the context's stream, writes the elapsed milliseconds of each
- * recorded kernel (less the reading of an empty event pair, measured in the same call) to ms (a HOST array of at least `capacity` floats) and the number of recorded
+ * recorded pair to ms (a HOST array of at least `capacity` floats) and the number of recorded
  * steps to *n_recorded (HOST), and restarts recording from zero.  capacity == 0 stops recording
  * and frees the events.  No device memory is involved. */
 int cnn_profile_begin(cnn_ctx* ctx, int capacity);

@@ -274,7 +274,7 @@ int run_backward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B
   const bool grouped = B <= GROUP_MAX_BATCH;
   const int blocks = grouped ? (B < ctx->gcap ? B : ctx->gcap) : blocks_for(ctx, B, false);
   const int G = grouped ? blocks : blocks * WAVES;
-  const bool timed = (size_t)(2 * ctx->ev_used + 3) < ctx->ev.size();
+  const bool timed = (size_t)(2 * ctx->ev_used + 1) < ctx->ev.size();
   if (timed) CNN_HIP_TRY(hipEventRecord(ctx->ev[2 * ctx->ev_used], ctx->stream));
   if (grouped)
     train_group_kernel<<<blocks, 64 * WAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, ctx->partial);
@@ -379,8 +379,7 @@ int cnn_profile_begin(cnn_ctx* ctx, int capacity) {
   for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
   ctx->ev.clear();
   ctx->ev_used = 0;
-  // two events per recorded step, plus one pair used to measure the cost of an empty pair
-  for (int i = 0; i < (capacity > 0 ? 2 * capacity + 2 : 0); ++i) {
+  for (int i = 0; i < 2 * capacity; ++i) {
     hipEvent_t e;
     if (hipEventCreate(&e) != hipSuccess) {
       (void)hipGetLastError();
@@ -397,31 +396,7 @@ int cnn_profile_read(cnn_ctx* ctx, float* ms, int capacity, int* n_recorded) {
   if (!ctx || !ms || !n_recorded || capacity < 0) return CNN_EINVAL;
   CNN_HIP_TRY(hipStreamSynchronize(ctx->stream));
   const int n = ctx->ev_used < capacity ? ctx->ev_used : capacity;
-  // What a pair of events reads with nothing between them is the cost of the records themselves;
-  // it is measured here (median of 9 empty pairs) and taken off every kernel's reading.
-  float empty = 0.0f;
-  if (ctx->ev.size() >= 2) {
-    const hipEvent_t e0 = ctx->ev[ctx->ev.size() - 2], e1 = ctx->ev[ctx->ev.size() - 1];
-    float t[9];
-    for (int k = 0; k < 9; ++k) {
-      CNN_HIP_TRY(hipEventRecord(e0, ctx->stream));
-      CNN_HIP_TRY(hipEventRecord(e1, ctx->stream));
-      CNN_HIP_TRY(hipEventSynchronize(e1));
-      CNN_HIP_TRY(hipEventElapsedTime(&t[k], e0, e1));
-    }
-    for (int a = 0; a < 9; ++a)
-      for (int b = a + 1; b < 9; ++b)
-        if (t[b] < t[a]) {
-          const float x = t[a];
-          t[a] = t[b];
-          t[b] = x;
-        }
-    empty = t[4];
-  }
-  for (int i = 0; i < n; ++i) {
-    CNN_HIP_TRY(hipEventElapsedTime(&ms[i], ctx->ev[2 * i], ctx->ev[2 * i + 1]));
-    ms[i] = ms[i] > empty ? ms[i] - empty : 0.0f;
-  }
+  for (int i = 0; i < n; ++i) CNN_HIP_TRY(hipEventElapsedTime(&ms[i], ctx->ev[2 * i], ctx->ev[2 * i + 1]));
   *n_recorded = n;
   ctx->ev_used = 0;
   return CNN_OK;
