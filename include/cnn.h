@@ -86,6 +86,16 @@ int cnn_gradient(cnn_ctx* ctx, const float* images, const int32_t* labels, int B
 int cnn_train_batch(cnn_ctx* ctx, const float* images, const int32_t* labels, int B, float lr,
                     float* loss_sum);
 
+/* One epoch of mini-batch gradient descent (Section 4.2: the training set is walked in batches,
+ * one update per batch): step k = 0 .. ceil(N / batch) - 1 is cnn_train_batch on the images
+ * [k * batch, min(N, (k + 1) * batch)) in index order, each with its own size as B (the last
+ * step may be shorter).  1 <= batch <= max_batch, N >= 1.  loss_sums (nullable, device,
+ * ceil(N / batch) floats) receives each step's sum_n L_n at the weights from before that step.
+ * Enqueues 2 * ceil(N / batch) kernels on the context's stream and returns without waiting; the
+ * result is bitwise the same as the equivalent sequence of cnn_train_batch calls. */
+int cnn_train_epoch(cnn_ctx* ctx, const float* images, const int32_t* labels, int N, int batch,
+                    float lr, float* loss_sums);
+
 /* Forward-only classification of N images (1 <= N <= max_batch): n_correct
  * (device int64) = number of images whose largest output (lowest index on ties)
  * equals the label; loss_sum (nullable) = sum_n L_n. */

@@ -30,6 +30,7 @@ SIGNATURES = {
     "cnn_forward_activations": (_i, [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp]),
     "cnn_gradient": (_i, [_vp, _vp, _vp, _i, _vp, _vp]),
     "cnn_train_batch": (_i, [_vp, _vp, _vp, _i, _f, _vp]),
+    "cnn_train_epoch": (_i, [_vp, _vp, _vp, _i, _i, _f, _vp]),
     "cnn_evaluate": (_i, [_vp, _vp, _vp, _i, _vp, _vp]),
     "cnn_profile_begin": (_i, [_vp, _i]),
     "cnn_profile_read": (_i, [_vp, _vp, _i, ctypes.POINTER(_i)]),
@@ -167,6 +168,15 @@ class CNN:
         _check(lib().cnn_train_batch(self._ctx, _ptr(images), _ptr(labels), images.shape[0], float(lr),
                                      _ptr(_dev(loss_sum))), "cnn_train_batch")
         return loss_sum
+
+    def train_epoch(self, images, labels, batch, lr, loss_sums=None):
+        """One pass over `images` in consecutive batches of `batch` (the last may be shorter)."""
+        images, labels = _dev(images), _dev(labels, torch.int32)
+        if loss_sums is not None and loss_sums.numel() < -(-images.shape[0] // int(batch)):
+            raise ValueError("loss_sums needs one float per step")
+        _check(lib().cnn_train_epoch(self._ctx, _ptr(images), _ptr(labels), images.shape[0], int(batch),
+                                     float(lr), _ptr(_dev(loss_sums))), "cnn_train_epoch")
+        return loss_sums
 
     def evaluate(self, images, labels):
         images, labels = _dev(images), _dev(labels, torch.int32)

@@ -446,4 +446,16 @@ int cnn_train_batch(cnn_ctx* ctx, const float* images, const int32_t* labels, in
   return run_backward(ctx, images, labels, B, lr / (float)B, nullptr, loss_sum);
 }
 
+int cnn_train_epoch(cnn_ctx* ctx, const float* images, const int32_t* labels, int N, int batch, float lr,
+                    float* loss_sums) {
+  if (!ctx || N < 1 || !batch_ok(ctx, batch) || !images || !labels || !aligned16(images)) return CNN_EINVAL;
+  for (int k = 0, first = 0; first < N; ++k, first += batch) {
+    const int B = N - first < batch ? N - first : batch;
+    const int rc = run_backward(ctx, images + (size_t)first * NI, labels + first, B, lr / (float)B, nullptr,
+                                loss_sums ? loss_sums + k : nullptr);
+    if (rc != CNN_OK) return rc;
+  }
+  return CNN_OK;
+}
+
 }  // extern "C"

@@ -140,11 +140,12 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
 
   f4 px = reinterpret_cast<const f4*>(images + (size_t)(blockIdx.x < (unsigned)B ? blockIdx.x : 0) * NI)[pix];
   int label_next = labels[blockIdx.x < (unsigned)B ? blockIdx.x : 0];  // in flight during the set-up too
-  load_tables<kTrain>(tab, tabg);
-  {
-    f4* raw = reinterpret_cast<f4*>(&s);
-    for (int e = t; e < (int)(sizeof(TrainLds) / 16); e += 64 * WAVES) raw[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-  }
+  TableLoad<kTrain> table;
+  table.fetch(tabg);
+  // every LDS cell that padded GEMM steps may read starts finite (the image area is written by the
+  // loop itself before its first barrier, so it is left alone here)
+  for (int e = t; e < NS1 / 4; e += 64 * WAVES) reinterpret_cast<f4*>(s.d_s1)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+  for (int e = t; e < POOL_FLOATS / 4; e += 64 * WAVES) reinterpret_cast<f4*>(s.pool)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
   GroupState st;
 #pragma unroll
   for (int k = 0; k < 3; ++k) {
@@ -165,11 +166,17 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
   st.g_b2 = 0.0f;
   st.loss = 0.0f;
   CNN_GROUP_MARK(1);
-  __syncthreads();
-  st.bias2 = tab.bias[n16];
+  // The table is committed inside the first trip of the image loop: the loop's lane-invariant
+  // address arithmetic, which the compiler hoists in front of the loop, then runs while the
+  // table's loads are still in flight.  Barrier (1) of that trip also publishes the table.
+  bool first = true;
 
   for (size_t n = blockIdx.x; n < (size_t)B; n += gridDim.x) {
     const int label = label_next;
+    if (first) {
+      table.commit(tab);
+      first = false;
+    }
     if (t < NI / 4) reinterpret_cast<f4*>(s.img)[t] = px;
     CNN_GROUP_MARK(2);
     __syncthreads();  // (1) image in LDS
@@ -177,6 +184,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
       px = reinterpret_cast<const f4*>(images + (n + gridDim.x) * NI)[pix];
       label_next = labels[n + gridDim.x];
     }
+    st.bias2 = tab.bias[n16];
 
     // ---- C1 forward + S1 for this wave's pixel groups --------------------------------------------
     float c1[3][6];

@@ -217,31 +217,44 @@ constexpr int table_max_multiplicity() {
   return most;
 }
 
-// Copies the expanded table from global memory into the workgroup's LDS; all 256 threads take part
-// and the caller follows with a workgroup barrier.  All of a thread's loads are in flight together.
+// Copies the expanded table from global memory into the workgroup's LDS in two halves, so that a
+// kernel can do other set-up work while the loads are in flight: `fetch` issues all of a thread's
+// 16-byte loads, `commit` stores them to LDS.  All 256 threads take part and the caller follows the
+// commit with a workgroup barrier.
+template <int MODE>
+struct TableLoad {
+  static constexpr int PIECES = LdsOf<MODE>::entries * 16, ROUNDS = (PIECES + 64 * WAVES - 1) / (64 * WAVES);
+  static constexpr int TAIL = (K1T_FLOATS + TAB_BIAS_FLOATS) / 4;
+  typedef OperandTable<LdsOf<MODE>::entries> Table;
+  static_assert(offsetof(Table, bias) == offsetof(Table, k1t) + sizeof(float) * K1T_FLOATS,
+                "k1t and bias are copied as one run");
+  f4 v[ROUNDS], tail;
+  __device__ __forceinline__ void fetch(const float* __restrict__ tabg) {
+    const int t = threadIdx.x;
+    const f4* src = reinterpret_cast<const f4*>(tabg);
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+      const int i = r * 64 * WAVES + t;
+      v[r] = src[i < PIECES ? i : 0];
+    }
+    tail = src[TABG_K1T / 4 + (t < TAIL ? t : 0)];
+  }
+  __device__ __forceinline__ void commit(Table& tab) const {
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+      const int i = r * 64 * WAVES + t;
+      if (i < PIECES) reinterpret_cast<f4*>(tab.e)[i] = v[r];
+    }
+    if (t < TAIL) reinterpret_cast<f4*>(tab.k1t)[t] = tail;
+  }
+};
 template <int MODE>
 __device__ __forceinline__ void load_tables(OperandTable<LdsOf<MODE>::entries>& tab,
                                             const float* __restrict__ tabg) {
-  constexpr int PIECES = LdsOf<MODE>::entries * 16, ROUNDS = (PIECES + 64 * WAVES - 1) / (64 * WAVES);
-  constexpr int TAIL = (K1T_FLOATS + TAB_BIAS_FLOATS) / 4;
-  static_assert(offsetof(OperandTable<LdsOf<MODE>::entries>, bias) ==
-                    offsetof(OperandTable<LdsOf<MODE>::entries>, k1t) + sizeof(float) * K1T_FLOATS,
-                "k1t and bias are copied as one run");
-  const int t = threadIdx.x;
-  const f4* src = reinterpret_cast<const f4*>(tabg);
-  f4 v[ROUNDS], tail;
-#pragma unroll
-  for (int r = 0; r < ROUNDS; ++r) {
-    const int i = r * 64 * WAVES + t;
-    v[r] = src[i < PIECES ? i : 0];
-  }
-  tail = src[TABG_K1T / 4 + (t < TAIL ? t : 0)];
-#pragma unroll
-  for (int r = 0; r < ROUNDS; ++r) {
-    const int i = r * 64 * WAVES + t;
-    if (i < PIECES) reinterpret_cast<f4*>(tab.e)[i] = v[r];
-  }
-  if (t < TAIL) reinterpret_cast<f4*>(tab.k1t)[t] = tail;
+  TableLoad<MODE> ld;
+  ld.fetch(tabg);
+  ld.commit(tab);
 }
 
 // ---- cross-lane sum of the C1 weight gradient ----------------------------------------------------

@@ -55,6 +55,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert not ctx.value
     assert L.cnn_forward(nul, fake, 1, fake) == EINVAL
     assert L.cnn_train_batch(nul, fake, fake, 1, 0.05, nul) == EINVAL
+    assert L.cnn_train_epoch(nul, fake, fake, 10, 5, 0.05, nul) == EINVAL
     assert L.cnn_evaluate(nul, fake, fake, 1, fake, nul) == EINVAL
     assert L.cnn_gradient(nul, fake, fake, 1, fake, nul) == EINVAL
     assert L.cnn_get_weights(nul, nul, nul, nul, nul, nul, nul) == EINVAL

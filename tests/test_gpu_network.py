@@ -126,6 +126,38 @@ def test_small_training_configuration():
     assert abs(host(loss)[0] - ref_loss) <= 1e-5 * ref_loss
 
 
+def test_epoch_call_matches_the_oracle_and_the_per_batch_calls():
+    """cnn_train_epoch over 450 images in batches of 100 (last batch 50): weights within 1e-4 of the
+    oracle's five steps, per-step losses, and bitwise equal to five cnn_train_batch calls."""
+    images, labels = inputs.make_batch(450, 31)
+    w = weights(biases=True)
+    d_im, d_lb = dev(images), dev(labels)
+    net = binding.CNN(w, max_batch=100)
+    losses = torch.zeros(5, dtype=torch.float32, device=DEV)
+    net.train_epoch(d_im, d_lb, 100, LR, losses)
+    w_epoch = host(net.get_weights_flat())
+    w_ref = inputs.flatten(w)
+    ref_losses = []
+    for first in range(0, 450, 100):
+        sl = slice(first, min(450, first + 100))
+        ref_losses.append(oracle.train_batch(images[sl], labels[sl], float(np.float32(LR)), w_ref))
+    g, r = inputs.unflatten(w_epoch), inputs.unflatten(w_ref)
+    for name in g:
+        assert_close(g[name], r[name], RTOL_W, "weights %s after the epoch call" % name)
+    np.testing.assert_allclose(host(losses), ref_losses, rtol=1e-5)
+    net2 = binding.CNN(w, max_batch=100)
+    loss1 = torch.zeros(1, dtype=torch.float32, device=DEV)
+    for first in range(0, 450, 100):
+        net2.train_batch(d_im[first:first + 100], d_lb[first:first + 100], LR, loss1)
+    w_steps = host(net2.get_weights_flat())
+    assert np.array_equal(w_epoch, w_steps)
+    # argument checks
+    with pytest.raises(binding.CnnError):
+        net.train_epoch(d_im, d_lb, 101, LR)      # batch above max_batch
+    with pytest.raises(ValueError):
+        net.train_epoch(d_im, d_lb, 100, LR, torch.zeros(4, dtype=torch.float32, device=DEV))
+
+
 def test_step_is_bitwise_reproducible_and_zero_rate_is_identity():
     images, labels = inputs.make_batch(300, 26)
     w = weights(biases=True)
