@@ -97,8 +97,9 @@ __global__ __launch_bounds__(64) void eval_reduce_kernel(const float* __restrict
   }
 }
 
-// Forward + backward over each wave's images; gradient sums -> partial[gw][PSTRIDE] (a wave
-// without images writes zeros).
+// Forward + backward over each wave's images.  The four waves of a workgroup then add their
+// gradient sums through LDS in a fixed order and the workgroup writes ONE partial row,
+// partial[blockIdx.x][PSTRIDE], with 16-byte stores (a wave without images contributes zeros).
 __global__ __launch_bounds__(64 * WAVES) void train_kernel(const float* __restrict__ images,
                                                           const int32_t* __restrict__ labels, int B,
                                                           const float* __restrict__ tabg,
@@ -123,7 +124,16 @@ __global__ __launch_bounds__(64 * WAVES) void train_kernel(const float* __restri
     wave_image<kTrain>(st, s, tab, px, nn < (size_t)B ? images + nn * NI : nullptr, labels[n], y, none, n);
   }
   CNN_KERNEL_MARK(2);
-  wave_flush(st, s, partial + gw * PSTRIDE);
+  wave_flush(st, reinterpret_cast<float*>(&s), s.pool + FLUSH_PARK);
+  __syncthreads();
+  {
+    const f4* r0 = reinterpret_cast<const f4*>(&lds[0]);
+    const f4* r1 = reinterpret_cast<const f4*>(&lds[1]);
+    const f4* r2 = reinterpret_cast<const f4*>(&lds[2]);
+    const f4* r3 = reinterpret_cast<const f4*>(&lds[3]);
+    f4* dst = reinterpret_cast<f4*>(partial + (size_t)blockIdx.x * PSTRIDE);
+    for (int i = threadIdx.x; i < PSTRIDE / 4; i += 64 * WAVES) dst[i] = (r0[i] + r1[i]) + (r2[i] + r3[i]);
+  }
   CNN_KERNEL_MARK(3);
   CNN_PHASE_FLUSH;
 }
@@ -211,7 +221,7 @@ struct cnn_ctx {
   float* w;             // [PSTRIDE]
   float* tabg;          // [TABG_FLOATS]: the operand table expanded from w, kept in step with it
   int32_t* dest;        // [PSTRIDE][2]: slots of tabg that hold parameter p
-  float* partial;       // [gcap][PSTRIDE]
+  float* partial;       // [partial_rows_for(max_batch)][PSTRIDE]
   float* eval_partial;  // [gcap][2]
   std::vector<hipEvent_t> ev;  // 2 per recorded step (before, after the fused kernel)
   int ev_used = 0;             // recorded steps
@@ -231,9 +241,17 @@ struct Layout {
   size_t w, tabg, dest, partial, eval_partial, total;
 };
 
+// Partial rows a step can write: one per workgroup, in the one-wave-per-image kernel (four waves
+// per workgroup) or in the small-batch kernel (one workgroup per image).
+inline int partial_rows_for(int max_batch) {
+  const int by_wave = gcap_for(max_batch) / WAVES;
+  const int by_group = max_batch < GROUP_MAX_BATCH ? max_batch : GROUP_MAX_BATCH;
+  return by_wave > by_group ? by_wave : by_group;
+}
+
 inline Layout layout_for(int max_batch) {
   Layout l;
-  const size_t g = (size_t)gcap_for(max_batch);
+  const size_t g = (size_t)partial_rows_for(max_batch);
   l.w = 0;
   l.tabg = align_up(l.w + sizeof(float) * PSTRIDE, 256);
   l.dest = align_up(l.tabg + sizeof(float) * TABG_FLOATS, 256);
@@ -273,7 +291,7 @@ int run_backward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B
                  float* grad_out, float* loss_sum) {
   const bool grouped = B <= GROUP_MAX_BATCH;
   const int blocks = grouped ? (B < ctx->gcap ? B : ctx->gcap) : blocks_for(ctx, B, false);
-  const int G = grouped ? blocks : blocks * WAVES;
+  const int G = blocks;  // one partial row per workgroup in both kernels
   const bool timed = (size_t)(2 * ctx->ev_used + 1) < ctx->ev.size();
   if (timed) CNN_HIP_TRY(hipEventRecord(ctx->ev[2 * ctx->ev_used], ctx->stream));
   if (grouped)

@@ -745,8 +745,14 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
   }
 }
 
-// Writes the wave's gradient sums to its partial row (every slot has exactly one writer).
-__device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, TrainLds& s, float* __restrict__ out) {
+// Writes the wave's gradient sums as one partial row (PSTRIDE floats in parameter order, the loss
+// in LOSS_SLOT, zeros after it) to `row`, every slot by exactly one lane.  `row` may be the start
+// of the wave's own LDS area (all of it is dead once the wave's images are done); `park` is
+// 16 * K1_VALUES floats of the same wave's LDS outside the row.
+constexpr int FLUSH_PARK = PSTRIDE - (NS1 + NI) + 48;  // offset into TrainLds::pool, past the row
+static_assert(sizeof(TrainLds) >= sizeof(float) * PSTRIDE, "a partial row fits a wave's LDS area");
+static_assert(FLUSH_PARK % 4 == 0 && FLUSH_PARK + 16 * K1_VALUES <= POOL_FLOATS, "park area inside the pool");
+__device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, float* row, float* park) {
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
 #pragma unroll
   for (int mt = 0; mt < 3; ++mt) {
@@ -755,41 +761,41 @@ __device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, TrainLds& s, f
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int o = 4 * mt + r;
-        if (o < 10) out[OFF_FC + o * NS2 + l + 64 * k] = st.acc_fc[mt][k][r];
+        if (o < 10) row[OFF_FC + o * NS2 + l + 64 * k] = st.acc_fc[mt][k][r];
       }
-    if (l < 4 && 4 * mt + l < 10) out[OFF_B + 4 * mt + l] = st.g_bq[mt];
+    if (l < 4 && 4 * mt + l < 10) row[OFF_B + 4 * mt + l] = st.g_bq[mt];
   }
-  if (l == 0) out[LOSS_SLOT] = st.loss;
+  if (l < PSTRIDE - LOSS_SLOT) row[LOSS_SLOT + l] = l == 0 ? st.loss : 0.0f;
 #pragma unroll
   for (int nt = 0; nt < 10; ++nt)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int j = 4 * q + r, tap = 16 * nt + n16;
-      if (j < 12 && tap < 150) out[OFF_K2 + j * 150 + tap] = st.acc_k2[nt][r];
+      if (j < 12 && tap < 150) row[OFF_K2 + j * 150 + tap] = st.acc_k2[nt][r];
     }
   {
     float v = st.g_b2;  // lane (q, j): sum over the four lane quarters
     v += __shfl_xor(v, 16);
     v += __shfl_xor(v, 32);
-    if (q == 0 && n16 < 12) out[OFF_B2 + n16] = v;
+    if (q == 0 && n16 < 12) row[OFF_B2 + n16] = v;
   }
   // C1 weights: sum over the sixteen 4-lane blocks, in a fixed order: row sums parked in the wave's
   // own LDS, then one lane per weight adds the four rows.
-  k1_park_row_sums(st.acc_k1, s.pool);
+  k1_park_row_sums(st.acc_k1, park);
   wave_sync();
 #pragma unroll
   for (int round = 0; round < 3; ++round) {
     const int t = l + 64 * round;
     if (t < 4 * K1_VALUES) {
-      const float x = (s.pool[t] + s.pool[4 * K1_VALUES + t]) + (s.pool[8 * K1_VALUES + t] + s.pool[12 * K1_VALUES + t]);
+      const float x = (park[t] + park[4 * K1_VALUES + t]) + (park[8 * K1_VALUES + t] + park[12 * K1_VALUES + t]);
       const int idx = k1_slot_param(t);
-      if (idx >= 0) out[idx] = x;
+      if (idx >= 0) row[idx] = x;
     }
   }
 #pragma unroll
   for (int i = 0; i < 6; ++i) {
     const float v = wave_sum(st.g_b1[i]);
-    if (l == 0) out[OFF_B1 + i] = v;
+    if (l == 0) row[OFF_B1 + i] = v;
   }
 }
 
