@@ -162,7 +162,7 @@ __global__ __launch_bounds__(256) void expand_kernel(const float* __restrict__ w
 // order, then a fixed tree over the strands) and either applies  w <- w - scale * g  (grad_out ==
 // nullptr) or stores g.  An updated parameter is also written to its slots of the expanded operand
 // table, dest[p][0..1] (-1 = none).  One workgroup per 64 parameters; the lanes of a wave read 64
-// consecutive floats of a row, and a strand keeps four row reads in flight.
+// consecutive floats of a row, and a strand keeps eight row reads in flight.
 constexpr int RSTRANDS = 16;
 __global__ __launch_bounds__(64 * RSTRANDS) void reduce_update_kernel(const float* __restrict__ partial, int G,
                                                                      float scale, float* __restrict__ w,
@@ -173,17 +173,28 @@ __global__ __launch_bounds__(64 * RSTRANDS) void reduce_update_kernel(const floa
   __shared__ float red[RSTRANDS][64];
   const int lane = threadIdx.x & 63, strand = threadIdx.x >> 6;
   const int p = blockIdx.x * 64 + lane;
-  const float* src = partial + p;
-  float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
-  int g = strand;
-  for (; g + 3 * RSTRANDS < G; g += 4 * RSTRANDS) {
-    a0 += src[(size_t)g * PSTRIDE];
-    a1 += src[(size_t)(g + RSTRANDS) * PSTRIDE];
-    a2 += src[(size_t)(g + 2 * RSTRANDS) * PSTRIDE];
-    a3 += src[(size_t)(g + 3 * RSTRANDS) * PSTRIDE];
+  // what the update needs besides the sum is fetched first, so that it arrives during the reduction
+  float w_old = 0.0f;
+  int d0 = -1, d1 = -1;
+  if (strand == 0 && !grad_out && p < NPARAM) {
+    w_old = w[p];
+    d0 = dest[2 * p];
+    d1 = dest[2 * p + 1];
   }
-  for (; g < G; g += RSTRANDS) a0 += src[(size_t)g * PSTRIDE];
-  red[strand][lane] = (a0 + a1) + (a2 + a3);
+  const float* src = partial + p;
+  // eight row reads in flight per strand; a row index past G reads nothing and adds 0.0
+  float a[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+  for (int g = strand; g < G; g += 8 * RSTRANDS) {
+    float r[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int row = g + k * RSTRANDS;
+      r[k] = row < G ? src[(size_t)row * PSTRIDE] : 0.0f;
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) a[k] += r[k];
+  }
+  red[strand][lane] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
   __syncthreads();
   if (strand == 0) {
     float t[RSTRANDS];
@@ -198,9 +209,8 @@ __global__ __launch_bounds__(64 * RSTRANDS) void reduce_update_kernel(const floa
       if (grad_out) {
         grad_out[p] = total;
       } else {
-        const float wn = fmaf(-scale, total, w[p]);
+        const float wn = fmaf(-scale, total, w_old);
         w[p] = wn;
-        const int d0 = dest[2 * p], d1 = dest[2 * p + 1];
         if (d0 >= 0) tabg[d0] = wn;
         if (d1 >= 0) tabg[d1] = wn;
       }
