@@ -407,6 +407,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
   float* b2s = b1s + 128;                           // [4 waves][64]: per-lane C2 bias sums
   float* scr = b2s + 256;                           // [64 lanes][20]: half of a wave's C2 gradient tiles
   k1_park_row_sums(st.acc_k1, k1s + wave * 16 * K1_VALUES);
+  CNN_GROUP_MARK(11);
 #pragma unroll
   for (int i = 0; i < 6; ++i) {
     float v = st.g_b1[i];
@@ -425,6 +426,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
   }
   CNN_GROUP_MARK(9);
   __syncthreads();
+  CNN_GROUP_MARK(12);
   if (wave >= 2) {
 #pragma unroll
     for (int k = 0; k < 5; ++k) {
@@ -450,6 +452,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
       }
     if (l < 4 && 4 * wave + l < 10) out[OFF_B + 4 * wave + l] = st.g_bq;
   }
+  CNN_GROUP_MARK(13);
   if (t < 4 * K1_VALUES) {  // one thread per parked C1 weight slot: sixteen row sums
     float x[16];
 #pragma unroll

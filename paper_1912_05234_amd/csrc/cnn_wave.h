@@ -261,7 +261,7 @@ __device__ __forceinline__ void load_tables(OperandTable<LdsOf<MODE>::entries>& 
 // acc_k1 holds, per 4-lane block, 42 used result registers: value v = 4 nt + r for maps 0..3 and
 // 28 + 2 nt + r for maps 4, 5 (tile nt < 7, column = lane % 4).  k1_park_row_sums folds the four
 // blocks of every 16-lane row with two DPP rotations and parks the row sums at
-// dst[(q * 42 + v) * 4 + sub] (q = lane / 16; conflict-free: rows are 168 floats = 8 banks apart).
+// dst[(q * 42 + v) * 4 + sub] (q = lane / 16, sub = lane % 4; rows are 168 floats = 8 banks apart).
 constexpr int K1_VALUES = 42;
 __device__ __forceinline__ void k1_park_row_sums(const f4 (&acc)[2][7], float* dst) {
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
@@ -275,7 +275,9 @@ __device__ __forceinline__ void k1_park_row_sums(const f4 (&acc)[2][7], float* d
         x += dpp_row_ror8(x);
         x += dpp_row_ror4(x);
         const int v = mt == 0 ? 4 * nt + r : 28 + 2 * nt + r;
-        if (n16 < 4) dst[(q * K1_VALUES + v) * 4 + n16] = x;
+        // after the two rotations the four lanes of a row with equal lane % 4 hold the same sum and
+        // store it to the same cell: no lane mask, no branch
+        dst[(q * K1_VALUES + v) * 4 + (n16 & 3)] = x;
       }
 }
 // Flat parameter index of parked slot t = 4 v + sub, or -1 for the unused columns of tile 6.
