@@ -3,14 +3,15 @@
 // Section 3); only the division of labour differs, to cut the latency of a single image when there
 // are too few images to give every SIMD its own:
 //
-//   C1 forward, C1 error and C1 weight gradient   pixel groups g = wave + 4 k (wave 0 takes three)
+//   C1 forward and C1 error                       pixel groups g = wave + 4 k (wave 0 takes three)
+//   C1 weight gradient                            GEMM steps 18 wave .. 18 wave + 17 (pixel rows 6 wave ..)
 //   C2 forward, C2 error                          pixel tile mt = wave
 //   output layer                                  outputs o = wave, wave + 4, wave + 8
 //   FC weight gradient                            waves 0..2 take the three 4-output row tiles
 //   C2 input error (col2im)                       wave 0: input maps 0..3, wave 1: maps 4, 5
 //   C2 weight gradient                            wave 2: pixels 0..31, wave 3: pixels 32..63
 //
-// Phases that hand data between waves are separated by workgroup barriers (seven per image); the
+// Phases that hand data between waves are separated by workgroup barriers (eight per image); the
 // two col2im waves never touch the same input map, so their read-add-write rounds need no barrier.
 #pragma once
 
@@ -20,9 +21,10 @@ namespace cnn {
 
 struct GroupState {
   int pix0[3];      // window origin of this lane in the wave's pixel groups g = wave + 4 k
+  int d1off[3];     // this lane's pixel of those groups inside a 24x24 map
   float bias2;      // b2[n16]
   f4 acc_k2[10];    // waves 2, 3: C2 weight gradient over their half of the pixels
-  f4 acc_k1[2][7];  // C1 weight gradient over this wave's pixel groups, per 4-lane block
+  f4 acc_k1[2];     // C1 weight gradient GEMM over this wave's 18 steps, T[(m,sh)][c]
   f4 acc_fc[3];     // waves 0..2: FC weight gradient rows o = 4 wave + r, columns lane + 64 k
   float g_bq;       // waves 0..2: FC bias gradient b[4 wave + lane % 4]
   float g_b1[6], g_b2, loss;
@@ -85,43 +87,20 @@ __device__ __forceinline__ void group_c1_forward(const GroupState& st, TrainLds&
   }
 }
 
-// C1 error of NS pixel groups into the staging area, then their share of the C1 weight gradient.
+// C1 error of this wave's NS pixel groups into the staged d1[6][24][24].
 template <int NS>
-__device__ __forceinline__ void group_c1_backward(GroupState& st, TrainLds& s, int wave,
-                                                  const float (&c1)[3][6]) {
-  const int l = threadIdx.x & 63, b = l >> 2, sub = l & 3;
+__device__ __forceinline__ void group_c1_error(GroupState& st, TrainLds& s, int wave, const float (&c1)[3][6]) {
+  const int l = threadIdx.x & 63, b = l >> 2;
 #pragma unroll
   for (int k = 0; k < NS; ++k) {
     const int g = wave + 4 * k;
-    float d1[6];
+    float* dst = s.pool + st.d1off[k];
 #pragma unroll
     for (int i = 0; i < 6; ++i) {
       const float c = c1[k][i];
-      d1[i] = s.d_s1[i * 144 + 16 * g + b] * 0.25f * c * (1.0f - c);
-      st.g_b1[i] += d1[i];
-    }
-    float2* dst = reinterpret_cast<float2*>(&s.pool[(g * 64 + l) * STG]);
-    dst[0] = float2{d1[0], d1[1]};
-    dst[1] = float2{d1[2], d1[3]};
-    dst[2] = float2{d1[4], d1[5]};
-  }
-  wave_sync();  // a wave reads only the staging cells it wrote itself
-#pragma unroll
-  for (int k = 0; k < NS; ++k) {
-    const int g = wave + 4 * k;
-    const float* pa = s.img + st.pix0[k] + sub;
-    const float* pb = s.img + st.pix0[k] + 28 * sub;
-    const float* sa = s.pool + (g * 64 + 4 * b) * STG + sub;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int pt = (t >> 1) * 28 + (t & 1);
-      const float a0 = sa[STG * t], a1 = sa[STG * t + 4];
-#pragma unroll
-      for (int nt = 0; nt < 7; ++nt) {
-        const float bv = nt < 5 ? pa[28 * nt + pt] : nt == 5 ? pb[4 + pt] : pa[116 + pt];
-        st.acc_k1[0][nt] = mfma4(a0, bv, st.acc_k1[0][nt]);
-        st.acc_k1[1][nt] = mfma4(a1, bv, st.acc_k1[1][nt]);
-      }
+      const float d1 = s.d_s1[i * 144 + 16 * g + b] * 0.25f * c * (1.0f - c);
+      st.g_b1[i] += d1;
+      dst[i * 576] = d1;
     }
   }
 }
@@ -151,13 +130,11 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
   for (int k = 0; k < 3; ++k) {
     const int g = wave + 4 * k < 9 ? wave + 4 * k : 8, win = 16 * g + b;
     st.pix0[k] = 2 * (win / 12) * 28 + 2 * (win % 12);
+    st.d1off[k] = (2 * (win / 12) + ((l >> 1) & 1)) * 24 + 2 * (win % 12) + (l & 1);
   }
 #pragma unroll
   for (int nt = 0; nt < 10; ++nt) st.acc_k2[nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-  for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-    for (int nt = 0; nt < 7; ++nt) st.acc_k1[mt][nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+  st.acc_k1[0] = st.acc_k1[1] = f4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
   for (int k = 0; k < 3; ++k) st.acc_fc[k] = f4{0.0f, 0.0f, 0.0f, 0.0f};
   st.g_bq = 0.0f;
@@ -391,22 +368,25 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     CNN_GROUP_MARK(7);
     __syncthreads();  // (6) d_s1 complete; s1, d_c2 no longer needed
 
-    // ---- C1 error and C1 weight gradient for this wave's pixel groups --------------------------------
+    // ---- C1 error for this wave's pixel groups, staged for everybody ----------------------------------
     if (wave == 0)
-      group_c1_backward<3>(st, s, wave, c1);
+      group_c1_error<3>(st, s, wave, c1);
     else
-      group_c1_backward<2>(st, s, wave, c1);
+      group_c1_error<2>(st, s, wave, c1);
+    __syncthreads();  // (7) d1 complete
+    // ---- C1 weight gradient: this wave's quarter of the GEMM's K range (pixel rows 6 wave .. 6 wave + 5)
+    c1g_accumulate<C1G_STEPS / WAVES>(st.acc_k1, s.pool + 144 * wave, s.img + 168 * wave);
     CNN_GROUP_MARK(8);
-    __syncthreads();  // (7) the image and the staging area are free again
+    __syncthreads();  // (8) the image and the staging area are free again
   }
 
   // ---- one partial row per workgroup: cross-wave sums through LDS in a fixed order -------------------
   // The operand table is dead after the last image; its storage takes the parked values.
-  float* k1s = tab.e;                               // [4 waves][4 rows][42][4]: C1 weight row sums
-  float* b1s = tab.e + 16 * 4 * K1_VALUES;          // [4 waves][4 rows][8]: C1 bias row sums
+  float* k1s = tab.e;                               // [4 waves][16][32]: parked C1 weight GEMM results
+  float* b1s = tab.e + WAVES * C1G_PARK;            // [4 waves][4 rows][8]: C1 bias row sums
   float* b2s = b1s + 128;                           // [4 waves][64]: per-lane C2 bias sums
   float* scr = b2s + 256;                           // [64 lanes][20]: half of a wave's C2 gradient tiles
-  k1_park_row_sums(st.acc_k1, k1s + wave * 16 * K1_VALUES);
+  c1g_park(st.acc_k1, k1s + wave * C1G_PARK);
   CNN_GROUP_MARK(11);
 #pragma unroll
   for (int i = 0; i < 6; ++i) {
@@ -453,16 +433,11 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     if (l < 4 && 4 * wave + l < 10) out[OFF_B + 4 * wave + l] = st.g_bq;
   }
   CNN_GROUP_MARK(13);
-  if (t < 4 * K1_VALUES) {  // one thread per parked C1 weight slot: sixteen row sums
-    float x[16];
-#pragma unroll
-    for (int k = 0; k < 16; ++k) x[k] = k1s[k * 4 * K1_VALUES + t];
-#pragma unroll
-    for (int k = 0; k < 16; k += 4) x[k] = (x[k] + x[k + 1]) + (x[k + 2] + x[k + 3]);
-    const int idx = k1_slot_param(t);
-    if (idx >= 0) out[idx] = (x[0] + x[4]) + (x[8] + x[12]);
-  } else if (t < 4 * K1_VALUES + 6) {
-    const int i = t - 4 * K1_VALUES;
+  if (t < 150) {  // one thread per C1 weight: the four waves' shares of the GEMM, both shifted halves
+    out[OFF_K1 + t] = (c1g_combine(k1s, t) + c1g_combine(k1s + C1G_PARK, t)) +
+                      (c1g_combine(k1s + 2 * C1G_PARK, t) + c1g_combine(k1s + 3 * C1G_PARK, t));
+  } else if (t < 156) {
+    const int i = t - 150;
     float x[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) x[k] = b1s[k * 8 + i];

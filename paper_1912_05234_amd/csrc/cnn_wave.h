@@ -10,7 +10,9 @@
 //   C2 input error        v_mfma_f32_16x16x4_f32: T[tap,pixel] = k2^T * d_c2 (K = 12 maps), then T is
 //                         added into d_s1 at (y+u, x+v) (the col2im form of `backin`: no zero padding)
 //                         in rounds of plain LDS read-add-write whose targets cannot collide
-//   C1 weight gradient    v_mfma_f32_4x4x1_f32: 16 blocks = 16 pixels, each a 4 maps x 4 taps outer product
+//   C1 weight gradient    v_mfma_f32_16x16x4_f32: M = 12(16) rows (map, x parity), N = 30(32) shifted taps,
+//                         K = 288 pixel pairs; the C1 error is staged in LDS as d1[6][24][24]
+//   FC weight gradient    v_mfma_f32_4x4x1_f32 rank-1 updates
 //   FC, pooling, sigmoid  fp32 VALU
 //
 // A workgroup is four such waves.  They share nothing but a read-only table of MFMA operands in
@@ -57,14 +59,13 @@ struct __align__(16) FwdLds {
 // Per-wave LDS of the training step.  d_s1 comes first: the col2im rows of the two padding maps
 // (c = 6, 7) add 0.0 at offsets up to 1152 floats past its start, which stays inside the struct.
 // `pool` holds, at the P_* offsets, the arrays that are dead by the time the C1 weight gradient
-// runs; that phase reuses the whole pool as its staging area.
+// runs; that phase reuses the whole pool for the staged C1 error.
 constexpr int P_S1 = 0;                 // s1[6][12][12] + 288 (padded K steps of the C2 forward read them)
 constexpr int P_S2 = P_S1 + NS1 + 288;  // s2[192]
 constexpr int P_DS2 = P_S2 + NS2;       // d_s2[192] + 64 (rows of the padding maps of the C2 tiles)
 constexpr int P_D2 = P_DS2 + NS2 + 64;  // d2[16][D2S]: error at C2's pre-activation, [map][pixel p]
 constexpr int P_END = P_D2 + 16 * D2S;
-constexpr int STG = 6;                  // floats per lane in the C1 error staging, [g][lane][6]
-constexpr int POOL_FLOATS = 9 * 64 * STG + 32;  // + the over-read of the last lane's padding rows
+constexpr int POOL_FLOATS = NC1 + 32;   // the C1 error d1[6][24][24] is staged over the whole pool
 static_assert(POOL_FLOATS >= P_END, "pool holds the forward/C2 arrays");
 struct __align__(16) TrainLds {
   float d_s1[NS1];  // error at S1 (col2im target)
@@ -175,12 +176,6 @@ enum BwdTile { kTileV0 = 0, kTileU4 = 5, kTileC = 6 };  // V(v) = kTileV0 + v
 __host__ __device__ constexpr int bwd_tap(int tile, int ri) {
   return tile < 5 ? 5 * ri + tile : tile == kTileU4 ? 20 + ri : (ri == 0 ? 24 : -1);
 }
-// ---- N order of the C1 weight-gradient outer products: tile nt < 7, column = lane%4 -> tap ----
-// nt 0..4: u = nt, v = sub (v < 4); nt 5: v = 4, u = sub (u < 4); nt 6: (4,4) in column 0 only.
-__host__ __device__ constexpr int k1_tap(int nt, int sub) {
-  return nt < 5 ? nt * 5 + sub : nt == 5 ? sub * 5 + 4 : (sub == 0 ? 24 : -1);
-}
-
 // Flat parameter index whose value slot i of the expanded table holds, or -1 for a zero.
 __host__ __device__ constexpr int table_source(int i) {
   if (i < TABG_K1T) {
@@ -257,36 +252,69 @@ __device__ __forceinline__ void load_tables(OperandTable<LdsOf<MODE>::entries>& 
   ld.commit(tab);
 }
 
-// ---- cross-lane sum of the C1 weight gradient ----------------------------------------------------
-// acc_k1 holds, per 4-lane block, 42 used result registers: value v = 4 nt + r for maps 0..3 and
-// 28 + 2 nt + r for maps 4, 5 (tile nt < 7, column = lane % 4).  k1_park_row_sums folds the four
-// blocks of every 16-lane row with two DPP rotations and parks the row sums at
-// dst[(q * 42 + v) * 4 + sub] (q = lane / 16, sub = lane % 4; rows are 168 floats = 8 banks apart).
-constexpr int K1_VALUES = 42;
-__device__ __forceinline__ void k1_park_row_sums(const f4 (&acc)[2][7], float* dst) {
+// ---- C1 weight gradient as one GEMM per image (16x16x4 MFMA) ------------------------------------
+//   g_k1[m][u][v] = sum_{y,x < 24} d1[m][y][x] * img[y+u][x+v]            (backweights, Section 3)
+// Pixels are taken in horizontal pairs x = 2X + sh (sh = 0, 1).  With v' = v + sh the image factor
+// img[y+u][2X+v'] no longer depends on sh, so
+//   T[(m,sh)][(u,v')] = sum_{y,X} d1[m][y][2X+sh] * img[y+u][2X+v'],   g_k1[m][u][v] = T[(m,0)][(u,v)] + T[(m,1)][(u,v+1)]
+// is a GEMM with M = 12 rows (m,sh) in one 16-row tile, N = 30 columns (u,v'), c = 6u + v', in two
+// 16-column tiles, and K = 288 pixel pairs in 72 steps of four: step kk covers row y = kk / 3 and
+// pairs X = 4 (kk % 3) + q, q = lane / 16.  d1 is staged in LDS as d1[m][24][24].
+//   A[i = lane%16][k = q] = d1[m = (i/2) % 6][y][2X + i%2]     (rows 12..15 repeat rows 0..3, dropped)
+//   B[k = q][j = lane%16] = img[y + u][2X + v'], c = 16 nt + j  (columns 30, 31 read tap 0, dropped)
+//   D[i = 4q + r][j]: register r of tile nt.
+constexpr int C1G_STEPS = 72;
+constexpr int C1G_PARK = 16 * 32;  // floats: T as [row i][column c]
+__host__ __device__ constexpr int c1g_imm_a(int kk) { return 24 * (kk / 3) + 8 * (kk % 3); }
+__host__ __device__ constexpr int c1g_imm_b(int kk) { return 28 * (kk / 3) + 8 * (kk % 3); }
+// Lane parts of the operand addresses (floats): d1 and the two image tiles.
+__device__ __forceinline__ void c1g_lane_offsets(int& a, int (&bt)[2]) {
+  const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
+  a = ((n16 >> 1) % 6) * 576 + (n16 & 1) + 2 * q;
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    const int c = 16 * nt + n16;
+    bt[nt] = (c < 30 ? (c / 6) * 28 + c % 6 : 0) + 2 * q;
+  }
+}
+// STEPS steps of the GEMM starting at pixel row y0 (a multiple of... any row): operands of step
+// kk + 2 are read while the two MFMAs of step kk issue.
+template <int STEPS>
+__device__ __forceinline__ void c1g_accumulate(f4 (&acc)[2], const float* d1, const float* img) {
+  int a, bt[2];
+  c1g_lane_offsets(a, bt);
+  const float* pa = d1 + a;
+  const float* pb0 = img + bt[0];
+  const float* pb1 = img + bt[1];
+  float oa[3], ob0[3], ob1[3];
+  auto load_step = [&](int kk, int slot) {
+    oa[slot] = pa[c1g_imm_a(kk)];
+    ob0[slot] = pb0[c1g_imm_b(kk)];
+    ob1[slot] = pb1[c1g_imm_b(kk)];
+  };
+  load_step(0, 0);
+  if (STEPS > 1) load_step(1, 1);
+#pragma unroll
+  for (int kk = 0; kk < STEPS; ++kk) {
+    if (kk + 2 < STEPS) load_step(kk + 2, (kk + 2) % 3);
+    acc[0] = mfma16(oa[kk % 3], ob0[kk % 3], acc[0]);
+    acc[1] = mfma16(oa[kk % 3], ob1[kk % 3], acc[1]);
+    if (kk + 2 < STEPS) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+  }
+}
+// Parks T: park[i * 32 + c] for the lane's rows i = 4q + r and columns c = 16 nt + lane%16.
+__device__ __forceinline__ void c1g_park(const f4 (&acc)[2], float* park) {
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
 #pragma unroll
-  for (int mt = 0; mt < 2; ++mt)
+  for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-    for (int nt = 0; nt < 7; ++nt)
-#pragma unroll
-      for (int r = 0; r < (mt == 0 ? 4 : 2); ++r) {
-        float x = acc[mt][nt][r];
-        x += dpp_row_ror8(x);
-        x += dpp_row_ror4(x);
-        const int v = mt == 0 ? 4 * nt + r : 28 + 2 * nt + r;
-        // after the two rotations the four lanes of a row with equal lane % 4 hold the same sum and
-        // store it to the same cell: no lane mask, no branch
-        dst[(q * K1_VALUES + v) * 4 + (n16 & 3)] = x;
-      }
+    for (int r = 0; r < 4; ++r) park[(4 * q + r) * 32 + 16 * nt + n16] = acc[nt][r];
 }
-// Flat parameter index of parked slot t = 4 v + sub, or -1 for the unused columns of tile 6.
-__device__ __forceinline__ int k1_slot_param(int t) {
-  const int v = t >> 2, sub = t & 3;
-  const int mt = v >= 28 ? 1 : 0, vv = v - 28 * mt;
-  const int nt = mt ? vv >> 1 : vv >> 2, r = mt ? vv & 1 : vv & 3;
-  const int tap = k1_tap(nt, sub);
-  return tap >= 0 ? OFF_K1 + (4 * mt + r) * 25 + tap : -1;
+// g_k1 element e = m * 25 + 5 u + v from a parked T.
+__device__ __forceinline__ float c1g_combine(const float* park, int e) {
+  const int m = e / 25, tap = e - 25 * m, u = tap / 5, v = tap - 5 * u;
+  return park[(2 * m) * 32 + 6 * u + v] + park[(2 * m + 1) * 32 + 6 * u + v + 1];
 }
 
 // Everything a wave keeps in registers across its images.
@@ -296,7 +324,8 @@ struct WaveState {
   float bias2;    // b2[n16]
   // training only
   f4 acc_k2[10];  // sum over images of d_c2 (x) s1 patches, D[j = 4q+r][tap = 16 nt + n16]
-  f4 acc_k1[2][7];  // per 4-lane block partial of d_c1 (x) image patches
+  f4 acc_k1[2];   // C1 weight gradient GEMM result T[(m,sh) = 4q+r][c = 16 nt + n16]
+  int d1off[9];   // offset of this lane's pixel of group g inside a 24x24 map
   f4 acc_fc[3][3];  // FC weight gradient, D_r(lane) = g_fc[o = 4 mt + r][i = lane + 64 k]
   float g_bq[3];    // FC bias gradient: lane l holds b[4 mt + l % 4] (the same in every quad)
   float g_b1[6], g_b2, loss;
@@ -313,15 +342,13 @@ __device__ __forceinline__ void wave_init(WaveState<MODE>& st, typename LdsOf<MO
   for (int g = 0; g < 9; ++g) {
     const int win = 16 * g + b;
     st.pix0[g] = 2 * (win / 12) * 28 + 2 * (win % 12);
+    if (MODE == kTrain) st.d1off[g] = (2 * (win / 12) + ((l >> 1) & 1)) * 24 + 2 * (win % 12) + (l & 1);
   }
   st.bias2 = 0.0f;  // read from the operand table once it is complete
   if (MODE == kTrain) {
 #pragma unroll
     for (int nt = 0; nt < 10; ++nt) st.acc_k2[nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < 7; ++nt) st.acc_k1[mt][nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    st.acc_k1[0] = st.acc_k1[1] = f4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int i = 0; i < 6; ++i) st.g_b1[i] = 0.0f;
     st.g_b2 = 0.0f;
@@ -688,7 +715,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
     CNN_PHASE(7);
     if (next_image) px = load_pixels(next_image);
     // ---- backavgpool through S1 and the derivative of C1's sigmoid for all nine pixel groups, staged
-    //      in LDS as [g][lane][6 maps] over the pool (s1, s2, d_s2, d2 are dead by now) ------------------
+    //      in LDS as d1[m][24][24] over the pool (s1, s2, d_s2, d2 are dead by now) ---------------------
 #pragma unroll
     for (int gp = 0; gp < 3; ++gp) {
       float up[3][6];
@@ -699,49 +726,20 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
 #pragma unroll
       for (int k = 0; k < 3; ++k) {
         const int g = 3 * gp + k;
-        float d1[6];
+        float* dst = s.pool + st.d1off[g];
 #pragma unroll
         for (int i = 0; i < 6; ++i) {
           const float c = c1[g][i];
-          d1[i] = up[k][i] * 0.25f * c * (1.0f - c);
-          st.g_b1[i] += d1[i];
+          const float d1 = up[k][i] * 0.25f * c * (1.0f - c);
+          st.g_b1[i] += d1;
+          dst[i * 576] = d1;
         }
-        float2* dst = reinterpret_cast<float2*>(&s.pool[(g * 64 + l) * STG]);
-        dst[0] = float2{d1[0], d1[1]};
-        dst[1] = float2{d1[2], d1[3]};
-        dst[2] = float2{d1[4], d1[5]};
       }
     }
     wave_sync();
     CNN_PHASE(8);
-    // ---- C1 backweights: per pixel (= 4-lane block) the outer product of 6(8) map errors and
-    //      25(28) image taps; 36 steps of 16 pixels, no synchronisation between them.  Rows of the
-    //      padding maps 6, 7 read the next lane's staging cells: finite, and their results are dropped.
-    {
-      // operands of step k+1 are read while the 14 MFMAs of step k issue (explicit double buffer)
-      float opa[2][2], opb[2][7];
-      auto load_step = [&](int k, float (&oa)[2], float (&ob)[7]) {
-        const int g = k >> 2, t = k & 3;
-        const int pt = (t >> 1) * 28 + (t & 1);                // sub-pixel t of the window
-        const float* pa = s.img + st.pix0[g] + sub;            // taps (u = nt, v = sub) and (4,4)
-        const float* pb = s.img + st.pix0[g] + 28 * sub;       // taps (u = sub, v = 4)
-        const float* sa = s.pool + (g * 64 + 4 * b) * STG + sub;
-        oa[0] = sa[STG * t];
-        oa[1] = sa[STG * t + 4];
-#pragma unroll
-        for (int nt = 0; nt < 7; ++nt) ob[nt] = nt < 5 ? pa[28 * nt + pt] : nt == 5 ? pb[4 + pt] : pa[116 + pt];
-      };
-      load_step(0, opa[0], opb[0]);
-#pragma unroll
-      for (int k = 0; k < 36; ++k) {
-        if (k + 1 < 36) load_step(k + 1, opa[(k + 1) & 1], opb[(k + 1) & 1]);
-#pragma unroll
-        for (int nt = 0; nt < 7; ++nt) {
-          st.acc_k1[0][nt] = mfma4(opa[k & 1][0], opb[k & 1][nt], st.acc_k1[0][nt]);
-          st.acc_k1[1][nt] = mfma4(opa[k & 1][1], opb[k & 1][nt], st.acc_k1[1][nt]);
-        }
-      }
-    }
+    // ---- C1 backweights: one GEMM over the image's 288 pixel pairs ------------------------------------
+    c1g_accumulate<C1G_STEPS>(st.acc_k1, s.pool, s.img);
     wave_sync();
     CNN_PHASE(9);
   }
@@ -750,10 +748,10 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
 // Writes the wave's gradient sums as one partial row (PSTRIDE floats in parameter order, the loss
 // in LOSS_SLOT, zeros after it) to `row`, every slot by exactly one lane.  `row` may be the start
 // of the wave's own LDS area (all of it is dead once the wave's images are done); `park` is
-// 16 * K1_VALUES floats of the same wave's LDS outside the row.
+// C1G_PARK floats of the same wave's LDS outside the row.
 constexpr int FLUSH_PARK = PSTRIDE - (NS1 + NI) + 48;  // offset into TrainLds::pool, past the row
 static_assert(sizeof(TrainLds) >= sizeof(float) * PSTRIDE, "a partial row fits a wave's LDS area");
-static_assert(FLUSH_PARK % 4 == 0 && FLUSH_PARK + 16 * K1_VALUES <= POOL_FLOATS, "park area inside the pool");
+static_assert(FLUSH_PARK % 4 == 0 && FLUSH_PARK + C1G_PARK <= POOL_FLOATS, "park area inside the pool");
 __device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, float* row, float* park) {
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
 #pragma unroll
@@ -781,18 +779,13 @@ __device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, float* row, fl
     v += __shfl_xor(v, 32);
     if (q == 0 && n16 < 12) row[OFF_B2 + n16] = v;
   }
-  // C1 weights: sum over the sixteen 4-lane blocks, in a fixed order: row sums parked in the wave's
-  // own LDS, then one lane per weight adds the four rows.
-  k1_park_row_sums(st.acc_k1, park);
+  // C1 weights: the two shifted halves of the GEMM result are joined through LDS
+  c1g_park(st.acc_k1, park);
   wave_sync();
 #pragma unroll
   for (int round = 0; round < 3; ++round) {
-    const int t = l + 64 * round;
-    if (t < 4 * K1_VALUES) {
-      const float x = (park[t] + park[4 * K1_VALUES + t]) + (park[8 * K1_VALUES + t] + park[12 * K1_VALUES + t]);
-      const int idx = k1_slot_param(t);
-      if (idx >= 0) row[idx] = x;
-    }
+    const int e = l + 64 * round;
+    if (e < 150) row[OFF_K1 + e] = c1g_combine(park, e);
   }
 #pragma unroll
   for (int i = 0; i < 6; ++i) {
