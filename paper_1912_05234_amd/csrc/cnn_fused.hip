@@ -138,15 +138,16 @@ __global__ __launch_bounds__(64 * WAVES) void train_kernel(const float* __restri
   CNN_PHASE_FLUSH;
 }
 
-// Small batches: four waves share one image (cnn_group.h); one partial row per workgroup.
-__global__ __launch_bounds__(64 * WAVES) void train_group_kernel(const float* __restrict__ images,
-                                                                const int32_t* __restrict__ labels, int B,
-                                                                const float* __restrict__ tabg,
-                                                                float* __restrict__ partial) {
+// Small batches: eight waves share one image (cnn_group.h); one partial row per workgroup.
+__global__ __launch_bounds__(64 * GWAVES) void train_group_kernel(const float* __restrict__ images,
+                                                              const int32_t* __restrict__ labels, int B,
+                                                              const float* __restrict__ tabg,
+                                                              float* __restrict__ partial) {
   __shared__ OperandTable<TAB_TRAIN_ENTRIES> tab;
   __shared__ TrainLds s;
+  __shared__ __align__(16) float d_s1b[D_S1B_FLOATS];
   __shared__ float ybuf[16];
-  group_train(images, labels, B, tabg, partial + (size_t)blockIdx.x * PSTRIDE, tab, s, ybuf);
+  group_train(images, labels, B, tabg, partial + (size_t)blockIdx.x * PSTRIDE, tab, s, d_s1b, ybuf);
 }
 
 // Expanded operand table from the flat parameter vector: tabg[i] = w[table_source(i)] or 0.
@@ -305,7 +306,7 @@ int run_backward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B
   const bool timed = (size_t)(2 * ctx->ev_used + 1) < ctx->ev.size();
   if (timed) CNN_HIP_TRY(hipEventRecord(ctx->ev[2 * ctx->ev_used], ctx->stream));
   if (grouped)
-    train_group_kernel<<<blocks, 64 * WAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, ctx->partial);
+    train_group_kernel<<<blocks, 64 * GWAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, ctx->partial);
   else
     train_kernel<<<blocks, 64 * WAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, ctx->partial);
   if (hipGetLastError() != hipSuccess) return CNN_EHIP;

@@ -1,30 +1,37 @@
-// Small-batch form of the fused step: FOUR WAVEFRONTS SHARE ONE IMAGE.  Same arithmetic, same
-// operand table, same LDS arrays and the same MFMA formulations as cnn_wave.h (arXiv 1912.05234,
-// Section 3); only the division of labour differs, to cut the latency of a single image when there
-// are too few images to give every SIMD its own:
+// Small-batch form of the fused step: EIGHT WAVEFRONTS (two per SIMD of a compute unit) SHARE ONE
+// IMAGE.  Same arithmetic, same operand table, same LDS arrays and the same MFMA formulations as
+// cnn_wave.h (arXiv 1912.05234, Section 3); only the division of labour differs, to cut the latency
+// of a single image when there are too few images to give every SIMD its own.  Two waves per SIMD
+// because one wave alone issues a vector instruction only every ~5 cycles, two reach ~2.4.
 //
-//   C1 forward and C1 error                       pixel groups g = wave + 4 k (wave 0 takes three)
-//   C1 weight gradient                            GEMM steps 18 wave .. 18 wave + 17 (pixel rows 6 wave ..)
-//   C2 forward, C2 error                          pixel tile mt = wave
-//   output layer                                  outputs o = wave, wave + 4, wave + 8
-//   FC weight gradient                            waves 0..2 take the three 4-output row tiles
-//   C2 input error (col2im)                       wave 0: input maps 0..3, wave 1: maps 4, 5
-//   C2 weight gradient                            wave 2: pixels 0..31, wave 3: pixels 32..63
+//   C1 forward and C1 error      pixel group g = wave (wave 0 also takes group 8)
+//   C1 weight gradient           GEMM steps 9 wave .. 9 wave + 8 (pixel rows 3 wave .. 3 wave + 2)
+//   C2 forward, C2 error         waves 0..3: pixel tile mt = wave (waves 4..7 clear the col2im targets)
+//   output layer                 outputs o = wave and wave + 8
+//   FC weight gradient           waves 0..2 take the three 4-output row tiles
+//   C2 input error (col2im)      waves 0..3: input maps 4 cg .. 4 cg + 3, cg = wave % 2, and pixel tiles
+//                                nt = 2 h, 2 h + 1, h = wave / 2; half h adds into its own copy of d_s1,
+//                                so no two waves ever touch the same cell; the C1 error reads both copies
+//   C2 weight gradient           wave 4: pixels 0..31, wave 5: pixels 32..63
 //
-// Phases that hand data between waves are separated by workgroup barriers (eight per image); the
-// two col2im waves never touch the same input map, so their read-add-write rounds need no barrier.
+// Phases that hand data between waves are separated by workgroup barriers (eight per image).
 #pragma once
 
 #include "cnn_wave.h"
 
 namespace cnn {
 
+constexpr int GWAVES = 8;  // waves per workgroup of the small-batch kernel
+// Second col2im target: [6][12][12] plus the cells behind it that the rows of the padding maps 6, 7
+// rewrite with themselves (+ 0.0), as they do behind the first target inside TrainLds.
+constexpr int D_S1B_FLOATS = NS1 + 304;
+
 struct GroupState {
-  int pix0[3];      // window origin of this lane in the wave's pixel groups g = wave + 4 k
-  int d1off[3];     // this lane's pixel of those groups inside a 24x24 map
+  int pix0[2];      // window origin of this lane in the wave's pixel groups g = wave + 8 k
+  int d1off[2];     // this lane's pixel of those groups inside a 24x24 map
   float bias2;      // b2[n16]
-  f4 acc_k2[10];    // waves 2, 3: C2 weight gradient over their half of the pixels
-  f4 acc_k1[2];     // C1 weight gradient GEMM over this wave's 18 steps, T[(m,sh)][c]
+  f4 acc_k2[10];    // waves 4, 5: C2 weight gradient over their half of the pixels
+  f4 acc_k1[2];     // C1 weight gradient GEMM over this wave's 9 steps, T[(m,sh)][c]
   f4 acc_fc[3];     // waves 0..2: FC weight gradient rows o = 4 wave + r, columns lane + 64 k
   float g_bq;       // waves 0..2: FC bias gradient b[4 wave + lane % 4]
   float g_b1[6], g_b2, loss;
@@ -34,7 +41,7 @@ struct GroupState {
 template <int NS>
 __device__ __forceinline__ void group_c1_forward(const GroupState& st, TrainLds& s,
                                                  const OperandTable<TAB_TRAIN_ENTRIES>& tab, int wave,
-                                                 float (&c1)[3][6]) {
+                                                 float (&c1)[2][6]) {
   const int l = threadIdx.x & 63, b = l >> 2, sub = l & 3;
   const float* ip[NS];
   {
@@ -68,7 +75,7 @@ __device__ __forceinline__ void group_c1_forward(const GroupState& st, TrainLds&
   const bool odd = sub & 1, hi = sub & 2;
 #pragma unroll
   for (int k = 0; k < NS; ++k) {
-    const int g = wave + 4 * k;
+    const int g = wave + GWAVES * k;
 #pragma unroll
     for (int i = 0; i < 6; ++i) c1[k][i] = logistic(c1[k][i]);
     const float s01 = (odd ? c1[k][1] : c1[k][0]) + quad_xor1(odd ? c1[k][0] : c1[k][1]);
@@ -76,29 +83,31 @@ __device__ __forceinline__ void group_c1_forward(const GroupState& st, TrainLds&
     const float tot = (hi ? s23 : s01) + quad_xor2(hi ? s01 : s23);
     s.pool[P_S1 + sub * 144 + 16 * g + b] = 0.25f * tot;
   }
-  // maps 4, 5: slots 0 and 1 together, slot 2 (wave 0 only) with itself
-#pragma unroll
-  for (int kp = 0; kp < (NS + 1) / 2; ++kp) {
-    const int k0 = 2 * kp, k1 = 2 * kp + 1 < NS ? 2 * kp + 1 : 2 * kp;
+  // maps 4, 5: lane sub -> map 4 + (sub & 1) of slot (sub & 2 ? last : first)
+  {
+    const int k0 = 0, k1 = NS - 1;
     const float sa = (odd ? c1[k0][5] : c1[k0][4]) + quad_xor1(odd ? c1[k0][4] : c1[k0][5]);
     const float sb = (odd ? c1[k1][5] : c1[k1][4]) + quad_xor1(odd ? c1[k1][4] : c1[k1][5]);
     const float tot = (hi ? sb : sa) + quad_xor2(hi ? sa : sb);
-    s.pool[P_S1 + (4 + (sub & 1)) * 144 + 16 * (wave + 4 * (hi ? k1 : k0)) + b] = 0.25f * tot;
+    s.pool[P_S1 + (4 + (sub & 1)) * 144 + 16 * (wave + GWAVES * (hi ? k1 : k0)) + b] = 0.25f * tot;
   }
 }
 
-// C1 error of this wave's NS pixel groups into the staged d1[6][24][24].
+// C1 error of this wave's NS pixel groups into the staged d1[6][24][24]; the error at S1 is the sum
+// of the two col2im copies.
 template <int NS>
-__device__ __forceinline__ void group_c1_error(GroupState& st, TrainLds& s, int wave, const float (&c1)[3][6]) {
+__device__ __forceinline__ void group_c1_error(GroupState& st, TrainLds& s, const float* d_s1b, int wave,
+                                               const float (&c1)[2][6]) {
   const int l = threadIdx.x & 63, b = l >> 2;
 #pragma unroll
   for (int k = 0; k < NS; ++k) {
-    const int g = wave + 4 * k;
+    const int g = wave + GWAVES * k;
     float* dst = s.pool + st.d1off[k];
 #pragma unroll
     for (int i = 0; i < 6; ++i) {
       const float c = c1[k][i];
-      const float d1 = s.d_s1[i * 144 + 16 * g + b] * 0.25f * c * (1.0f - c);
+      const float up = s.d_s1[i * 144 + 16 * g + b] + d_s1b[i * 144 + 16 * g + b];
+      const float d1 = up * 0.25f * c * (1.0f - c);
       st.g_b1[i] += d1;
       dst[i * 576] = d1;
     }
@@ -106,11 +115,13 @@ __device__ __forceinline__ void group_c1_error(GroupState& st, TrainLds& s, int 
 }
 
 // The whole step for the workgroup's images n = blockIdx.x, blockIdx.x + gridDim.x, ...; one
-// partial row per workgroup.  `ybuf` is 16 floats of LDS for the network output.
+// partial row per workgroup.  `d_s1b` is the second col2im target (D_S1B_FLOATS floats), `ybuf` 16
+// floats of LDS for the network output.
 __device__ __forceinline__ void group_train(const float* __restrict__ images,
                                             const int32_t* __restrict__ labels, int B,
                                             const float* __restrict__ tabg, float* __restrict__ out,
-                                            OperandTable<TAB_TRAIN_ENTRIES>& tab, TrainLds& s, float* ybuf) {
+                                            OperandTable<TAB_TRAIN_ENTRIES>& tab, TrainLds& s, float* d_s1b,
+                                            float* ybuf) {
   const int t = threadIdx.x, wave = t >> 6, l = t & 63, q = l >> 4, n16 = l & 15, b = l >> 2, sub = l & 3;
   const int pp = 12 * ((n16 & 3) >> 1) + 2 * (n16 >> 2) + (n16 & 1);
   const float* tl = tab.e + l;
@@ -119,16 +130,19 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
 
   f4 px = reinterpret_cast<const f4*>(images + (size_t)(blockIdx.x < (unsigned)B ? blockIdx.x : 0) * NI)[pix];
   int label_next = labels[blockIdx.x < (unsigned)B ? blockIdx.x : 0];  // in flight during the set-up too
-  TableLoad<kTrain> table;
+  TableLoad<kTrain, 64 * GWAVES> table;
   table.fetch(tabg);
   // every LDS cell that padded GEMM steps may read starts finite (the image area is written by the
   // loop itself before its first barrier, so it is left alone here)
-  for (int e = t; e < NS1 / 4; e += 64 * WAVES) reinterpret_cast<f4*>(s.d_s1)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-  for (int e = t; e < POOL_FLOATS / 4; e += 64 * WAVES) reinterpret_cast<f4*>(s.pool)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+  for (int e = t; e < D_S1B_FLOATS / 4; e += 64 * GWAVES) {
+    if (e < NS1 / 4) reinterpret_cast<f4*>(s.d_s1)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    reinterpret_cast<f4*>(d_s1b)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+  }
+  for (int e = t; e < POOL_FLOATS / 4; e += 64 * GWAVES) reinterpret_cast<f4*>(s.pool)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
   GroupState st;
 #pragma unroll
-  for (int k = 0; k < 3; ++k) {
-    const int g = wave + 4 * k < 9 ? wave + 4 * k : 8, win = 16 * g + b;
+  for (int k = 0; k < 2; ++k) {
+    const int g = wave + GWAVES * k < 9 ? wave + GWAVES * k : 8, win = 16 * g + b;
     st.pix0[k] = 2 * (win / 12) * 28 + 2 * (win % 12);
     st.d1off[k] = (2 * (win / 12) + ((l >> 1) & 1)) * 24 + 2 * (win % 12) + (l & 1);
   }
@@ -164,17 +178,17 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     st.bias2 = tab.bias[n16];
 
     // ---- C1 forward + S1 for this wave's pixel groups --------------------------------------------
-    float c1[3][6];
+    float c1[2][6];
     if (wave == 0)
-      group_c1_forward<3>(st, s, tab, wave, c1);
-    else
       group_c1_forward<2>(st, s, tab, wave, c1);
+    else
+      group_c1_forward<1>(st, s, tab, wave, c1);
     CNN_GROUP_MARK(3);
     __syncthreads();  // (2) S1 complete
 
-    // ---- C2 forward for pixel tile mt = wave, S2 ---------------------------------------------------
+    // ---- C2 forward for pixel tile mt = wave, S2 (waves 0..3); the others clear the col2im targets ---
     f4 c2v = f4{st.bias2, st.bias2, st.bias2, st.bias2};
-    {
+    if (wave < 4) {
       const float* a12 = s.pool + P_S1 + pp + 12 * q + 24 * wave;
       const float* a1 = s.pool + P_S1 + pp + q + 24 * wave;
       const float* a144 = s.pool + P_S1 + pp + 144 * q + 24 * wave;
@@ -194,17 +208,22 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
 #pragma unroll
       for (int r = 0; r < 4; ++r) c2v[r] = logistic(c2v[r]);
       if (n16 < 12) s.pool[P_S2 + n16 * 16 + 4 * wave + q] = 0.25f * ((c2v[0] + c2v[1]) + (c2v[2] + c2v[3]));
+    } else {
+      for (int e = t - 256; e < NS1 / 4; e += 256) {
+        reinterpret_cast<f4*>(s.d_s1)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+        reinterpret_cast<f4*>(d_s1b)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+      }
     }
     CNN_GROUP_MARK(4);
-    __syncthreads();  // (3) S2 complete
+    __syncthreads();  // (3) S2 complete, col2im targets cleared
 
-    // ---- output layer: this wave's outputs; then everybody reads all ten -----------------------------
+    // ---- output layer: this wave's outputs o = wave, wave + 8 -----------------------------------------
     float sv[3];
 #pragma unroll
     for (int k = 0; k < 3; ++k) sv[k] = s.pool[P_S2 + l + 64 * k];
 #pragma unroll
-    for (int j = 0; j < 3; ++j) {
-      const int o = wave + 4 * j;  // wave-uniform
+    for (int j = 0; j < 2; ++j) {
+      const int o = wave + GWAVES * j;  // wave-uniform
       if (o < NY) {
         float p = tl[(TAB_FCW + 3 * o) * 64] * sv[0];
         p = fmaf(tl[(TAB_FCW + 3 * o + 1) * 64], sv[1], p);
@@ -213,70 +232,67 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
         if (l == 0) ybuf[o] = yo;
       }
     }
-    // wave 3 clears the col2im target while the others finish
-    if (wave == 3)
-      for (int e = l; e < NS1 / 4; e += 64) reinterpret_cast<f4*>(s.d_s1)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
     CNN_GROUP_MARK(5);
     __syncthreads();  // (4) yhat complete
-    float delta[10];
-    {
-      float lsum = 0.0f;
+    if (wave < 4) {
+      float delta[10];
+      {
+        float lsum = 0.0f;
 #pragma unroll
-      for (int o = 0; o < 10; ++o) {
-        const float yo = ybuf[o];
-        const float e = yo - (o == label ? 1.0f : 0.0f);
-        lsum = fmaf(e, e, lsum);
-        delta[o] = e * yo * (1.0f - yo);
+        for (int o = 0; o < 10; ++o) {
+          const float yo = ybuf[o];
+          const float e = yo - (o == label ? 1.0f : 0.0f);
+          lsum = fmaf(e, e, lsum);
+          delta[o] = e * yo * (1.0f - yo);
+        }
+        if (wave == 0) st.loss = fmaf(0.5f, lsum, st.loss);
       }
-      if (wave == 0) st.loss = fmaf(0.5f, lsum, st.loss);
-    }
-    if (wave < 3) {  // FC backweights / backbias, row tile mt = wave
-      float d[4];
+      if (wave < 3) {  // FC backweights / backbias, row tile mt = wave
+        float d[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        float v = 0.0f;
+        for (int r = 0; r < 4; ++r) {
+          float v = 0.0f;
 #pragma unroll
-        for (int mt = 0; mt < 3; ++mt)
-          if (4 * mt + r < 10) v = wave == mt ? delta[4 * mt + r] : v;
-        d[r] = v;
+          for (int mt = 0; mt < 3; ++mt)
+            if (4 * mt + r < 10) v = wave == mt ? delta[4 * mt + r] : v;
+          d[r] = v;
+        }
+        const float aq = (sub & 2) ? ((sub & 1) ? d[3] : d[2]) : ((sub & 1) ? d[1] : d[0]);
+        st.g_bq += aq;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) st.acc_fc[k] = mfma4(aq, sv[k], st.acc_fc[k]);
       }
-      const float aq = (sub & 2) ? ((sub & 1) ? d[3] : d[2]) : ((sub & 1) ? d[1] : d[0]);
-      st.g_bq += aq;
+      // ---- error at C2 for this wave's tile: the lane's own element of the error at S2,
+      //      d_s2[i] = sum_o fc[o][i] delta[o] with i = 16 n16 + 4 wave + q, then backavgpool and sigmoid' --
+      {
+        const int i = n16 * 16 + 4 * wave + q;
+        const float* fcw = tab.e + (TAB_FCW + (i >> 6)) * 64 + (i & 63);
+        float up = 0.0f;
 #pragma unroll
-      for (int k = 0; k < 3; ++k) st.acc_fc[k] = mfma4(aq, sv[k], st.acc_fc[k]);
-    }
-    // error at S2 (every wave computes and writes all of it: identical values, no barrier needed)
+        for (int o = 0; o < 10; ++o) up = fmaf(fcw[3 * o * 64], delta[o], up);
+        up *= 0.25f;
+        f4 d2v;
 #pragma unroll
-    for (int k = 0; k < 3; ++k) {
-      float d = 0.0f;
-#pragma unroll
-      for (int o = 0; o < 10; ++o) d = fmaf(tl[(TAB_FCW + 3 * o + k) * 64], delta[o], d);
-      s.pool[P_DS2 + l + 64 * k] = d;
-    }
-    wave_sync();
-    // ---- error at C2 for this wave's tile -----------------------------------------------------------
-    {
-      const float up = s.pool[P_DS2 + n16 * 16 + 4 * wave + q] * 0.25f;
-      f4 d2v;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) d2v[r] = up * c2v[r] * (1.0f - c2v[r]);
-      *reinterpret_cast<f4*>(&s.pool[P_D2 + n16 * D2S + 16 * wave + 4 * q]) = d2v;
-      st.g_b2 += (d2v[0] + d2v[1]) + (d2v[2] + d2v[3]);
+        for (int r = 0; r < 4; ++r) d2v[r] = n16 < 12 ? up * c2v[r] * (1.0f - c2v[r]) : 0.0f;
+        *reinterpret_cast<f4*>(&s.pool[P_D2 + n16 * D2S + 16 * wave + 4 * q]) = d2v;
+        st.g_b2 += (d2v[0] + d2v[1]) + (d2v[2] + d2v[3]);
+      }
     }
     CNN_GROUP_MARK(6);
-    __syncthreads();  // (5) d_c2 complete, d_s1 cleared
+    __syncthreads();  // (5) d_c2 complete
 
-    if (wave < 2) {
-      // ---- C2 input error for input maps 4 wave .. 4 wave + 3 (col2im rounds of cnn_wave.h) ---------
-      const int cg = wave;
-      float bd[3][4];
+    if (wave < 4) {
+      // ---- C2 input error for input maps 4 cg .. 4 cg + 3 from the pixel tiles nt = 2 h, 2 h + 1
+      //      (col2im rounds of cnn_wave.h restricted to those tiles: levels 4 h .. 4 h + 6) ---------------
+      const int cg = wave & 1, h = wave >> 1;
+      float bd[3][2];
 #pragma unroll
       for (int sidx = 0; sidx < 3; ++sidx)
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) bd[sidx][nt] = s.pool[P_D2 + (4 * sidx + q) * D2S + 16 * nt + n16];
+        for (int j = 0; j < 2; ++j) bd[sidx][j] = s.pool[P_D2 + (4 * sidx + q) * D2S + 16 * (2 * h + j) + n16];
       const float* ta = tl + (TAB_AB + cg * 21) * 64;
-      f4 t4[4];
-      float t44[4];
+      f4 t4[2];
+      float t44[2];
       {
         float au[3], ac[3];
 #pragma unroll
@@ -285,65 +301,55 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
           ac[sidx] = ta[(kTileC * 3 + sidx) * 64];
         }
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
+        for (int j = 0; j < 2; ++j) {
           f4 a = f4{0.0f, 0.0f, 0.0f, 0.0f}, c = a;
 #pragma unroll
           for (int sidx = 0; sidx < 3; ++sidx) {
-            a = mfma16(au[sidx], bd[sidx][nt], a);
-            c = mfma16(ac[sidx], bd[sidx][nt], c);
+            a = mfma16(au[sidx], bd[sidx][j], a);
+            c = mfma16(ac[sidx], bd[sidx][j], c);
           }
-          t4[nt] = a;
-          t44[nt] = c[0];
+          t4[j] = a;
+          t44[j] = c[0];
         }
       }
-      float* tgt = s.d_s1 + 144 * q + pp + 576 * cg;
+      float* tgt = (h ? d_s1b : s.d_s1) + 144 * q + pp + 576 * cg + 48 * h;
 #pragma unroll
       for (int v = 0; v < 5; ++v) {
-        f4 tv[4];
+        f4 tv[2];
         {
           float av[3];
 #pragma unroll
           for (int sidx = 0; sidx < 3; ++sidx) av[sidx] = ta[((kTileV0 + v) * 3 + sidx) * 64];
 #pragma unroll
-          for (int nt = 0; nt < 4; ++nt) {
+          for (int j = 0; j < 2; ++j) {
             f4 a = f4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int sidx = 0; sidx < 3; ++sidx) a = mfma16(av[sidx], bd[sidx][nt], a);
-            tv[nt] = a;
+            for (int sidx = 0; sidx < 3; ++sidx) a = mfma16(av[sidx], bd[sidx][j], a);
+            tv[j] = a;
           }
         }
-        {
-          float e[6], old[6];
+        const float tu4[2] = {v < 4 ? t4[0][v < 4 ? v : 0] : t44[0], v < 4 ? t4[1][v < 4 ? v : 0] : t44[1]};
+        {  // even levels 2 (2 h + mm), mm < 4: (j = mm, u = 0) + (mm - 1, 2) + (mm - 2, 4)
+          const float e[4] = {tv[0][0], tv[1][0] + tv[0][2], tv[1][2] + tu4[0], tu4[1]};
+          float old[4];
 #pragma unroll
-          for (int m = 0; m < 6; ++m) {
-            float acc = 0.0f;
-            if (m < 4) acc = tv[m < 4 ? m : 0][0];
-            if (m >= 1 && m <= 4) acc += tv[m >= 1 ? m - 1 : 0][2];
-            if (m >= 2) acc += v < 4 ? t4[m >= 2 ? m - 2 : 0][v < 4 ? v : 0] : t44[m >= 2 ? m - 2 : 0];
-            e[m] = acc;
-            old[m] = tgt[24 * m + v];
-          }
+          for (int mm = 0; mm < 4; ++mm) old[mm] = tgt[24 * mm + v];
 #pragma unroll
-          for (int m = 0; m < 6; ++m) tgt[24 * m + v] = old[m] + e[m];
+          for (int mm = 0; mm < 4; ++mm) tgt[24 * mm + v] = old[mm] + e[mm];
         }
         wave_sync();
-        {
-          float e[5], old[5];
+        {  // odd levels 2 (2 h + mm) + 1, mm < 3: (j = mm, u = 1) + (mm - 1, 3)
+          const float e[3] = {tv[0][1], tv[1][1] + tv[0][3], tv[1][3]};
+          float old[3];
 #pragma unroll
-          for (int m = 0; m < 5; ++m) {
-            float acc = 0.0f;
-            if (m < 4) acc = tv[m < 4 ? m : 0][1];
-            if (m >= 1) acc += tv[m >= 1 ? m - 1 : 0][3];
-            e[m] = acc;
-            old[m] = tgt[24 * m + 12 + v];
-          }
+          for (int mm = 0; mm < 3; ++mm) old[mm] = tgt[24 * mm + 12 + v];
 #pragma unroll
-          for (int m = 0; m < 5; ++m) tgt[24 * m + 12 + v] = old[m] + e[m];
+          for (int mm = 0; mm < 3; ++mm) tgt[24 * mm + 12 + v] = old[mm] + e[mm];
         }
         wave_sync();
       }
-    } else {
-      // ---- C2 weight gradient over pixel tiles S = 2 (wave - 2), 2 (wave - 2) + 1 ---------------------
+    } else if (wave < 6) {
+      // ---- C2 weight gradient over pixel tiles S = 2 (wave - 4), 2 (wave - 4) + 1 ---------------------
       const float* bsrc[10];
 #pragma unroll
       for (int nt = 0; nt < 10; ++nt) {
@@ -353,10 +359,8 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
       }
 #pragma unroll
       for (int ss = 0; ss < 2; ++ss) {
-        const int S = 2 * (wave - 2) + ss;  // wave-uniform
+        const int S = 2 * (wave - 4) + ss;  // wave-uniform
         const f4 a = *reinterpret_cast<const f4*>(&s.pool[P_D2 + n16 * D2S + 16 * S + 4 * q]);
-        const float* bs0 = nullptr;
-        (void)bs0;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int imm = 12 * (r >> 1) + (r & 1);
@@ -366,26 +370,27 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
       }
     }
     CNN_GROUP_MARK(7);
-    __syncthreads();  // (6) d_s1 complete; s1, d_c2 no longer needed
+    __syncthreads();  // (6) both d_s1 copies complete; s1, d_c2 no longer needed
 
     // ---- C1 error for this wave's pixel groups, staged for everybody ----------------------------------
     if (wave == 0)
-      group_c1_error<3>(st, s, wave, c1);
+      group_c1_error<2>(st, s, d_s1b, wave, c1);
     else
-      group_c1_error<2>(st, s, wave, c1);
+      group_c1_error<1>(st, s, d_s1b, wave, c1);
     __syncthreads();  // (7) d1 complete
-    // ---- C1 weight gradient: this wave's quarter of the GEMM's K range (pixel rows 6 wave .. 6 wave + 5)
-    c1g_accumulate<C1G_STEPS / WAVES>(st.acc_k1, s.pool + 144 * wave, s.img + 168 * wave);
+    // ---- C1 weight gradient: this wave's eighth of the GEMM's K range (pixel rows 3 wave .. 3 wave + 2)
+    c1g_accumulate<C1G_STEPS / GWAVES>(st.acc_k1, s.pool + 72 * wave, s.img + 84 * wave);
     CNN_GROUP_MARK(8);
     __syncthreads();  // (8) the image and the staging area are free again
   }
 
   // ---- one partial row per workgroup: cross-wave sums through LDS in a fixed order -------------------
-  // The operand table is dead after the last image; its storage takes the parked values.
-  float* k1s = tab.e;                               // [4 waves][16][32]: parked C1 weight GEMM results
-  float* b1s = tab.e + WAVES * C1G_PARK;            // [4 waves][4 rows][8]: C1 bias row sums
-  float* b2s = b1s + 128;                           // [4 waves][64]: per-lane C2 bias sums
-  float* scr = b2s + 256;                           // [64 lanes][20]: half of a wave's C2 gradient tiles
+  // The operand table and the pool are dead after the last image; their storage takes the parked values.
+  float* k1s = tab.e;                               // [8 waves][16][32]: parked C1 weight GEMM results
+  float* b1s = tab.e + GWAVES * C1G_PARK;           // [8 waves][4 rows][8]: C1 bias row sums
+  float* b2s = b1s + 256;                           // [4 waves][64]: per-lane C2 bias sums
+  float* scr = s.pool;                              // [2][64 lanes][20]: half of a wave's C2 gradient tiles
+  static_assert(GWAVES * C1G_PARK + 256 + 256 <= TAB_TRAIN_ENTRIES * 64 && 2560 <= POOL_FLOATS, "flush scratch fits");
   c1g_park(st.acc_k1, k1s + wave * C1G_PARK);
   CNN_GROUP_MARK(11);
 #pragma unroll
@@ -397,27 +402,27 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     v += dpp_row_mirror(v);
     if (n16 == 0) b1s[(wave * 4 + q) * 8 + i] = v;
   }
-  b2s[wave * 64 + l] = st.g_b2;  // lane (q, j) of this wave's pixel tile
-  // waves 2 and 3 each hold half of the C2 weight gradient: wave 3 hands over tiles 0..4, wave 2 tiles 5..9
-  if (wave >= 2) {
+  if (wave < 4) b2s[wave * 64 + l] = st.g_b2;  // lane (q, j) of this wave's pixel tile
+  // waves 4 and 5 each hold half of the C2 weight gradient: wave 5 hands over tiles 0..4, wave 4 tiles 5..9
+  if (wave == 4 || wave == 5) {
 #pragma unroll
     for (int k = 0; k < 5; ++k)
-      *reinterpret_cast<f4*>(&scr[(wave - 2) * 1280 + l * 20 + 4 * k]) = st.acc_k2[wave == 3 ? k : 5 + k];
+      *reinterpret_cast<f4*>(&scr[(wave - 4) * 1280 + l * 20 + 4 * k]) = st.acc_k2[wave == 5 ? k : 5 + k];
   }
   CNN_GROUP_MARK(9);
   __syncthreads();
   CNN_GROUP_MARK(12);
-  if (wave >= 2) {
+  if (wave == 4 || wave == 5) {
 #pragma unroll
     for (int k = 0; k < 5; ++k) {
-      const int nt = wave == 2 ? k : 5 + k;
-      const f4 mine = st.acc_k2[wave == 2 ? k : 5 + k];
-      const f4 other = *reinterpret_cast<const f4*>(&scr[(3 - wave) * 1280 + l * 20 + 4 * k]);
+      const int nt = wave == 4 ? k : 5 + k;
+      const f4 mine = st.acc_k2[wave == 4 ? k : 5 + k];
+      const f4 other = *reinterpret_cast<const f4*>(&scr[(5 - wave) * 1280 + l * 20 + 4 * k]);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int j = 4 * q + r, tap = 16 * nt + n16;
-        // wave 2's share is always the left operand, so the sum does not depend on who adds
-        const float v = wave == 2 ? mine[r] + other[r] : other[r] + mine[r];
+        // wave 4's share is always the left operand, so the sum does not depend on who adds
+        const float v = wave == 4 ? mine[r] + other[r] : other[r] + mine[r];
         if (j < 12 && tap < 150) out[OFF_K2 + j * 150 + tap] = v;
       }
     }
@@ -433,25 +438,34 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     if (l < 4 && 4 * wave + l < 10) out[OFF_B + 4 * wave + l] = st.g_bq;
   }
   CNN_GROUP_MARK(13);
-  if (t < 150) {  // one thread per C1 weight: the four waves' shares of the GEMM, both shifted halves
-    out[OFF_K1 + t] = (c1g_combine(k1s, t) + c1g_combine(k1s + C1G_PARK, t)) +
-                      (c1g_combine(k1s + 2 * C1G_PARK, t) + c1g_combine(k1s + 3 * C1G_PARK, t));
-  } else if (t < 156) {
-    const int i = t - 150;
-    float x[16];
+  if (wave >= 6 || (wave == 3 && l >= 32)) {
+    // one thread per C1 weight (waves 6, 7 have nothing else to store; 22 lanes of wave 3 take the
+    // rest): the eight waves' shares of the GEMM, both shifted halves
+    const int e = wave >= 6 ? t - 384 : 96 + l;
+    if (e < 150) {
+      float x[GWAVES];
 #pragma unroll
-    for (int k = 0; k < 16; ++k) x[k] = b1s[k * 8 + i];
+      for (int k = 0; k < GWAVES; ++k) x[k] = c1g_combine(k1s + k * C1G_PARK, e);
+      out[OFF_K1 + e] = ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
+    }
+  }
+  if (wave == 3) {
+    if (l < 6) {  // C1 biases: 8 waves x 4 rows
+      float x[32];
 #pragma unroll
-    for (int k = 0; k < 16; k += 4) x[k] = (x[k] + x[k + 1]) + (x[k + 2] + x[k + 3]);
-    out[OFF_B1 + i] = (x[0] + x[4]) + (x[8] + x[12]);
-  } else if (t >= 192 && t < 204) {
-    const int j = t - 192;
-    float x[16];
+      for (int k = 0; k < 32; ++k) x[k] = b1s[k * 8 + l];
 #pragma unroll
-    for (int k = 0; k < 16; ++k) x[k] = b2s[k * 16 + j];
+      for (int k = 0; k < 32; k += 4) x[k] = (x[k] + x[k + 1]) + (x[k + 2] + x[k + 3]);
+      out[OFF_B1 + l] = ((x[0] + x[4]) + (x[8] + x[12])) + ((x[16] + x[20]) + (x[24] + x[28]));
+    } else if (l >= 16 && l < 28) {  // C2 biases: 4 waves x 4 lane quarters
+      const int j = l - 16;
+      float x[16];
 #pragma unroll
-    for (int k = 0; k < 16; k += 4) x[k] = (x[k] + x[k + 1]) + (x[k + 2] + x[k + 3]);
-    out[OFF_B2 + j] = (x[0] + x[4]) + (x[8] + x[12]);
+      for (int k = 0; k < 16; ++k) x[k] = b2s[k * 16 + j];
+#pragma unroll
+      for (int k = 0; k < 16; k += 4) x[k] = (x[k] + x[k + 1]) + (x[k + 2] + x[k + 3]);
+      out[OFF_B2 + j] = (x[0] + x[4]) + (x[8] + x[12]);
+    }
   }
   if (t == 0) out[LOSS_SLOT] = st.loss;
   CNN_GROUP_MARK(10);

@@ -214,11 +214,11 @@ constexpr int table_max_multiplicity() {
 
 // Copies the expanded table from global memory into the workgroup's LDS in two halves, so that a
 // kernel can do other set-up work while the loads are in flight: `fetch` issues all of a thread's
-// 16-byte loads, `commit` stores them to LDS.  All 256 threads take part and the caller follows the
-// commit with a workgroup barrier.
-template <int MODE>
+// 16-byte loads, `commit` stores them to LDS.  All THREADS threads of the workgroup take part and
+// the caller follows the commit with a workgroup barrier.
+template <int MODE, int THREADS = 64 * WAVES>
 struct TableLoad {
-  static constexpr int PIECES = LdsOf<MODE>::entries * 16, ROUNDS = (PIECES + 64 * WAVES - 1) / (64 * WAVES);
+  static constexpr int PIECES = LdsOf<MODE>::entries * 16, ROUNDS = (PIECES + THREADS - 1) / THREADS;
   static constexpr int TAIL = (K1T_FLOATS + TAB_BIAS_FLOATS) / 4;
   typedef OperandTable<LdsOf<MODE>::entries> Table;
   static_assert(offsetof(Table, bias) == offsetof(Table, k1t) + sizeof(float) * K1T_FLOATS,
@@ -229,7 +229,7 @@ struct TableLoad {
     const f4* src = reinterpret_cast<const f4*>(tabg);
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
-      const int i = r * 64 * WAVES + t;
+      const int i = r * THREADS + t;
       v[r] = src[i < PIECES ? i : 0];
     }
     tail = src[TABG_K1T / 4 + (t < TAIL ? t : 0)];
@@ -238,7 +238,7 @@ struct TableLoad {
     const int t = threadIdx.x;
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
-      const int i = r * 64 * WAVES + t;
+      const int i = r * THREADS + t;
       if (i < PIECES) reinterpret_cast<f4*>(tab.e)[i] = v[r];
     }
     if (t < TAIL) reinterpret_cast<f4*>(tab.k1t)[t] = tail;
