@@ -12,7 +12,8 @@
 //   C2 input error (col2im)      waves 0..3: input maps 4 cg .. 4 cg + 3, cg = wave % 2, and pixel tiles
 //                                nt = 2 h, 2 h + 1, h = wave / 2; half h adds into its own copy of d_s1,
 //                                so no two waves ever touch the same cell; the C1 error reads both copies
-//   C2 weight gradient           wave 4: pixels 0..31, wave 5: pixels 32..63
+//   C2 weight gradient           waves 4..7: tap tiles nt = 0-2, 3-5, 6-7, 8-9 over all 64 pixels (each wave
+//                                owns whole columns of the result, so nothing has to be added across waves)
 //
 // Phases that hand data between waves are separated by workgroup barriers (eight per image).
 #pragma once
@@ -26,15 +27,53 @@ constexpr int GWAVES = 8;  // waves per workgroup of the small-batch kernel
 // rewrite with themselves (+ 0.0), as they do behind the first target inside TrainLds.
 constexpr int D_S1B_FLOATS = NS1 + 304;
 
+// Tap tiles of the C2 weight gradient owned by wave 4 + i: first tile and count.
+__host__ __device__ constexpr int k2_first(int i) { return i < 2 ? 3 * i : 2 + 2 * i; }
+__host__ __device__ constexpr int k2_count(int i) { return i < 2 ? 3 : 2; }
+
 struct GroupState {
   int pix0[2];      // window origin of this lane in the wave's pixel groups g = wave + 8 k
   int d1off[2];     // this lane's pixel of those groups inside a 24x24 map
   float bias2;      // b2[n16]
-  f4 acc_k2[10];    // waves 4, 5: C2 weight gradient over their half of the pixels
+  f4 acc_k2[3];     // waves 4..7: C2 weight gradient tiles nt = k2_first(wave - 4) + k
   f4 acc_k1[2];     // C1 weight gradient GEMM over this wave's 9 steps, T[(m,sh)][c]
   f4 acc_fc[3];     // waves 0..2: FC weight gradient rows o = 4 wave + r, columns lane + 64 k
   float g_bq;       // waves 0..2: FC bias gradient b[4 wave + lane % 4]
   float g_b1[6], g_b2, loss;
+};
+
+// C1 weights for the small-batch kernel.  The 150 weights and 6 biases are wave-uniform; eight waves
+// fetching them as 64-lane LDS broadcasts (1 KB returned per 16-byte read) would keep the
+// workgroup's LDS return path busy for a few thousand cycles per image.  Instead every lane keeps
+// ten of them, wr[j] = value 16 j + lane % 16 of the list (tap-major: index 6 tap + map, then the
+// biases at 150..155), and a multiply reads its weight from lane IDX % 16 of the lane's own
+// 16-lane row through a DPP row broadcast.
+template <int N>
+__device__ __forceinline__ float dpp_row_bcast(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x150 + N, 0xF, 0xF, true));
+}
+template <int IDX>
+__device__ __forceinline__ float c1_weight(const float (&wr)[10]) {
+  return dpp_row_bcast<IDX & 15>(wr[IDX >> 4]);
+}
+template <int TAP, int NS>
+struct C1Taps {  // taps TAP .. 24 of the 5x5 kernel, all six maps
+  static __device__ __forceinline__ void run(float (&c1)[2][6], const float (&wr)[10], const float* const (&ip)[NS]) {
+    float x[NS];
+#pragma unroll
+    for (int k = 0; k < NS; ++k) x[k] = ip[k][(TAP / 5) * 28 + TAP % 5];
+    const float w[6] = {c1_weight<6 * TAP>(wr),     c1_weight<6 * TAP + 1>(wr), c1_weight<6 * TAP + 2>(wr),
+                        c1_weight<6 * TAP + 3>(wr), c1_weight<6 * TAP + 4>(wr), c1_weight<6 * TAP + 5>(wr)};
+#pragma unroll
+    for (int i = 0; i < 6; ++i)
+#pragma unroll
+      for (int k = 0; k < NS; ++k) c1[k][i] = fmaf(w[i], x[k], c1[k][i]);
+    C1Taps<TAP + 1, NS>::run(c1, wr, ip);
+  }
+};
+template <int NS>
+struct C1Taps<25, NS> {
+  static __device__ __forceinline__ void run(float (&)[2][6], const float (&)[10], const float* const (&)[NS]) {}
 };
 
 // C1 forward for NS pixel groups of this wave: returns the activations in c1[k][map].
@@ -42,35 +81,25 @@ template <int NS>
 __device__ __forceinline__ void group_c1_forward(const GroupState& st, TrainLds& s,
                                                  const OperandTable<TAB_TRAIN_ENTRIES>& tab, int wave,
                                                  float (&c1)[2][6]) {
-  const int l = threadIdx.x & 63, b = l >> 2, sub = l & 3;
+  const int l = threadIdx.x & 63, n16 = l & 15, b = l >> 2, sub = l & 3;
+  float wr[10];
+#pragma unroll
+  for (int j = 0; j < 10; ++j) {
+    const int idx = 16 * j + n16;  // k1t is [tap][8] with the biases in row 25
+    wr[j] = tab.k1t[idx < 150 ? (idx / 6) * 8 + idx % 6 : idx < 156 ? 25 * 8 + (idx - 150) : 0];
+  }
   const float* ip[NS];
+#pragma unroll
+  for (int k = 0; k < NS; ++k) ip[k] = s.img + st.pix0[k] + (sub >> 1) * 28 + (sub & 1);
   {
-    const f4 ba = *reinterpret_cast<const f4*>(&tab.k1t[25 * 8]);
-    const float2 bb = *reinterpret_cast<const float2*>(&tab.k1t[25 * 8 + 4]);
+    const float bias[6] = {c1_weight<150>(wr), c1_weight<151>(wr), c1_weight<152>(wr),
+                           c1_weight<153>(wr), c1_weight<154>(wr), c1_weight<155>(wr)};
 #pragma unroll
-    for (int k = 0; k < NS; ++k) {
-      ip[k] = s.img + st.pix0[k] + (sub >> 1) * 28 + (sub & 1);
-      c1[k][0] = ba[0]; c1[k][1] = ba[1]; c1[k][2] = ba[2]; c1[k][3] = ba[3];
-      c1[k][4] = bb.x;  c1[k][5] = bb.y;
-    }
+    for (int k = 0; k < NS; ++k)
+#pragma unroll
+      for (int i = 0; i < 6; ++i) c1[k][i] = bias[i];
   }
-#pragma unroll 1
-  for (int u = 0; u < 5; ++u) {
-    const float* ku = tab.k1t + u * 40;
-#pragma unroll
-    for (int v = 0; v < 5; ++v) {
-      const f4 wa = *reinterpret_cast<const f4*>(&ku[v * 8]);
-      const float2 wb = *reinterpret_cast<const float2*>(&ku[v * 8 + 4]);
-      const float wt[6] = {wa[0], wa[1], wa[2], wa[3], wb.x, wb.y};
-      float x[NS];
-#pragma unroll
-      for (int k = 0; k < NS; ++k) x[k] = ip[k][u * 28 + v];
-#pragma unroll
-      for (int i = 0; i < 6; ++i)
-#pragma unroll
-        for (int k = 0; k < NS; ++k) c1[k][i] = fmaf(wt[i], x[k], c1[k][i]);
-    }
-  }
+  C1Taps<0, NS>::run(c1, wr, ip);
   // sigmoid and S1 = avgpool(C1) by the quad butterfly of cnn_wave.h
   const bool odd = sub & 1, hi = sub & 2;
 #pragma unroll
@@ -147,7 +176,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     st.d1off[k] = (2 * (win / 12) + ((l >> 1) & 1)) * 24 + 2 * (win % 12) + (l & 1);
   }
 #pragma unroll
-  for (int nt = 0; nt < 10; ++nt) st.acc_k2[nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+  for (int k = 0; k < 3; ++k) st.acc_k2[k] = f4{0.0f, 0.0f, 0.0f, 0.0f};
   st.acc_k1[0] = st.acc_k1[1] = f4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
   for (int k = 0; k < 3; ++k) st.acc_fc[k] = f4{0.0f, 0.0f, 0.0f, 0.0f};
@@ -348,24 +377,25 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
         }
         wave_sync();
       }
-    } else if (wave < 6) {
-      // ---- C2 weight gradient over pixel tiles S = 2 (wave - 4), 2 (wave - 4) + 1 ---------------------
-      const float* bsrc[10];
+    } else {
+      // ---- C2 weight gradient: this wave's tap tiles over all four pixel tiles ---------------------------
+      const int first = k2_first(wave - 4), count = k2_count(wave - 4);  // wave-uniform
+      const float* bsrc[3];
 #pragma unroll
-      for (int nt = 0; nt < 10; ++nt) {
-        const int tap = 16 * nt + n16;
+      for (int k = 0; k < 3; ++k) {
+        const int tap = 16 * (first + (k < count ? k : 0)) + n16;
         const int c = tap / 25, rem = tap - 25 * c, u = rem / 5, v = rem - 5 * u;
-        bsrc[nt] = s.pool + P_S1 + (tap < 150 ? c * 144 + u * 12 + v : 0) + 2 * q;
+        bsrc[k] = s.pool + P_S1 + (tap < 150 ? c * 144 + u * 12 + v : 0) + 2 * q;
       }
 #pragma unroll
-      for (int ss = 0; ss < 2; ++ss) {
-        const int S = 2 * (wave - 4) + ss;  // wave-uniform
+      for (int S = 0; S < 4; ++S) {
         const f4 a = *reinterpret_cast<const f4*>(&s.pool[P_D2 + n16 * D2S + 16 * S + 4 * q]);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int imm = 12 * (r >> 1) + (r & 1);
-#pragma unroll
-          for (int nt = 0; nt < 10; ++nt) st.acc_k2[nt] = mfma16(a[r], bsrc[nt][24 * S + imm], st.acc_k2[nt]);
+          st.acc_k2[0] = mfma16(a[r], bsrc[0][24 * S + imm], st.acc_k2[0]);
+          st.acc_k2[1] = mfma16(a[r], bsrc[1][24 * S + imm], st.acc_k2[1]);
+          if (count == 3) st.acc_k2[2] = mfma16(a[r], bsrc[2][24 * S + imm], st.acc_k2[2]);
         }
       }
     }
@@ -385,12 +415,11 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
   }
 
   // ---- one partial row per workgroup: cross-wave sums through LDS in a fixed order -------------------
-  // The operand table and the pool are dead after the last image; their storage takes the parked values.
+  // The operand table is dead after the last image; its storage takes the parked values.
   float* k1s = tab.e;                               // [8 waves][16][32]: parked C1 weight GEMM results
   float* b1s = tab.e + GWAVES * C1G_PARK;           // [8 waves][4 rows][8]: C1 bias row sums
   float* b2s = b1s + 256;                           // [4 waves][64]: per-lane C2 bias sums
-  float* scr = s.pool;                              // [2][64 lanes][20]: half of a wave's C2 gradient tiles
-  static_assert(GWAVES * C1G_PARK + 256 + 256 <= TAB_TRAIN_ENTRIES * 64 && 2560 <= POOL_FLOATS, "flush scratch fits");
+  static_assert(GWAVES * C1G_PARK + 256 + 256 <= TAB_TRAIN_ENTRIES * 64, "flush scratch fits the table");
   c1g_park(st.acc_k1, k1s + wave * C1G_PARK);
   CNN_GROUP_MARK(11);
 #pragma unroll
@@ -403,29 +432,18 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     if (n16 == 0) b1s[(wave * 4 + q) * 8 + i] = v;
   }
   if (wave < 4) b2s[wave * 64 + l] = st.g_b2;  // lane (q, j) of this wave's pixel tile
-  // waves 4 and 5 each hold half of the C2 weight gradient: wave 5 hands over tiles 0..4, wave 4 tiles 5..9
-  if (wave == 4 || wave == 5) {
-#pragma unroll
-    for (int k = 0; k < 5; ++k)
-      *reinterpret_cast<f4*>(&scr[(wave - 4) * 1280 + l * 20 + 4 * k]) = st.acc_k2[wave == 5 ? k : 5 + k];
-  }
   CNN_GROUP_MARK(9);
   __syncthreads();
   CNN_GROUP_MARK(12);
-  if (wave == 4 || wave == 5) {
+  if (wave >= 4) {  // C2 weights: every wave stores the columns (tap tiles) it owns
+    const int first = k2_first(wave - 4), count = k2_count(wave - 4);
 #pragma unroll
-    for (int k = 0; k < 5; ++k) {
-      const int nt = wave == 4 ? k : 5 + k;
-      const f4 mine = st.acc_k2[wave == 4 ? k : 5 + k];
-      const f4 other = *reinterpret_cast<const f4*>(&scr[(5 - wave) * 1280 + l * 20 + 4 * k]);
+    for (int k = 0; k < 3; ++k)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int j = 4 * q + r, tap = 16 * nt + n16;
-        // wave 4's share is always the left operand, so the sum does not depend on who adds
-        const float v = wave == 4 ? mine[r] + other[r] : other[r] + mine[r];
-        if (j < 12 && tap < 150) out[OFF_K2 + j * 150 + tap] = v;
+        const int j = 4 * q + r, tap = 16 * (first + k) + n16;
+        if (k < count && j < 12 && tap < 150) out[OFF_K2 + j * 150 + tap] = st.acc_k2[k][r];
       }
-    }
   }
   if (wave < 3) {
 #pragma unroll
