@@ -42,14 +42,16 @@ typedef struct cnn_ctx cnn_ctx; /* opaque, host memory owned by the library */
 
 const char* cnn_strerror(int code);
 
-/* Device bytes cnn_init needs for batches of up to max_batch images
- * (weights, per-workgroup gradient partials, reduction scratch).  0 if max_batch < 1. */
+/* Device bytes cnn_init needs for batches of up to max_batch images (weights, their copy laid out
+ * as the kernels' matrix operands, per-workgroup gradient partials, reduction scratch).
+ * 0 if max_batch < 1. */
 size_t cnn_workspace_bytes(int max_batch);
 
 /* Creates a context over caller-owned device `workspace` (>= cnn_workspace_bytes(max_batch),
  * 256-byte aligned; must outlive the context) and copies the six parameter
  * arrays into it (device pointers; a NULL array means zeros, the usual start
- * for the biases).  All later calls on the context run on `hip_stream`. */
+ * for the biases).  All later calls on the context run on `hip_stream`.  Unlike the other calls,
+ * cnn_init also makes one small synchronous host-to-device copy (an index table). */
 int cnn_init(cnn_ctx** out, void* workspace, size_t workspace_bytes, int max_batch,
              const float* k1, const float* b1, const float* k2, const float* b2,
              const float* fc, const float* b, void* hip_stream);
