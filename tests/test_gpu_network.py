@@ -158,6 +158,28 @@ def test_epoch_call_matches_the_oracle_and_the_per_batch_calls():
         net.train_epoch(d_im, d_lb, 100, LR, torch.zeros(4, dtype=torch.float32, device=DEV))
 
 
+def test_operand_table_follows_the_weights_through_updates():
+    """The kernels read the weights from a copy laid out as matrix operands that the update kernel
+    patches in place.  After several steps (small-batch and large-batch kernels, biases moving too)
+    a context rebuilt from the current weights must give bitwise the same outputs and gradients."""
+    images, labels = inputs.make_batch(900, 41)
+    d_im, d_lb = dev(images), dev(labels)
+    net = binding.CNN(weights(biases=True), max_batch=600)
+    for first, size in ((0, 100), (100, 37), (137, 300), (437, 463)):   # 300 and 463 use the large-batch kernel
+        net.train_batch(d_im[first:first + size], d_lb[first:first + size], LR)
+    fresh = binding.CNN({k: host(v) for k, v in net.get_weights().items()}, max_batch=600)
+    probe_im, probe_lb = d_im[:600], d_lb[:600]
+    assert np.array_equal(host(net.forward(probe_im)), host(fresh.forward(probe_im)))
+    for size in (64, 600):
+        g_a, l_a = net.gradient(probe_im[:size], probe_lb[:size])
+        g_b, l_b = fresh.gradient(probe_im[:size], probe_lb[:size])
+        assert np.array_equal(host(g_a), host(g_b)) and np.array_equal(host(l_a), host(l_b))
+    # and set_weights rebuilds it too
+    net.set_weights(weights(seed=77))
+    ref = binding.CNN(weights(seed=77), max_batch=600)
+    assert np.array_equal(host(net.forward(probe_im)), host(ref.forward(probe_im)))
+
+
 def test_step_is_bitwise_reproducible_and_zero_rate_is_identity():
     images, labels = inputs.make_batch(300, 26)
     w = weights(biases=True)
