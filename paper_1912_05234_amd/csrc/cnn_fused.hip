@@ -301,7 +301,7 @@ int run_forward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B,
 int run_backward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B, float scale,
                  float* grad_out, float* loss_sum) {
   const bool grouped = B <= GROUP_MAX_BATCH;
-  const int blocks = grouped ? (B < ctx->gcap ? B : ctx->gcap) : blocks_for(ctx, B, false);
+  const int blocks = grouped ? B : blocks_for(ctx, B, false);  // small batches: one workgroup per image
   const int G = blocks;  // one partial row per workgroup in both kernels
   const bool timed = (size_t)(2 * ctx->ev_used + 1) < ctx->ev.size();
   if (timed) CNN_HIP_TRY(hipEventRecord(ctx->ev[2 * ctx->ev_used], ctx->stream));

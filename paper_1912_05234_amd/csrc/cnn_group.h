@@ -6,7 +6,7 @@
 //
 //   C1 forward and C1 error      pixel group g = wave (wave 0 also takes group 8)
 //   C1 weight gradient           GEMM steps 9 wave .. 9 wave + 8 (pixel rows 3 wave .. 3 wave + 2)
-//   C2 forward, C2 error         waves 0..3: pixel tile mt = wave (waves 4..7 clear the col2im targets)
+//   C2 forward, C2 error         waves 0..3: pixel tile mt = wave
 //   output layer                 outputs o = wave and wave + 8
 //   FC weight gradient           waves 0..2 take the three 4-output row tiles
 //   C2 input error (col2im)      waves 0..3: input maps 4 cg .. 4 cg + 3, cg = wave % 2, and pixel tiles
@@ -15,7 +15,8 @@
 //   C2 weight gradient           waves 4..7: tap tiles nt = 0-2, 3-5, 6-7, 8-9 over all 64 pixels (each wave
 //                                owns whole columns of the result, so nothing has to be added across waves)
 //
-// Phases that hand data between waves are separated by workgroup barriers (eight per image).
+// Phases that hand data between waves are separated by workgroup barriers (eight).  A workgroup
+// handles exactly one image: the grid is one workgroup per image of the batch.
 #pragma once
 
 #include "cnn_wave.h"
@@ -143,7 +144,7 @@ __device__ __forceinline__ void group_c1_error(GroupState& st, TrainLds& s, cons
   }
 }
 
-// The whole step for the workgroup's images n = blockIdx.x, blockIdx.x + gridDim.x, ...; one
+// The whole step for the workgroup's image n = blockIdx.x (the grid is one workgroup per image); one
 // partial row per workgroup.  `d_s1b` is the second col2im target (D_S1B_FLOATS floats), `ybuf` 16
 // floats of LDS for the network output.
 __device__ __forceinline__ void group_train(const float* __restrict__ images,
@@ -158,11 +159,11 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
   CNN_GROUP_MARK(0);
 
   f4 px = reinterpret_cast<const f4*>(images + (size_t)(blockIdx.x < (unsigned)B ? blockIdx.x : 0) * NI)[pix];
-  int label_next = labels[blockIdx.x < (unsigned)B ? blockIdx.x : 0];  // in flight during the set-up too
+  const int label = labels[blockIdx.x < (unsigned)B ? blockIdx.x : 0];  // in flight during the set-up too
   TableLoad<kTrain, 64 * GWAVES> table;
   table.fetch(tabg);
-  // every LDS cell that padded GEMM steps may read starts finite (the image area is written by the
-  // loop itself before its first barrier, so it is left alone here)
+  // every LDS cell that padded GEMM steps may read starts finite, and both col2im targets start at
+  // zero (the image area is written below, before the first barrier, so it is left alone here)
   for (int e = t; e < D_S1B_FLOATS / 4; e += 64 * GWAVES) {
     if (e < NS1 / 4) reinterpret_cast<f4*>(s.d_s1)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
     reinterpret_cast<f4*>(d_s1b)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
@@ -186,24 +187,14 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
   st.g_b2 = 0.0f;
   st.loss = 0.0f;
   CNN_GROUP_MARK(1);
-  // The table is committed inside the first trip of the image loop: the loop's lane-invariant
-  // address arithmetic, which the compiler hoists in front of the loop, then runs while the
-  // table's loads are still in flight.  Barrier (1) of that trip also publishes the table.
-  bool first = true;
-
-  for (size_t n = blockIdx.x; n < (size_t)B; n += gridDim.x) {
-    const int label = label_next;
-    if (first) {
-      table.commit(tab);
-      first = false;
-    }
+  // The lane-invariant address arithmetic of the phases below is independent of the table, so the
+  // compiler is free to run it while the table's loads are still in flight; barrier (1) publishes
+  // the table together with the image.
+  {
+    table.commit(tab);
     if (t < NI / 4) reinterpret_cast<f4*>(s.img)[t] = px;
     CNN_GROUP_MARK(2);
-    __syncthreads();  // (1) image in LDS
-    if (n + gridDim.x < (size_t)B) {
-      px = reinterpret_cast<const f4*>(images + (n + gridDim.x) * NI)[pix];
-      label_next = labels[n + gridDim.x];
-    }
+    __syncthreads();  // (1) image and operand table in LDS
     st.bias2 = tab.bias[n16];
 
     // ---- C1 forward + S1 for this wave's pixel groups --------------------------------------------
@@ -215,7 +206,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     CNN_GROUP_MARK(3);
     __syncthreads();  // (2) S1 complete
 
-    // ---- C2 forward for pixel tile mt = wave, S2 (waves 0..3); the others clear the col2im targets ---
+    // ---- C2 forward for pixel tile mt = wave, S2 (waves 0..3) -----------------------------------------
     f4 c2v = f4{st.bias2, st.bias2, st.bias2, st.bias2};
     if (wave < 4) {
       const float* a12 = s.pool + P_S1 + pp + 12 * q + 24 * wave;
@@ -237,14 +228,9 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
 #pragma unroll
       for (int r = 0; r < 4; ++r) c2v[r] = logistic(c2v[r]);
       if (n16 < 12) s.pool[P_S2 + n16 * 16 + 4 * wave + q] = 0.25f * ((c2v[0] + c2v[1]) + (c2v[2] + c2v[3]));
-    } else {
-      for (int e = t - 256; e < NS1 / 4; e += 256) {
-        reinterpret_cast<f4*>(s.d_s1)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-        reinterpret_cast<f4*>(d_s1b)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-      }
     }
     CNN_GROUP_MARK(4);
-    __syncthreads();  // (3) S2 complete, col2im targets cleared
+    __syncthreads();  // (3) S2 complete
 
     // ---- output layer: this wave's outputs o = wave, wave + 8 -----------------------------------------
     float sv[3];
@@ -411,11 +397,11 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     // ---- C1 weight gradient: this wave's eighth of the GEMM's K range (pixel rows 3 wave .. 3 wave + 2)
     c1g_accumulate<C1G_STEPS / GWAVES>(st.acc_k1, s.pool + 72 * wave, s.img + 84 * wave);
     CNN_GROUP_MARK(8);
-    __syncthreads();  // (8) the image and the staging area are free again
+    __syncthreads();  // (8) every wave is done with the operand table and the pool
   }
 
   // ---- one partial row per workgroup: cross-wave sums through LDS in a fixed order -------------------
-  // The operand table is dead after the last image; its storage takes the parked values.
+  // The operand table is dead now; its storage takes the parked values.
   float* k1s = tab.e;                               // [8 waves][16][32]: parked C1 weight GEMM results
   float* b1s = tab.e + GWAVES * C1G_PARK;           // [8 waves][4 rows][8]: C1 bias row sums
   float* b2s = b1s + 256;                           // [4 waves][64]: per-lane C2 bias sums
