@@ -162,7 +162,7 @@ __global__ __launch_bounds__(256) void expand_kernel(const float* __restrict__ w
 // Adds the G partial rows in a fixed order (sixteen interleaved strands, each summed in row
 // order, then a fixed tree over the strands) and either applies  w <- w - scale * g  (grad_out ==
 // nullptr) or stores g.  An updated parameter is also written to its slots of the expanded operand
-// table, dest[p][0..1] (-1 = none).  One workgroup per 64 parameters; the lanes of a wave read 64
+// table, dest[p][0..3] (-1 = none).  One workgroup per 64 parameters; the lanes of a wave read 64
 // consecutive floats of a row, and a strand keeps eight row reads in flight.
 constexpr int RSTRANDS = 16;
 __global__ __launch_bounds__(64 * RSTRANDS) void reduce_update_kernel(const float* __restrict__ partial, int G,
@@ -176,11 +176,10 @@ __global__ __launch_bounds__(64 * RSTRANDS) void reduce_update_kernel(const floa
   const int p = blockIdx.x * 64 + lane;
   // what the update needs besides the sum is fetched first, so that it arrives during the reduction
   float w_old = 0.0f;
-  int d0 = -1, d1 = -1;
+  int4 d = int4{-1, -1, -1, -1};
   if (strand == 0 && !grad_out && p < NPARAM) {
     w_old = w[p];
-    d0 = dest[2 * p];
-    d1 = dest[2 * p + 1];
+    d = reinterpret_cast<const int4*>(dest)[p];
   }
   const float* src = partial + p;
   // eight row reads in flight per strand; a row index past G reads nothing and adds 0.0
@@ -212,8 +211,10 @@ __global__ __launch_bounds__(64 * RSTRANDS) void reduce_update_kernel(const floa
       } else {
         const float wn = fmaf(-scale, total, w_old);
         w[p] = wn;
-        if (d0 >= 0) tabg[d0] = wn;
-        if (d1 >= 0) tabg[d1] = wn;
+        if (d.x >= 0) tabg[d.x] = wn;
+        if (d.y >= 0) tabg[d.y] = wn;
+        if (d.z >= 0) tabg[d.z] = wn;
+        if (d.w >= 0) tabg[d.w] = wn;
       }
     } else if (p == LOSS_SLOT && loss_sum) {
       *loss_sum = total;
@@ -231,7 +232,7 @@ struct cnn_ctx {
   int fwd_gcap;  // cap on forward-only waves
   float* w;             // [PSTRIDE]
   float* tabg;          // [TABG_FLOATS]: the operand table expanded from w, kept in step with it
-  int32_t* dest;        // [PSTRIDE][2]: slots of tabg that hold parameter p
+  int32_t* dest;        // [PSTRIDE][TABLE_MAX_DEST]: slots of tabg that hold parameter p
   float* partial;       // [partial_rows_for(max_batch)][PSTRIDE]
   float* eval_partial;  // [gcap][2]
   std::vector<hipEvent_t> ev;  // 2 per recorded step (before, after the fused kernel)
@@ -266,7 +267,7 @@ inline Layout layout_for(int max_batch) {
   l.w = 0;
   l.tabg = align_up(l.w + sizeof(float) * PSTRIDE, 256);
   l.dest = align_up(l.tabg + sizeof(float) * TABG_FLOATS, 256);
-  l.partial = align_up(l.dest + sizeof(int32_t) * 2 * PSTRIDE, 256);
+  l.partial = align_up(l.dest + sizeof(int32_t) * TABLE_MAX_DEST * PSTRIDE, 256);
   l.eval_partial = align_up(l.partial + sizeof(float) * PSTRIDE * g, 256);
   l.total = align_up(l.eval_partial + sizeof(float) * 2 * (size_t)gcap_for(max_batch, FWD_GCAP), 256);
   return l;
@@ -380,11 +381,15 @@ int cnn_init(cnn_ctx** out, void* workspace, size_t workspace_bytes, int max_bat
   ctx->eval_partial = reinterpret_cast<float*>(base + l.eval_partial);
   {
     // inverse of table_source: where each parameter sits in the expanded table
-    static_assert(table_max_multiplicity() <= TABLE_MAX_DEST, "a parameter has at most two table slots");
-    std::vector<int32_t> dest(2 * PSTRIDE, -1);
+    static_assert(TABLE_MAX_DEST == 4 && table_max_multiplicity() <= TABLE_MAX_DEST,
+                  "the update kernel reads a parameter's table slots as one int4");
+    std::vector<int32_t> dest(TABLE_MAX_DEST * PSTRIDE, -1);
     for (int i = 0; i < TABG_FLOATS; ++i) {
       const int p = table_source(i);
-      if (p >= 0) dest[2 * p + (dest[2 * p] < 0 ? 0 : 1)] = i;
+      if (p < 0) continue;
+      int k = 0;
+      while (dest[TABLE_MAX_DEST * p + k] >= 0) ++k;  // < TABLE_MAX_DEST by the assertion above
+      dest[TABLE_MAX_DEST * p + k] = i;
     }
     // synchronous copy: the host vector may go away as soon as the call returns
     if (hipMemcpy(ctx->dest, dest.data(), sizeof(int32_t) * dest.size(), hipMemcpyHostToDevice) != hipSuccess ||

@@ -4,7 +4,7 @@
 // of a single image when there are too few images to give every SIMD its own.  Two waves per SIMD
 // because one wave alone issues a vector instruction only every ~5 cycles, two reach ~2.4.
 //
-//   C1 forward and C1 error      pixel group g = wave (wave 0 also takes group 8)
+//   C1 forward and C1 error      GEMM tiles T = wave, wave + 8 (waves 0, 1 also T = wave + 16), cnn_wave.h
 //   C1 weight gradient           GEMM steps 9 wave .. 9 wave + 8 (pixel rows 3 wave .. 3 wave + 2)
 //   C2 forward, C2 error         waves 0..3: pixel tile mt = wave
 //   output layer                 outputs o = wave and wave + 8
@@ -33,113 +33,55 @@ __host__ __device__ constexpr int k2_first(int i) { return i < 2 ? 3 * i : 2 + 2
 __host__ __device__ constexpr int k2_count(int i) { return i < 2 ? 3 : 2; }
 
 struct GroupState {
-  int pix0[2];      // window origin of this lane in the wave's pixel groups g = wave + 8 k
-  int d1off[2];     // this lane's pixel of those groups inside a 24x24 map
   float bias2;      // b2[n16]
   f4 acc_k2[3];     // waves 4..7: C2 weight gradient tiles nt = k2_first(wave - 4) + k
   f4 acc_k1[2];     // C1 weight gradient GEMM over this wave's 9 steps, T[(m,sh)][c]
   f4 acc_fc[3];     // waves 0..2: FC weight gradient rows o = 4 wave + r, columns lane + 64 k
   float g_bq;       // waves 0..2: FC bias gradient b[4 wave + lane % 4]
-  float g_b1[6], g_b2, loss;
+  float g_b1[2];    // C1 bias gradient of maps 2q, 2q + 1 over this lane's pixels
+  float g_b2, loss;
 };
 
-// C1 weights for the small-batch kernel.  The 150 weights and 6 biases are wave-uniform; eight waves
-// fetching them as 64-lane LDS broadcasts (1 KB returned per 16-byte read) would keep the
-// workgroup's LDS return path busy for a few thousand cycles per image.  Instead every lane keeps
-// ten of them, wr[j] = value 16 j + lane % 16 of the list (tap-major: index 6 tap + map, then the
-// biases at 150..155), and a multiply reads its weight from lane IDX % 16 of the lane's own
-// 16-lane row through a DPP row broadcast.
-template <int N>
-__device__ __forceinline__ float dpp_row_bcast(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x150 + N, 0xF, 0xF, true));
-}
-template <int IDX>
-__device__ __forceinline__ float c1_weight(const float (&wr)[10]) {
-  return dpp_row_bcast<IDX & 15>(wr[IDX >> 4]);
-}
-template <int TAP, int NS>
-struct C1Taps {  // taps TAP .. 24 of the 5x5 kernel, all six maps
-  static __device__ __forceinline__ void run(float (&c1)[2][6], const float (&wr)[10], const float* const (&ip)[NS]) {
-    float x[NS];
+// C1 forward + S1 for this wave's NT tiles T = wave + 8 k of the C1 GEMM (cnn_wave.h): returns the
+// activations in c1[k].  All MFMAs first (two independent chains at a time), then the sigmoids and
+// the pooling.
+template <int NT>
+__device__ __forceinline__ void group_c1_forward(TrainLds& s, const OperandTable<TAB_TRAIN_ENTRIES>& tab, int wave,
+                                                 const C1Lane& ln, f4 (&c1)[3]) {
+  const int l = threadIdx.x & 63, q = l >> 4;
+  float wa[C1F_KSTEPS];
 #pragma unroll
-    for (int k = 0; k < NS; ++k) x[k] = ip[k][(TAP / 5) * 28 + TAP % 5];
-    const float w[6] = {c1_weight<6 * TAP>(wr),     c1_weight<6 * TAP + 1>(wr), c1_weight<6 * TAP + 2>(wr),
-                        c1_weight<6 * TAP + 3>(wr), c1_weight<6 * TAP + 4>(wr), c1_weight<6 * TAP + 5>(wr)};
-#pragma unroll
-    for (int i = 0; i < 6; ++i)
-#pragma unroll
-      for (int k = 0; k < NS; ++k) c1[k][i] = fmaf(w[i], x[k], c1[k][i]);
-    C1Taps<TAP + 1, NS>::run(c1, wr, ip);
+  for (int ks = 0; ks < C1F_KSTEPS; ++ks) wa[ks] = tab.e[(TAB_C1A + ks) * 64 + l];
+  f4 binit = f4{0.0f, 0.0f, 0.0f, 0.0f};
+  if (q < 3) {
+    const float2 bq = *reinterpret_cast<const float2*>(&tab.bias[TAB_BIAS_B1 + 2 * q]);
+    binit = f4{bq.x, bq.x, bq.y, bq.y};
   }
-};
-template <int NS>
-struct C1Taps<25, NS> {
-  static __device__ __forceinline__ void run(float (&)[2][6], const float (&)[10], const float* const (&)[NS]) {}
-};
-
-// C1 forward for NS pixel groups of this wave: returns the activations in c1[k][map].
-template <int NS>
-__device__ __forceinline__ void group_c1_forward(const GroupState& st, TrainLds& s,
-                                                 const OperandTable<TAB_TRAIN_ENTRIES>& tab, int wave,
-                                                 float (&c1)[2][6]) {
-  const int l = threadIdx.x & 63, n16 = l & 15, b = l >> 2, sub = l & 3;
-  float wr[10];
+  c1f_gemm_pair(wa, ln, s.img + c1f_tile_img(wave), s.img + c1f_tile_img(wave + 8), binit, c1[0], c1[1]);
+  if (NT == 3) c1f_gemm_one(wa, ln, s.img + c1f_tile_img(wave + 16), binit, c1[2]);
 #pragma unroll
-  for (int j = 0; j < 10; ++j) {
-    const int idx = 16 * j + n16;  // k1t is [tap][8] with the biases in row 25
-    wr[j] = tab.k1t[idx < 150 ? (idx / 6) * 8 + idx % 6 : idx < 156 ? 25 * 8 + (idx - 150) : 0];
-  }
-  const float* ip[NS];
-#pragma unroll
-  for (int k = 0; k < NS; ++k) ip[k] = s.img + st.pix0[k] + (sub >> 1) * 28 + (sub & 1);
-  {
-    const float bias[6] = {c1_weight<150>(wr), c1_weight<151>(wr), c1_weight<152>(wr),
-                           c1_weight<153>(wr), c1_weight<154>(wr), c1_weight<155>(wr)};
-#pragma unroll
-    for (int k = 0; k < NS; ++k)
-#pragma unroll
-      for (int i = 0; i < 6; ++i) c1[k][i] = bias[i];
-  }
-  C1Taps<0, NS>::run(c1, wr, ip);
-  // sigmoid and S1 = avgpool(C1) by the quad butterfly of cnn_wave.h
-  const bool odd = sub & 1, hi = sub & 2;
-#pragma unroll
-  for (int k = 0; k < NS; ++k) {
-    const int g = wave + GWAVES * k;
-#pragma unroll
-    for (int i = 0; i < 6; ++i) c1[k][i] = logistic(c1[k][i]);
-    const float s01 = (odd ? c1[k][1] : c1[k][0]) + quad_xor1(odd ? c1[k][0] : c1[k][1]);
-    const float s23 = (odd ? c1[k][3] : c1[k][2]) + quad_xor1(odd ? c1[k][2] : c1[k][3]);
-    const float tot = (hi ? s23 : s01) + quad_xor2(hi ? s01 : s23);
-    s.pool[P_S1 + sub * 144 + 16 * g + b] = 0.25f * tot;
-  }
-  // maps 4, 5: lane sub -> map 4 + (sub & 1) of slot (sub & 2 ? last : first)
-  {
-    const int k0 = 0, k1 = NS - 1;
-    const float sa = (odd ? c1[k0][5] : c1[k0][4]) + quad_xor1(odd ? c1[k0][4] : c1[k0][5]);
-    const float sb = (odd ? c1[k1][5] : c1[k1][4]) + quad_xor1(odd ? c1[k1][4] : c1[k1][5]);
-    const float tot = (hi ? sb : sa) + quad_xor2(hi ? sa : sb);
-    s.pool[P_S1 + (4 + (sub & 1)) * 144 + 16 * (wave + GWAVES * (hi ? k1 : k0)) + b] = 0.25f * tot;
-  }
+  for (int k = 0; k < NT; ++k) c1f_finish(c1[k], ln, s.pool + P_S1 + c1f_tile_s1(wave + 8 * k));
 }
 
-// C1 error of this wave's NS pixel groups into the staged d1[6][24][24]; the error at S1 is the sum
-// of the two col2im copies.
-template <int NS>
+// C1 error of this wave's tiles into the staged d1[6][24][24]; the error at S1 is the sum of the two
+// col2im copies.  Lanes q = 3 hold padding rows.
+template <int NT>
 __device__ __forceinline__ void group_c1_error(GroupState& st, TrainLds& s, const float* d_s1b, int wave,
-                                               const float (&c1)[2][6]) {
-  const int l = threadIdx.x & 63, b = l >> 2;
+                                               const C1Lane& ln, const f4 (&c1)[3]) {
+  const int q = (threadIdx.x & 63) >> 4;
+  if (q < 3) {
 #pragma unroll
-  for (int k = 0; k < NS; ++k) {
-    const int g = wave + GWAVES * k;
-    float* dst = s.pool + st.d1off[k];
-#pragma unroll
-    for (int i = 0; i < 6; ++i) {
-      const float c = c1[k][i];
-      const float up = s.d_s1[i * 144 + 16 * g + b] + d_s1b[i * 144 + 16 * g + b];
-      const float d1 = up * 0.25f * c * (1.0f - c);
-      st.g_b1[i] += d1;
-      dst[i * 576] = d1;
+    for (int k = 0; k < NT; ++k) {
+      const int T = wave + 8 * k, o = ln.s1 + c1f_tile_s1(T);
+      const float up0 = (s.d_s1[o] + d_s1b[o]) * 0.25f, up1 = (s.d_s1[o + 144] + d_s1b[o + 144]) * 0.25f;
+      const f4 c = c1[k];
+      const float2 da = float2{up0 * c[0] * (1.0f - c[0]), up0 * c[1] * (1.0f - c[1])};
+      const float2 db = float2{up1 * c[2] * (1.0f - c[2]), up1 * c[3] * (1.0f - c[3])};
+      st.g_b1[0] += da.x + da.y;
+      st.g_b1[1] += db.x + db.y;
+      float* dst = s.pool + ln.c1 + c1f_tile_c1(T);
+      *reinterpret_cast<float2*>(dst) = da;
+      *reinterpret_cast<float2*>(dst + 576) = db;
     }
   }
 }
@@ -170,20 +112,14 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
   }
   for (int e = t; e < POOL_FLOATS / 4; e += 64 * GWAVES) reinterpret_cast<f4*>(s.pool)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
   GroupState st;
-#pragma unroll
-  for (int k = 0; k < 2; ++k) {
-    const int g = wave + GWAVES * k < 9 ? wave + GWAVES * k : 8, win = 16 * g + b;
-    st.pix0[k] = 2 * (win / 12) * 28 + 2 * (win % 12);
-    st.d1off[k] = (2 * (win / 12) + ((l >> 1) & 1)) * 24 + 2 * (win % 12) + (l & 1);
-  }
+  const C1Lane ln = c1f_lane();
 #pragma unroll
   for (int k = 0; k < 3; ++k) st.acc_k2[k] = f4{0.0f, 0.0f, 0.0f, 0.0f};
   st.acc_k1[0] = st.acc_k1[1] = f4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
   for (int k = 0; k < 3; ++k) st.acc_fc[k] = f4{0.0f, 0.0f, 0.0f, 0.0f};
   st.g_bq = 0.0f;
-#pragma unroll
-  for (int i = 0; i < 6; ++i) st.g_b1[i] = 0.0f;
+  st.g_b1[0] = st.g_b1[1] = 0.0f;
   st.g_b2 = 0.0f;
   st.loss = 0.0f;
   CNN_GROUP_MARK(1);
@@ -198,11 +134,11 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     st.bias2 = tab.bias[n16];
 
     // ---- C1 forward + S1 for this wave's pixel groups --------------------------------------------
-    float c1[2][6];
-    if (wave == 0)
-      group_c1_forward<2>(st, s, tab, wave, c1);
+    f4 c1[3];
+    if (wave < 2)
+      group_c1_forward<3>(s, tab, wave, ln, c1);
     else
-      group_c1_forward<1>(st, s, tab, wave, c1);
+      group_c1_forward<2>(s, tab, wave, ln, c1);
     CNN_GROUP_MARK(3);
     __syncthreads();  // (2) S1 complete
 
@@ -389,10 +325,10 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     __syncthreads();  // (6) both d_s1 copies complete; s1, d_c2 no longer needed
 
     // ---- C1 error for this wave's pixel groups, staged for everybody ----------------------------------
-    if (wave == 0)
-      group_c1_error<2>(st, s, d_s1b, wave, c1);
+    if (wave < 2)
+      group_c1_error<3>(st, s, d_s1b, wave, ln, c1);
     else
-      group_c1_error<1>(st, s, d_s1b, wave, c1);
+      group_c1_error<2>(st, s, d_s1b, wave, ln, c1);
     __syncthreads();  // (7) d1 complete
     // ---- C1 weight gradient: this wave's eighth of the GEMM's K range (pixel rows 3 wave .. 3 wave + 2)
     c1g_accumulate<C1G_STEPS / GWAVES>(st.acc_k1, s.pool + 72 * wave, s.img + 84 * wave);
@@ -403,19 +339,19 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
   // ---- one partial row per workgroup: cross-wave sums through LDS in a fixed order -------------------
   // The operand table is dead now; its storage takes the parked values.
   float* k1s = tab.e;                               // [8 waves][16][32]: parked C1 weight GEMM results
-  float* b1s = tab.e + GWAVES * C1G_PARK;           // [8 waves][4 rows][8]: C1 bias row sums
+  float* b1s = tab.e + GWAVES * C1G_PARK;           // [8 waves][8]: C1 bias sums (256 floats reserved)
   float* b2s = b1s + 256;                           // [4 waves][64]: per-lane C2 bias sums
   static_assert(GWAVES * C1G_PARK + 256 + 256 <= TAB_TRAIN_ENTRIES * 64, "flush scratch fits the table");
   c1g_park(st.acc_k1, k1s + wave * C1G_PARK);
   CNN_GROUP_MARK(11);
 #pragma unroll
-  for (int i = 0; i < 6; ++i) {
-    float v = st.g_b1[i];
+  for (int k = 0; k < 2; ++k) {  // C1 biases: lanes (q, .) hold maps 2q, 2q + 1
+    float v = st.g_b1[k];
     v += quad_xor1(v);
     v += quad_xor2(v);
     v += dpp_row_half_mirror(v);
     v += dpp_row_mirror(v);
-    if (n16 == 0) b1s[(wave * 4 + q) * 8 + i] = v;
+    if (n16 == 0 && q < 3) b1s[wave * 8 + 2 * q + k] = v;
   }
   if (wave < 4) b2s[wave * 64 + l] = st.g_b2;  // lane (q, j) of this wave's pixel tile
   CNN_GROUP_MARK(9);
@@ -454,13 +390,11 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     }
   }
   if (wave == 3) {
-    if (l < 6) {  // C1 biases: 8 waves x 4 rows
-      float x[32];
+    if (l < 6) {  // C1 biases: the eight waves' sums
+      float x[GWAVES];
 #pragma unroll
-      for (int k = 0; k < 32; ++k) x[k] = b1s[k * 8 + l];
-#pragma unroll
-      for (int k = 0; k < 32; k += 4) x[k] = (x[k] + x[k + 1]) + (x[k + 2] + x[k + 3]);
-      out[OFF_B1 + l] = ((x[0] + x[4]) + (x[8] + x[12])) + ((x[16] + x[20]) + (x[24] + x[28]));
+      for (int k = 0; k < GWAVES; ++k) x[k] = b1s[k * 8 + l];
+      out[OFF_B1 + l] = ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
     } else if (l >= 16 && l < 28) {  // C2 biases: 4 waves x 4 lane quarters
       const int j = l - 16;
       float x[16];

@@ -77,12 +77,14 @@ constexpr int TAB_BF = 0;          // 38: C2 forward B operand, k2[j = n16][tap(
 constexpr int TAB_FCW = 38;        // 30: fc[o][lane + 64 k] at entry 3 o + k
 constexpr int TAB_FWD_ENTRIES = 68;
 constexpr int TAB_AB = 68;         // 42: C2 input-error A operand, entry (cg*7 + tile)*3 + s
-constexpr int TAB_TRAIN_ENTRIES = 110;
+constexpr int TAB_C1A = 110;       // 8: C1 forward A operand of the small-batch kernel, W[(m,sh) = n16][tap 4 ks + q]
+constexpr int TAB_TRAIN_ENTRIES = 118;
 // After the [entry][lane] part: C1 weights by tap, k1t[tap][8] = k1[0..5][tap], 0, 0 for tap < 25 and
 // the biases b1 in row 25; every lane reads the same row (an LDS broadcast).
 constexpr int K1T_FLOATS = 26 * 8;
 // Last: the biases read per image, bias[0..11] = b2, bias[16..25] = b, zeros elsewhere.
 constexpr int TAB_BIAS_FLOATS = 32;
+constexpr int TAB_BIAS_B = 16, TAB_BIAS_B1 = 26;  // bias[16..25] = b, bias[26..31] = b1
 template <int ENTRIES>
 struct __align__(16) OperandTable {
   float e[ENTRIES * 64];
@@ -176,6 +178,96 @@ enum BwdTile { kTileV0 = 0, kTileU4 = 5, kTileC = 6 };  // V(v) = kTileV0 + v
 __host__ __device__ constexpr int bwd_tap(int tile, int ri) {
   return tile < 5 ? 5 * ri + tile : tile == kTileU4 ? 20 + ri : (ri == 0 ? 24 : -1);
 }
+// ---- C1 forward as a GEMM (16x16x4 MFMA) -----------------------------------------------------------
+// Output pixels are taken in horizontal pairs x = 2X + sh (sh = 0, 1).  With v' = v + sh the image
+// factor img[y+u][2X+v'] does not depend on sh:
+//   pre[(m,sh)][(y,X)] = b1[m] + sum_{u < 5, v' < 6} W[(m,sh)][(u,v')] * img[y+u][2X+v'],
+//   W[(m,sh)][(u,v')] = k1[m][u][v'-sh]  (zero where v'-sh is outside 0..4).
+// M = 12 rows (m,sh), i = 2m + sh, in one 16-row tile; K = 30 taps t = 6u + v' in 8 steps of four
+// (t = 4 ks + q); N = 288 pixel pairs in 18 tiles of 16.  Tile T = 3 ty + tx covers the 2 x 4 block of
+// pooling windows wy = 2 ty + a, wx = 4 tx + bx; column j = lane%16 = 4 bx + 2 a + dy is the pair
+// (y = 2 wy + dy, X = wx).  Lanes j and j^1 are the two rows of one window and a lane's result
+// registers of one map (sh = 0, 1) are its two columns, so avgpool is two adds and one DPP add.
+//   A[i = lane%16][k = q] = W[i][4 ks + q]      (rows 12..15 and taps 30, 31 are zero)
+//   B[k = q][j = lane%16] = img[y + u][2X + v']
+//   D[i = 4q + r][j]: map m = 2q + r/2, sh = r%2, in result register r (lanes q = 3 hold padding rows).
+constexpr int C1F_TILES = 18, C1F_KSTEPS = 8;
+__host__ __device__ constexpr int c1f_weight(int ks, int lane) {  // flat parameter index or -1
+  const int q = lane >> 4, i = lane & 15, t = 4 * ks + q;
+  if (t >= 30 || i >= 12) return -1;
+  const int u = t / 6, v = t % 6 - (i & 1);
+  return v >= 0 && v < 5 ? OFF_K1 + (i >> 1) * 25 + u * 5 + v : -1;
+}
+// Offsets (floats) that depend on the tile only: image, pooled [6][12][12] arrays, [6][24][24] arrays.
+__host__ __device__ constexpr int c1f_tile_img(int T) { return (T / 3) * 112 + (T % 3) * 8; }
+__host__ __device__ constexpr int c1f_tile_s1(int T) { return (T / 3) * 24 + (T % 3) * 4; }
+__host__ __device__ constexpr int c1f_tile_c1(int T) { return (T / 3) * 96 + (T % 3) * 8; }
+// Offsets that depend on the lane only.
+struct C1Lane {
+  int img[C1F_KSTEPS];  // B operand of K step ks
+  int s1;               // map 2q of a pooled array (map 2q + 1 is 144 further)
+  int c1;               // map 2q, sh = 0 of a [6][24][24] array (map 2q + 1 is 576 further)
+};
+__device__ __forceinline__ C1Lane c1f_lane() {
+  const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
+  const int dy = n16 & 1, a = (n16 >> 1) & 1, bx = n16 >> 2;
+  C1Lane o;
+#pragma unroll
+  for (int ks = 0; ks < C1F_KSTEPS; ++ks) {
+    const int t = 4 * ks + q, tt = t < 30 ? t : 0;
+    o.img[ks] = (2 * a + dy + tt / 6) * 28 + 2 * bx + tt % 6;
+  }
+  o.s1 = 2 * q * 144 + a * 12 + bx;
+  o.c1 = 2 * q * 576 + (2 * a + dy) * 24 + 2 * bx;
+  return o;
+}
+// Pre-activations of two tiles at once (two independent accumulation chains); img0 / img1 point at
+// the tiles' origins in the image.  The B operand of step ks + 1 is read while step ks issues.
+__device__ __forceinline__ void c1f_gemm_pair(const float (&wa)[C1F_KSTEPS], const C1Lane& ln, const float* img0,
+                                              const float* img1, f4 binit, f4& d0, f4& d1) {
+  d0 = binit;
+  d1 = binit;
+  float x0[3], x1[3];
+  x0[0] = img0[ln.img[0]];
+  x1[0] = img1[ln.img[0]];
+  x0[1] = img0[ln.img[1]];
+  x1[1] = img1[ln.img[1]];
+#pragma unroll
+  for (int ks = 0; ks < C1F_KSTEPS; ++ks) {
+    if (ks + 2 < C1F_KSTEPS) {
+      x0[(ks + 2) % 3] = img0[ln.img[ks + 2]];
+      x1[(ks + 2) % 3] = img1[ln.img[ks + 2]];
+    }
+    d0 = mfma16(wa[ks], x0[ks % 3], d0);
+    d1 = mfma16(wa[ks], x1[ks % 3], d1);
+  }
+}
+// The same for a single tile (one chain).
+__device__ __forceinline__ void c1f_gemm_one(const float (&wa)[C1F_KSTEPS], const C1Lane& ln, const float* img0,
+                                             f4 binit, f4& d0) {
+  d0 = binit;
+  float x0[3];
+  x0[0] = img0[ln.img[0]];
+  x0[1] = img0[ln.img[1]];
+#pragma unroll
+  for (int ks = 0; ks < C1F_KSTEPS; ++ks) {
+    if (ks + 2 < C1F_KSTEPS) x0[(ks + 2) % 3] = img0[ln.img[ks + 2]];
+    d0 = mfma16(wa[ks], x0[ks % 3], d0);
+  }
+}
+// sigmoid in place, then S1 = avgpool for the tile's windows: s1 points at the tile's origin in the
+// pooled array.  Lanes j and j^1 store the same value to the same cell; the padding rows of lanes
+// q = 3 land in the (finite, never used) cells behind the sixth map.
+__device__ __forceinline__ void c1f_finish(f4& d, const C1Lane& ln, float* s1) {
+#pragma unroll
+  for (int r = 0; r < 4; ++r) d[r] = logistic(d[r]);
+  float p0 = d[0] + d[1], p1 = d[2] + d[3];
+  p0 += quad_xor1(p0);
+  p1 += quad_xor1(p1);
+  s1[ln.s1] = 0.25f * p0;
+  s1[ln.s1 + 144] = 0.25f * p1;
+}
+
 // Flat parameter index whose value slot i of the expanded table holds, or -1 for a zero.
 __host__ __device__ constexpr int table_source(int i) {
   if (i < TABG_K1T) {
@@ -188,6 +280,7 @@ __host__ __device__ constexpr int table_source(int i) {
       const int o = (e - TAB_FCW) / 3, k = (e - TAB_FCW) % 3;
       return OFF_FC + o * NS2 + l + 64 * k;
     }
+    if (e >= TAB_C1A) return c1f_weight(e - TAB_C1A, l);
     const int t = e - TAB_AB, sidx = t % 3, tile = (t / 3) % 7, cg = t / 21;
     const int c = 4 * cg + (n16 >> 2), tap = bwd_tap(tile, n16 & 3);
     return c < 6 && tap >= 0 ? OFF_K2 + (4 * sidx + q) * 150 + c * 25 + tap : -1;
@@ -197,11 +290,13 @@ __host__ __device__ constexpr int table_source(int i) {
     return m < 6 ? (tap < 25 ? OFF_K1 + m * 25 + tap : OFF_B1 + m) : -1;
   }
   const int k = i - TABG_BIAS;
-  return k < 12 ? OFF_B2 + k : (k >= 16 && k < 16 + NY ? OFF_B + (k - 16) : -1);
+  return k < 12 ? OFF_B2 + k
+                : k >= TAB_BIAS_B && k < TAB_BIAS_B + NY ? OFF_B + (k - TAB_BIAS_B)
+                                                         : k >= TAB_BIAS_B1 ? OFF_B1 + (k - TAB_BIAS_B1) : -1;
 }
-// No parameter sits in more than two slots: the SGD kernel refreshes the expanded table by writing
-// every updated parameter to (at most) two recorded places.
-constexpr int TABLE_MAX_DEST = 2;
+// No parameter sits in more than four slots (a C1 weight: once by tap, twice as shifted GEMM operand):
+// the SGD kernel refreshes the expanded table by writing every updated parameter to its recorded places.
+constexpr int TABLE_MAX_DEST = 4;
 constexpr int table_max_multiplicity() {
   int count[NPARAM] = {};
   int most = 0;
