@@ -31,7 +31,7 @@ PEAK_FP32_TFLOPS = 157.3              # MI355X vector / matrix fp32
 PEAK_HBM_GBS = 8000.0
 LR = 0.05
 N_TRAIN, N_EVAL = 60000, 10000
-GROUP_MAX_BATCH = 256                 # batches up to this size run train_group_kernel, larger ones train_kernel
+GROUP_MAX_BATCH = 640                 # batches up to this size run train_group_kernel, larger ones train_kernel
 # HBM bytes per launch of the fused kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same
 # command (profiles/train_group_kernel_batch100.md, profiles/train_kernel_batch60000.md), scaled by
 # what the counters read for a plain 256 MiB copy (FETCH x2.0, WRITE x1.0).  Only for the batch

@@ -50,7 +50,7 @@ def test_forward_activations(B):
         np.testing.assert_array_equal(yhat[n], acts["y"][n])
 
 
-@pytest.mark.parametrize("B", [1, 3, 100, 257])
+@pytest.mark.parametrize("B", [1, 3, 100, 257, 640, 641])  # 640 is the last size of the small-batch kernel
 def test_batch_gradient(B):
     images, labels = inputs.make_batch(B, 22)
     w = weights(biases=True)
@@ -162,21 +162,21 @@ def test_operand_table_follows_the_weights_through_updates():
     """The kernels read the weights from a copy laid out as matrix operands that the update kernel
     patches in place.  After several steps (small-batch and large-batch kernels, biases moving too)
     a context rebuilt from the current weights must give bitwise the same outputs and gradients."""
-    images, labels = inputs.make_batch(900, 41)
+    images, labels = inputs.make_batch(1800, 41)
     d_im, d_lb = dev(images), dev(labels)
-    net = binding.CNN(weights(biases=True), max_batch=600)
-    for first, size in ((0, 100), (100, 37), (137, 300), (437, 463)):   # 300 and 463 use the large-batch kernel
+    net = binding.CNN(weights(biases=True), max_batch=1000)
+    for first, size in ((0, 100), (100, 37), (137, 700), (837, 963)):   # 700 and 963 use the large-batch kernel
         net.train_batch(d_im[first:first + size], d_lb[first:first + size], LR)
-    fresh = binding.CNN({k: host(v) for k, v in net.get_weights().items()}, max_batch=600)
-    probe_im, probe_lb = d_im[:600], d_lb[:600]
+    fresh = binding.CNN({k: host(v) for k, v in net.get_weights().items()}, max_batch=1000)
+    probe_im, probe_lb = d_im[:1000], d_lb[:1000]
     assert np.array_equal(host(net.forward(probe_im)), host(fresh.forward(probe_im)))
-    for size in (64, 600):
+    for size in (64, 1000):
         g_a, l_a = net.gradient(probe_im[:size], probe_lb[:size])
         g_b, l_b = fresh.gradient(probe_im[:size], probe_lb[:size])
         assert np.array_equal(host(g_a), host(g_b)) and np.array_equal(host(l_a), host(l_b))
     # and set_weights rebuilds it too
     net.set_weights(weights(seed=77))
-    ref = binding.CNN(weights(seed=77), max_batch=600)
+    ref = binding.CNN(weights(seed=77), max_batch=1000)
     assert np.array_equal(host(net.forward(probe_im)), host(ref.forward(probe_im)))
 
 
