@@ -36,7 +36,7 @@ GROUP_MAX_BATCH = 640                 # batches up to this size run train_group_
 # command (profiles/train_group_kernel_batch100.md, profiles/train_kernel_batch60000.md), scaled by
 # what the counters read for a plain 256 MiB copy (FETCH x2.0, WRITE x1.0).  Only for the batch
 # sizes that were profiled; other sizes report null.
-MEASURED_TRAFFIC_BYTES = {100: 2417869, 60000: 194824602}
+MEASURED_TRAFFIC_BYTES = {100: 2358477, 60000: 194842214}
 
 
 def main():
@@ -139,7 +139,7 @@ def main():
             "frac": achieved_tflops / PEAK_FP32_TFLOPS,
             "traffic": MEASURED_TRAFFIC_BYTES.get(args.batch),
             "traffic_unit": "HBM bytes per launch (algorithmic: %d image bytes + %d partial-row bytes)"
-                            % (args.batch * BYTES_PER_IMAGE, min(args.batch, 256) * 15616),
+                            % (args.batch * BYTES_PER_IMAGE, (args.batch if args.batch <= GROUP_MAX_BATCH else min((args.batch + 3) // 4, 256)) * 15616),
             "kernel_ms": kernel_ms,
             "flop_per_launch": FLOP_PER_IMAGE_TRAIN * args.batch,
             "hbm_frac_whole_step": value * BYTES_PER_IMAGE / 1e9 / PEAK_HBM_GBS,
