@@ -17,8 +17,10 @@
 //
 // A workgroup is four such waves.  They share nothing but a read-only table of MFMA operands in
 // LDS (the C2 and FC weights, laid out [entry][lane] exactly as the instructions consume them),
-// built once per kernel; after that single workgroup barrier the waves never synchronise with
-// each other, only with themselves.
+// copied once per kernel from its ready-made image in global memory; after that single workgroup
+// barrier the waves do not synchronise with each other until they join their gradient sums at
+// the end of the kernel.  The same table, helpers and GEMM formulations serve the small-batch
+// kernel (cnn_group.h), where eight waves share one image and C1 forward is a GEMM too.
 //
 // Pixel order.  A lane quad (4 consecutive lanes) is one 2x2 pooling window, so
 // avgpool is a sum inside the quad (C1) or inside a lane's four MFMA result
@@ -121,13 +123,6 @@ __device__ __forceinline__ float dpp_row_half_mirror(float v) {
 }
 __device__ __forceinline__ float dpp_row_mirror(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));
-}
-// rotate right by 4 / by 8 lanes inside each row of 16 lanes
-__device__ __forceinline__ float dpp_row_ror4(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x124, 0xF, 0xF, true));
-}
-__device__ __forceinline__ float dpp_row_ror8(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x128, 0xF, 0xF, true));
 }
 // Sum over the 64 lanes in a fixed order, same value in every lane: quad, 8, 16 lanes by DPP,
 // then the four rows of 16 through scalar registers.
