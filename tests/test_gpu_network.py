@@ -227,6 +227,29 @@ def test_ragged_batch_beyond_the_workgroup_cap():
     assert int(host(n_ok)[0]) == int((yhat.argmax(1) == labels).sum())
 
 
+def test_kernel_timing_aid():
+    """cnn_profile_begin / cnn_profile_read: one reading per recorded step, only the first
+    `capacity` steps are recorded, readings are positive and of a plausible size, and recording
+    does not change the result."""
+    images, labels = inputs.make_batch(300, 43)
+    d_im, d_lb = dev(images), dev(labels)
+    w = weights()
+    plain, timed = binding.CNN(w, max_batch=100), binding.CNN(w, max_batch=100)
+    timed.profile_begin(4)
+    for net in (plain, timed):
+        for first in (0, 100, 200):
+            net.train_batch(d_im[first:first + 100], d_lb[first:first + 100], LR)
+    ms = timed.profile_read(4)
+    assert len(ms) == 3 and all(0.0 < t < 5.0 for t in ms)
+    for first in (0, 100, 200, 0, 100, 200):      # six steps, capacity four
+        timed.train_batch(d_im[first:first + 100], d_lb[first:first + 100], LR)
+        plain.train_batch(d_im[first:first + 100], d_lb[first:first + 100], LR)
+    assert len(timed.profile_read(4)) == 4
+    timed.profile_begin(0)
+    assert timed.profile_read(4) == []
+    assert np.array_equal(host(plain.get_weights_flat()), host(timed.get_weights_flat()))
+
+
 def test_context_errors():
     net = binding.CNN(weights(), max_batch=8)
     images, labels = inputs.make_batch(9, 29)
