@@ -12,7 +12,7 @@
 //   C2 input error (col2im)      waves 0..3: input maps 4 cg .. 4 cg + 3, cg = wave % 2, and pixel tiles
 //                                nt = 2 h, 2 h + 1, h = wave / 2; half h adds into its own copy of d_s1,
 //                                so no two waves ever touch the same cell; the C1 error reads both copies
-//   C2 weight gradient           waves 4..7: tap tiles nt = 0-2, 3-5, 6-7, 8-9 over all 64 pixels (each wave
+//   C2 weight gradient           waves 4..7: tap tiles nt = 0-1, 2-3, 4-6, 7-9 over all 64 pixels (each wave
 //                                owns whole columns of the result, so nothing has to be added across waves)
 //
 // Phases that hand data between waves are separated by workgroup barriers (eight).  A workgroup
@@ -29,8 +29,8 @@ constexpr int GWAVES = 8;  // waves per workgroup of the small-batch kernel
 constexpr int D_S1B_FLOATS = NS1 + 304;
 
 // Tap tiles of the C2 weight gradient owned by wave 4 + i: first tile and count.
-__host__ __device__ constexpr int k2_first(int i) { return i < 2 ? 3 * i : 2 + 2 * i; }
-__host__ __device__ constexpr int k2_count(int i) { return i < 2 ? 3 : 2; }
+__host__ __device__ constexpr int k2_first(int i) { return i < 2 ? 2 * i : 3 * i - 2; }
+__host__ __device__ constexpr int k2_count(int i) { return i < 2 ? 2 : 3; }
 
 struct GroupState {
   float bias2;      // b2[n16]
@@ -83,6 +83,23 @@ __device__ __forceinline__ void group_c1_error(GroupState& st, TrainLds& s, cons
       *reinterpret_cast<float2*>(dst) = da;
       *reinterpret_cast<float2*>(dst + 576) = db;
     }
+  }
+}
+
+// C2 weight gradient for COUNT tap tiles over all four pixel tiles: sixteen K steps in one straight
+// line (no branches), so that the operand reads of later steps are issued under the MFMAs of
+// earlier ones.  bsrc[k] points at the lane's tap of tile k in s1.
+template <int COUNT>
+__device__ __forceinline__ void group_k2_gradient(f4 (&acc)[3], const TrainLds& s, const float* const (&bsrc)[3]) {
+  const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
+  f4 a[4];
+#pragma unroll
+  for (int S = 0; S < 4; ++S) a[S] = *reinterpret_cast<const f4*>(&s.pool[P_D2 + n16 * D2S + 16 * S + 4 * q]);
+#pragma unroll
+  for (int step = 0; step < 16; ++step) {
+    const int S = step >> 2, r = step & 3, off = 24 * S + 12 * (r >> 1) + (r & 1);
+#pragma unroll
+    for (int k = 0; k < COUNT; ++k) acc[k] = mfma16(a[S][r], bsrc[k][off], acc[k]);
   }
 }
 
@@ -309,17 +326,10 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
         const int c = tap / 25, rem = tap - 25 * c, u = rem / 5, v = rem - 5 * u;
         bsrc[k] = s.pool + P_S1 + (tap < 150 ? c * 144 + u * 12 + v : 0) + 2 * q;
       }
-#pragma unroll
-      for (int S = 0; S < 4; ++S) {
-        const f4 a = *reinterpret_cast<const f4*>(&s.pool[P_D2 + n16 * D2S + 16 * S + 4 * q]);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int imm = 12 * (r >> 1) + (r & 1);
-          st.acc_k2[0] = mfma16(a[r], bsrc[0][24 * S + imm], st.acc_k2[0]);
-          st.acc_k2[1] = mfma16(a[r], bsrc[1][24 * S + imm], st.acc_k2[1]);
-          if (count == 3) st.acc_k2[2] = mfma16(a[r], bsrc[2][24 * S + imm], st.acc_k2[2]);
-        }
-      }
+      if (count == 3)
+        group_k2_gradient<3>(st.acc_k2, s, bsrc);
+      else
+        group_k2_gradient<2>(st.acc_k2, s, bsrc);
     }
     CNN_GROUP_MARK(7);
     __syncthreads();  // (6) both d_s1 copies complete; s1, d_c2 no longer needed
