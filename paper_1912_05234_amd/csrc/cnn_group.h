@@ -5,7 +5,7 @@
 // because one wave alone issues a vector instruction only every ~5 cycles, two reach ~2.4.
 //
 //   C1 forward and C1 error      GEMM tiles T = wave, wave + 8 (waves 0, 1 also T = wave + 16), cnn_wave.h
-//   C1 weight gradient           GEMM steps 9 wave .. 9 wave + 8 (pixel rows 3 wave .. 3 wave + 2)
+//   C1 weight gradient           the GEMM's K steps that belong to the wave's own C1 tiles
 //   C2 forward, C2 error         waves 0..3: pixel tile mt = wave
 //   output layer                 outputs o = wave and wave + 8
 //   FC weight gradient           waves 0..2 take the three 4-output row tiles
@@ -15,7 +15,8 @@
 //   C2 weight gradient           waves 4..7: tap tiles nt = 0-1, 2-3, 4-6, 7-9 over all 64 pixels (each wave
 //                                owns whole columns of the result, so nothing has to be added across waves)
 //
-// Phases that hand data between waves are separated by workgroup barriers (eight).  A workgroup
+// Phases that hand data between waves are separated by workgroup barriers (six, plus one in the
+// final cross-wave sums).  A workgroup
 // handles exactly one image: the grid is one workgroup per image of the batch.
 #pragma once
 
@@ -35,7 +36,7 @@ __host__ __device__ constexpr int k2_count(int i) { return i < 2 ? 2 : 3; }
 struct GroupState {
   float bias2;      // b2[n16]
   f4 acc_k2[3];     // waves 4..7: C2 weight gradient tiles nt = k2_first(wave - 4) + k
-  f4 acc_k1[2];     // C1 weight gradient GEMM over this wave's 9 steps, T[(m,sh)][c]
+  f4 acc_k1[2];     // C1 weight gradient GEMM over the K steps of this wave's tiles, T[(m,sh)][c]
   f4 acc_fc[3];     // waves 0..2: FC weight gradient rows o = 4 wave + r, columns lane + 64 k
   float g_bq;       // waves 0..2: FC bias gradient b[4 wave + lane % 4]
   float g_b1[2];    // C1 bias gradient of maps 2q, 2q + 1 over this lane's pixels
@@ -334,20 +335,30 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     CNN_GROUP_MARK(7);
     __syncthreads();  // (6) both d_s1 copies complete; s1, d_c2 no longer needed
 
-    // ---- C1 error for this wave's pixel groups, staged for everybody ----------------------------------
-    if (wave < 2)
+    // ---- C1 error for this wave's tiles, then the K steps of the C1 weight gradient GEMM that belong
+    //      to the same tiles: a wave reads only the d1 cells it staged itself, so no barrier -------------
+    const float* d1t[3];
+    const float* imgt[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      const int T = wave + 8 * k < C1F_TILES ? wave + 8 * k : wave;
+      d1t[k] = s.pool + c1f_tile_c1(T);
+      imgt[k] = s.img + c1f_tile_img(T);
+    }
+    if (wave < 2) {
       group_c1_error<3>(st, s, d_s1b, wave, ln, c1);
-    else
+      wave_sync();
+      c1g_accumulate_tiles<3>(st.acc_k1, d1t, imgt);
+    } else {
       group_c1_error<2>(st, s, d_s1b, wave, ln, c1);
-    __syncthreads();  // (7) d1 complete
-    // ---- C1 weight gradient: this wave's eighth of the GEMM's K range (pixel rows 3 wave .. 3 wave + 2)
-    c1g_accumulate<C1G_STEPS / GWAVES>(st.acc_k1, s.pool + 72 * wave, s.img + 84 * wave);
+      wave_sync();
+      c1g_accumulate_tiles<2>(st.acc_k1, d1t, imgt);
+    }
     CNN_GROUP_MARK(8);
-    __syncthreads();  // (8) every wave is done with the operand table and the pool
   }
 
   // ---- one partial row per workgroup: cross-wave sums through LDS in a fixed order -------------------
-  // The operand table is dead now; its storage takes the parked values.
+  // Nothing has read the operand table since barrier (6); its storage takes the parked values.
   float* k1s = tab.e;                               // [8 waves][16][32]: parked C1 weight GEMM results
   float* b1s = tab.e + GWAVES * C1G_PARK;           // [8 waves][8]: C1 bias sums (256 floats reserved)
   float* b2s = b1s + 256;                           // [4 waves][64]: per-lane C2 bias sums

@@ -367,8 +367,8 @@ __device__ __forceinline__ void c1g_lane_offsets(int& a, int (&bt)[2]) {
     bt[nt] = (c < 30 ? (c / 6) * 28 + c % 6 : 0) + 2 * q;
   }
 }
-// STEPS steps of the GEMM starting at pixel row y0 (a multiple of... any row): operands of step
-// kk + 2 are read while the two MFMAs of step kk issue.
+// STEPS steps of the GEMM from the given origins of d1 and the image: operands of step kk + 2 are
+// read while the two MFMAs of step kk issue.
 template <int STEPS>
 __device__ __forceinline__ void c1g_accumulate(f4 (&acc)[2], const float* d1, const float* img) {
   int a, bt[2];
@@ -390,6 +390,33 @@ __device__ __forceinline__ void c1g_accumulate(f4 (&acc)[2], const float* d1, co
     acc[0] = mfma16(oa[kk % 3], ob0[kk % 3], acc[0]);
     acc[1] = mfma16(oa[kk % 3], ob1[kk % 3], acc[1]);
     if (kk + 2 < STEPS) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+  }
+}
+// The same GEMM restricted to the K steps of NT tiles of the C1 forward tiling (c1f_tile_*): tile T
+// covers four pixel rows and one group of four pixel pairs, i.e. four K steps whose operand
+// offsets are the tile's origin plus 24 (d1) or 28 (image) floats per row.  d1t[k] / imgt[k] point
+// at the origins of tile k.
+template <int NT>
+__device__ __forceinline__ void c1g_accumulate_tiles(f4 (&acc)[2], const float* const (&d1t)[3],
+                                                     const float* const (&imgt)[3]) {
+  int a, bt[2];
+  c1g_lane_offsets(a, bt);
+  float oa[3], ob0[3], ob1[3];
+  auto load_step = [&](int st, int slot) {
+    const int k = st >> 2, row = st & 3;
+    oa[slot] = d1t[k][a + 24 * row];
+    ob0[slot] = imgt[k][bt[0] + 28 * row];
+    ob1[slot] = imgt[k][bt[1] + 28 * row];
+  };
+  load_step(0, 0);
+  load_step(1, 1);
+#pragma unroll
+  for (int st = 0; st < 4 * NT; ++st) {
+    if (st + 2 < 4 * NT) load_step(st + 2, (st + 2) % 3);
+    acc[0] = mfma16(oa[st % 3], ob0[st % 3], acc[0]);
+    acc[1] = mfma16(oa[st % 3], ob1[st % 3], acc[1]);
+    if (st + 2 < 4 * NT) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
     __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
   }
 }
