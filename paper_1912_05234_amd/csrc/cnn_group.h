@@ -16,8 +16,8 @@
 //                                owns whole columns of the result, so nothing has to be added across waves)
 //
 // Phases that hand data between waves are separated by workgroup barriers (six, plus one in the
-// final cross-wave sums).  A workgroup
-// handles exactly one image: the grid is one workgroup per image of the batch.
+// final cross-wave sums).  A workgroup handles exactly one image: the grid is one workgroup per
+// image of the batch.
 #pragma once
 
 #include "cnn_wave.h"
@@ -112,7 +112,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
                                             const float* __restrict__ tabg, float* __restrict__ out,
                                             OperandTable<TAB_TRAIN_ENTRIES>& tab, TrainLds& s, float* d_s1b,
                                             float* ybuf) {
-  const int t = threadIdx.x, wave = t >> 6, l = t & 63, q = l >> 4, n16 = l & 15, b = l >> 2, sub = l & 3;
+  const int t = threadIdx.x, wave = t >> 6, l = t & 63, q = l >> 4, n16 = l & 15, sub = l & 3;
   const int pp = 12 * ((n16 & 3) >> 1) + 2 * (n16 >> 2) + (n16 & 1);
   const float* tl = tab.e + l;
   const int pix = t < NI / 4 ? t : 0;  // the 16-byte piece of the image this thread moves
@@ -151,7 +151,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
     __syncthreads();  // (1) image and operand table in LDS
     st.bias2 = tab.bias[n16];
 
-    // ---- C1 forward + S1 for this wave's pixel groups --------------------------------------------
+    // ---- C1 forward + S1 for this wave's tiles ---------------------------------------------------------
     f4 c1[3];
     if (wave < 2)
       group_c1_forward<3>(s, tab, wave, ln, c1);
@@ -197,7 +197,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
         float p = tl[(TAB_FCW + 3 * o) * 64] * sv[0];
         p = fmaf(tl[(TAB_FCW + 3 * o + 1) * 64], sv[1], p);
         p = fmaf(tl[(TAB_FCW + 3 * o + 2) * 64], sv[2], p);
-        const float yo = logistic(wave_sum(p) + tab.bias[16 + o]);
+        const float yo = logistic(wave_sum(p) + tab.bias[TAB_BIAS_B + o]);
         if (l == 0) ybuf[o] = yo;
       }
     }

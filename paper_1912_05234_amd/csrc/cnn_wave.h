@@ -648,7 +648,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
     float p = tl[(TAB_FCW + 3 * o) * 64] * sv[0];
     p = fmaf(tl[(TAB_FCW + 3 * o + 1) * 64], sv[1], p);
     p = fmaf(tl[(TAB_FCW + 3 * o + 2) * 64], sv[2], p);
-    y[o] = logistic(wave_sum(p) + tab.bias[16 + o]);
+    y[o] = logistic(wave_sum(p) + tab.bias[TAB_BIAS_B + o]);
   }
   if constexpr (MODE == kTrain) {
     // ---- output error, FC backweights / backbias / backin ------------------------------------------
