@@ -50,7 +50,8 @@ def test_forward_activations(B):
         np.testing.assert_array_equal(yhat[n], acts["y"][n])
 
 
-@pytest.mark.parametrize("B", [1, 3, 100, 257, 640, 641])  # 640 is the last size of the small-batch kernel
+# 640 is the last size of the small-batch kernel; 1023 / 1025 / 1500 straddle one image per wave
+@pytest.mark.parametrize("B", [1, 3, 63, 100, 257, 512, 640, 641, 1023, 1025, 1500])
 def test_batch_gradient(B):
     images, labels = inputs.make_batch(B, 22)
     w = weights(biases=True)
