@@ -228,6 +228,24 @@ def test_ragged_batch_beyond_the_workgroup_cap():
     assert int(host(n_ok)[0]) == int((yhat.argmax(1) == labels).sum())
 
 
+@pytest.mark.parametrize("B", [5, 700])   # small-batch and large-batch kernels
+def test_saturated_sigmoids_stay_finite(B):
+    """Weights fifty times the usual size drive every sigmoid to 0 or 1: exp overflows to inf and the
+    reciprocal must give exactly 0, never NaN; outputs and gradients still match the oracle."""
+    images, labels = inputs.make_batch(B, 47)
+    w = {k: (50.0 * v).astype(np.float32) for k, v in weights(biases=True).items()}
+    net = binding.CNN(w, max_batch=B)
+    yhat = host(net.forward(dev(images)))
+    grad, loss = net.gradient(dev(images), dev(labels))
+    assert np.isfinite(yhat).all() and np.isfinite(host(grad)).all() and np.isfinite(host(loss)).all()
+    wflat = inputs.flatten(w)
+    ref_y = np.stack([oracle.forward(images[n], wflat)["y"] for n in range(min(B, 16))])
+    assert_close(yhat[:len(ref_y)], ref_y, RTOL_ACT, "saturated yhat")
+    ref_loss, ref_g = oracle_grad(images, labels, wflat)
+    assert_close(host(grad), ref_g, 2e-5, "saturated gradient")
+    assert abs(host(loss)[0] - ref_loss) <= 1e-5 * max(ref_loss, 1.0)
+
+
 def test_kernel_timing_aid():
     """cnn_profile_begin / cnn_profile_read: one reading per recorded step, only the first
     `capacity` steps are recorded, readings are positive and of a plausible size, and recording
