@@ -36,7 +36,7 @@ GROUP_MAX_BATCH = 640                 # batches up to this size run train_group_
 # command (profiles/train_group_kernel_batch100.md, profiles/train_kernel_batch60000.md), scaled by
 # what the counters read for a plain 256 MiB copy (FETCH x2.0, WRITE x1.0).  Only for the batch
 # sizes that were profiled; other sizes report null.
-MEASURED_TRAFFIC_BYTES = {100: 2376909, 60000: 194842214}
+MEASURED_TRAFFIC_BYTES = {100: 2376909, 60000: 194844672}
 
 
 def main():

@@ -82,7 +82,7 @@ __device__ __forceinline__ void group_c1_error(GroupState& st, TrainLds& s, cons
       st.g_b1[1] += db.x + db.y;
       float* dst = s.pool + ln.c1 + c1f_tile_c1(T);
       *reinterpret_cast<float2*>(dst) = da;
-      *reinterpret_cast<float2*>(dst + 576) = db;
+      *reinterpret_cast<float2*>(dst + D1_MAP) = db;
     }
   }
 }

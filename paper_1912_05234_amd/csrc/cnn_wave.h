@@ -67,7 +67,11 @@ constexpr int P_S2 = P_S1 + NS1 + 288;  // s2[192]
 constexpr int P_DS2 = P_S2 + NS2;       // d_s2[192] + 64 (rows of the padding maps of the C2 tiles)
 constexpr int P_D2 = P_DS2 + NS2 + 64;  // d2[16][D2S]: error at C2's pre-activation, [map][pixel p]
 constexpr int P_END = P_D2 + 16 * D2S;
-constexpr int POOL_FLOATS = NC1 + 32;   // the C1 error d1[6][24][24] is staged over the whole pool
+// The C1 error is staged over the whole pool as d1[6][24][24] with the maps D1_MAP floats apart: the
+// gradient GEMM's A operand reads all six maps in one instruction, and a map stride of 576 (a
+// multiple of the 32 banks) would put them on the same four banks.
+constexpr int D1_MAP = 24 * 24 + 4;
+constexpr int POOL_FLOATS = 6 * D1_MAP + 32;
 static_assert(POOL_FLOATS >= P_END, "pool holds the forward/C2 arrays");
 struct __align__(16) TrainLds {
   float d_s1[NS1];  // error at S1 (col2im target)
@@ -201,7 +205,7 @@ __host__ __device__ constexpr int c1f_tile_c1(int T) { return (T / 3) * 96 + (T 
 struct C1Lane {
   int img[C1F_KSTEPS];  // B operand of K step ks
   int s1;               // map 2q of a pooled array (map 2q + 1 is 144 further)
-  int c1;               // map 2q, sh = 0 of a [6][24][24] array (map 2q + 1 is 576 further)
+  int c1;               // map 2q, sh = 0 of the staged d1 (map 2q + 1 is D1_MAP further)
 };
 __device__ __forceinline__ C1Lane c1f_lane() {
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
@@ -213,7 +217,7 @@ __device__ __forceinline__ C1Lane c1f_lane() {
     o.img[ks] = (2 * a + dy + tt / 6) * 28 + 2 * bx + tt % 6;
   }
   o.s1 = 2 * q * 144 + a * 12 + bx;
-  o.c1 = 2 * q * 576 + (2 * a + dy) * 24 + 2 * bx;
+  o.c1 = 2 * q * D1_MAP + (2 * a + dy) * 24 + 2 * bx;
   return o;
 }
 // Pre-activations of two tiles at once (two independent accumulation chains); img0 / img1 point at
@@ -349,7 +353,7 @@ __device__ __forceinline__ void load_tables(OperandTable<LdsOf<MODE>::entries>& 
 //   T[(m,sh)][(u,v')] = sum_{y,X} d1[m][y][2X+sh] * img[y+u][2X+v'],   g_k1[m][u][v] = T[(m,0)][(u,v)] + T[(m,1)][(u,v+1)]
 // is a GEMM with M = 12 rows (m,sh) in one 16-row tile, N = 30 columns (u,v'), c = 6u + v', in two
 // 16-column tiles, and K = 288 pixel pairs in 72 steps of four: step kk covers row y = kk / 3 and
-// pairs X = 4 (kk % 3) + q, q = lane / 16.  d1 is staged in LDS as d1[m][24][24].
+// pairs X = 4 (kk % 3) + q, q = lane / 16.  d1 is staged in LDS as d1[m][24][24], maps D1_MAP apart.
 //   A[i = lane%16][k = q] = d1[m = (i/2) % 6][y][2X + i%2]     (rows 12..15 repeat rows 0..3, dropped)
 //   B[k = q][j = lane%16] = img[y + u][2X + v'], c = 16 nt + j  (columns 30, 31 read tap 0, dropped)
 //   D[i = 4q + r][j]: register r of tile nt.
@@ -360,7 +364,7 @@ __host__ __device__ constexpr int c1g_imm_b(int kk) { return 28 * (kk / 3) + 8 *
 // Lane parts of the operand addresses (floats): d1 and the two image tiles.
 __device__ __forceinline__ void c1g_lane_offsets(int& a, int (&bt)[2]) {
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
-  a = ((n16 >> 1) % 6) * 576 + (n16 & 1) + 2 * q;
+  a = ((n16 >> 1) % 6) * D1_MAP + (n16 & 1) + 2 * q;
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const int c = 16 * nt + n16;
@@ -849,7 +853,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
           const float c = c1[g][i];
           const float d1 = up[k][i] * 0.25f * c * (1.0f - c);
           st.g_b1[i] += d1;
-          dst[i * 576] = d1;
+          dst[i * D1_MAP] = d1;
         }
       }
     }
