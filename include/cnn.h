@@ -120,7 +120,9 @@ int cnn_profile_read(cnn_ctx* ctx, float* ms, int capacity, int* n_recorded);
  * conv = valid cross-correlation, no kernel flip (listing `conv`), over all Cin
  * input maps per output map plus bias (listing `mconv`), no activation:
  *   out[b,co,y,x] = bias[co] + sum_{ci,u,v} in[b,ci,y+u,x+v] * k[co,ci,u,v]
- * with Ho = H-KH+1, Wo = W-KW+1 (both must be >= 1).  bias may be NULL. */
+ * with Ho = H-KH+1, Wo = W-KW+1 (both must be >= 1).  bias may be NULL.  All tensors are device
+ * memory, 16-byte aligned, fp32, and finite: the matrix-core kernels multiply padding lanes by
+ * zero, which a NaN or infinity in the input would turn into NaN. */
 int cnn_conv_fwd(const float* in, const float* k, const float* bias, float* out, int B, int Cin,
                  int H, int W, int Cout, int KH, int KW, void* hip_stream);
 /* `backin` summed over output maps: d_in[b,ci,p,q] = sum_co sum_{u,v : 0<=p-u<Ho, 0<=q-v<Wo}
@@ -129,9 +131,15 @@ int cnn_conv_bwd_input(const float* d_out, const float* k, float* d_in, int B, i
                        int W, int Cout, int KH, int KW, void* hip_stream);
 /* `backweights` and `backbias`, summed over the batch:
  *   d_k[co,ci,u,v] = sum_{b,y,x} in[b,ci,y+u,x+v] * d_out[b,co,y,x];  d_bias[co] = sum d_out[:,co].
- * d_bias may be NULL.  Deterministic summation order. */
+ * d_bias may be NULL.  `workspace` is device memory (16-byte aligned) for partial sums that the call
+ * may overwrite; with at least cnn_conv_bwd_weight_workspace_bytes() bytes the matrix-core kernel
+ * runs, with NULL or fewer bytes a slower kernel that needs none.  The summation order is fixed in
+ * either case (the two orders differ).  The size query returns 0 for invalid arguments and for
+ * shapes only the slower kernel serves. */
+size_t cnn_conv_bwd_weight_workspace_bytes(int B, int Cin, int H, int W, int Cout, int KH, int KW);
 int cnn_conv_bwd_weight(const float* in, const float* d_out, float* d_k, float* d_bias, int B,
-                        int Cin, int H, int W, int Cout, int KH, int KW, void* hip_stream);
+                        int Cin, int H, int W, int Cout, int KH, int KW, void* workspace,
+                        size_t workspace_bytes, void* hip_stream);
 /* Listing `avgpool` over [B,C,H,W] (H, W even) -> [B,C,H/2,W/2]. */
 int cnn_avgpool_fwd(const float* in, float* out, int B, int C, int H, int W, void* hip_stream);
 /* Listing `backavgpool`: d_out[B,C,Ho,Wo] -> d_in[B,C,2Ho,2Wo] = d_out[..,y/2,x/2] / 4. */
@@ -143,9 +151,11 @@ int cnn_fc_fwd(const float* in, const float* w, const float* bias, float* out, i
 /* d_in[b,i] = sum_o w[o,i] * d_out[b,o]. */
 int cnn_fc_bwd_input(const float* d_out, const float* w, float* d_in, int B, int I, int O,
                      void* hip_stream);
-/* d_w[o,i] = sum_b d_out[b,o] * in[b,i];  d_bias[o] = sum_b d_out[b,o] (nullable). */
+/* d_w[o,i] = sum_b d_out[b,o] * in[b,i];  d_bias[o] = sum_b d_out[b,o] (nullable).  Workspace as
+ * for cnn_conv_bwd_weight. */
+size_t cnn_fc_bwd_weight_workspace_bytes(int B, int I, int O);
 int cnn_fc_bwd_weight(const float* in, const float* d_out, float* d_w, float* d_bias, int B, int I,
-                      int O, void* hip_stream);
+                      int O, void* workspace, size_t workspace_bytes, void* hip_stream);
 /* Listing `sigmoid`: y = 1 / (1 + exp(-x)), n elements. */
 int cnn_logistic_fwd(const float* x, float* y, size_t n, void* hip_stream);
 /* Its derivative through the stored output: d_x = d_y * y * (1 - y). */

@@ -36,12 +36,14 @@ SIGNATURES = {
     "cnn_profile_read": (_i, [_vp, _vp, _i, ctypes.POINTER(_i)]),
     "cnn_conv_fwd": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp]),
     "cnn_conv_bwd_input": (_i, [_vp, _vp, _vp] + [_i] * 7 + [_vp]),
-    "cnn_conv_bwd_weight": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp]),
+    "cnn_conv_bwd_weight_workspace_bytes": (_sz, [_i] * 7),
+    "cnn_conv_bwd_weight": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp, _sz, _vp]),
     "cnn_avgpool_fwd": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
     "cnn_avgpool_bwd": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
     "cnn_fc_fwd": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _vp]),
     "cnn_fc_bwd_input": (_i, [_vp, _vp, _vp, _i, _i, _i, _vp]),
-    "cnn_fc_bwd_weight": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _vp]),
+    "cnn_fc_bwd_weight_workspace_bytes": (_sz, [_i] * 3),
+    "cnn_fc_bwd_weight": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _vp, _sz, _vp]),
     "cnn_logistic_fwd": (_i, [_vp, _vp, _sz, _vp]),
     "cnn_logistic_bwd": (_i, [_vp, _vp, _vp, _sz, _vp]),
 }
@@ -220,15 +222,24 @@ def conv_bwd_input(d_out, k, H, W):
     return d_in
 
 
-def conv_bwd_weight(inp, d_out, want_bias=True):
+def _workspace(nbytes, device, use):
+    if not use or nbytes == 0:
+        return None, 0
+    return torch.empty((nbytes,), dtype=torch.uint8, device=device), nbytes
+
+
+def conv_bwd_weight(inp, d_out, want_bias=True, workspace=True):
+    """workspace=False passes none, which selects the kernel that needs no partial sums."""
     inp, d_out = _dev(inp), _dev(d_out)
     B, Cin, H, W = inp.shape
     Cout, Ho, Wo = d_out.shape[1:]
     KH, KW = H - Ho + 1, W - Wo + 1
     d_k = torch.empty((Cout, Cin, KH, KW), dtype=torch.float32, device=inp.device)
     d_b = torch.empty((Cout,), dtype=torch.float32, device=inp.device) if want_bias else None
+    ws, nbytes = _workspace(lib().cnn_conv_bwd_weight_workspace_bytes(B, Cin, H, W, Cout, KH, KW), inp.device,
+                            workspace)
     _check(lib().cnn_conv_bwd_weight(_ptr(inp), _ptr(d_out), _ptr(d_k), _ptr(d_b), B, Cin, H, W, Cout, KH,
-                                     KW, _stream()), "cnn_conv_bwd_weight")
+                                     KW, _ptr(ws), nbytes, _stream()), "cnn_conv_bwd_weight")
     return d_k, d_b
 
 
@@ -266,14 +277,15 @@ def fc_bwd_input(d_out, w):
     return d_in
 
 
-def fc_bwd_weight(inp, d_out, want_bias=True):
+def fc_bwd_weight(inp, d_out, want_bias=True, workspace=True):
     inp, d_out = _dev(inp), _dev(d_out)
     B, I = inp.shape
     O = d_out.shape[1]
     d_w = torch.empty((O, I), dtype=torch.float32, device=inp.device)
     d_b = torch.empty((O,), dtype=torch.float32, device=inp.device) if want_bias else None
-    _check(lib().cnn_fc_bwd_weight(_ptr(inp), _ptr(d_out), _ptr(d_w), _ptr(d_b), B, I, O, _stream()),
-           "cnn_fc_bwd_weight")
+    ws, nbytes = _workspace(lib().cnn_fc_bwd_weight_workspace_bytes(B, I, O), inp.device, workspace)
+    _check(lib().cnn_fc_bwd_weight(_ptr(inp), _ptr(d_out), _ptr(d_w), _ptr(d_b), B, I, O, _ptr(ws), nbytes,
+                                   _stream()), "cnn_fc_bwd_weight")
     return d_w, d_b
 
 

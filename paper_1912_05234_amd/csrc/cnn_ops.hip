@@ -1,8 +1,11 @@
 // Stateless per-operation kernels (general shapes) and their C entry points.
 // Definitions: arXiv 1912.05234, Section 3 -- listings conv, mconv, sigmoid,
-// avgpool, backweights, backbias, backin, backavgpool.  These are the plain,
-// one-thread-per-output forms; the fused training step lives in cnn_fused.hip.
+// avgpool, backweights, backbias, backin, backavgpool.  Convolutions and fully
+// connected layers whose operands fit in LDS run as implicit GEMMs on the matrix
+// cores (cnn_igemm.h); the plain one-thread-per-output kernels below serve every
+// other shape.  The fused training step lives in cnn_fused.hip.
 #include "cnn_common.h"
+#include "cnn_igemm.h"
 
 namespace {
 
@@ -200,6 +203,103 @@ __global__ __launch_bounds__(TPB) void logistic_bwd_kernel(const float* __restri
 
 inline int launched() { return hipGetLastError() == hipSuccess ? CNN_OK : CNN_EHIP; }
 
+// ---- launch plans of the matrix-core kernels ----------------------------------------------------
+constexpr int LDS_LIMIT = 64 * 1024;   // bytes of LDS one workgroup may use
+constexpr int LDS_TARGET = 36 * 1024;  // preferred, so that four workgroups share a compute unit
+constexpr int MAX_GROUP = 64;          // images per group
+constexpr int MAX_PARTIALS = 512;      // workgroups (partial sums) of the weight gradient
+
+struct ConvPlan {
+  igemm::ConvArgs a;
+  int tp = 0;  // pixel tiles per wave job; 0: the shape does not fit, use the plain kernel
+  unsigned grid = 0;
+  size_t lds_bytes = 0;
+};
+
+// dst[B][M][OH][OW] from src[B][SC][SH][SW] staged with a border of (pady, padx).
+ConvPlan plan_conv(const float* src, const float* w, const float* bias, float* dst, int B, int M, int SC,
+                   int SH, int SW, int KH, int KW, int OH, int OW, int pady, int padx, int flip) {
+  ConvPlan p;
+  igemm::ConvArgs& a = p.a;
+  a.src = src, a.w = w, a.bias = bias, a.dst = dst;
+  a.B = B, a.M = M, a.SC = SC, a.SH = SH, a.SW = SW, a.KH = KH, a.KW = KW, a.OH = OH, a.OW = OW;
+  a.pady = pady, a.padx = padx, a.flip = flip, a.zero_fill = (pady || padx) ? 1 : 0;
+  const long long K = (long long)SC * KH * KW, LW = SW + 2LL * padx, LP = (SH + 2LL * pady) * LW, LI = SC * LP;
+  const long long OHOW = (long long)OH * OW, MT = (M + 15) / 16, S = (K + 3) / 4;
+  if (MT * S * 64 + 4 * S + 16 * MT + LI + 2 * OHOW + 16 > LDS_LIMIT / 4) return p;  // not even one image
+  a.K = (int)K, a.LW = (int)LW, a.LP = (int)LP, a.LI = (int)LI, a.MT = (int)MT, a.S = (int)S;
+  auto bytes = [&](int nb) {
+    a.NB = nb;
+    return (long long)igemm::conv_lds(a).total * 4;
+  };
+  if (bytes(1) > LDS_LIMIT) return p;
+  int nb_limit = 1, nb_target = 1;
+  for (int nb = 2; nb <= MAX_GROUP && nb <= B && bytes(nb) <= LDS_LIMIT; ++nb) {
+    nb_limit = nb;
+    if (bytes(nb) <= LDS_TARGET) nb_target = nb;
+  }
+  const int nb_tiles = (int)((64 + OHOW - 1) / OHOW);  // four tiles of pixels, one per wave
+  const int nb_fill = (B + 1023) / 1024;               // beyond about a thousand groups, larger ones
+  int nb = nb_tiles > nb_fill ? nb_tiles : nb_fill;
+  const int cap = nb_target >= nb_tiles ? nb_target : nb_limit;
+  if (nb > cap) nb = cap;
+  a.NB = nb;
+  a.groups = (B + nb - 1) / nb;
+  const long long PT = (nb * OHOW + 15) / 16;
+  p.tp = PT * MT >= 16 ? 4 : PT * MT >= 8 ? 2 : 1;
+  p.grid = (unsigned)(a.groups < 2048 ? a.groups : 2048);
+  p.lds_bytes = (size_t)bytes(nb);
+  a.inv_khkw = 1.0f / (float)(KH * KW), a.inv_kw = 1.0f / (float)KW, a.inv_ohow = 1.0f / (float)OHOW;
+  a.inv_ow = 1.0f / (float)OW, a.inv_sw = 1.0f / (float)SW, a.inv_sh = 1.0f / (float)SH;
+  return p;
+}
+
+int launch_conv(const ConvPlan& p, hipStream_t stream) {
+  switch (p.tp) {
+    case 4: igemm::conv_kernel<4><<<p.grid, igemm::THREADS, p.lds_bytes, stream>>>(p.a); break;
+    case 2: igemm::conv_kernel<2><<<p.grid, igemm::THREADS, p.lds_bytes, stream>>>(p.a); break;
+    default: igemm::conv_kernel<1><<<p.grid, igemm::THREADS, p.lds_bytes, stream>>>(p.a); break;
+  }
+  return launched();
+}
+
+struct WgradPlan {
+  igemm::WgradArgs a;
+  bool fits = false;
+  unsigned gx = 0, gy = 0;
+  size_t lds_bytes = 0, workspace_bytes = 0;
+};
+
+WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
+  WgradPlan p;
+  igemm::WgradArgs& a = p.a;
+  a.in = nullptr, a.d_out = nullptr, a.part = nullptr;
+  a.B = B, a.Cin = Cin, a.H = H, a.W = W, a.Cout = Cout, a.KH = KH, a.KW = KW;
+  a.Ho = H - KH + 1, a.Wo = W - KW + 1;
+  const long long K = (long long)Cin * KH * KW, HoWo = (long long)a.Ho * a.Wo, per_image = (long long)Cin * H * W;
+  if (per_image + 18 * (HoWo + 36) > LDS_LIMIT / 4 || K + 1 > (1 << 20)) return p;
+  a.K = (int)K, a.MT = (Cout + 15) / 16, a.NT = (int)((K + 1 + 15) / 16), a.NTG = (a.NT + 15) / 16;
+  auto bytes = [&](int nb) {
+    a.NB = nb;
+    a.NP = igemm::round4((int)(nb * HoWo));
+    a.NPS = a.NP + ((2 - a.NP) % 32 + 32) % 32;
+    return (long long)igemm::wgrad_lds(a).total * 4;
+  };
+  if (bytes(1) > LDS_LIMIT) return p;
+  int nb = 1;
+  const int nb_fill = (B + MAX_PARTIALS - 1) / MAX_PARTIALS;
+  for (int c = 2; c <= MAX_GROUP && c <= B && c <= nb_fill && bytes(c) <= LDS_TARGET; ++c) nb = c;
+  p.lds_bytes = (size_t)bytes(nb);
+  a.groups = (B + nb - 1) / nb;
+  p.gx = (unsigned)(a.groups < MAX_PARTIALS ? a.groups : MAX_PARTIALS);
+  p.gy = (unsigned)(a.MT * a.NTG);
+  p.workspace_bytes = (size_t)p.gx * a.MT * a.NT * 256 * sizeof(float);
+  a.inv_khkw = 1.0f / (float)(KH * KW), a.inv_kw = 1.0f / (float)KW;
+  a.inv_howo = 1.0f / (float)HoWo, a.inv_wo = 1.0f / (float)a.Wo;
+  p.fits = true;
+  return p;
+}
+
 inline bool conv_args_ok(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
   return B >= 1 && Cin >= 1 && Cout >= 1 && KH >= 1 && KW >= 1 && H >= KH && W >= KW &&
          (size_t)Cout * Cin * KH * KW + (size_t)Cout < (size_t)1 << 30;
@@ -213,6 +313,8 @@ int cnn_conv_fwd(const float* in, const float* k, const float* bias, float* out,
                  int W, int Cout, int KH, int KW, void* hip_stream) {
   if (!in || !k || !out || !conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;
   if (!aligned16(in) || !aligned16(k) || !aligned16(out) || (bias && !aligned16(bias))) return CNN_EINVAL;
+  const ConvPlan p = plan_conv(in, k, bias, out, B, Cout, Cin, H, W, KH, KW, H - KH + 1, W - KW + 1, 0, 0, 0);
+  if (p.tp) return launch_conv(p, (hipStream_t)hip_stream);
   const size_t total = (size_t)B * Cout * (H - KH + 1) * (W - KW + 1);
   conv_fwd_kernel<<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(in, k, bias, out, total, Cin, H,
                                                                          W, Cout, KH, KW);
@@ -223,17 +325,36 @@ int cnn_conv_bwd_input(const float* d_out, const float* k, float* d_in, int B, i
                        int Cout, int KH, int KW, void* hip_stream) {
   if (!d_out || !k || !d_in || !conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;
   if (!aligned16(d_out) || !aligned16(k) || !aligned16(d_in)) return CNN_EINVAL;
+  const ConvPlan p = plan_conv(d_out, k, nullptr, d_in, B, Cin, Cout, H - KH + 1, W - KW + 1, KH, KW, H, W,
+                               KH - 1, KW - 1, 1);
+  if (p.tp) return launch_conv(p, (hipStream_t)hip_stream);
   const size_t total = (size_t)B * Cin * H * W;
   conv_bwd_input_kernel<<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(d_out, k, d_in, total, Cin,
                                                                                H, W, Cout, KH, KW);
   return launched();
 }
 
+size_t cnn_conv_bwd_weight_workspace_bytes(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
+  if (!conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return 0;
+  return plan_wgrad(B, Cin, H, W, Cout, KH, KW).workspace_bytes;
+}
+
 int cnn_conv_bwd_weight(const float* in, const float* d_out, float* d_k, float* d_bias, int B, int Cin,
-                        int H, int W, int Cout, int KH, int KW, void* hip_stream) {
+                        int H, int W, int Cout, int KH, int KW, void* workspace, size_t workspace_bytes,
+                        void* hip_stream) {
   if (!in || !d_out || !d_k || !conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;
   if (!aligned16(in) || !aligned16(d_out) || !aligned16(d_k) || (d_bias && !aligned16(d_bias)))
     return CNN_EINVAL;
+  if (workspace && !aligned16(workspace)) return CNN_EINVAL;
+  WgradPlan p = plan_wgrad(B, Cin, H, W, Cout, KH, KW);
+  if (p.fits && workspace && workspace_bytes >= p.workspace_bytes) {
+    p.a.in = in, p.a.d_out = d_out, p.a.part = static_cast<float*>(workspace);
+    igemm::wgrad_kernel<<<dim3(p.gx, p.gy), igemm::THREADS, p.lds_bytes, (hipStream_t)hip_stream>>>(p.a);
+    const unsigned blocks = (unsigned)(((size_t)Cout * (p.a.K + 1) + 15) / 16);
+    igemm::wgrad_reduce_kernel<<<blocks, igemm::THREADS, 0, (hipStream_t)hip_stream>>>(
+        p.a.part, (int)p.gx, p.a.MT, p.a.NT, Cout, p.a.K, d_k, d_bias);
+    return launched();
+  }
   const unsigned blocks = (unsigned)(Cout * Cin * KH * KW + (d_bias ? Cout : 0));
   conv_bwd_weight_kernel<<<blocks, TPB, 0, (hipStream_t)hip_stream>>>(in, d_out, d_k, d_bias, B, Cin, H,
                                                                       W, Cout, KH, KW);
@@ -260,6 +381,8 @@ int cnn_fc_fwd(const float* in, const float* w, const float* bias, float* out, i
                void* hip_stream) {
   if (!in || !w || !out || B < 1 || I < 1 || O < 1) return CNN_EINVAL;
   if (!aligned16(in) || !aligned16(w) || !aligned16(out) || (bias && !aligned16(bias))) return CNN_EINVAL;
+  const ConvPlan p = plan_conv(in, w, bias, out, B, O, I, 1, 1, 1, 1, 1, 1, 0, 0, 0);
+  if (p.tp) return launch_conv(p, (hipStream_t)hip_stream);
   const size_t total = (size_t)B * O;
   fc_fwd_kernel<<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(in, w, bias, out, total, I, O);
   return launched();
@@ -269,17 +392,27 @@ int cnn_fc_bwd_input(const float* d_out, const float* w, float* d_in, int B, int
                      void* hip_stream) {
   if (!d_out || !w || !d_in || B < 1 || I < 1 || O < 1) return CNN_EINVAL;
   if (!aligned16(d_out) || !aligned16(w) || !aligned16(d_in)) return CNN_EINVAL;
+  const ConvPlan p = plan_conv(d_out, w, nullptr, d_in, B, I, O, 1, 1, 1, 1, 1, 1, 0, 0, 1);
+  if (p.tp) return launch_conv(p, (hipStream_t)hip_stream);
   const size_t total = (size_t)B * I;
   fc_bwd_input_kernel<<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(d_out, w, d_in, total, I, O);
   return launched();
 }
 
+size_t cnn_fc_bwd_weight_workspace_bytes(int B, int I, int O) {
+  return cnn_conv_bwd_weight_workspace_bytes(B, I, 1, 1, O, 1, 1);
+}
+
 int cnn_fc_bwd_weight(const float* in, const float* d_out, float* d_w, float* d_bias, int B, int I, int O,
-                      void* hip_stream) {
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!in || !d_out || !d_w || B < 1 || I < 1 || O < 1 || (size_t)I * O + O >= (size_t)1 << 30)
     return CNN_EINVAL;
   if (!aligned16(in) || !aligned16(d_out) || !aligned16(d_w) || (d_bias && !aligned16(d_bias)))
     return CNN_EINVAL;
+  if (workspace && workspace_bytes >= cnn_fc_bwd_weight_workspace_bytes(B, I, O) &&
+      cnn_fc_bwd_weight_workspace_bytes(B, I, O) > 0)
+    return cnn_conv_bwd_weight(in, d_out, d_w, d_bias, B, I, 1, 1, O, 1, 1, workspace, workspace_bytes,
+                               hip_stream);
   const unsigned blocks = (unsigned)(O * I + (d_bias ? O : 0));
   fc_bwd_weight_kernel<<<blocks, TPB, 0, (hipStream_t)hip_stream>>>(in, d_out, d_w, d_bias, B, I, O);
   return launched();

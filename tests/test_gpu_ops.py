@@ -20,9 +20,23 @@ def host(t):
     return t.cpu().numpy()
 
 
-# (B, Cin, H, W, Cout, KH, KW): the network's two layers, ragged shapes, 1x1 and full-size kernels
+# (B, Cin, H, W, Cout, KH, KW): the network's two layers, ragged shapes, 1x1 and full-size kernels,
+# more than 16 output maps (two M tiles) and more than 256 taps (two groups of N tiles), batches that
+# make every workgroup loop over several image groups with a ragged last one, and two shapes too
+# large for LDS (served by the plain kernels)
 CONV_CASES = [(3, 1, 28, 28, 6, 5, 5), (5, 6, 12, 12, 12, 5, 5), (2, 3, 9, 7, 4, 3, 2), (1, 2, 5, 5, 3, 1, 1),
-              (4, 12, 4, 4, 10, 4, 4), (1, 1, 6, 5, 1, 6, 5), (37, 2, 11, 13, 5, 4, 6)]
+              (4, 12, 4, 4, 10, 4, 4), (1, 1, 6, 5, 1, 6, 5), (37, 2, 11, 13, 5, 4, 6), (3, 3, 8, 8, 20, 3, 3),
+              (2, 30, 6, 6, 5, 3, 3), (2600, 2, 6, 6, 3, 3, 3), (1300, 6, 12, 12, 12, 5, 5), (131, 1, 3, 3, 1, 2, 2),
+              (2, 3, 80, 80, 4, 3, 3), (1, 40, 20, 20, 2, 5, 5)]
+
+
+def test_workspace_query_matches_the_kernel_choice():
+    L = binding.lib()
+    assert L.cnn_conv_bwd_weight_workspace_bytes(100, 6, 12, 12, 12, 5, 5) > 0
+    assert L.cnn_conv_bwd_weight_workspace_bytes(2, 3, 80, 80, 4, 3, 3) == 0      # does not fit in LDS
+    assert L.cnn_conv_bwd_weight_workspace_bytes(0, 6, 12, 12, 12, 5, 5) == 0     # invalid
+    assert L.cnn_fc_bwd_weight_workspace_bytes(100, 192, 10) == L.cnn_conv_bwd_weight_workspace_bytes(
+        100, 192, 1, 1, 10, 1, 1)
 
 
 def oracle_conv_fwd(x, k, b):
@@ -67,11 +81,12 @@ def test_conv_bwd_weight(case):
         for co in range(Cout):
             ref_k[co] += oracle.backweights(d[n, co][None].astype(np.float64), x[n].astype(np.float64))
             ref_b[co] += oracle.backbias(d[n, co].astype(np.float64))
-    d_k, d_b = binding.conv_bwd_weight(dev(x), dev(d))
-    assert_close(host(d_k), ref_k, RTOL_ACT, "conv_bwd_weight")
-    assert_close(host(d_b), ref_b, RTOL_ACT, "conv_bwd_bias")
-    d_k2, none = binding.conv_bwd_weight(dev(x), dev(d), want_bias=False)
-    assert none is None and torch.equal(d_k2, d_k)   # deterministic order
+    for workspace in (True, False):   # the matrix-core kernel, then the one that needs no workspace
+        d_k, d_b = binding.conv_bwd_weight(dev(x), dev(d), workspace=workspace)
+        assert_close(host(d_k), ref_k, RTOL_ACT, "conv_bwd_weight")
+        assert_close(host(d_b), ref_b, RTOL_ACT, "conv_bwd_bias")
+        d_k2, none = binding.conv_bwd_weight(dev(x), dev(d), want_bias=False, workspace=workspace)
+        assert none is None and torch.equal(d_k2, d_k)   # deterministic order
 
 
 @pytest.mark.parametrize("shape", [(2, 6, 24, 24), (3, 12, 8, 8), (1, 1, 2, 2), (5, 3, 6, 10)])
@@ -84,7 +99,7 @@ def test_avgpool_fwd_bwd(shape):
     assert abs(up.astype(np.float64).sum() - d.astype(np.float64).sum()) <= 1e-6 * np.abs(d).sum()
 
 
-@pytest.mark.parametrize("B,I,O", [(7, 192, 10), (1, 1, 1), (300, 33, 5)])
+@pytest.mark.parametrize("B,I,O", [(7, 192, 10), (1, 1, 1), (300, 33, 5), (5000, 192, 10), (70, 20, 300)])
 def test_fc(B, I, O):
     x, w, b = inputs.make_signed((B, I), 10), inputs.make_signed((O, I), 11), inputs.make_signed((O,), 12)
     d = inputs.make_signed((B, O), 13)
@@ -95,9 +110,10 @@ def test_fc(B, I, O):
     assert_close(host(binding.fc_fwd(dev(x), dev(w), dev(b))), x64 @ w64.T + b, RTOL_ACT, "fc_fwd")
     assert_close(host(binding.fc_fwd(dev(x), dev(w), None)), x64 @ w64.T, RTOL_ACT, "fc_fwd no bias")
     assert_close(host(binding.fc_bwd_input(dev(d), dev(w))), d64 @ w64, RTOL_ACT, "fc_bwd_input")
-    d_w, d_b = binding.fc_bwd_weight(dev(x), dev(d))
-    assert_close(host(d_w), d64.T @ x64, RTOL_ACT, "fc_bwd_weight")
-    assert_close(host(d_b), d64.sum(0), RTOL_ACT, "fc_bwd_bias")
+    for workspace in (True, False):
+        d_w, d_b = binding.fc_bwd_weight(dev(x), dev(d), workspace=workspace)
+        assert_close(host(d_w), d64.T @ x64, RTOL_ACT, "fc_bwd_weight")
+        assert_close(host(d_b), d64.sum(0), RTOL_ACT, "fc_bwd_bias")
 
 
 def test_logistic():
