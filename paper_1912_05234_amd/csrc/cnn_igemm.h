@@ -4,17 +4,19 @@
 // same operation with a kernel as large as its input (Section 3), here H = W = KH = KW = 1.
 //
 // Every operation is an implicit GEMM D[M x N] = A[M x K] * B[K x N] in 16 x 16 tiles with K taken four
-// at a time; lane l = 16 q + j of a wave supplies A[i = j][k = q] and B[k = q][j] and receives
-// D[i = 4 q + r][j] in result register r.  The operand that is gathered (image patches) is staged in
-// LDS once per group of images and addressed as (offset of the K index) + (offset of the N or M
-// index), both from small LDS tables, so no index arithmetic is left in the inner loop.
+// at a time (one "step"); lane l = 16 q + j of a wave supplies A[i = j][k = q] and B[k = q][j] and
+// receives D[i = 4 q + r][j] in result register r.  The operand that is gathered (image patches) is
+// staged in LDS once per group of images and addressed as (offset of the K index) + (offset of the N
+// index), both from small LDS tables, so no index arithmetic is left in the inner loop.  Steps are
+// taken in blocks of four: the dense operand and the K offsets of a block are one 16-byte LDS read
+// each, and the reads of block i + 1 are issued under the matrix instructions of block i.
 //
 //   forward          M = Cout          K = Cin*KH*KW        N = pixels of the group's outputs
 //   input gradient   M = Cin           K = Cout*KH*KW       N = pixels of the group's inputs; the
 //                    output error is staged with a zero border of (KH-1, KW-1) and the kernel is
 //                    read flipped, which turns backin into a forward convolution
-//   weight gradient  M = Cout          K = pixels of all images   N = Cin*KH*KW taps + one column of
-//                    ones (the bias gradient)
+//   weight gradient  M = Cout          K = pixels of all images   N = Cin*KH*KW taps; the bias
+//                    gradient is summed while the output error is staged
 #pragma once
 
 #include "cnn_common.h"
@@ -23,12 +25,25 @@ namespace cnn {
 namespace igemm {
 
 using f4 = float __attribute__((ext_vector_type(4)));
+using i4 = int __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ f4 mfma16(float a, float b, f4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
 constexpr int THREADS = 256;  // four waves per workgroup
 constexpr int WAVES = THREADS / 64;
+// Staged data of the next group of images travels through registers while the current group is
+// computed: up to PFV 16-byte items or PFS 4-byte items per thread (larger groups are copied
+// directly, without overlap).  Stage modes:
+constexpr int PFV = 8, PFS = 16;  // the scalar items live in the first PFS / 4 vector registers
+constexpr int STAGE_DIRECT = 0, STAGE_VECTOR = 1, STAGE_SCALAR = 2;
+
+// Workgroup barrier that orders LDS accesses only: global loads and stores stay in flight across it.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 
 // e / d and e % d for 0 <= e < 2^22, d >= 1, inv = 1.0f / d: the float estimate is off by at most
 // one and is corrected.
@@ -45,6 +60,77 @@ __device__ __forceinline__ void divmod(int e, int d, float inv, int& quo, int& r
   quo = qv;
   rem = rv;
 }
+__host__ __device__ inline int round4(int v) { return (v + 3) & ~3; }
+// Row stride (floats) of a table read 16 bytes per lane with one row per lane: a multiple of 4 that
+// is not a multiple of 8, so that eight consecutive rows start in eight different groups of four banks.
+__host__ __device__ inline int row_stride(int blocks) { return 4 * blocks + ((blocks & 1) ? 0 : 4); }
+
+// One block (four steps) of matrix instructions for NTILE accumulators: a[s] against b[s][t].
+template <int NTILE>
+__device__ __forceinline__ void block_mfma(f4 (&acc)[NTILE], const f4& a, const float (&b)[4][NTILE]) {
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int t = 0; t < NTILE; ++t) acc[t] = mfma16(a[s], b[s][t], acc[t]);
+}
+// The gathered operand of one block: b[s][t] = staged[k[s] + off[t]] (byte offsets).
+template <int NTILE>
+__device__ __forceinline__ void block_gather(float (&b)[4][NTILE], const char* staged, const i4& k,
+                                             const int (&off)[NTILE]) {
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int t = 0; t < NTILE; ++t) b[s][t] = *reinterpret_cast<const float*>(staged + k[s] + off[t]);
+}
+// Asks the scheduler to issue one LDS read after each matrix instruction of a block.
+template <int NTILE>
+__device__ __forceinline__ void block_interleave() {
+#pragma unroll
+  for (int i = 0; i < 4 * NTILE; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+}
+// Blocks first, first + stride, ... (count of them) of a GEMM for NTILE tiles that share the dense
+// operand: `dense` is the lane's row of 16-byte entries, `koff` the row of its q, both indexed by
+// block; `last` is the highest block index that may be read (prefetches are clamped to it).
+template <int NTILE>
+__device__ __forceinline__ void gemm_blocks(f4 (&acc)[NTILE], const f4* dense, const i4* koff,
+                                            const char* staged, const int (&off)[NTILE], int first,
+                                            int stride, int count, int last) {
+  if (count <= 0) return;
+  auto at = [&](int i) {
+    const int b = first + i * stride;
+    return b < last ? b : last;
+  };
+  i4 k0 = koff[at(0)], k1 = koff[at(1)];
+  f4 a0 = dense[at(0)], a1;
+  float b0[4][NTILE], b1[4][NTILE];
+  block_gather<NTILE>(b0, staged, k0, off);
+  int i = 0;
+  for (; i + 2 < count; i += 2) {  // two blocks per trip; at least one more block follows
+    a1 = dense[at(i + 1)];
+    block_gather<NTILE>(b1, staged, k1, off);
+    k0 = koff[at(i + 2)];
+    block_mfma<NTILE>(acc, a0, b0);
+    block_interleave<NTILE>();
+    a0 = dense[at(i + 2)];
+    block_gather<NTILE>(b0, staged, k0, off);
+    k1 = koff[at(i + 3)];
+    block_mfma<NTILE>(acc, a1, b1);
+    block_interleave<NTILE>();
+  }
+  if (i + 2 == count) {  // the last two blocks: nothing left to fetch ahead
+    a1 = dense[at(i + 1)];
+    block_gather<NTILE>(b1, staged, k1, off);
+    block_mfma<NTILE>(acc, a0, b0);
+    block_interleave<NTILE>();
+    block_mfma<NTILE>(acc, a1, b1);
+  } else {
+    block_mfma<NTILE>(acc, a0, b0);
+  }
+}
 
 // ---- forward and input gradient -----------------------------------------------------------------------
 // The staged tensor src[B][SC][SH][SW] is held in LDS per image as SC planes of LP floats with rows
@@ -60,51 +146,27 @@ struct ConvArgs {
   int pady, padx;      // origin of the data inside a plane
   int KH, KW, OH, OW;  // kernel and output extents
   int NB, groups;      // images per group, number of groups
-  int MT, S;           // tiles of M, steps of K
+  int MT, R;           // tiles of M; rows of an M tile held in LDS: min(16, M), row R stays zero
+  int NBK, SP;         // blocks of four K steps; row stride of the two K-indexed tables (floats)
   int flip;            // 0: A[m][(c,u,v)] = w[m][c][u][v];  1: A[m][(c,u,v)] = w[c][m][KH-1-u][KW-1-v]
   int zero_fill;       // the planes have a border that must read as zero
-  float inv_khkw, inv_kw, inv_ohow, inv_ow, inv_sw, inv_sh;
+  int stage;           // STAGE_*: VECTOR needs SC*SH*SW % 4 == 0 and no border
+  float inv_sp, inv_r1, inv_khkw, inv_kw, inv_ohow, inv_ow, inv_sw, inv_sh;
 };
-// LDS layout (floats / ints), in this order; sizes are rounded up to multiples of 4.
+// LDS layout in floats, in this order.
 struct ConvLds {
   int wt, koff, bias, poff, ooff, x, total;
 };
-__host__ __device__ inline int round4(int v) { return (v + 3) & ~3; }
 __host__ __device__ inline ConvLds conv_lds(const ConvArgs& a) {
   ConvLds l;
-  l.wt = 0;                              // [MT][S][64] A operand in lane order
-  l.koff = l.wt + a.MT * a.S * 64;       // [4 S] LDS offset of K index kk (0 for padding)
-  l.bias = l.koff + 4 * a.S;             // [16 MT]
-  l.poff = l.bias + 16 * a.MT;           // [NB*OH*OW] LDS offset of output pixel n
+  l.wt = 0;  // [MT*(R+1)*4 rows: M tile, row i, q][SP]: A[i][4 s + q] at [s]
+  l.koff = l.wt + a.MT * (a.R + 1) * 4 * a.SP;  // [4 rows: q][SP]: byte offset of K index 4 s + q (0 for padding)
+  l.bias = l.koff + 4 * a.SP;          // [16 MT]
+  l.poff = l.bias + 16 * a.MT;         // [NB*OH*OW] byte offset of output pixel n in the staged images
   l.ooff = l.poff + round4(a.NB * a.OH * a.OW);  // [NB*OH*OW] offset of pixel n in dst (channel 0)
   l.x = l.ooff + round4(a.NB * a.OH * a.OW);     // [NB*LI] staged images
   l.total = l.x + round4(a.NB * a.LI);
   return l;
-}
-
-// TP pixel tiles against the M tile whose A operands start at `wa` (lane part included): the
-// operands of step s + 1 and the K offset of step s + 2 are read while step s issues.
-template <int TP>
-__device__ __forceinline__ void conv_tiles(f4 (&acc)[TP], const float* wa, const int* ko, const float* x,
-                                           const int (&po)[TP], int S) {
-  int k1 = ko[0], k2 = ko[S > 1 ? 4 : 0];
-  float a = wa[0], b[TP];
-#pragma unroll
-  for (int t = 0; t < TP; ++t) b[t] = x[k1 + po[t]];
-  for (int s = 0; s < S; ++s) {
-    const int s1 = s + 1 < S ? s + 1 : S - 1, s2 = s + 2 < S ? s + 2 : S - 1;
-    const int k3 = ko[4 * s2];
-    const float an = wa[64 * s1];
-    float bn[TP];
-#pragma unroll
-    for (int t = 0; t < TP; ++t) bn[t] = x[k2 + po[t]];
-#pragma unroll
-    for (int t = 0; t < TP; ++t) acc[t] = mfma16(a, b[t], acc[t]);
-    a = an;
-    k2 = k3;
-#pragma unroll
-    for (int t = 0; t < TP; ++t) b[t] = bn[t];
-  }
 }
 
 template <int TP>
@@ -121,84 +183,153 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
   const int KHKW = g.KH * g.KW, OHOW = g.OH * g.OW;
 
   // ---- tables, once per workgroup ----
-  for (int e = t; e < g.MT * g.S * 64; e += THREADS) {
-    const int lane = e & 63, sidx = e >> 6, s = sidx % g.S, mt = sidx / g.S;
-    const int m = 16 * mt + (lane & 15), kk = 4 * s + (lane >> 4);
-    float v = 0.0f;
-    if (m < g.M && kk < g.K) {
-      if (!g.flip) {
-        v = g.w[(size_t)m * g.K + kk];
-      } else {
-        int c, rem, u, vv;
-        divmod(kk, KHKW, g.inv_khkw, c, rem);
-        divmod(rem, g.KW, g.inv_kw, u, vv);
-        v = g.w[((size_t)c * g.M + m) * KHKW + (g.KH - 1 - u) * g.KW + (g.KW - 1 - vv)];
+  const int wt_total = g.MT * (g.R + 1) * 4 * g.SP;
+  for (int e0 = t; e0 < wt_total; e0 += 4 * THREADS) {  // four independent loads in flight per thread
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = e0 + u * THREADS;
+      v[u] = 0.0f;
+      if (e < wt_total) {
+        int row, s, tile, ri;
+        divmod(e, g.SP, g.inv_sp, row, s);
+        divmod(row >> 2, g.R + 1, g.inv_r1, tile, ri);
+        const int m = 16 * tile + ri, kk = 4 * s + (row & 3);
+        if (ri < g.R && m < g.M && kk < g.K) {
+          if (!g.flip) {
+            v[u] = g.w[(size_t)m * g.K + kk];
+          } else {
+            int c, rem, uu, vv;
+            divmod(kk, KHKW, g.inv_khkw, c, rem);
+            divmod(rem, g.KW, g.inv_kw, uu, vv);
+            v[u] = g.w[((size_t)c * g.M + m) * KHKW + (g.KH - 1 - uu) * g.KW + (g.KW - 1 - vv)];
+          }
+        }
       }
     }
-    wt[e] = v;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (e0 + u * THREADS < wt_total) wt[e0 + u * THREADS] = v[u];
   }
-  for (int kk = t; kk < 4 * g.S; kk += THREADS) {
+  for (int e = t; e < 4 * g.SP; e += THREADS) {
+    int qq, s;
+    divmod(e, g.SP, g.inv_sp, qq, s);
+    const int kk = 4 * s + qq;
     int off = 0;
     if (kk < g.K) {
       int c, rem, u, vv;
       divmod(kk, KHKW, g.inv_khkw, c, rem);
       divmod(rem, g.KW, g.inv_kw, u, vv);
-      off = c * g.LP + u * g.LW + vv;
+      off = 4 * (c * g.LP + u * g.LW + vv);
     }
-    koff[kk] = off;
+    koff[e] = off;
   }
   for (int m = t; m < 16 * g.MT; m += THREADS) bl[m] = (g.bias && m < g.M) ? g.bias[m] : 0.0f;
   for (int n = t; n < g.NB * OHOW; n += THREADS) {
     int img, r, y, xx;
     divmod(n, OHOW, g.inv_ohow, img, r);
     divmod(r, g.OW, g.inv_ow, y, xx);
-    poff[n] = img * g.LI + y * g.LW + xx;
+    poff[n] = 4 * (img * g.LI + y * g.LW + xx);
     ooff[n] = img * g.M * OHOW + r;
   }
   if (g.zero_fill)
     for (int e = t; e < g.NB * g.LI; e += THREADS) x[e] = 0.0f;
 
   const int per_image = g.SC * g.SH * g.SW;
+  // LDS index of staged element e of a group (flat, or into the bordered planes)
+  auto target = [&](int e) {
+    if (!g.zero_fill) return e;
+    int row, xx, ic, y;
+    divmod(e, g.SW, g.inv_sw, row, xx);
+    divmod(row, g.SH, g.inv_sh, ic, y);
+    return ic * g.LP + (y + g.pady) * g.LW + g.padx + xx;
+  };
+  f4 pv[PFV];
+  int ptgt[PFS];
+  if (g.stage == STAGE_SCALAR) {
+#pragma unroll
+    for (int i = 0; i < PFS; ++i) {
+      const int e = t + THREADS * i;
+      ptgt[i] = e < g.NB * per_image ? target(e) : 0;
+    }
+  }
+  // Loads of group grp into registers (nothing for STAGE_DIRECT) ...
+  auto issue = [&](int grp) {
+    const int b0 = grp * g.NB, count = min(g.NB, g.B - b0) * per_image;
+    const float* src = g.src + (size_t)b0 * per_image;
+    if (g.stage == STAGE_VECTOR) {
+#pragma unroll
+      for (int i = 0; i < PFV; ++i)
+        if (t + THREADS * i < count >> 2) pv[i] = reinterpret_cast<const f4*>(src)[t + THREADS * i];
+    } else if (g.stage == STAGE_SCALAR) {
+#pragma unroll
+      for (int i = 0; i < PFS; ++i)
+        if (t + THREADS * i < count) pv[i >> 2][i & 3] = src[t + THREADS * i];
+    }
+  };
+  // ... and from there (or, STAGE_DIRECT, from memory) into LDS.
+  auto commit = [&](int grp) {
+    const int b0 = grp * g.NB, count = min(g.NB, g.B - b0) * per_image;
+    if (g.stage == STAGE_VECTOR) {
+#pragma unroll
+      for (int i = 0; i < PFV; ++i)
+        if (t + THREADS * i < count >> 2) reinterpret_cast<f4*>(x)[t + THREADS * i] = pv[i];
+    } else if (g.stage == STAGE_SCALAR) {
+#pragma unroll
+      for (int i = 0; i < PFS; ++i)
+        if (t + THREADS * i < count) x[ptgt[i]] = pv[i >> 2][i & 3];
+    } else {
+      const float* src = g.src + (size_t)b0 * per_image;
+      for (int e = t; e < count; e += THREADS) x[target(e)] = src[e];
+    }
+  };
+
+  if ((int)blockIdx.x < g.groups) issue(blockIdx.x);
   for (int grp = blockIdx.x; grp < g.groups; grp += gridDim.x) {
     const int b0 = grp * g.NB, nb = min(g.NB, g.B - b0);
-    const float* src = g.src + (size_t)b0 * per_image;
-    __syncthreads();  // tables (first pass) / the previous group's reads are complete
-    const int count = nb * per_image;
-    if (!g.zero_fill) {
-      for (int e = t; e < count; e += THREADS) x[e] = src[e];  // LI == per_image: a flat copy
-    } else {
-      for (int e = t; e < count; e += THREADS) {
-        int row, xx, ic, y;
-        divmod(e, g.SW, g.inv_sw, row, xx);
-        divmod(row, g.SH, g.inv_sh, ic, y);
-        x[ic * g.LP + (y + g.pady) * g.LW + g.padx + xx] = src[e];
-      }
-    }
-    __syncthreads();
+    lds_barrier();  // tables (first pass) / the previous group's reads are complete
+    commit(grp);
+    lds_barrier();
+    if (grp + (int)gridDim.x < g.groups) issue(grp + gridDim.x);
 
     const int N = nb * OHOW, PT = (N + 15) >> 4, PG = (PT + TP - 1) / TP;
-    float* dst = g.dst + (size_t)b0 * g.M * OHOW;
+    char* dst = reinterpret_cast<char*>(g.dst + (size_t)b0 * g.M * OHOW);  // byte offsets below fit 32 bits
     for (int job = wave; job < PG * g.MT; job += WAVES) {
       const int pg = job / g.MT, mt = job - pg * g.MT;
+      const int nrow = g.M - 16 * mt - 4 * q;  // result registers r < nrow of this lane are rows of D
+      const bool full = 16 * (pg * TP + TP) <= N;  // no padding pixels in this job's tiles
       int po[TP];
+      unsigned oo[TP];
       f4 acc[TP];
       const f4 binit = *reinterpret_cast<const f4*>(&bl[16 * mt + 4 * q]);
 #pragma unroll
       for (int tt = 0; tt < TP; ++tt) {
-        const int n = 16 * (pg * TP + tt) + j;
-        po[tt] = poff[n < N ? n : N - 1];
+        const int n = 16 * (pg * TP + tt) + j, nn = n < N ? n : N - 1;
+        po[tt] = poff[nn];
+        oo[tt] = 4u * (unsigned)(ooff[nn] + (16 * mt + 4 * q) * OHOW);
         acc[tt] = binit;
       }
-      conv_tiles<TP>(acc, wt + (size_t)mt * g.S * 64 + l, koff + q, x, po, g.S);
+      const int arow = (mt * (g.R + 1) + (16 * mt + j < g.M ? j : g.R)) * 4 + q;
+      gemm_blocks<TP>(acc, reinterpret_cast<const f4*>(wt + (size_t)arow * g.SP),
+                      reinterpret_cast<const i4*>(koff + q * g.SP), reinterpret_cast<const char*>(x), po, 0, 1,
+                      g.NBK, g.NBK - 1);
+      if (full) {  // wave-uniform: the common case carries no per-pixel predicates
 #pragma unroll
-      for (int tt = 0; tt < TP; ++tt) {
-        const int n = 16 * (pg * TP + tt) + j;
-        if (n < N) {
-          float* o = dst + ooff[n] + (size_t)(16 * mt + 4 * q) * OHOW;
+        for (int r = 0; r < 4; ++r)
+          if (r < nrow) {
 #pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if (16 * mt + 4 * q + r < g.M) o[(size_t)r * OHOW] = acc[tt][r];
-        }
+            for (int tt = 0; tt < TP; ++tt)
+              *reinterpret_cast<float*>(dst + (oo[tt] + 4u * (unsigned)(r * OHOW))) = acc[tt][r];
+          }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (r < nrow) {
+#pragma unroll
+            for (int tt = 0; tt < TP; ++tt)
+              if (16 * (pg * TP + tt) + j < N)
+                *reinterpret_cast<float*>(dst + (oo[tt] + 4u * (unsigned)(r * OHOW))) = acc[tt][r];
+          }
       }
     }
   }
@@ -206,59 +337,44 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
 
 // ---- weight and bias gradient --------------------------------------------------------------------------
 // in[B][Cin][H][W], d_out[B][Cout][Ho][Wo].  Workgroup (bx, by) sums the images of groups bx, bx +
-// gridDim.x, ... into the D tiles of M tile mt = by / NTG and N tiles 16 (by % NTG) + wave + 4 i
-// (i < 4), and writes them to part[bx][mt][nt][16][16].  Column K of D is the bias gradient.
+// gridDim.x, ... for M tile mt = by / NTG and the tap tiles of group ntg = by % NTG.  With three or
+// more tap tiles in all, wave w owns tiles 16 ntg + w + 4 i (i < 4) and KS = 1; with two (one) tap
+// tiles the waves split the pixels as well: tile w % 2 (0), K slice w / 2 (w) of KS = 2 (4), a slice
+// taking every KS-th block.  Results go to part[bx*KS + slice][mt][nt][16][16] and, for ntg = 0, the
+// bias sums to bpart[bx][16 mt + c] (bpart follows part).
 struct WgradArgs {
   const float* in;
   const float* d_out;
   float* part;
   int B, Cin, H, W, Cout, Ho, Wo, KH, KW;
   int K;          // Cin*KH*KW taps
-  int MT, NT;     // tiles of Cout and of K + 1 columns
-  int NTG;        // groups of 16 N tiles
+  int MT, NT;     // tiles of Cout and of the K taps
+  int NTG;        // groups of 16 tap tiles
+  int KS;         // K slices per workgroup
+  int R;          // rows of the staged error: min(16, Cout); row R stays zero
   int NB, groups;
-  int NP;         // pixel slots of a group: NB*Ho*Wo rounded up to a multiple of 4
-  int NPS;        // row stride of the staged error, NP rounded up to 2 mod 32 (conflict-free A reads)
+  int NBK, SP;    // blocks of 16 pixel slots per full group; row stride of the K-indexed tables
+  int stage_x;    // STAGE_* of the input images (VECTOR needs Cin*H*W % 4 == 0)
+  int stage_d;    // STAGE_SCALAR: the output error travels through registers (needs 16 NBK <= THREADS*PFD)
   float inv_khkw, inv_kw, inv_howo, inv_wo;
 };
+constexpr int PFD = 2;  // pixel slots per thread of the output error held in registers (all 16 channels)
 struct WgradLds {
   int pb, so, dy, x, total;
 };
 __host__ __device__ inline WgradLds wgrad_lds(const WgradArgs& a) {
   WgradLds l;
-  l.pb = 0;                 // [NP] LDS offset of pixel slot n in x (0 for padding slots)
-  l.so = l.pb + a.NP;       // [NP] offset of pixel slot n in d_out (channel 0), -1 for padding slots
-  l.dy = l.so + a.NP;       // [16][NPS] output error of the M tile, zero in padding slots
-  l.x = l.dy + 16 * a.NPS;  // [NB][Cin*H*W]
+  l.pb = 0;                         // [4 rows: q][SP] byte offset in x of pixel slot 4 s + q (0 for padding)
+  l.so = l.pb + 4 * a.SP;           // [16 NBK] offset of pixel slot n in d_out (channel 0)
+  l.dy = l.so + 16 * a.NBK;         // [(R + 1)*4 rows: channel, q][SP] output error at slot 4 s + q
+  l.x = l.dy + (a.R + 1) * 4 * a.SP;  // [NB][Cin*H*W]
   l.total = l.x + round4(a.NB * a.Cin * a.H * a.W);
   return l;
 }
 
-template <int TW>
-__device__ __forceinline__ void wgrad_tiles(f4 (&acc)[4], const float* da, const int* pb, const float* x,
-                                            const int (&toff)[4], const bool (&ones)[4], int S) {
-  int p1 = pb[0], p2 = pb[S > 1 ? 4 : 0];
-  float a = da[0], b[TW];
-#pragma unroll
-  for (int i = 0; i < TW; ++i) b[i] = ones[i] ? 1.0f : x[p1 + toff[i]];
-  for (int s = 0; s < S; ++s) {
-    const int s1 = s + 1 < S ? s + 1 : S - 1, s2 = s + 2 < S ? s + 2 : S - 1;
-    const int p3 = pb[4 * s2];
-    const float an = da[4 * s1];
-    float bn[TW];
-#pragma unroll
-    for (int i = 0; i < TW; ++i) bn[i] = ones[i] ? 1.0f : x[p2 + toff[i]];
-#pragma unroll
-    for (int i = 0; i < TW; ++i) acc[i] = mfma16(a, b[i], acc[i]);
-    a = an;
-    p2 = p3;
-#pragma unroll
-    for (int i = 0; i < TW; ++i) b[i] = bn[i];
-  }
-}
-
-__global__ __launch_bounds__(THREADS) void wgrad_kernel(const WgradArgs g) {
+__global__ __launch_bounds__(THREADS, 2) void wgrad_kernel(const WgradArgs g) {
   extern __shared__ __align__(16) float lds[];
+  __shared__ float bred[WAVES][16];
   const WgradLds L = wgrad_lds(g);
   int* pb = reinterpret_cast<int*>(lds + L.pb);
   int* so = reinterpret_cast<int*>(lds + L.so);
@@ -267,90 +383,223 @@ __global__ __launch_bounds__(THREADS) void wgrad_kernel(const WgradArgs g) {
   const int t = threadIdx.x, wave = t >> 6, l = t & 63, q = l >> 4, j = l & 15;
   const int KHKW = g.KH * g.KW, HoWo = g.Ho * g.Wo, HW = g.H * g.W, per_image = g.Cin * HW;
   const int mt = blockIdx.y / g.NTG, ntg = blockIdx.y - mt * g.NTG;
+  const int rows = min(16, g.Cout - 16 * mt);
 
-  for (int n = t; n < g.NP; n += THREADS) {
-    int pbv = 0, sov = -1;
+  for (int n = t; n < 16 * g.NBK; n += THREADS) {
+    int pbv = 0, sov = 0;
     if (n < g.NB * HoWo) {
       int img, r, y, xx;
       divmod(n, HoWo, g.inv_howo, img, r);
       divmod(r, g.Wo, g.inv_wo, y, xx);
-      pbv = img * per_image + y * g.W + xx;
+      pbv = 4 * (img * per_image + y * g.W + xx);
       sov = img * g.Cout * HoWo + r;
     }
-    pb[n] = pbv;
+    pb[(n & 3) * g.SP + (n >> 2)] = pbv;
     so[n] = sov;
   }
-  // this lane's column of each of the wave's tiles
-  int toff[4], nvalid = 0;
-  bool ones[4];
+  for (int e = t; e < 4 * g.SP; e += THREADS) dy[g.R * 4 * g.SP + e] = 0.0f;  // the zero row
+
+  // this wave's tiles and K slice; this lane's column (tap) of each tile
+  const int tile0 = g.KS == 1 ? wave : g.KS == 2 ? (wave & 1) : 0;
+  const int slice = g.KS == 1 ? 0 : g.KS == 2 ? (wave >> 1) : wave;
+  int toff[4], ntile = 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int nt = 16 * ntg + wave + 4 * i, col = 16 * nt + j;
-    if (nt < g.NT) nvalid = i + 1;
+    const int nt = 16 * ntg + tile0 + 4 * i, col = 16 * nt + j;
+    if (nt < g.NT && (g.KS == 1 || i == 0)) ntile = i + 1;
     toff[i] = 0;
-    ones[i] = col == g.K;
     if (col < g.K) {
       int c, rem, u, vv;
       divmod(col, KHKW, g.inv_khkw, c, rem);
       divmod(rem, g.KW, g.inv_kw, u, vv);
-      toff[i] = c * HW + u * g.W + vv;
+      toff[i] = 4 * (c * HW + u * g.W + vv);
     }
   }
   f4 acc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) acc[i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+  float bsum[16];
+#pragma unroll
+  for (int c = 0; c < 16; ++c) bsum[c] = 0.0f;
+  const f4* dense = reinterpret_cast<const f4*>(dy + (size_t)((j < rows ? j : g.R) * 4 + q) * g.SP);
+  const i4* koff = reinterpret_cast<const i4*>(pb + q * g.SP);
 
-  for (int grp = blockIdx.x; grp < g.groups; grp += gridDim.x) {
-    const int b0 = grp * g.NB, nb = min(g.NB, g.B - b0);
-    __syncthreads();
+  // Staging: the images as they are (zero past the last image of a ragged group); the output error
+  // of the M tile's channels by pixel slot, zero past the group's pixels, summed per channel on the
+  // way.  Thread t always handles slots t, t + THREADS, ..., so the bias sums do not depend on the path.
+  f4 pv[PFV];
+  float pd[PFD][16];
+  int sreg[PFD];
+#pragma unroll
+  for (int i = 0; i < PFD; ++i) sreg[i] = 0;
+  auto issue = [&](int grp) {
+    const int b0 = grp * g.NB, nb = min(g.NB, g.B - b0), count = nb * per_image, npx = nb * HoWo;
     const float* src = g.in + (size_t)b0 * per_image;
-    for (int e = t; e < g.NB * per_image; e += THREADS) x[e] = e < nb * per_image ? src[e] : 0.0f;
-    const float* dsrc = g.d_out + (size_t)b0 * g.Cout * HoWo;
-    const int nvalid_px = nb * HoWo;
-    for (int c = 0; c < 16; ++c) {
-      const int co = 16 * mt + c;
-      for (int n = t; n < g.NP; n += THREADS)
-        dy[c * g.NPS + n] = (co < g.Cout && n < nvalid_px) ? dsrc[so[n] + (size_t)co * HoWo] : 0.0f;
+    if (g.stage_x == STAGE_VECTOR) {
+#pragma unroll
+      for (int i = 0; i < PFV; ++i)
+        if (t + THREADS * i < count >> 2) pv[i] = reinterpret_cast<const f4*>(src)[t + THREADS * i];
+    } else if (g.stage_x == STAGE_SCALAR) {
+#pragma unroll
+      for (int i = 0; i < PFS; ++i)
+        if (t + THREADS * i < count) pv[i >> 2][i & 3] = src[t + THREADS * i];
     }
-    __syncthreads();
-    const int S = (nvalid_px + 3) >> 2;  // slots past nvalid_px up to the next multiple of 4 are zero
-    const float* da = dy + j * g.NPS + q;
-    switch (nvalid) {
-      case 4: wgrad_tiles<4>(acc, da, pb + q, x, toff, ones, S); break;
-      case 3: wgrad_tiles<3>(acc, da, pb + q, x, toff, ones, S); break;
-      case 2: wgrad_tiles<2>(acc, da, pb + q, x, toff, ones, S); break;
-      case 1: wgrad_tiles<1>(acc, da, pb + q, x, toff, ones, S); break;
+    if (g.stage_d == STAGE_SCALAR) {
+      const float* dsrc = g.d_out + ((size_t)b0 * g.Cout + 16 * mt) * HoWo;
+#pragma unroll
+      for (int i = 0; i < PFD; ++i)
+        if (t + THREADS * i < npx) {
+#pragma unroll
+          for (int c = 0; c < 16; ++c)
+            if (c < rows) pd[i][c] = dsrc[(size_t)c * HoWo + sreg[i]];
+        }
+    }
+  };
+  auto commit = [&](int grp) {
+    const int b0 = grp * g.NB, nb = min(g.NB, g.B - b0), count = nb * per_image, npx = nb * HoWo;
+    const int nbk = (npx + 15) >> 4;  // slots npx .. 16 nbk - 1 are staged as zero
+    if (g.stage_x == STAGE_VECTOR) {
+#pragma unroll
+      for (int i = 0; i < PFV; ++i) {
+        const int e = t + THREADS * i;
+        if (e < (g.NB * per_image) >> 2)
+          reinterpret_cast<f4*>(x)[e] = e < count >> 2 ? pv[i] : f4{0.0f, 0.0f, 0.0f, 0.0f};
+      }
+    } else if (g.stage_x == STAGE_SCALAR) {
+#pragma unroll
+      for (int i = 0; i < PFS; ++i) {
+        const int e = t + THREADS * i;
+        if (e < g.NB * per_image) x[e] = e < count ? pv[i >> 2][i & 3] : 0.0f;
+      }
+    } else {
+      const float* src = g.in + (size_t)b0 * per_image;
+      for (int e = t; e < g.NB * per_image; e += THREADS) x[e] = e < count ? src[e] : 0.0f;
+    }
+    if (g.stage_d == STAGE_SCALAR) {
+#pragma unroll
+      for (int i = 0; i < PFD; ++i) {
+        const int n = t + THREADS * i;
+        if (n < 16 * nbk) {
+#pragma unroll
+          for (int c = 0; c < 16; ++c)
+            if (c < rows) {
+              const float v = n < npx ? pd[i][c] : 0.0f;
+              dy[(c * 4 + (n & 3)) * g.SP + (n >> 2)] = v;
+              bsum[c] += v;
+            }
+        }
+      }
+    } else {
+      const float* dsrc = g.d_out + ((size_t)b0 * g.Cout + 16 * mt) * HoWo;
+      for (int n = t; n < 16 * nbk; n += THREADS) {
+        const int sv = so[n];
+        float v[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) v[c] = (c < rows && n < npx) ? dsrc[(size_t)c * HoWo + sv] : 0.0f;
+#pragma unroll
+        for (int c = 0; c < 16; ++c)
+          if (c < rows) {
+            dy[(c * 4 + (n & 3)) * g.SP + (n >> 2)] = v[c];
+            bsum[c] += v[c];
+          }
+      }
+    }
+  };
+
+  lds_barrier();  // tables
+  if (g.stage_d == STAGE_SCALAR) {
+#pragma unroll
+    for (int i = 0; i < PFD; ++i)
+      if (t + THREADS * i < 16 * g.NBK) sreg[i] = so[t + THREADS * i];
+  }
+  if ((int)blockIdx.x < g.groups) issue(blockIdx.x);
+  for (int grp = blockIdx.x; grp < g.groups; grp += gridDim.x) {
+    const int nbk = (min(g.NB, g.B - grp * g.NB) * HoWo + 15) >> 4;
+    lds_barrier();  // the previous group's reads are complete
+    commit(grp);
+    lds_barrier();
+    if (grp + (int)gridDim.x < g.groups) issue(grp + gridDim.x);
+    const int count = nbk > slice ? (nbk - slice + g.KS - 1) / g.KS : 0;
+    const char* xb = reinterpret_cast<const char*>(x);
+    switch (ntile) {
+      case 4: gemm_blocks<4>(acc, dense, koff, xb, toff, slice, g.KS, count, nbk - 1); break;
+      case 3: {
+        f4(&a3)[3] = reinterpret_cast<f4(&)[3]>(acc);
+        const int(&t3)[3] = reinterpret_cast<const int(&)[3]>(toff);
+        gemm_blocks<3>(a3, dense, koff, xb, t3, slice, g.KS, count, nbk - 1);
+        break;
+      }
+      case 2: {
+        f4(&a2)[2] = reinterpret_cast<f4(&)[2]>(acc);
+        const int(&t2)[2] = reinterpret_cast<const int(&)[2]>(toff);
+        gemm_blocks<2>(a2, dense, koff, xb, t2, slice, g.KS, count, nbk - 1);
+        break;
+      }
+      case 1: {
+        f4(&a1)[1] = reinterpret_cast<f4(&)[1]>(acc);
+        const int(&t1)[1] = reinterpret_cast<const int(&)[1]>(toff);
+        gemm_blocks<1>(a1, dense, koff, xb, t1, slice, g.KS, count, nbk - 1);
+        break;
+      }
       default: break;
     }
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int nt = 16 * ntg + wave + 4 * i;
-    if (nt < g.NT) {
-      float* o = g.part + (((size_t)blockIdx.x * g.MT + mt) * g.NT + nt) * 256 + 64 * q + j;
+    const int nt = 16 * ntg + tile0 + 4 * i;
+    if (i < ntile) {
+      float* o = g.part + ((((size_t)blockIdx.x * g.KS + slice) * g.MT + mt) * g.NT + nt) * 256 + 64 * q + j;
 #pragma unroll
       for (int r = 0; r < 4; ++r) o[16 * r] = acc[i][r];
     }
   }
+  if (ntg == 0) {  // bias sums: lanes by a fixed butterfly, then the four waves in order
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+      float v = bsum[c];
+#pragma unroll
+      for (int m = 32; m > 0; m >>= 1) v += __shfl_xor(v, m, 64);
+      if (l == 0) bred[wave][c] = v;
+    }
+    lds_barrier();
+    if (t < 16) {
+      float* bpart = g.part + (size_t)gridDim.x * g.KS * g.MT * g.NT * 256;
+      bpart[(size_t)blockIdx.x * g.MT * 16 + 16 * mt + t] = (bred[0][t] + bred[1][t]) + (bred[2][t] + bred[3][t]);
+    }
+  }
 }
 
-// d_k[co][tap] and d_bias[co] = sum over the G partial tiles in ascending order of g within sixteen
-// interleaved strands, the strands then combined by a fixed tree: one thread strand per output.
-__global__ __launch_bounds__(THREADS) void wgrad_reduce_kernel(const float* __restrict__ part, int G, int MT,
-                                                               int NT, int Cout, int K,
+// d_k[co][tap] = sum over the GP partial tiles, d_bias[co] = sum over the GB partial bias rows, each
+// in sixteen interleaved strands taken in ascending order and combined by a fixed tree.
+__global__ __launch_bounds__(THREADS) void wgrad_reduce_kernel(const float* __restrict__ part, int GP, int GB,
+                                                               int MT, int NT, int Cout, int K,
                                                                float* __restrict__ d_k,
                                                                float* __restrict__ d_bias) {
   __shared__ float red[THREADS];
   const int strand = threadIdx.x >> 4, el = blockIdx.x * 16 + (threadIdx.x & 15);
-  const int total = Cout * (K + 1);
+  const int nk = Cout * K, total = nk + (d_bias ? Cout : 0);
   float sum = 0.0f;
-  int co = 0, col = 0;
   if (el < total) {
-    co = el / (K + 1);
-    col = el - co * (K + 1);
-    const float* p = part + ((size_t)(co >> 4) * NT + (col >> 4)) * 256 + (co & 15) * 16 + (col & 15);
-    const size_t gstride = (size_t)MT * NT * 256;
-    for (int gi = strand; gi < G; gi += 16) sum += p[gi * gstride];
+    const float* p;
+    size_t stride;
+    int G;
+    if (el < nk) {
+      const int co = el / K, col = el - co * K;
+      p = part + ((size_t)(co >> 4) * NT + (col >> 4)) * 256 + (co & 15) * 16 + (col & 15);
+      stride = (size_t)MT * NT * 256;
+      G = GP;
+    } else {
+      p = part + (size_t)GP * MT * NT * 256 + (el - nk);
+      stride = (size_t)MT * 16;
+      G = GB;
+    }
+    int gi = strand;
+    for (; gi + 48 < G; gi += 64) {
+      const float v0 = p[gi * stride], v1 = p[(gi + 16) * stride], v2 = p[(gi + 32) * stride],
+                  v3 = p[(gi + 48) * stride];
+      sum = (((sum + v0) + v1) + v2) + v3;
+    }
+    for (; gi < G; gi += 16) sum += p[gi * stride];
   }
   red[threadIdx.x] = sum;
   __syncthreads();
@@ -359,10 +608,10 @@ __global__ __launch_bounds__(THREADS) void wgrad_reduce_kernel(const float* __re
     __syncthreads();
   }
   if (strand == 0 && el < total) {
-    if (col < K)
-      d_k[(size_t)co * K + col] = red[threadIdx.x];
-    else if (d_bias)
-      d_bias[co] = red[threadIdx.x];
+    if (el < nk)
+      d_k[el] = red[threadIdx.x];
+    else
+      d_bias[el - nk] = red[threadIdx.x];
   }
 }
 

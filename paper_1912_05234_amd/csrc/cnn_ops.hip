@@ -204,10 +204,20 @@ __global__ __launch_bounds__(TPB) void logistic_bwd_kernel(const float* __restri
 inline int launched() { return hipGetLastError() == hipSuccess ? CNN_OK : CNN_EHIP; }
 
 // ---- launch plans of the matrix-core kernels ----------------------------------------------------
-constexpr int LDS_LIMIT = 64 * 1024;   // bytes of LDS one workgroup may use
-constexpr int LDS_TARGET = 36 * 1024;  // preferred, so that four workgroups share a compute unit
-constexpr int MAX_GROUP = 64;          // images per group
-constexpr int MAX_PARTIALS = 512;      // workgroups (partial sums) of the weight gradient
+constexpr int LDS_LIMIT = 64 * 1024 - 512;  // bytes of dynamic LDS one workgroup may ask for
+constexpr int LDS_TARGET = 48 * 1024;       // preferred, so that three workgroups share a compute unit
+constexpr int CU_LDS = 160 * 1024;
+constexpr int NUM_CU = 256;
+constexpr int MAX_GROUP = 64;               // images per group
+constexpr int MAX_PARTIALS = 512;           // workgroup columns (partial sums) of the weight gradient
+
+// Workgroups that keep every compute unit as full as the LDS use allows (at most four each).
+unsigned resident_workgroups(size_t lds_bytes) {
+  size_t per_cu = CU_LDS / (lds_bytes + 512);
+  if (per_cu > 8) per_cu = 8;
+  if (per_cu < 1) per_cu = 1;
+  return (unsigned)(NUM_CU * per_cu);
+}
 
 struct ConvPlan {
   igemm::ConvArgs a;
@@ -225,30 +235,47 @@ ConvPlan plan_conv(const float* src, const float* w, const float* bias, float* d
   a.B = B, a.M = M, a.SC = SC, a.SH = SH, a.SW = SW, a.KH = KH, a.KW = KW, a.OH = OH, a.OW = OW;
   a.pady = pady, a.padx = padx, a.flip = flip, a.zero_fill = (pady || padx) ? 1 : 0;
   const long long K = (long long)SC * KH * KW, LW = SW + 2LL * padx, LP = (SH + 2LL * pady) * LW, LI = SC * LP;
-  const long long OHOW = (long long)OH * OW, MT = (M + 15) / 16, S = (K + 3) / 4;
-  if (MT * S * 64 + 4 * S + 16 * MT + LI + 2 * OHOW + 16 > LDS_LIMIT / 4) return p;  // not even one image
-  a.K = (int)K, a.LW = (int)LW, a.LP = (int)LP, a.LI = (int)LI, a.MT = (int)MT, a.S = (int)S;
+  const long long OHOW = (long long)OH * OW, MT = (M + 15) / 16, NBK = (K + 15) / 16;
+  const long long R = M < 16 ? M : 16;
+  if ((MT * (R + 1) * 4 + 4) * (4 * NBK + 4) + 16 * MT + LI + 2 * OHOW + 16 > LDS_LIMIT / 4) return p;  // not even one image
+  a.K = (int)K, a.LW = (int)LW, a.LP = (int)LP, a.LI = (int)LI, a.MT = (int)MT, a.R = (int)R, a.NBK = (int)NBK;
+  a.SP = igemm::row_stride(a.NBK);
   auto bytes = [&](int nb) {
     a.NB = nb;
     return (long long)igemm::conv_lds(a).total * 4;
   };
   if (bytes(1) > LDS_LIMIT) return p;
-  int nb_limit = 1, nb_target = 1;
-  for (int nb = 2; nb <= MAX_GROUP && nb <= B && bytes(nb) <= LDS_LIMIT; ++nb) {
-    nb_limit = nb;
-    if (bytes(nb) <= LDS_TARGET) nb_target = nb;
+  // Images per group: enough for four pixel tiles, more when the batch is large, within the LDS
+  // target; among the admissible sizes the one that wastes the fewest matrix instructions on
+  // padding tiles and idle waves.
+  const int nb_tiles = (int)((64 + OHOW - 1) / OHOW);
+  int nb_want = (B + 2047) / 2048;
+  if (nb_want < nb_tiles) nb_want = nb_tiles;
+  if (nb_want > MAX_GROUP) nb_want = MAX_GROUP;
+  if (nb_want > B) nb_want = B;
+  double best = -1.0;
+  int best_nb = 1, best_tp = 1;
+  for (int nb = 1; nb <= nb_want; ++nb) {
+    const long long by = bytes(nb);
+    if (by > LDS_LIMIT || (by > LDS_TARGET && nb > nb_tiles)) break;
+    for (int tp = 4; tp >= 1; tp >>= 1) {
+      const long long PT = (nb * OHOW + 15) / 16, jobs = ((PT + tp - 1) / tp) * MT;
+      const double used = (double)nb * OHOW / 16.0 * MT, slots = (double)((jobs + 3) / 4) * 4 * tp;
+      const double score = used / slots * (tp == 4 ? 1.02 : 1.0);  // ties: share the dense operand
+      if (score >= best) best = score, best_nb = nb, best_tp = tp;
+    }
   }
-  const int nb_tiles = (int)((64 + OHOW - 1) / OHOW);  // four tiles of pixels, one per wave
-  const int nb_fill = (B + 1023) / 1024;               // beyond about a thousand groups, larger ones
-  int nb = nb_tiles > nb_fill ? nb_tiles : nb_fill;
-  const int cap = nb_target >= nb_tiles ? nb_target : nb_limit;
-  if (nb > cap) nb = cap;
-  a.NB = nb;
-  a.groups = (B + nb - 1) / nb;
-  const long long PT = (nb * OHOW + 15) / 16;
-  p.tp = PT * MT >= 16 ? 4 : PT * MT >= 8 ? 2 : 1;
-  p.grid = (unsigned)(a.groups < 2048 ? a.groups : 2048);
-  p.lds_bytes = (size_t)bytes(nb);
+  a.NB = best_nb;
+  p.tp = best_tp;
+  a.groups = (B + a.NB - 1) / a.NB;
+  p.lds_bytes = (size_t)bytes(a.NB);
+  const unsigned resident = resident_workgroups(p.lds_bytes);
+  p.grid = (unsigned)a.groups < resident ? (unsigned)a.groups : resident;
+  const long long per_image = (long long)SC * SH * SW, per_group = a.NB * per_image;
+  a.stage = (!a.zero_fill && per_image % 4 == 0 && per_group / 4 <= igemm::THREADS * igemm::PFV)
+                ? igemm::STAGE_VECTOR
+                : per_group <= igemm::THREADS * igemm::PFS ? igemm::STAGE_SCALAR : igemm::STAGE_DIRECT;
+  a.inv_sp = 1.0f / (float)a.SP, a.inv_r1 = 1.0f / (float)(a.R + 1);
   a.inv_khkw = 1.0f / (float)(KH * KW), a.inv_kw = 1.0f / (float)KW, a.inv_ohow = 1.0f / (float)OHOW;
   a.inv_ow = 1.0f / (float)OW, a.inv_sw = 1.0f / (float)SW, a.inv_sh = 1.0f / (float)SH;
   return p;
@@ -277,12 +304,14 @@ WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
   a.B = B, a.Cin = Cin, a.H = H, a.W = W, a.Cout = Cout, a.KH = KH, a.KW = KW;
   a.Ho = H - KH + 1, a.Wo = W - KW + 1;
   const long long K = (long long)Cin * KH * KW, HoWo = (long long)a.Ho * a.Wo, per_image = (long long)Cin * H * W;
-  if (per_image + 18 * (HoWo + 36) > LDS_LIMIT / 4 || K + 1 > (1 << 20)) return p;
-  a.K = (int)K, a.MT = (Cout + 15) / 16, a.NT = (int)((K + 1 + 15) / 16), a.NTG = (a.NT + 15) / 16;
+  if (per_image + 10 * (HoWo + 36) > LDS_LIMIT / 4 || K > (1 << 20)) return p;
+  a.K = (int)K, a.MT = (Cout + 15) / 16, a.NT = (int)((K + 15) / 16), a.NTG = (a.NT + 15) / 16;
+  a.KS = a.NT >= 3 ? 1 : a.NT == 2 ? 2 : 4;
+  a.R = Cout < 16 ? Cout : 16;
   auto bytes = [&](int nb) {
     a.NB = nb;
-    a.NP = igemm::round4((int)(nb * HoWo));
-    a.NPS = a.NP + ((2 - a.NP) % 32 + 32) % 32;
+    a.NBK = (int)((nb * HoWo + 15) / 16);
+    a.SP = igemm::row_stride(a.NBK);
     return (long long)igemm::wgrad_lds(a).total * 4;
   };
   if (bytes(1) > LDS_LIMIT) return p;
@@ -291,9 +320,18 @@ WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
   for (int c = 2; c <= MAX_GROUP && c <= B && c <= nb_fill && bytes(c) <= LDS_TARGET; ++c) nb = c;
   p.lds_bytes = (size_t)bytes(nb);
   a.groups = (B + nb - 1) / nb;
-  p.gx = (unsigned)(a.groups < MAX_PARTIALS ? a.groups : MAX_PARTIALS);
+  unsigned gx = resident_workgroups(p.lds_bytes) / (unsigned)(a.MT * a.NTG);
+  if (gx < 1) gx = 1;
+  if (gx > MAX_PARTIALS) gx = MAX_PARTIALS;
+  if (gx > (unsigned)a.groups) gx = (unsigned)a.groups;
+  p.gx = gx;
   p.gy = (unsigned)(a.MT * a.NTG);
-  p.workspace_bytes = (size_t)p.gx * a.MT * a.NT * 256 * sizeof(float);
+  p.workspace_bytes = ((size_t)gx * a.KS * a.MT * a.NT * 256 + (size_t)gx * a.MT * 16) * sizeof(float);
+  const long long per_group = nb * per_image;
+  a.stage_x = (per_image % 4 == 0 && per_group / 4 <= igemm::THREADS * igemm::PFV)
+                  ? igemm::STAGE_VECTOR
+                  : per_group <= igemm::THREADS * igemm::PFS ? igemm::STAGE_SCALAR : igemm::STAGE_DIRECT;
+  a.stage_d = 16 * a.NBK <= igemm::THREADS * igemm::PFD ? igemm::STAGE_SCALAR : igemm::STAGE_DIRECT;
   a.inv_khkw = 1.0f / (float)(KH * KW), a.inv_kw = 1.0f / (float)KW;
   a.inv_howo = 1.0f / (float)HoWo, a.inv_wo = 1.0f / (float)a.Wo;
   p.fits = true;
@@ -350,9 +388,9 @@ int cnn_conv_bwd_weight(const float* in, const float* d_out, float* d_k, float* 
   if (p.fits && workspace && workspace_bytes >= p.workspace_bytes) {
     p.a.in = in, p.a.d_out = d_out, p.a.part = static_cast<float*>(workspace);
     igemm::wgrad_kernel<<<dim3(p.gx, p.gy), igemm::THREADS, p.lds_bytes, (hipStream_t)hip_stream>>>(p.a);
-    const unsigned blocks = (unsigned)(((size_t)Cout * (p.a.K + 1) + 15) / 16);
+    const unsigned blocks = (unsigned)(((size_t)Cout * p.a.K + Cout + 15) / 16);
     igemm::wgrad_reduce_kernel<<<blocks, igemm::THREADS, 0, (hipStream_t)hip_stream>>>(
-        p.a.part, (int)p.gx, p.a.MT, p.a.NT, Cout, p.a.K, d_k, d_bias);
+        p.a.part, (int)p.gx * p.a.KS, (int)p.gx, p.a.MT, p.a.NT, Cout, p.a.K, d_k, d_bias);
     return launched();
   }
   const unsigned blocks = (unsigned)(Cout * Cin * KH * KW + (d_bias ? Cout : 0));
