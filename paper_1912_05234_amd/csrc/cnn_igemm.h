@@ -93,9 +93,10 @@ __device__ __forceinline__ void block_interleave() {
   __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 }
 // Blocks first, first + stride, ... (count of them) of a GEMM for NTILE tiles that share the dense
-// operand: `dense` is the lane's row of 16-byte entries, `koff` the row of its q, both indexed by
-// block; `last` is the highest block index that may be read (prefetches are clamped to it).
-template <int NTILE>
+// operand: `dense` points at the lane's 16-byte entry of block 0, the entries of consecutive blocks
+// DSTEP entries apart; `koff` is the row of its q, indexed by block; `last` is the highest block index
+// that may be read (prefetches are clamped to it).
+template <int NTILE, int DSTEP>
 __device__ __forceinline__ void gemm_blocks(f4 (&acc)[NTILE], const f4* dense, const i4* koff,
                                             const char* staged, const int (&off)[NTILE], int first,
                                             int stride, int count, int last) {
@@ -105,24 +106,24 @@ __device__ __forceinline__ void gemm_blocks(f4 (&acc)[NTILE], const f4* dense, c
     return b < last ? b : last;
   };
   i4 k0 = koff[at(0)], k1 = koff[at(1)];
-  f4 a0 = dense[at(0)], a1;
+  f4 a0 = dense[DSTEP * at(0)], a1;
   float b0[4][NTILE], b1[4][NTILE];
   block_gather<NTILE>(b0, staged, k0, off);
   int i = 0;
   for (; i + 2 < count; i += 2) {  // two blocks per trip; at least one more block follows
-    a1 = dense[at(i + 1)];
+    a1 = dense[DSTEP * at(i + 1)];
     block_gather<NTILE>(b1, staged, k1, off);
     k0 = koff[at(i + 2)];
     block_mfma<NTILE>(acc, a0, b0);
     block_interleave<NTILE>();
-    a0 = dense[at(i + 2)];
+    a0 = dense[DSTEP * at(i + 2)];
     block_gather<NTILE>(b0, staged, k0, off);
     k1 = koff[at(i + 3)];
     block_mfma<NTILE>(acc, a1, b1);
     block_interleave<NTILE>();
   }
   if (i + 2 == count) {  // the last two blocks: nothing left to fetch ahead
-    a1 = dense[at(i + 1)];
+    a1 = dense[DSTEP * at(i + 1)];
     block_gather<NTILE>(b1, staged, k1, off);
     block_mfma<NTILE>(acc, a0, b0);
     block_interleave<NTILE>();
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
         acc[tt] = binit;
       }
       const int arow = (mt * (g.R + 1) + (16 * mt + j < g.M ? j : g.R)) * 4 + q;
-      gemm_blocks<TP>(acc, reinterpret_cast<const f4*>(wt + (size_t)arow * g.SP),
+      gemm_blocks<TP, 1>(acc, reinterpret_cast<const f4*>(wt + (size_t)arow * g.SP),
                       reinterpret_cast<const i4*>(koff + q * g.SP), reinterpret_cast<const char*>(x), po, 0, 1,
                       g.NBK, g.NBK - 1);
       if (full) {  // wave-uniform: the common case carries no per-pixel predicates
@@ -342,6 +343,11 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
 // tiles the waves split the pixels as well: tile w % 2 (0), K slice w / 2 (w) of KS = 2 (4), a slice
 // taking every KS-th block.  Results go to part[bx*KS + slice][mt][nt][16][16] and, for ntg = 0, the
 // bias sums to bpart[bx][16 mt + c] (bpart follows part).
+//
+// K runs over the pixel slots n of a group (image-major, padded with zeros to whole blocks of 16).
+// Step s4 of block blk takes, in lane group q, slot n = 16 blk + 4 q + s4: a lane's four A values of a
+// block are then consecutive pixels of one channel, so the output error is staged as it lies in
+// memory, one row per channel.
 struct WgradArgs {
   const float* in;
   const float* d_out;
@@ -353,31 +359,32 @@ struct WgradArgs {
   int KS;         // K slices per workgroup
   int R;          // rows of the staged error: min(16, Cout); row R stays zero
   int NB, groups;
-  int NBK, SP;    // blocks of 16 pixel slots per full group; row stride of the K-indexed tables
+  int NBK, NPS;   // blocks of 16 pixel slots per full group; row stride of the staged error (floats)
   int stage_x;    // STAGE_* of the input images (VECTOR needs Cin*H*W % 4 == 0)
-  int stage_d;    // STAGE_SCALAR: the output error travels through registers (needs 16 NBK <= THREADS*PFD)
+  int stage_d;    // STAGE_* of the output error (VECTOR needs Ho*Wo % 4 == 0)
   float inv_khkw, inv_kw, inv_howo, inv_wo;
 };
-constexpr int PFD = 2;  // pixel slots per thread of the output error held in registers (all 16 channels)
+// Sixteen threads stage one channel of the output error: up to PFDV 16-byte or PFDS 4-byte items each.
+constexpr int PFDV = 10, PFDS = 16;
 struct WgradLds {
-  int pb, so, dy, x, total;
+  int pb, dy, x, total;
 };
+// Row stride of the staged error: 16-byte reads by eight lanes of consecutive channels then fall
+// into eight different groups of four banks.
+__host__ __device__ inline int error_row_stride(int blocks) { return 16 * blocks + 4; }
 __host__ __device__ inline WgradLds wgrad_lds(const WgradArgs& a) {
   WgradLds l;
-  l.pb = 0;                         // [4 rows: q][SP] byte offset in x of pixel slot 4 s + q (0 for padding)
-  l.so = l.pb + 4 * a.SP;           // [16 NBK] offset of pixel slot n in d_out (channel 0)
-  l.dy = l.so + 16 * a.NBK;         // [(R + 1)*4 rows: channel, q][SP] output error at slot 4 s + q
-  l.x = l.dy + (a.R + 1) * 4 * a.SP;  // [NB][Cin*H*W]
+  l.pb = 0;                     // [4 rows: q][NBK][4] byte offset in x of slot 16 blk + 4 q + s4 (0 for padding)
+  l.dy = l.pb + 16 * a.NBK;     // [R + 1 rows: channel][NPS] output error by pixel slot
+  l.x = l.dy + (a.R + 1) * a.NPS;  // [NB][Cin*H*W]
   l.total = l.x + round4(a.NB * a.Cin * a.H * a.W);
   return l;
 }
 
 __global__ __launch_bounds__(THREADS, 2) void wgrad_kernel(const WgradArgs g) {
   extern __shared__ __align__(16) float lds[];
-  __shared__ float bred[WAVES][16];
   const WgradLds L = wgrad_lds(g);
   int* pb = reinterpret_cast<int*>(lds + L.pb);
-  int* so = reinterpret_cast<int*>(lds + L.so);
   float* dy = lds + L.dy;
   float* x = lds + L.x;
   const int t = threadIdx.x, wave = t >> 6, l = t & 63, q = l >> 4, j = l & 15;
@@ -386,18 +393,16 @@ __global__ __launch_bounds__(THREADS, 2) void wgrad_kernel(const WgradArgs g) {
   const int rows = min(16, g.Cout - 16 * mt);
 
   for (int n = t; n < 16 * g.NBK; n += THREADS) {
-    int pbv = 0, sov = 0;
+    int pbv = 0;
     if (n < g.NB * HoWo) {
       int img, r, y, xx;
       divmod(n, HoWo, g.inv_howo, img, r);
       divmod(r, g.Wo, g.inv_wo, y, xx);
       pbv = 4 * (img * per_image + y * g.W + xx);
-      sov = img * g.Cout * HoWo + r;
     }
-    pb[(n & 3) * g.SP + (n >> 2)] = pbv;
-    so[n] = sov;
+    pb[((((n >> 2) & 3) * g.NBK + (n >> 4)) << 2) + (n & 3)] = pbv;
   }
-  for (int e = t; e < 4 * g.SP; e += THREADS) dy[g.R * 4 * g.SP + e] = 0.0f;  // the zero row
+  for (int e = t; e < g.NPS; e += THREADS) dy[g.R * g.NPS + e] = 0.0f;  // the zero row
 
   // this wave's tiles and K slice; this lane's column (tap) of each tile
   const int tile0 = g.KS == 1 ? wave : g.KS == 2 ? (wave & 1) : 0;
@@ -418,20 +423,31 @@ __global__ __launch_bounds__(THREADS, 2) void wgrad_kernel(const WgradArgs g) {
   f4 acc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) acc[i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-  float bsum[16];
-#pragma unroll
-  for (int c = 0; c < 16; ++c) bsum[c] = 0.0f;
-  const f4* dense = reinterpret_cast<const f4*>(dy + (size_t)((j < rows ? j : g.R) * 4 + q) * g.SP);
-  const i4* koff = reinterpret_cast<const i4*>(pb + q * g.SP);
+  const f4* dense = reinterpret_cast<const f4*>(dy + (size_t)(j < rows ? j : g.R) * g.NPS + 4 * q);
+  const i4* koff = reinterpret_cast<const i4*>(pb) + q * g.NBK;
 
-  // Staging: the images as they are (zero past the last image of a ragged group); the output error
-  // of the M tile's channels by pixel slot, zero past the group's pixels, summed per channel on the
-  // way.  Thread t always handles slots t, t + THREADS, ..., so the bias sums do not depend on the path.
-  f4 pv[PFV];
-  float pd[PFD][16];
-  int sreg[PFD];
+  // Staging.  Images: as they lie in memory, zero past the last image of a ragged group.  Output
+  // error: thread t copies items lane16, lane16 + 16, ... of channel t / 16 of the M tile (an item is
+  // four pixel slots or one), zero from the group's last pixel up to whole blocks, and sums what it
+  // copies: the bias gradient.
+  const int ch = t >> 4, lane16 = t & 15;
+  const bool stager = ch < rows;
+  const int isz = g.stage_d == STAGE_VECTOR ? 4 : 1;  // pixel slots per item
+  f4 pv[PFV], pd[PFDV];
+  int soff[PFDS];  // offset of the thread's item i in d_out, relative to the group's channel
+  float bsum = 0.0f;
+  auto slot_source = [&](int n) {  // pixel slot n < NB*Ho*Wo
+    int img, r;
+    divmod(n, HoWo, g.inv_howo, img, r);
+    return img * g.Cout * HoWo + r;
+  };
+  if (g.stage_d != STAGE_DIRECT) {
 #pragma unroll
-  for (int i = 0; i < PFD; ++i) sreg[i] = 0;
+    for (int i = 0; i < PFDS; ++i) {
+      const int n = (lane16 + 16 * i) * isz;
+      soff[i] = (i < (g.stage_d == STAGE_VECTOR ? PFDV : PFDS) && n < g.NB * HoWo) ? slot_source(n) : 0;
+    }
+  }
   auto issue = [&](int grp) {
     const int b0 = grp * g.NB, nb = min(g.NB, g.B - b0), count = nb * per_image, npx = nb * HoWo;
     const float* src = g.in + (size_t)b0 * per_image;
@@ -444,15 +460,17 @@ __global__ __launch_bounds__(THREADS, 2) void wgrad_kernel(const WgradArgs g) {
       for (int i = 0; i < PFS; ++i)
         if (t + THREADS * i < count) pv[i >> 2][i & 3] = src[t + THREADS * i];
     }
-    if (g.stage_d == STAGE_SCALAR) {
-      const float* dsrc = g.d_out + ((size_t)b0 * g.Cout + 16 * mt) * HoWo;
+    if (stager) {
+      const float* dsrc = g.d_out + ((size_t)b0 * g.Cout + 16 * mt + ch) * HoWo;
+      if (g.stage_d == STAGE_VECTOR) {
 #pragma unroll
-      for (int i = 0; i < PFD; ++i)
-        if (t + THREADS * i < npx) {
+        for (int i = 0; i < PFDV; ++i)
+          if (4 * (lane16 + 16 * i) < npx) pd[i] = *reinterpret_cast<const f4*>(dsrc + soff[i]);
+      } else if (g.stage_d == STAGE_SCALAR) {
 #pragma unroll
-          for (int c = 0; c < 16; ++c)
-            if (c < rows) pd[i][c] = dsrc[(size_t)c * HoWo + sreg[i]];
-        }
+        for (int i = 0; i < PFDS; ++i)
+          if (lane16 + 16 * i < npx) pd[i >> 2][i & 3] = dsrc[soff[i]];
+      }
     }
   };
   auto commit = [&](int grp) {
@@ -475,70 +493,66 @@ __global__ __launch_bounds__(THREADS, 2) void wgrad_kernel(const WgradArgs g) {
       const float* src = g.in + (size_t)b0 * per_image;
       for (int e = t; e < g.NB * per_image; e += THREADS) x[e] = e < count ? src[e] : 0.0f;
     }
-    if (g.stage_d == STAGE_SCALAR) {
+    if (stager) {
+      float* drow = dy + ch * g.NPS;
+      if (g.stage_d == STAGE_VECTOR) {
 #pragma unroll
-      for (int i = 0; i < PFD; ++i) {
-        const int n = t + THREADS * i;
-        if (n < 16 * nbk) {
-#pragma unroll
-          for (int c = 0; c < 16; ++c)
-            if (c < rows) {
-              const float v = n < npx ? pd[i][c] : 0.0f;
-              dy[(c * 4 + (n & 3)) * g.SP + (n >> 2)] = v;
-              bsum[c] += v;
-            }
-        }
-      }
-    } else {
-      const float* dsrc = g.d_out + ((size_t)b0 * g.Cout + 16 * mt) * HoWo;
-      for (int n = t; n < 16 * nbk; n += THREADS) {
-        const int sv = so[n];
-        float v[16];
-#pragma unroll
-        for (int c = 0; c < 16; ++c) v[c] = (c < rows && n < npx) ? dsrc[(size_t)c * HoWo + sv] : 0.0f;
-#pragma unroll
-        for (int c = 0; c < 16; ++c)
-          if (c < rows) {
-            dy[(c * 4 + (n & 3)) * g.SP + (n >> 2)] = v[c];
-            bsum[c] += v[c];
+        for (int i = 0; i < PFDV; ++i) {
+          const int n = 4 * (lane16 + 16 * i);
+          if (n < 16 * nbk) {
+            const f4 v = n < npx ? pd[i] : f4{0.0f, 0.0f, 0.0f, 0.0f};
+            *reinterpret_cast<f4*>(drow + n) = v;
+            bsum += (v[0] + v[1]) + (v[2] + v[3]);
           }
+        }
+      } else if (g.stage_d == STAGE_SCALAR) {
+#pragma unroll
+        for (int i = 0; i < PFDS; ++i) {
+          const int n = lane16 + 16 * i;
+          if (n < 16 * nbk) {
+            const float v = n < npx ? pd[i >> 2][i & 3] : 0.0f;
+            drow[n] = v;
+            bsum += v;
+          }
+        }
+      } else {
+        const float* dsrc = g.d_out + ((size_t)b0 * g.Cout + 16 * mt + ch) * HoWo;
+        for (int n = lane16; n < 16 * nbk; n += 16) {
+          const float v = n < npx ? dsrc[slot_source(n)] : 0.0f;
+          drow[n] = v;
+          bsum += v;
+        }
       }
     }
   };
 
-  lds_barrier();  // tables
-  if (g.stage_d == STAGE_SCALAR) {
-#pragma unroll
-    for (int i = 0; i < PFD; ++i)
-      if (t + THREADS * i < 16 * g.NBK) sreg[i] = so[t + THREADS * i];
-  }
   if ((int)blockIdx.x < g.groups) issue(blockIdx.x);
   for (int grp = blockIdx.x; grp < g.groups; grp += gridDim.x) {
     const int nbk = (min(g.NB, g.B - grp * g.NB) * HoWo + 15) >> 4;
-    lds_barrier();  // the previous group's reads are complete
+    lds_barrier();  // tables (first pass) / the previous group's reads are complete
     commit(grp);
     lds_barrier();
     if (grp + (int)gridDim.x < g.groups) issue(grp + gridDim.x);
     const int count = nbk > slice ? (nbk - slice + g.KS - 1) / g.KS : 0;
     const char* xb = reinterpret_cast<const char*>(x);
     switch (ntile) {
-      case 4: gemm_blocks<4>(acc, dense, koff, xb, toff, slice, g.KS, count, nbk - 1); break;
+      case 4: gemm_blocks<4, 4>(acc, dense, koff, xb, toff, slice, g.KS, count, nbk - 1); break;
       case 3: {
         f4(&a3)[3] = reinterpret_cast<f4(&)[3]>(acc);
         const int(&t3)[3] = reinterpret_cast<const int(&)[3]>(toff);
-        gemm_blocks<3>(a3, dense, koff, xb, t3, slice, g.KS, count, nbk - 1);
+        gemm_blocks<3, 4>(a3, dense, koff, xb, t3, slice, g.KS, count, nbk - 1);
         break;
       }
       case 2: {
         f4(&a2)[2] = reinterpret_cast<f4(&)[2]>(acc);
         const int(&t2)[2] = reinterpret_cast<const int(&)[2]>(toff);
-        gemm_blocks<2>(a2, dense, koff, xb, t2, slice, g.KS, count, nbk - 1);
+        gemm_blocks<2, 4>(a2, dense, koff, xb, t2, slice, g.KS, count, nbk - 1);
         break;
       }
       case 1: {
         f4(&a1)[1] = reinterpret_cast<f4(&)[1]>(acc);
         const int(&t1)[1] = reinterpret_cast<const int(&)[1]>(toff);
-        gemm_blocks<1>(a1, dense, koff, xb, t1, slice, g.KS, count, nbk - 1);
+        gemm_blocks<1, 4>(a1, dense, koff, xb, t1, slice, g.KS, count, nbk - 1);
         break;
       }
       default: break;
@@ -553,18 +567,12 @@ __global__ __launch_bounds__(THREADS, 2) void wgrad_kernel(const WgradArgs g) {
       for (int r = 0; r < 4; ++r) o[16 * r] = acc[i][r];
     }
   }
-  if (ntg == 0) {  // bias sums: lanes by a fixed butterfly, then the four waves in order
+  if (ntg == 0) {  // bias sums: the sixteen threads of a channel by a fixed butterfly
 #pragma unroll
-    for (int c = 0; c < 16; ++c) {
-      float v = bsum[c];
-#pragma unroll
-      for (int m = 32; m > 0; m >>= 1) v += __shfl_xor(v, m, 64);
-      if (l == 0) bred[wave][c] = v;
-    }
-    lds_barrier();
-    if (t < 16) {
+    for (int m = 8; m > 0; m >>= 1) bsum += __shfl_xor(bsum, m, 16);
+    if (lane16 == 0) {
       float* bpart = g.part + (size_t)gridDim.x * g.KS * g.MT * g.NT * 256;
-      bpart[(size_t)blockIdx.x * g.MT * 16 + 16 * mt + t] = (bred[0][t] + bred[1][t]) + (bred[2][t] + bred[3][t]);
+      bpart[(size_t)blockIdx.x * g.MT * 16 + 16 * mt + ch] = bsum;
     }
   }
 }

@@ -311,13 +311,17 @@ WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
   auto bytes = [&](int nb) {
     a.NB = nb;
     a.NBK = (int)((nb * HoWo + 15) / 16);
-    a.SP = igemm::row_stride(a.NBK);
+    a.NPS = igemm::error_row_stride(a.NBK);
     return (long long)igemm::wgrad_lds(a).total * 4;
   };
   if (bytes(1) > LDS_LIMIT) return p;
   int nb = 1;
   const int nb_fill = (B + MAX_PARTIALS - 1) / MAX_PARTIALS;
-  for (int c = 2; c <= MAX_GROUP && c <= B && c <= nb_fill && bytes(c) <= LDS_TARGET; ++c) nb = c;
+  // more images per group while the partial sums stay at MAX_PARTIALS columns, LDS stays within the
+  // target and the output error still travels through registers
+  const long long slots = HoWo % 4 == 0 ? 64LL * igemm::PFDV : 16LL * igemm::PFDS;
+  for (int c = 2; c <= MAX_GROUP && c <= B && c <= nb_fill && bytes(c) <= LDS_TARGET && 16LL * a.NBK <= slots; ++c)
+    nb = c;
   p.lds_bytes = (size_t)bytes(nb);
   a.groups = (B + nb - 1) / nb;
   unsigned gx = resident_workgroups(p.lds_bytes) / (unsigned)(a.MT * a.NTG);
@@ -331,7 +335,9 @@ WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
   a.stage_x = (per_image % 4 == 0 && per_group / 4 <= igemm::THREADS * igemm::PFV)
                   ? igemm::STAGE_VECTOR
                   : per_group <= igemm::THREADS * igemm::PFS ? igemm::STAGE_SCALAR : igemm::STAGE_DIRECT;
-  a.stage_d = 16 * a.NBK <= igemm::THREADS * igemm::PFD ? igemm::STAGE_SCALAR : igemm::STAGE_DIRECT;
+  a.stage_d = (HoWo % 4 == 0 && 4 * a.NBK <= 16 * igemm::PFDV)
+                  ? igemm::STAGE_VECTOR
+                  : 16 * a.NBK <= 16 * igemm::PFDS ? igemm::STAGE_SCALAR : igemm::STAGE_DIRECT;
   a.inv_khkw = 1.0f / (float)(KH * KW), a.inv_kw = 1.0f / (float)KW;
   a.inv_howo = 1.0f / (float)HoWo, a.inv_wo = 1.0f / (float)a.Wo;
   p.fits = true;
