@@ -1,0 +1,97 @@
+"""Times the stateless per-operation entry points at the network's layer shapes.
+
+    python -m paper_1912_05234_amd.bench_ops [--batch 10000] [--steps 50]
+
+One JSON line per operation: the average duration of the call's kernels between two HIP events
+on the stream the binding launches on, the useful arithmetic (2 flops per multiply-add of the
+operation's definition; padding the kernels add is not counted) and its share of the fp32
+matrix-core peak.  Inputs are synthetic and resident in device memory.
+"""
+import argparse
+import json
+import sys
+
+import torch
+
+from . import binding
+
+PEAK_TFLOPS = 157.3  # MI355X, fp32 matrix and vector alike
+
+# name: (Cin, H, W, Cout, KH, KW) -- the paper's C1 and C2 (Section 3, listing `forward`)
+CONVS = {"C1": (1, 28, 28, 6, 5, 5), "C2": (6, 12, 12, 12, 5, 5)}
+FC = (192, 10)
+
+
+def time_call(fn, steps, warmup=5):
+    for _ in range(warmup):
+        fn()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(steps):
+        fn()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) * 1e3 / steps  # microseconds
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--batch", type=int, default=10000)
+    ap.add_argument("--steps", type=int, default=50)
+    args = ap.parse_args(argv)
+    if not torch.cuda.is_available():
+        sys.exit("bench_ops needs a GPU")
+    dev, B = "cuda:0", args.batch
+    gen = torch.Generator(device="cpu").manual_seed(7)
+
+    def rnd(*shape):
+        return (torch.rand(*shape, generator=gen) * 2 - 1).to(dev)
+
+    def report(layer, op, us, flops, extra=None):
+        tf = flops / us / 1e6
+        line = {"layer": layer, "op": op, "batch": B, "us": round(us, 2), "tflops": round(tf, 2),
+                "frac_of_fp32_peak": round(tf / PEAK_TFLOPS, 4)}
+        line.update(extra or {})
+        print(json.dumps(line), flush=True)
+
+    for name, (Cin, H, W, Cout, KH, KW) in CONVS.items():
+        Ho, Wo = H - KH + 1, W - KW + 1
+        x, k, b, d = rnd(B, Cin, H, W), rnd(Cout, Cin, KH, KW), rnd(Cout), rnd(B, Cout, Ho, Wo)
+        flops = 2.0 * B * Cout * Ho * Wo * Cin * KH * KW
+        # outputs and workspace allocated once, outside the timed calls
+        out = torch.empty(B, Cout, Ho, Wo, device=dev)
+        d_in = torch.empty(B, Cin, H, W, device=dev)
+        d_k, d_b = torch.empty_like(k), torch.empty_like(b)
+        L = binding.lib()
+        nbytes = L.cnn_conv_bwd_weight_workspace_bytes(B, Cin, H, W, Cout, KH, KW)
+        ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
+        p, s = binding._ptr, binding._stream
+        calls = {
+            "conv_fwd": lambda: L.cnn_conv_fwd(p(x), p(k), p(b), p(out), B, Cin, H, W, Cout, KH, KW, s()),
+            "conv_bwd_input": lambda: L.cnn_conv_bwd_input(p(d), p(k), p(d_in), B, Cin, H, W, Cout, KH, KW, s()),
+            "conv_bwd_weight": lambda: L.cnn_conv_bwd_weight(p(x), p(d), p(d_k), p(d_b), B, Cin, H, W, Cout, KH,
+                                                             KW, p(ws), nbytes, s()),
+        }
+        for op, fn in calls.items():
+            assert fn() == 0, op
+            report(name, op, time_call(fn, args.steps), flops)
+    I, O = FC
+    x, w, b, d = rnd(B, I), rnd(O, I), rnd(O), rnd(B, O)
+    out, d_in, d_w, d_b = torch.empty(B, O, device=dev), torch.empty(B, I, device=dev), torch.empty_like(w), torch.empty_like(b)
+    L = binding.lib()
+    nbytes = L.cnn_fc_bwd_weight_workspace_bytes(B, I, O)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=dev)
+    p, s = binding._ptr, binding._stream
+    calls = {
+        "fc_fwd": lambda: L.cnn_fc_fwd(p(x), p(w), p(b), p(out), B, I, O, s()),
+        "fc_bwd_input": lambda: L.cnn_fc_bwd_input(p(d), p(w), p(d_in), B, I, O, s()),
+        "fc_bwd_weight": lambda: L.cnn_fc_bwd_weight(p(x), p(d), p(d_w), p(d_b), B, I, O, p(ws), nbytes, s()),
+    }
+    for op, fn in calls.items():
+        assert fn() == 0, op
+        report("FC", op, time_call(fn, args.steps), 2.0 * B * I * O)
+
+
+if __name__ == "__main__":
+    main()

@@ -17,6 +17,14 @@
 //                    read flipped, which turns backin into a forward convolution
 //   weight gradient  M = Cout          K = pixels of all images   N = Cin*KH*KW taps; the bias
 //                    gradient is summed while the output error is staged
+//
+// Column packing (forward and input gradient, few output channels): P horizontally adjacent output
+// pixels x = P X + sh share one GEMM column (y, X) and take P rows (m, sh) instead.  With v' = v + sh
+// the gathered operand staged[c][y+u][P X + v'] does not depend on sh, so
+//   D[(m,sh)][(y,X)] = sum_{c,u,v' < KW+P-1} W[(m,sh)][(c,u,v')] * staged[c][y+u][P X + v'],
+//   W[(m,sh)][(c,u,v')] = k[m][c][u][v'-sh]  (zero where v'-sh is outside 0..KW-1):
+// a 16-row tile is filled by M*P rows and the number of matrix instructions falls by
+// P*KW / (KW+P-1).  P = 1 is the plain form.
 #pragma once
 
 #include "cnn_common.h"
@@ -141,18 +149,19 @@ struct ConvArgs {
   const float* w;     // [Cout][Cin][KH][KW]
   const float* bias;  // M values or null
   float* dst;
-  int B, M, K;         // images, rows of D, reduction length SC*KH*KW
+  int B, M, K;         // images, output channels, reduction length SC*KH*(KW+P-1)
+  int P, MR, KWP, OWP; // column packing: pixels per column, rows of D = M*P, KW+P-1, OW/P
   int SC, SH, SW;      // staged tensor: channels, rows, columns
   int LW, LP, LI;      // LDS strides: row, plane, image (LI = SC*LP)
   int pady, padx;      // origin of the data inside a plane
   int KH, KW, OH, OW;  // kernel and output extents
   int NB, groups;      // images per group, number of groups
-  int MT, R;           // tiles of M; rows of an M tile held in LDS: min(16, M), row R stays zero
+  int MT, R;           // tiles of the MR rows; rows of a tile held in LDS: min(16, MR), row R stays zero
   int NBK, SP;         // blocks of four K steps; row stride of the two K-indexed tables (floats)
   int flip;            // 0: A[m][(c,u,v)] = w[m][c][u][v];  1: A[m][(c,u,v)] = w[c][m][KH-1-u][KW-1-v]
   int zero_fill;       // the planes have a border that must read as zero
   int stage;           // STAGE_*: VECTOR needs SC*SH*SW % 4 == 0 and no border
-  float inv_sp, inv_r1, inv_khkw, inv_kw, inv_ohow, inv_ow, inv_sw, inv_sh;
+  float inv_sp, inv_r1, inv_p, inv_khkwp, inv_kwp, inv_ohowp, inv_owp, inv_sw, inv_sh;
 };
 // LDS layout in floats, in this order.
 struct ConvLds {
@@ -163,9 +172,9 @@ __host__ __device__ inline ConvLds conv_lds(const ConvArgs& a) {
   l.wt = 0;  // [MT*(R+1)*4 rows: M tile, row i, q][SP]: A[i][4 s + q] at [s]
   l.koff = l.wt + a.MT * (a.R + 1) * 4 * a.SP;  // [4 rows: q][SP]: byte offset of K index 4 s + q (0 for padding)
   l.bias = l.koff + 4 * a.SP;          // [16 MT]
-  l.poff = l.bias + 16 * a.MT;         // [NB*OH*OW] byte offset of output pixel n in the staged images
-  l.ooff = l.poff + round4(a.NB * a.OH * a.OW);  // [NB*OH*OW] offset of pixel n in dst (channel 0)
-  l.x = l.ooff + round4(a.NB * a.OH * a.OW);     // [NB*LI] staged images
+  l.poff = l.bias + 16 * a.MT;         // [NB*OH*OWP] byte offset of column n in the staged images
+  l.ooff = l.poff + round4(a.NB * a.OH * a.OWP);  // [NB*OH*OWP] offset of column n in dst (channel 0, sh 0)
+  l.x = l.ooff + round4(a.NB * a.OH * a.OWP);     // [NB*LI] staged images
   l.total = l.x + round4(a.NB * a.LI);
   return l;
 }
@@ -181,7 +190,7 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
   int* ooff = reinterpret_cast<int*>(lds + L.ooff);
   float* x = lds + L.x;
   const int t = threadIdx.x, wave = t >> 6, l = t & 63, q = l >> 4, j = l & 15;
-  const int KHKW = g.KH * g.KW, OHOW = g.OH * g.OW;
+  const int KHKW = g.KH * g.KW, KHKWP = g.KH * g.KWP, OHOW = g.OH * g.OW, OHOWP = g.OH * g.OWP;
 
   // ---- tables, once per workgroup ----
   const int wt_total = g.MT * (g.R + 1) * 4 * g.SP;
@@ -195,16 +204,16 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
         int row, s, tile, ri;
         divmod(e, g.SP, g.inv_sp, row, s);
         divmod(row >> 2, g.R + 1, g.inv_r1, tile, ri);
-        const int m = 16 * tile + ri, kk = 4 * s + (row & 3);
-        if (ri < g.R && m < g.M && kk < g.K) {
-          if (!g.flip) {
-            v[u] = g.w[(size_t)m * g.K + kk];
-          } else {
-            int c, rem, uu, vv;
-            divmod(kk, KHKW, g.inv_khkw, c, rem);
-            divmod(rem, g.KW, g.inv_kw, uu, vv);
-            v[u] = g.w[((size_t)c * g.M + m) * KHKW + (g.KH - 1 - uu) * g.KW + (g.KW - 1 - vv)];
-          }
+        const int mrow = 16 * tile + ri, kk = 4 * s + (row & 3);
+        if (ri < g.R && mrow < g.MR && kk < g.K) {
+          int m, sh, c, rem, uu, vp;
+          divmod(mrow, g.P, g.inv_p, m, sh);
+          divmod(kk, KHKWP, g.inv_khkwp, c, rem);
+          divmod(rem, g.KWP, g.inv_kwp, uu, vp);
+          const int vv = vp - sh;
+          if (vv >= 0 && vv < g.KW)
+            v[u] = !g.flip ? g.w[((size_t)m * g.SC + c) * KHKW + uu * g.KW + vv]
+                           : g.w[((size_t)c * g.M + m) * KHKW + (g.KH - 1 - uu) * g.KW + (g.KW - 1 - vv)];
         }
       }
     }
@@ -218,20 +227,32 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
     const int kk = 4 * s + qq;
     int off = 0;
     if (kk < g.K) {
-      int c, rem, u, vv;
-      divmod(kk, KHKW, g.inv_khkw, c, rem);
-      divmod(rem, g.KW, g.inv_kw, u, vv);
-      off = 4 * (c * g.LP + u * g.LW + vv);
+      int c, rem, u, vp;
+      divmod(kk, KHKWP, g.inv_khkwp, c, rem);
+      divmod(rem, g.KWP, g.inv_kwp, u, vp);
+      off = 4 * (c * g.LP + u * g.LW + vp);
     }
     koff[e] = off;
   }
-  for (int m = t; m < 16 * g.MT; m += THREADS) bl[m] = (g.bias && m < g.M) ? g.bias[m] : 0.0f;
-  for (int n = t; n < g.NB * OHOW; n += THREADS) {
+  for (int mrow = t; mrow < 16 * g.MT; mrow += THREADS) {
+    int m, sh;
+    divmod(mrow, g.P, g.inv_p, m, sh);
+    bl[mrow] = (g.bias && mrow < g.MR) ? g.bias[m] : 0.0f;
+  }
+  for (int n = t; n < g.NB * OHOWP; n += THREADS) {
     int img, r, y, xx;
-    divmod(n, OHOW, g.inv_ohow, img, r);
-    divmod(r, g.OW, g.inv_ow, y, xx);
-    poff[n] = 4 * (img * g.LI + y * g.LW + xx);
-    ooff[n] = img * g.M * OHOW + r;
+    divmod(n, OHOWP, g.inv_ohowp, img, r);
+    divmod(r, g.OWP, g.inv_owp, y, xx);
+    poff[n] = 4 * (img * g.LI + y * g.LW + g.P * xx);
+    ooff[n] = img * g.M * OHOW + y * g.OW + g.P * xx;
+  }
+  // byte offset in dst of this lane's result register r in M tile 0 (packed forms have one M tile)
+  unsigned ro0[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    int m, sh;
+    divmod(4 * q + r, g.P, g.inv_p, m, sh);
+    ro0[r] = 4u * (unsigned)(m * OHOW + sh);
   }
   if (g.zero_fill)
     for (int e = t; e < g.NB * g.LI; e += THREADS) x[e] = 0.0f;
@@ -293,11 +314,14 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
     lds_barrier();
     if (grp + (int)gridDim.x < g.groups) issue(grp + gridDim.x);
 
-    const int N = nb * OHOW, PT = (N + 15) >> 4, PG = (PT + TP - 1) / TP;
+    const int N = nb * OHOWP, PT = (N + 15) >> 4, PG = (PT + TP - 1) / TP;
     char* dst = reinterpret_cast<char*>(g.dst + (size_t)b0 * g.M * OHOW);  // byte offsets below fit 32 bits
     for (int job = wave; job < PG * g.MT; job += WAVES) {
       const int pg = job / g.MT, mt = job - pg * g.MT;
-      const int nrow = g.M - 16 * mt - 4 * q;  // result registers r < nrow of this lane are rows of D
+      const int nrow = g.MR - 16 * mt - 4 * q;  // result registers r < nrow of this lane are rows of D
+      unsigned ro[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ro[r] = ro0[r] + 64u * (unsigned)(mt * OHOW);
       const bool full = 16 * (pg * TP + TP) <= N;  // no padding pixels in this job's tiles
       int po[TP];
       unsigned oo[TP];
@@ -307,10 +331,10 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
       for (int tt = 0; tt < TP; ++tt) {
         const int n = 16 * (pg * TP + tt) + j, nn = n < N ? n : N - 1;
         po[tt] = poff[nn];
-        oo[tt] = 4u * (unsigned)(ooff[nn] + (16 * mt + 4 * q) * OHOW);
+        oo[tt] = 4u * (unsigned)ooff[nn];
         acc[tt] = binit;
       }
-      const int arow = (mt * (g.R + 1) + (16 * mt + j < g.M ? j : g.R)) * 4 + q;
+      const int arow = (mt * (g.R + 1) + (16 * mt + j < g.MR ? j : g.R)) * 4 + q;
       gemm_blocks<TP, 1>(acc, reinterpret_cast<const f4*>(wt + (size_t)arow * g.SP),
                       reinterpret_cast<const i4*>(koff + q * g.SP), reinterpret_cast<const char*>(x), po, 0, 1,
                       g.NBK, g.NBK - 1);
@@ -320,7 +344,7 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
           if (r < nrow) {
 #pragma unroll
             for (int tt = 0; tt < TP; ++tt)
-              *reinterpret_cast<float*>(dst + (oo[tt] + 4u * (unsigned)(r * OHOW))) = acc[tt][r];
+              *reinterpret_cast<float*>(dst + (oo[tt] + ro[r])) = acc[tt][r];
           }
       } else {
 #pragma unroll
@@ -329,7 +353,7 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
 #pragma unroll
             for (int tt = 0; tt < TP; ++tt)
               if (16 * (pg * TP + tt) + j < N)
-                *reinterpret_cast<float*>(dst + (oo[tt] + 4u * (unsigned)(r * OHOW))) = acc[tt][r];
+                *reinterpret_cast<float*>(dst + (oo[tt] + ro[r])) = acc[tt][r];
           }
       }
     }

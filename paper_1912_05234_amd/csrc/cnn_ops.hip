@@ -226,18 +226,21 @@ struct ConvPlan {
   size_t lds_bytes = 0;
 };
 
-// dst[B][M][OH][OW] from src[B][SC][SH][SW] staged with a border of (pady, padx).
-ConvPlan plan_conv(const float* src, const float* w, const float* bias, float* dst, int B, int M, int SC,
-                   int SH, int SW, int KH, int KW, int OH, int OW, int pady, int padx, int flip) {
+// dst[B][M][OH][OW] from src[B][SC][SH][SW] staged with a border of (pady, padx), P output pixels
+// per GEMM column.  tp = 0 when the operands do not fit in LDS.
+ConvPlan plan_conv_packed(const float* src, const float* w, const float* bias, float* dst, int B, int M,
+                          int SC, int SH, int SW, int KH, int KW, int OH, int OW, int pady, int padx, int flip,
+                          int P) {
   ConvPlan p;
   igemm::ConvArgs& a = p.a;
   a.src = src, a.w = w, a.bias = bias, a.dst = dst;
   a.B = B, a.M = M, a.SC = SC, a.SH = SH, a.SW = SW, a.KH = KH, a.KW = KW, a.OH = OH, a.OW = OW;
   a.pady = pady, a.padx = padx, a.flip = flip, a.zero_fill = (pady || padx) ? 1 : 0;
-  const long long K = (long long)SC * KH * KW, LW = SW + 2LL * padx, LP = (SH + 2LL * pady) * LW, LI = SC * LP;
-  const long long OHOW = (long long)OH * OW, MT = (M + 15) / 16, NBK = (K + 15) / 16;
-  const long long R = M < 16 ? M : 16;
-  if ((MT * (R + 1) * 4 + 4) * (4 * NBK + 4) + 16 * MT + LI + 2 * OHOW + 16 > LDS_LIMIT / 4) return p;  // not even one image
+  a.P = P, a.MR = M * P, a.KWP = KW + P - 1, a.OWP = OW / P;
+  const long long K = (long long)SC * KH * a.KWP, LW = SW + 2LL * padx, LP = (SH + 2LL * pady) * LW, LI = SC * LP;
+  const long long COLS = (long long)OH * a.OWP, MT = ((long long)a.MR + 15) / 16, NBK = (K + 15) / 16;
+  const long long R = a.MR < 16 ? a.MR : 16;
+  if ((MT * (R + 1) * 4 + 4) * (4 * NBK + 4) + 16 * MT + LI + 2 * COLS + 16 > LDS_LIMIT / 4) return p;  // not even one image
   a.K = (int)K, a.LW = (int)LW, a.LP = (int)LP, a.LI = (int)LI, a.MT = (int)MT, a.R = (int)R, a.NBK = (int)NBK;
   a.SP = igemm::row_stride(a.NBK);
   auto bytes = [&](int nb) {
@@ -245,10 +248,10 @@ ConvPlan plan_conv(const float* src, const float* w, const float* bias, float* d
     return (long long)igemm::conv_lds(a).total * 4;
   };
   if (bytes(1) > LDS_LIMIT) return p;
-  // Images per group: enough for four pixel tiles, more when the batch is large, within the LDS
+  // Images per group: enough for four column tiles, more when the batch is large, within the LDS
   // target; among the admissible sizes the one that wastes the fewest matrix instructions on
   // padding tiles and idle waves.
-  const int nb_tiles = (int)((64 + OHOW - 1) / OHOW);
+  const int nb_tiles = (int)((64 + COLS - 1) / COLS);
   int nb_want = (B + 2047) / 2048;
   if (nb_want < nb_tiles) nb_want = nb_tiles;
   if (nb_want > MAX_GROUP) nb_want = MAX_GROUP;
@@ -258,10 +261,10 @@ ConvPlan plan_conv(const float* src, const float* w, const float* bias, float* d
   for (int nb = 1; nb <= nb_want; ++nb) {
     const long long by = bytes(nb);
     if (by > LDS_LIMIT || (by > LDS_TARGET && nb > nb_tiles)) break;
-    for (int tp = 4; tp >= 1; tp >>= 1) {
-      const long long PT = (nb * OHOW + 15) / 16, jobs = ((PT + tp - 1) / tp) * MT;
-      const double used = (double)nb * OHOW / 16.0 * MT, slots = (double)((jobs + 3) / 4) * 4 * tp;
-      const double score = used / slots * (tp == 4 ? 1.02 : 1.0);  // ties: share the dense operand
+    for (int tp = 1; tp <= 4; tp <<= 1) {
+      const long long PT = (nb * COLS + 15) / 16, jobs = ((PT + tp - 1) / tp) * MT;
+      const double used = (double)nb * COLS / 16.0 * MT, slots = (double)((jobs + 3) / 4) * 4 * tp;
+      const double score = used / slots * (1.0 + 0.005 * tp);  // near ties: share the dense operand
       if (score >= best) best = score, best_nb = nb, best_tp = tp;
     }
   }
@@ -275,10 +278,24 @@ ConvPlan plan_conv(const float* src, const float* w, const float* bias, float* d
   a.stage = (!a.zero_fill && per_image % 4 == 0 && per_group / 4 <= igemm::THREADS * igemm::PFV)
                 ? igemm::STAGE_VECTOR
                 : per_group <= igemm::THREADS * igemm::PFS ? igemm::STAGE_SCALAR : igemm::STAGE_DIRECT;
-  a.inv_sp = 1.0f / (float)a.SP, a.inv_r1 = 1.0f / (float)(a.R + 1);
-  a.inv_khkw = 1.0f / (float)(KH * KW), a.inv_kw = 1.0f / (float)KW, a.inv_ohow = 1.0f / (float)OHOW;
-  a.inv_ow = 1.0f / (float)OW, a.inv_sw = 1.0f / (float)SW, a.inv_sh = 1.0f / (float)SH;
+  a.inv_sp = 1.0f / (float)a.SP, a.inv_r1 = 1.0f / (float)(a.R + 1), a.inv_p = 1.0f / (float)P;
+  a.inv_khkwp = 1.0f / (float)(KH * a.KWP), a.inv_kwp = 1.0f / (float)a.KWP;
+  a.inv_ohowp = 1.0f / (float)COLS, a.inv_owp = 1.0f / (float)a.OWP;
+  a.inv_sw = 1.0f / (float)SW, a.inv_sh = 1.0f / (float)SH;
   return p;
+}
+
+// The packing factor: the largest divisor P of OW with M*P <= 16 whose operands fit in LDS (a wider
+// kernel row costs LDS for the weight table); 1 for kernels one column wide, where packing gains nothing.
+ConvPlan plan_conv(const float* src, const float* w, const float* bias, float* dst, int B, int M, int SC,
+                   int SH, int SW, int KH, int KW, int OH, int OW, int pady, int padx, int flip) {
+  if (KW > 1)
+    for (int P = 16 / M; P >= 2; --P) {
+      if (OW % P) continue;
+      const ConvPlan p = plan_conv_packed(src, w, bias, dst, B, M, SC, SH, SW, KH, KW, OH, OW, pady, padx, flip, P);
+      if (p.tp) return p;
+    }
+  return plan_conv_packed(src, w, bias, dst, B, M, SC, SH, SW, KH, KW, OH, OW, pady, padx, flip, 1);
 }
 
 int launch_conv(const ConvPlan& p, hipStream_t stream) {
