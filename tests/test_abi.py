@@ -76,3 +76,19 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.cnn_fc_bwd_weight(fake, fake, fake, odd, 1, 4, 4, nul, 0, nul) == EINVAL
     assert L.cnn_logistic_fwd(fake, fake, 0, nul) == EINVAL
     assert L.cnn_logistic_bwd(fake, nul, fake, 4, nul) == EINVAL
+
+
+def test_weight_gradient_workspace_query():
+    """Host-only logic: the size query follows the launch plan and rejects what the call rejects."""
+    L = binding.lib()
+    q = L.cnn_conv_bwd_weight_workspace_bytes
+    c2 = q(100, 6, 12, 12, 12, 5, 5)
+    assert c2 > 0 and c2 % 4 == 0
+    # one 16 x 16 tile per 16 output maps and 16 taps, per partial-sum column, plus 16 bias sums per column
+    assert (c2 // 4) % (10 * 256 + 16) == 0
+    assert q(100000, 6, 12, 12, 12, 5, 5) == 512 * (10 * 256 + 16) * 4          # the column count is capped
+    assert q(2, 3, 80, 80, 4, 3, 3) == 0      # does not fit in LDS: the plain kernel needs no workspace
+    assert q(0, 6, 12, 12, 12, 5, 5) == 0     # invalid batch
+    assert q(1, 1, 8, 8, 1, 9, 3) == 0        # kernel larger than the input
+    assert L.cnn_fc_bwd_weight_workspace_bytes(100, 192, 10) == q(100, 192, 1, 1, 10, 1, 1) > 0
+
