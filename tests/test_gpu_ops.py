@@ -123,3 +123,43 @@ def test_logistic():
     for n in (1, 255, 257, 1000003):
         xs = inputs.make_signed((n,), 15) * 8
         assert_close(host(binding.logistic_fwd(dev(xs))), oracle.sigmoid(xs), RTOL_ACT, "logistic n=%d" % n)
+
+
+@pytest.mark.parametrize("B", [37, 1300])
+def test_training_gradient_assembled_from_per_op_calls(B):
+    """The paper's whole forward/backward chain (Section 3) built from the stateless entry points
+    gives the gradient of the fused step: two GPU paths that share no kernels, each also checked
+    against the oracle elsewhere."""
+    w = inputs.make_weights()
+    images, labels = inputs.make_batch(B, 77)
+    net = binding.CNN(w, max_batch=B)
+    g_fused, loss = net.gradient(dev(images), dev(labels))
+    g_fused = host(g_fused).astype(np.float64)
+    net.close()
+
+    x = dev(images).reshape(B, 1, 28, 28)
+    k1, b1, k2, b2, fc, b = (dev(w[n]) for n in ("k1", "b1", "k2", "b2", "fc", "b"))
+    k1 = k1.reshape(6, 1, 5, 5)                                      # the paper's k1 has no input-map axis
+    c1 = binding.logistic_fwd(binding.conv_fwd(x, k1, b1))
+    s1 = binding.avgpool_fwd(c1)
+    c2 = binding.logistic_fwd(binding.conv_fwd(s1, k2, b2))
+    s2 = binding.avgpool_fwd(c2)
+    s2f, fcw = s2.reshape(B, 192), fc.reshape(10, 192)
+    y = binding.logistic_fwd(binding.fc_fwd(s2f, fcw, b))
+    target = torch.zeros_like(y)
+    target[torch.arange(B), dev(labels).long()] = 1.0
+    d_pre = binding.logistic_bwd(y, y - target)                      # (y - t) y (1 - y)
+    d_fc, d_b = binding.fc_bwd_weight(s2f, d_pre)
+    d_s2 = binding.fc_bwd_input(d_pre, fcw).reshape(B, 12, 4, 4)
+    d_c2 = binding.logistic_bwd(c2, binding.avgpool_bwd(d_s2))
+    d_k2, d_b2 = binding.conv_bwd_weight(s1, d_c2)
+    d_s1 = binding.conv_bwd_input(d_c2, k2, 12, 12)
+    d_c1 = binding.logistic_bwd(c1, binding.avgpool_bwd(d_s1))
+    d_k1, d_b1 = binding.conv_bwd_weight(x, d_c1)
+    parts = dict(zip(("k1", "b1", "k2", "b2", "fc", "b"), (d_k1, d_b1, d_k2, d_b2, d_fc, d_b)))
+    ref = inputs.unflatten(g_fused)
+    for name, t in parts.items():
+        assert_close(host(t).reshape(ref[name].shape), ref[name], 2e-5, "gradient of %s from per-op calls" % name)
+    ref_loss = 0.5 * float(((host(y).astype(np.float64) - host(target)) ** 2).sum())
+    assert abs(float(host(loss)[0]) - ref_loss) <= 1e-5 * ref_loss
+
