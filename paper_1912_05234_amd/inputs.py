@@ -10,7 +10,10 @@ Recipe (one numpy PCG64 stream per call, draw order fixed):
            [-1/sqrt(fan_in), +1/sqrt(fan_in)) with fan_in 25 / 150 / 192,
            drawn in that order; biases b1, b2, b are zero;
   images:  float32 uniform [0, 1);
-  labels:  int32 uniform over {0..9}, drawn after the images of the same call.
+  labels:  int32 uniform over {0..9}, drawn after the images of the same call;
+  digits:  a learnable stand-in for MNIST (`make_digits`): ten fixed prototypes, each the sum of six
+           Gaussian strokes at positions drawn once from the prototype seed, and per sample a label,
+           a shift of up to two pixels each way and uniform pixel noise, clipped to [0, 1].
 """
 import numpy as np
 
@@ -53,6 +56,38 @@ def make_batch(n, seed):
     rng = _rng(seed)
     images = rng.random((n, 28, 28), dtype=np.float32)
     labels = rng.integers(0, 10, size=n, dtype=np.int32)
+    return images, labels
+
+
+PROTOTYPE_SEED = 28281010
+
+
+def digit_prototypes():
+    """float32 [10, 32, 32]: one blob pattern per class on a canvas with a two-pixel margin."""
+    rng = _rng(PROTOTYPE_SEED)
+    yy, xx = np.mgrid[0:32, 0:32].astype(np.float64)
+    protos = np.zeros((10, 32, 32))
+    for c in range(10):
+        for _ in range(6):
+            cy, cx = rng.uniform(7.0, 25.0, size=2)
+            sy, sx = rng.uniform(1.5, 4.0, size=2)
+            protos[c] += np.exp(-0.5 * (((yy - cy) / sy) ** 2 + ((xx - cx) / sx) ** 2))
+        protos[c] /= protos[c].max()
+    return protos.astype(np.float32)
+
+
+def make_digits(n, seed, noise=0.25):
+    """(images float32 [n,28,28] in [0,1], labels int32 [n]): shifted, noisy class prototypes."""
+    rng = _rng(seed)
+    protos = digit_prototypes()
+    labels = rng.integers(0, 10, size=n, dtype=np.int32)
+    dy = rng.integers(0, 5, size=n)
+    dx = rng.integers(0, 5, size=n)
+    images = np.empty((n, 28, 28), np.float32)
+    for i in range(n):
+        images[i] = protos[labels[i], dy[i]:dy[i] + 28, dx[i]:dx[i] + 28]
+    images += (rng.random((n, 28, 28), dtype=np.float32) - 0.5) * np.float32(2.0 * noise)
+    np.clip(images, 0.0, 1.0, out=images)
     return images, labels
 
 
