@@ -52,8 +52,8 @@ def main():
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        sys.exit("bench.py: this build is a single-GPU kernel study; run it with --gpus 1 "
-                 "(no multi-GPU path exists, see DESIGN.md)")
+        sys.exit("bench.py: the library is a single-GPU kernel study with no multi-GPU path; "
+                 "run it with --gpus 1")
 
     import numpy as np
     import torch

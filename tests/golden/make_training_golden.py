@@ -2,7 +2,7 @@
 """Writes the stored expected values of the full-size training configurations.
 
 Calls ONLY the CPU oracle (oracle/) and the seeded input generator; nothing here touches the GPU
-library.  Workload (BASELINE configs 2-4): 60000 synthetic training images and 10000 evaluation
+library.  Workload (the full-MNIST-sized configurations): 60000 synthetic training images and 10000 evaluation
 images (paper_1912_05234_amd/inputs.py, seeds below), batch 100, rate 0.05, weights from the default
 seed.  Outputs, all float64/int64 in one .npz beside this script:
   grad_1000 / grad_10000 / grad_60000, loss_*   summed gradient and loss of the first 1000 / 10000 /
