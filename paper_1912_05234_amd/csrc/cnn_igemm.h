@@ -103,15 +103,19 @@ __device__ __forceinline__ void block_interleave() {
 // Blocks first, first + stride, ... (count of them) of a GEMM for NTILE tiles that share the dense
 // operand: `dense` points at the lane's 16-byte entry of block 0, the entries of consecutive blocks
 // DSTEP entries apart; `koff` is the row of its q, indexed by block; `last` is the highest block index
-// that may be read (prefetches are clamped to it).
-template <int NTILE, int DSTEP>
+// that may be read (prefetches are clamped to it).  With ASUM the lane's dense operands are also
+// summed into *asum (each block once, in block order).
+template <int NTILE, int DSTEP, bool ASUM = false>
 __device__ __forceinline__ void gemm_blocks(f4 (&acc)[NTILE], const f4* dense, const i4* koff,
                                             const char* staged, const int (&off)[NTILE], int first,
-                                            int stride, int count, int last) {
+                                            int stride, int count, int last, float* asum = nullptr) {
   if (count <= 0) return;
   auto at = [&](int i) {
     const int b = first + i * stride;
     return b < last ? b : last;
+  };
+  auto add = [&](const f4& a) {
+    if (ASUM) *asum += (a[0] + a[1]) + (a[2] + a[3]);
   };
   i4 k0 = koff[at(0)], k1 = koff[at(1)];
   f4 a0 = dense[DSTEP * at(0)], a1;
@@ -123,21 +127,26 @@ __device__ __forceinline__ void gemm_blocks(f4 (&acc)[NTILE], const f4* dense, c
     block_gather<NTILE>(b1, staged, k1, off);
     k0 = koff[at(i + 2)];
     block_mfma<NTILE>(acc, a0, b0);
+    add(a0);
     block_interleave<NTILE>();
     a0 = dense[DSTEP * at(i + 2)];
     block_gather<NTILE>(b0, staged, k0, off);
     k1 = koff[at(i + 3)];
     block_mfma<NTILE>(acc, a1, b1);
+    add(a1);
     block_interleave<NTILE>();
   }
   if (i + 2 == count) {  // the last two blocks: nothing left to fetch ahead
     a1 = dense[DSTEP * at(i + 1)];
     block_gather<NTILE>(b1, staged, k1, off);
     block_mfma<NTILE>(acc, a0, b0);
+    add(a0);
     block_interleave<NTILE>();
     block_mfma<NTILE>(acc, a1, b1);
+    add(a1);
   } else {
     block_mfma<NTILE>(acc, a0, b0);
+    add(a0);
   }
 }
 
@@ -365,13 +374,19 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
 // gridDim.x, ... for M tile mt = by / NTG and the tap tiles of group ntg = by % NTG.  With three or
 // more tap tiles in all, wave w owns tiles 16 ntg + w + 4 i (i < 4) and KS = 1; with two (one) tap
 // tiles the waves split the pixels as well: tile w % 2 (0), K slice w / 2 (w) of KS = 2 (4), a slice
-// taking every KS-th block.  Results go to part[bx*KS + slice][mt][nt][16][16] and, for ntg = 0, the
-// bias sums to bpart[bx][16 mt + c] (bpart follows part).
+// taking every KS-th block.  Results go to part[bx*KS + slice][mt][nt][16][16]; the waves that own
+// tile 0 also sum their A operands, the bias gradient, into bpart[bx*KS + slice][16 mt + c] (bpart
+// follows part).
 //
 // K runs over the pixel slots n of a group (image-major, padded with zeros to whole blocks of 16).
 // Step s4 of block blk takes, in lane group q, slot n = 16 blk + 4 q + s4: a lane's four A values of a
 // block are then consecutive pixels of one channel, so the output error is staged as it lies in
 // memory, one row per channel.
+//
+// Staging uses the direct global-to-LDS load: a wave's instruction moves 64 items of VB bytes (16, or
+// 4 when an image or a map is not a multiple of four floats) from per-lane addresses to 64 VB
+// consecutive bytes of LDS, with no registers and no LDS write instructions in between.  Two LDS
+// buffers alternate: the loads of group i + 1 are issued before the matrix instructions of group i.
 struct WgradArgs {
   const float* in;
   const float* d_out;
@@ -384,33 +399,46 @@ struct WgradArgs {
   int R;          // rows of the staged error: min(16, Cout); row R stays zero
   int NB, groups;
   int NBK, NPS;   // blocks of 16 pixel slots per full group; row stride of the staged error (floats)
-  int stage_x;    // STAGE_* of the input images (VECTOR needs Cin*H*W % 4 == 0)
-  int stage_d;    // STAGE_* of the output error (VECTOR needs Ho*Wo % 4 == 0)
+  int XS;         // floats of one staged image buffer (whole load instructions)
+  int vec;        // 1: 16-byte items (Cin*H*W and Ho*Wo multiples of 4), 0: 4-byte items
   float inv_khkw, inv_kw, inv_howo, inv_wo;
 };
-// Sixteen threads stage one channel of the output error: up to PFDV 16-byte or PFDS 4-byte items each.
-constexpr int PFDV = 10, PFDS = 16;
 struct WgradLds {
-  int pb, dy, x, total;
+  int pb, buf, dy, x, buf_floats, total;  // dy and x are offsets inside a buffer
 };
 // Row stride of the staged error: 16-byte reads by eight lanes of consecutive channels then fall
 // into eight different groups of four banks.
 __host__ __device__ inline int error_row_stride(int blocks) { return 16 * blocks + 4; }
 __host__ __device__ inline WgradLds wgrad_lds(const WgradArgs& a) {
   WgradLds l;
-  l.pb = 0;                     // [4 rows: q][NBK][4] byte offset in x of slot 16 blk + 4 q + s4 (0 for padding)
-  l.dy = l.pb + 16 * a.NBK;     // [R + 1 rows: channel][NPS] output error by pixel slot
-  l.x = l.dy + (a.R + 1) * a.NPS;  // [NB][Cin*H*W]
-  l.total = l.x + round4(a.NB * a.Cin * a.H * a.W);
+  l.pb = 0;                  // [4 rows: q][NBK][4] byte offset in x of slot 16 blk + 4 q + s4 (0 for padding)
+  l.buf = l.pb + 16 * a.NBK;  // two buffers of buf_floats each:
+  l.dy = 0;                  //   [R + 1 rows: channel][NPS] output error by pixel slot
+  l.x = (a.R + 1) * a.NPS;   //   [XS] images of the group
+  l.buf_floats = l.x + a.XS;
+  l.total = l.buf + 2 * l.buf_floats;
   return l;
 }
 
-__global__ __launch_bounds__(THREADS, 2) void wgrad_kernel(const WgradArgs g) {
+// One direct global-to-LDS load: lane l moves VB bytes from its own address `src` to lds_base + l VB
+// (lds_base must be the same in every lane).  Counted by vmcnt like any vector memory load.
+template <int VB>
+__device__ __forceinline__ void load_to_lds(const float* src, float* lds_base);
+template <>
+__device__ __forceinline__ void load_to_lds<16>(const float* src, float* lds_base) {
+  __builtin_amdgcn_global_load_lds(src, lds_base, 16, 0, 0);
+}
+template <>
+__device__ __forceinline__ void load_to_lds<4>(const float* src, float* lds_base) {
+  __builtin_amdgcn_global_load_lds(src, lds_base, 4, 0, 0);
+}
+
+template <int VB>  // bytes per lane of a staging load
+__global__ __launch_bounds__(THREADS) void wgrad_kernel(const WgradArgs g) {
   extern __shared__ __align__(16) float lds[];
+  constexpr int V = VB / 4, CH = 64 * V;  // floats per lane and per load instruction
   const WgradLds L = wgrad_lds(g);
   int* pb = reinterpret_cast<int*>(lds + L.pb);
-  float* dy = lds + L.dy;
-  float* x = lds + L.x;
   const int t = threadIdx.x, wave = t >> 6, l = t & 63, q = l >> 4, j = l & 15;
   const int KHKW = g.KH * g.KW, HoWo = g.Ho * g.Wo, HW = g.H * g.W, per_image = g.Cin * HW;
   const int mt = blockIdx.y / g.NTG, ntg = blockIdx.y - mt * g.NTG;
@@ -426,7 +454,10 @@ __global__ __launch_bounds__(THREADS, 2) void wgrad_kernel(const WgradArgs g) {
     }
     pb[((((n >> 2) & 3) * g.NBK + (n >> 4)) << 2) + (n & 3)] = pbv;
   }
-  for (int e = t; e < g.NPS; e += THREADS) dy[g.R * g.NPS + e] = 0.0f;  // the zero row
+  // Both buffers start as zeros: the zero row stays so, and image cells that a ragged first group
+  // never loads must read as finite numbers (they meet zeros of the output error).
+  for (int e = t; e < 2 * L.buf_floats; e += THREADS) lds[L.buf + e] = 0.0f;
+  lds_barrier();
 
   // this wave's tiles and K slice; this lane's column (tap) of each tile
   const int tile0 = g.KS == 1 ? wave : g.KS == 2 ? (wave & 1) : 0;
@@ -447,140 +478,114 @@ __global__ __launch_bounds__(THREADS, 2) void wgrad_kernel(const WgradArgs g) {
   f4 acc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) acc[i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-  const f4* dense = reinterpret_cast<const f4*>(dy + (size_t)(j < rows ? j : g.R) * g.NPS + 4 * q);
+  const bool sums_bias = ntg == 0 && tile0 == 0;  // wave-uniform
+  float asum = 0.0f;
+  const int arow = (j < rows ? j : g.R) * g.NPS + 4 * q;
   const i4* koff = reinterpret_cast<const i4*>(pb) + q * g.NBK;
 
-  // Staging.  Images: as they lie in memory, zero past the last image of a ragged group.  Output
-  // error: thread t copies items lane16, lane16 + 16, ... of channel t / 16 of the M tile (an item is
-  // four pixel slots or one), zero from the group's last pixel up to whole blocks, and sums what it
-  // copies: the bias gradient.
-  const int ch = t >> 4, lane16 = t & 15;
-  const bool stager = ch < rows;
-  const int isz = g.stage_d == STAGE_VECTOR ? 4 : 1;  // pixel slots per item
-  f4 pv[PFV], pd[PFDV];
-  int soff[PFDS];  // offset of the thread's item i in d_out, relative to the group's channel
-  float bsum = 0.0f;
-  auto slot_source = [&](int n) {  // pixel slot n < NB*Ho*Wo
-    int img, r;
-    divmod(n, HoWo, g.inv_howo, img, r);
-    return img * g.Cout * HoWo + r;
-  };
-  if (g.stage_d != STAGE_DIRECT) {
+  // Source offset (floats, channel 0 of the group) of the lane's item in chunk wave + 4 i of a row
+  // of the output error: fixed for the whole kernel.
+  constexpr int DCH = 4;  // chunks of a row per wave: rows of up to 16 CH slots
+  int soff[DCH];
 #pragma unroll
-    for (int i = 0; i < PFDS; ++i) {
-      const int n = (lane16 + 16 * i) * isz;
-      soff[i] = (i < (g.stage_d == STAGE_VECTOR ? PFDV : PFDS) && n < g.NB * HoWo) ? slot_source(n) : 0;
+  for (int i = 0; i < DCH; ++i) {
+    const int n = (wave + WAVES * i) * CH + l * V;
+    soff[i] = 0;
+    if (n < g.NB * HoWo) {
+      int img, r;
+      divmod(n, HoWo, g.inv_howo, img, r);
+      soff[i] = img * g.Cout * HoWo + r;
     }
   }
-  auto issue = [&](int grp) {
+  // Loads of group grp into buffer `buf` (LDS float offset).
+  auto issue = [&](int grp, int buf) {
     const int b0 = grp * g.NB, nb = min(g.NB, g.B - b0), count = nb * per_image, npx = nb * HoWo;
     const float* src = g.in + (size_t)b0 * per_image;
-    if (g.stage_x == STAGE_VECTOR) {
-#pragma unroll
-      for (int i = 0; i < PFV; ++i)
-        if (t + THREADS * i < count >> 2) pv[i] = reinterpret_cast<const f4*>(src)[t + THREADS * i];
-    } else if (g.stage_x == STAGE_SCALAR) {
-#pragma unroll
-      for (int i = 0; i < PFS; ++i)
-        if (t + THREADS * i < count) pv[i >> 2][i & 3] = src[t + THREADS * i];
+    // images: items past the group's data re-read its last item (the cells they fill meet zeros)
+    for (int c = wave; c * CH < count; c += WAVES) {
+      const int e = min(c * CH + l * V, count - V);
+      load_to_lds<VB>(src + e, lds + buf + L.x + c * CH);
     }
-    if (stager) {
-      const float* dsrc = g.d_out + ((size_t)b0 * g.Cout + 16 * mt + ch) * HoWo;
-      if (g.stage_d == STAGE_VECTOR) {
+    // output error: row by row, lanes past the group's pixels load nothing (zeroed below)
+    const float* dsrc = g.d_out + ((size_t)b0 * g.Cout + 16 * mt) * HoWo;
+    for (int r = 0; r < rows; ++r) {
 #pragma unroll
-        for (int i = 0; i < PFDV; ++i)
-          if (4 * (lane16 + 16 * i) < npx) pd[i] = *reinterpret_cast<const f4*>(dsrc + soff[i]);
-      } else if (g.stage_d == STAGE_SCALAR) {
-#pragma unroll
-        for (int i = 0; i < PFDS; ++i)
-          if (lane16 + 16 * i < npx) pd[i >> 2][i & 3] = dsrc[soff[i]];
-      }
-    }
-  };
-  auto commit = [&](int grp) {
-    const int b0 = grp * g.NB, nb = min(g.NB, g.B - b0), count = nb * per_image, npx = nb * HoWo;
-    const int nbk = (npx + 15) >> 4;  // slots npx .. 16 nbk - 1 are staged as zero
-    if (g.stage_x == STAGE_VECTOR) {
-#pragma unroll
-      for (int i = 0; i < PFV; ++i) {
-        const int e = t + THREADS * i;
-        if (e < (g.NB * per_image) >> 2)
-          reinterpret_cast<f4*>(x)[e] = e < count >> 2 ? pv[i] : f4{0.0f, 0.0f, 0.0f, 0.0f};
-      }
-    } else if (g.stage_x == STAGE_SCALAR) {
-#pragma unroll
-      for (int i = 0; i < PFS; ++i) {
-        const int e = t + THREADS * i;
-        if (e < g.NB * per_image) x[e] = e < count ? pv[i >> 2][i & 3] : 0.0f;
-      }
-    } else {
-      const float* src = g.in + (size_t)b0 * per_image;
-      for (int e = t; e < g.NB * per_image; e += THREADS) x[e] = e < count ? src[e] : 0.0f;
-    }
-    if (stager) {
-      float* drow = dy + ch * g.NPS;
-      if (g.stage_d == STAGE_VECTOR) {
-#pragma unroll
-        for (int i = 0; i < PFDV; ++i) {
-          const int n = 4 * (lane16 + 16 * i);
-          if (n < 16 * nbk) {
-            const f4 v = n < npx ? pd[i] : f4{0.0f, 0.0f, 0.0f, 0.0f};
-            *reinterpret_cast<f4*>(drow + n) = v;
-            bsum += (v[0] + v[1]) + (v[2] + v[3]);
-          }
-        }
-      } else if (g.stage_d == STAGE_SCALAR) {
-#pragma unroll
-        for (int i = 0; i < PFDS; ++i) {
-          const int n = lane16 + 16 * i;
-          if (n < 16 * nbk) {
-            const float v = n < npx ? pd[i >> 2][i & 3] : 0.0f;
-            drow[n] = v;
-            bsum += v;
-          }
-        }
-      } else {
-        const float* dsrc = g.d_out + ((size_t)b0 * g.Cout + 16 * mt + ch) * HoWo;
-        for (int n = lane16; n < 16 * nbk; n += 16) {
-          const float v = n < npx ? dsrc[slot_source(n)] : 0.0f;
-          drow[n] = v;
-          bsum += v;
+      for (int i = 0; i < DCH; ++i) {
+        const int c = wave + WAVES * i;
+        if (c * CH < npx) {  // wave-uniform
+          if (c * CH + l * V < npx)
+            load_to_lds<VB>(dsrc + (size_t)r * HoWo + soff[i], lds + buf + L.dy + r * g.NPS + c * CH);
         }
       }
+    }
+    // slots npx .. 16 nbk - 1 of every row read as zero
+    const int nbk = (npx + 15) >> 4, tail = 16 * nbk - npx;
+    for (int e = t; e < rows * tail; e += THREADS) {
+      int r, k;
+      divmod(e, tail, 1.0f / (float)tail, r, k);
+      lds[buf + L.dy + r * g.NPS + npx + k] = 0.0f;
     }
   };
 
-  if ((int)blockIdx.x < g.groups) issue(blockIdx.x);
+  int cur = L.buf;
+  if ((int)blockIdx.x < g.groups) issue(blockIdx.x, cur);
   for (int grp = blockIdx.x; grp < g.groups; grp += gridDim.x) {
     const int nbk = (min(g.NB, g.B - grp * g.NB) * HoWo + 15) >> 4;
-    lds_barrier();  // tables (first pass) / the previous group's reads are complete
-    commit(grp);
-    lds_barrier();
-    if (grp + (int)gridDim.x < g.groups) issue(grp + gridDim.x);
+    __builtin_amdgcn_s_waitcnt(0);  // this wave's loads have landed in LDS
+    lds_barrier();                  // ... and everybody's; the other buffer is no longer read
+    const int nxt = cur == L.buf ? L.buf + L.buf_floats : L.buf;
+    if (grp + (int)gridDim.x < g.groups) issue(grp + gridDim.x, nxt);
     const int count = nbk > slice ? (nbk - slice + g.KS - 1) / g.KS : 0;
-    const char* xb = reinterpret_cast<const char*>(x);
-    switch (ntile) {
-      case 4: gemm_blocks<4, 4>(acc, dense, koff, xb, toff, slice, g.KS, count, nbk - 1); break;
-      case 3: {
-        f4(&a3)[3] = reinterpret_cast<f4(&)[3]>(acc);
-        const int(&t3)[3] = reinterpret_cast<const int(&)[3]>(toff);
-        gemm_blocks<3, 4>(a3, dense, koff, xb, t3, slice, g.KS, count, nbk - 1);
-        break;
+    const f4* dense = reinterpret_cast<const f4*>(lds + cur + L.dy + arow);
+    const char* xb = reinterpret_cast<const char*>(lds + cur + L.x);
+    if (sums_bias) {
+      switch (ntile) {
+        case 4: gemm_blocks<4, 4, true>(acc, dense, koff, xb, toff, slice, g.KS, count, nbk - 1, &asum); break;
+        case 3: {
+          f4(&a3)[3] = reinterpret_cast<f4(&)[3]>(acc);
+          const int(&t3)[3] = reinterpret_cast<const int(&)[3]>(toff);
+          gemm_blocks<3, 4, true>(a3, dense, koff, xb, t3, slice, g.KS, count, nbk - 1, &asum);
+          break;
+        }
+        case 2: {
+          f4(&a2)[2] = reinterpret_cast<f4(&)[2]>(acc);
+          const int(&t2)[2] = reinterpret_cast<const int(&)[2]>(toff);
+          gemm_blocks<2, 4, true>(a2, dense, koff, xb, t2, slice, g.KS, count, nbk - 1, &asum);
+          break;
+        }
+        case 1: {
+          f4(&a1)[1] = reinterpret_cast<f4(&)[1]>(acc);
+          const int(&t1)[1] = reinterpret_cast<const int(&)[1]>(toff);
+          gemm_blocks<1, 4, true>(a1, dense, koff, xb, t1, slice, g.KS, count, nbk - 1, &asum);
+          break;
+        }
+        default: break;
       }
-      case 2: {
-        f4(&a2)[2] = reinterpret_cast<f4(&)[2]>(acc);
-        const int(&t2)[2] = reinterpret_cast<const int(&)[2]>(toff);
-        gemm_blocks<2, 4>(a2, dense, koff, xb, t2, slice, g.KS, count, nbk - 1);
-        break;
+    } else {
+      switch (ntile) {
+        case 4: gemm_blocks<4, 4>(acc, dense, koff, xb, toff, slice, g.KS, count, nbk - 1); break;
+        case 3: {
+          f4(&a3)[3] = reinterpret_cast<f4(&)[3]>(acc);
+          const int(&t3)[3] = reinterpret_cast<const int(&)[3]>(toff);
+          gemm_blocks<3, 4>(a3, dense, koff, xb, t3, slice, g.KS, count, nbk - 1);
+          break;
+        }
+        case 2: {
+          f4(&a2)[2] = reinterpret_cast<f4(&)[2]>(acc);
+          const int(&t2)[2] = reinterpret_cast<const int(&)[2]>(toff);
+          gemm_blocks<2, 4>(a2, dense, koff, xb, t2, slice, g.KS, count, nbk - 1);
+          break;
+        }
+        case 1: {
+          f4(&a1)[1] = reinterpret_cast<f4(&)[1]>(acc);
+          const int(&t1)[1] = reinterpret_cast<const int(&)[1]>(toff);
+          gemm_blocks<1, 4>(a1, dense, koff, xb, t1, slice, g.KS, count, nbk - 1);
+          break;
+        }
+        default: break;
       }
-      case 1: {
-        f4(&a1)[1] = reinterpret_cast<f4(&)[1]>(acc);
-        const int(&t1)[1] = reinterpret_cast<const int(&)[1]>(toff);
-        gemm_blocks<1, 4>(a1, dense, koff, xb, t1, slice, g.KS, count, nbk - 1);
-        break;
-      }
-      default: break;
     }
+    cur = nxt;
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -591,12 +596,12 @@ __global__ __launch_bounds__(THREADS, 2) void wgrad_kernel(const WgradArgs g) {
       for (int r = 0; r < 4; ++r) o[16 * r] = acc[i][r];
     }
   }
-  if (ntg == 0) {  // bias sums: the sixteen threads of a channel by a fixed butterfly
-#pragma unroll
-    for (int m = 8; m > 0; m >>= 1) bsum += __shfl_xor(bsum, m, 16);
-    if (lane16 == 0) {
+  if (sums_bias) {  // lane (j, q) summed channel j over its quarter of every block: add the four q
+    asum += __shfl_xor(asum, 16, 64);
+    asum += __shfl_xor(asum, 32, 64);
+    if (q == 0) {
       float* bpart = g.part + (size_t)gridDim.x * g.KS * g.MT * g.NT * 256;
-      bpart[(size_t)blockIdx.x * g.MT * 16 + 16 * mt + ch] = bsum;
+      bpart[((size_t)blockIdx.x * g.KS + slice) * g.MT * 16 + 16 * mt + j] = asum;
     }
   }
 }

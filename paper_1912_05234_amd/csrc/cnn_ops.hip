@@ -206,10 +206,11 @@ inline int launched() { return hipGetLastError() == hipSuccess ? CNN_OK : CNN_EH
 // ---- launch plans of the matrix-core kernels ----------------------------------------------------
 constexpr int LDS_LIMIT = 64 * 1024 - 512;  // bytes of dynamic LDS one workgroup may ask for
 constexpr int LDS_TARGET = 48 * 1024;       // preferred, so that three workgroups share a compute unit
+constexpr int WGRAD_LDS_TARGET = 36 * 1024; // both buffers of the weight gradient: four workgroups per compute unit
 constexpr int CU_LDS = 160 * 1024;
 constexpr int NUM_CU = 256;
 constexpr int MAX_GROUP = 64;               // images per group
-constexpr int MAX_PARTIALS = 512;           // workgroup columns (partial sums) of the weight gradient
+constexpr int MAX_PARTIALS = 1024;          // workgroup columns (partial sums) of the weight gradient
 
 // Workgroups that keep every compute unit as full as the LDS use allows (at most four each).
 unsigned resident_workgroups(size_t lds_bytes) {
@@ -321,23 +322,25 @@ WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
   a.B = B, a.Cin = Cin, a.H = H, a.W = W, a.Cout = Cout, a.KH = KH, a.KW = KW;
   a.Ho = H - KH + 1, a.Wo = W - KW + 1;
   const long long K = (long long)Cin * KH * KW, HoWo = (long long)a.Ho * a.Wo, per_image = (long long)Cin * H * W;
-  if (per_image + 10 * (HoWo + 36) > LDS_LIMIT / 4 || K > (1 << 20)) return p;
+  if (2 * (per_image + 2 * HoWo) > LDS_LIMIT / 4 || K > (1 << 20)) return p;
   a.K = (int)K, a.MT = (Cout + 15) / 16, a.NT = (int)((K + 15) / 16), a.NTG = (a.NT + 15) / 16;
   a.KS = a.NT >= 3 ? 1 : a.NT == 2 ? 2 : 4;
   a.R = Cout < 16 ? Cout : 16;
+  a.vec = (per_image % 4 == 0 && HoWo % 4 == 0) ? 1 : 0;
+  const int chunk = a.vec ? 256 : 64;  // floats per staging load instruction
   auto bytes = [&](int nb) {
     a.NB = nb;
     a.NBK = (int)((nb * HoWo + 15) / 16);
     a.NPS = igemm::error_row_stride(a.NBK);
+    a.XS = (int)((nb * per_image + chunk - 1) / chunk * chunk);
     return (long long)igemm::wgrad_lds(a).total * 4;
   };
-  if (bytes(1) > LDS_LIMIT) return p;
+  if (HoWo > 16LL * chunk || bytes(1) > LDS_LIMIT) return p;
   int nb = 1;
   const int nb_fill = (B + MAX_PARTIALS - 1) / MAX_PARTIALS;
-  // more images per group while the partial sums stay at MAX_PARTIALS columns, LDS stays within the
-  // target and the output error still travels through registers
-  const long long slots = HoWo % 4 == 0 ? 64LL * igemm::PFDV : 16LL * igemm::PFDS;
-  for (int c = 2; c <= MAX_GROUP && c <= B && c <= nb_fill && bytes(c) <= LDS_TARGET && 16LL * a.NBK <= slots; ++c)
+  // more images per group while the partial sums stay at MAX_PARTIALS columns, the two buffers stay
+  // within the LDS target and a row of the output error within sixteen load instructions
+  for (int c = 2; c <= MAX_GROUP && c <= B && c <= nb_fill && bytes(c) <= WGRAD_LDS_TARGET && c * HoWo <= 16LL * chunk; ++c)
     nb = c;
   p.lds_bytes = (size_t)bytes(nb);
   a.groups = (B + nb - 1) / nb;
@@ -347,14 +350,7 @@ WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
   if (gx > (unsigned)a.groups) gx = (unsigned)a.groups;
   p.gx = gx;
   p.gy = (unsigned)(a.MT * a.NTG);
-  p.workspace_bytes = ((size_t)gx * a.KS * a.MT * a.NT * 256 + (size_t)gx * a.MT * 16) * sizeof(float);
-  const long long per_group = nb * per_image;
-  a.stage_x = (per_image % 4 == 0 && per_group / 4 <= igemm::THREADS * igemm::PFV)
-                  ? igemm::STAGE_VECTOR
-                  : per_group <= igemm::THREADS * igemm::PFS ? igemm::STAGE_SCALAR : igemm::STAGE_DIRECT;
-  a.stage_d = (HoWo % 4 == 0 && 4 * a.NBK <= 16 * igemm::PFDV)
-                  ? igemm::STAGE_VECTOR
-                  : 16 * a.NBK <= 16 * igemm::PFDS ? igemm::STAGE_SCALAR : igemm::STAGE_DIRECT;
+  p.workspace_bytes = ((size_t)gx * a.KS * a.MT * a.NT * 256 + (size_t)gx * a.KS * a.MT * 16) * sizeof(float);
   a.inv_khkw = 1.0f / (float)(KH * KW), a.inv_kw = 1.0f / (float)KW;
   a.inv_howo = 1.0f / (float)HoWo, a.inv_wo = 1.0f / (float)a.Wo;
   p.fits = true;
@@ -410,10 +406,13 @@ int cnn_conv_bwd_weight(const float* in, const float* d_out, float* d_k, float* 
   WgradPlan p = plan_wgrad(B, Cin, H, W, Cout, KH, KW);
   if (p.fits && workspace && workspace_bytes >= p.workspace_bytes) {
     p.a.in = in, p.a.d_out = d_out, p.a.part = static_cast<float*>(workspace);
-    igemm::wgrad_kernel<<<dim3(p.gx, p.gy), igemm::THREADS, p.lds_bytes, (hipStream_t)hip_stream>>>(p.a);
+    if (p.a.vec)
+      igemm::wgrad_kernel<16><<<dim3(p.gx, p.gy), igemm::THREADS, p.lds_bytes, (hipStream_t)hip_stream>>>(p.a);
+    else
+      igemm::wgrad_kernel<4><<<dim3(p.gx, p.gy), igemm::THREADS, p.lds_bytes, (hipStream_t)hip_stream>>>(p.a);
     const unsigned blocks = (unsigned)(((size_t)Cout * p.a.K + Cout + 15) / 16);
     igemm::wgrad_reduce_kernel<<<blocks, igemm::THREADS, 0, (hipStream_t)hip_stream>>>(
-        p.a.part, (int)p.gx * p.a.KS, (int)p.gx, p.a.MT, p.a.NT, Cout, p.a.K, d_k, d_bias);
+        p.a.part, (int)p.gx * p.a.KS, (int)p.gx * p.a.KS, p.a.MT, p.a.NT, Cout, p.a.K, d_k, d_bias);
     return launched();
   }
   const unsigned blocks = (unsigned)(Cout * Cin * KH * KW + (d_bias ? Cout : 0));
