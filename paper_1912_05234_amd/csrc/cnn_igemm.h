@@ -378,30 +378,37 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
 // tile 0 also sum their A operands, the bias gradient, into bpart[bx*KS + slice][16 mt + c] (bpart
 // follows part).
 //
+// With column packing (few output channels, P > 1) the rows are (co, sh), a pixel slot is the group
+// (y, X) of P adjacent pixels and the columns are the shifted taps (ci, u, v' < KW+P-1):
+//   T[(co,sh)][(ci,u,v')] = sum_{slots} d_out[co][y][P X + sh] * in[ci][y+u][P X + v'],
+//   d_k[co][ci][u][v] = sum_sh T[(co,sh)][(ci,u,v+sh)]        (the second kernel adds the P terms).
+//
 // K runs over the pixel slots n of a group (image-major, padded with zeros to whole blocks of 16).
 // Step s4 of block blk takes, in lane group q, slot n = 16 blk + 4 q + s4: a lane's four A values of a
 // block are then consecutive pixels of one channel, so the output error is staged as it lies in
 // memory, one row per channel.
 //
-// Staging uses the direct global-to-LDS load: a wave's instruction moves 64 items of VB bytes (16, or
-// 4 when an image or a map is not a multiple of four floats) from per-lane addresses to 64 VB
-// consecutive bytes of LDS, with no registers and no LDS write instructions in between.  Two LDS
+// Staging uses the direct global-to-LDS load: a wave's instruction moves 64 items of 16 or 4 bytes
+// (4 when an image or a map is not a multiple of four floats, or the rows are packed) from per-lane
+// addresses to consecutive bytes of LDS, with no registers and no LDS write instructions in between.  Two LDS
 // buffers alternate: the loads of group i + 1 are issued before the matrix instructions of group i.
 struct WgradArgs {
   const float* in;
   const float* d_out;
   float* part;
   int B, Cin, H, W, Cout, Ho, Wo, KH, KW;
-  int K;          // Cin*KH*KW taps
-  int MT, NT;     // tiles of Cout and of the K taps
-  int NTG;        // groups of 16 tap tiles
+  int P, MR, KWP, WOP;  // column packing as in the forward form: rows (co, sh) = Cout*P, KW+P-1, Wo/P
+  int K;          // columns of D: the Cin*KH*KWP (shifted) taps
+  int MT, NT;     // tiles of the MR rows and of the K columns
+  int NTG;        // groups of 16 column tiles
   int KS;         // K slices per workgroup
-  int R;          // rows of the staged error: min(16, Cout); row R stays zero
+  int R;          // rows of the staged error: min(16, MR); row R stays zero
   int NB, groups;
   int NBK, NPS;   // blocks of 16 pixel slots per full group; row stride of the staged error (floats)
   int XS;         // floats of one staged image buffer (whole load instructions)
-  int vec;        // 1: 16-byte items (Cin*H*W and Ho*Wo multiples of 4), 0: 4-byte items
-  float inv_khkw, inv_kw, inv_howo, inv_wo;
+  int vec_x;      // 16-byte items for the images (Cin*H*W a multiple of 4), else 4-byte
+  int vec_d;      // 16-byte items for the output error (P = 1 and Ho*Wo a multiple of 4), else 4-byte
+  float inv_p, inv_khkwp, inv_kwp, inv_spi, inv_wop;
 };
 struct WgradLds {
   int pb, buf, dy, x, buf_floats, total;  // dy and x are offsets inside a buffer
@@ -433,24 +440,25 @@ __device__ __forceinline__ void load_to_lds<4>(const float* src, float* lds_base
   __builtin_amdgcn_global_load_lds(src, lds_base, 4, 0, 0);
 }
 
-template <int VB>  // bytes per lane of a staging load
+template <int VBX, int VBD>  // bytes per lane of a staging load: images, output error
 __global__ __launch_bounds__(THREADS) void wgrad_kernel(const WgradArgs g) {
   extern __shared__ __align__(16) float lds[];
-  constexpr int V = VB / 4, CH = 64 * V;  // floats per lane and per load instruction
+  constexpr int VX = VBX / 4, CHX = 64 * VX;  // floats per lane and per load instruction, images
+  constexpr int VD = VBD / 4, CHD = 64 * VD;  // ... output error
   const WgradLds L = wgrad_lds(g);
   int* pb = reinterpret_cast<int*>(lds + L.pb);
   const int t = threadIdx.x, wave = t >> 6, l = t & 63, q = l >> 4, j = l & 15;
-  const int KHKW = g.KH * g.KW, HoWo = g.Ho * g.Wo, HW = g.H * g.W, per_image = g.Cin * HW;
+  const int KHKWP = g.KH * g.KWP, HoWo = g.Ho * g.Wo, SPI = g.Ho * g.WOP, HW = g.H * g.W, per_image = g.Cin * HW;
   const int mt = blockIdx.y / g.NTG, ntg = blockIdx.y - mt * g.NTG;
-  const int rows = min(16, g.Cout - 16 * mt);
+  const int rows = min(16, g.MR - 16 * mt);
 
   for (int n = t; n < 16 * g.NBK; n += THREADS) {
     int pbv = 0;
-    if (n < g.NB * HoWo) {
+    if (n < g.NB * SPI) {
       int img, r, y, xx;
-      divmod(n, HoWo, g.inv_howo, img, r);
-      divmod(r, g.Wo, g.inv_wo, y, xx);
-      pbv = 4 * (img * per_image + y * g.W + xx);
+      divmod(n, SPI, g.inv_spi, img, r);
+      divmod(r, g.WOP, g.inv_wop, y, xx);
+      pbv = 4 * (img * per_image + y * g.W + g.P * xx);
     }
     pb[((((n >> 2) & 3) * g.NBK + (n >> 4)) << 2) + (n & 3)] = pbv;
   }
@@ -469,10 +477,10 @@ __global__ __launch_bounds__(THREADS) void wgrad_kernel(const WgradArgs g) {
     if (nt < g.NT && (g.KS == 1 || i == 0)) ntile = i + 1;
     toff[i] = 0;
     if (col < g.K) {
-      int c, rem, u, vv;
-      divmod(col, KHKW, g.inv_khkw, c, rem);
-      divmod(rem, g.KW, g.inv_kw, u, vv);
-      toff[i] = 4 * (c * HW + u * g.W + vv);
+      int c, rem, u, vp;
+      divmod(col, KHKWP, g.inv_khkwp, c, rem);
+      divmod(rem, g.KWP, g.inv_kwp, u, vp);
+      toff[i] = 4 * (c * HW + u * g.W + vp);
     }
   }
   f4 acc[4];
@@ -483,38 +491,47 @@ __global__ __launch_bounds__(THREADS) void wgrad_kernel(const WgradArgs g) {
   const int arow = (j < rows ? j : g.R) * g.NPS + 4 * q;
   const i4* koff = reinterpret_cast<const i4*>(pb) + q * g.NBK;
 
-  // Source offset (floats, channel 0 of the group) of the lane's item in chunk wave + 4 i of a row
-  // of the output error: fixed for the whole kernel.
-  constexpr int DCH = 4;  // chunks of a row per wave: rows of up to 16 CH slots
+  // Source offset (floats, channel 0 and shift 0 of the group) of the lane's item in chunk
+  // wave + 4 i of a row of the output error: fixed for the whole kernel.
+  constexpr int DCH = 4;  // chunks of a row per wave: rows of up to 16 CHD slots
   int soff[DCH];
 #pragma unroll
   for (int i = 0; i < DCH; ++i) {
-    const int n = (wave + WAVES * i) * CH + l * V;
+    const int n = (wave + WAVES * i) * CHD + l * VD;
     soff[i] = 0;
-    if (n < g.NB * HoWo) {
-      int img, r;
-      divmod(n, HoWo, g.inv_howo, img, r);
-      soff[i] = img * g.Cout * HoWo + r;
+    if (n < g.NB * SPI) {
+      int img, r, y, xx;
+      divmod(n, SPI, g.inv_spi, img, r);
+      divmod(r, g.WOP, g.inv_wop, y, xx);
+      soff[i] = img * g.Cout * HoWo + y * g.Wo + g.P * xx;
     }
   }
   // Loads of group grp into buffer `buf` (LDS float offset).
   auto issue = [&](int grp, int buf) {
-    const int b0 = grp * g.NB, nb = min(g.NB, g.B - b0), count = nb * per_image, npx = nb * HoWo;
+    const int b0 = grp * g.NB, nb = min(g.NB, g.B - b0), count = nb * per_image, npx = nb * SPI;
     const float* src = g.in + (size_t)b0 * per_image;
     // images: items past the group's data re-read its last item (the cells they fill meet zeros)
-    for (int c = wave; c * CH < count; c += WAVES) {
-      const int e = min(c * CH + l * V, count - V);
-      load_to_lds<VB>(src + e, lds + buf + L.x + c * CH);
+    for (int c = wave; c * CHX < count; c += WAVES) {
+      const int e = min(c * CHX + l * VX, count - VX);
+      load_to_lds<VBX>(src + e, lds + buf + L.x + c * CHX);
     }
-    // output error: row by row, lanes past the group's pixels load nothing (zeroed below)
-    const float* dsrc = g.d_out + ((size_t)b0 * g.Cout + 16 * mt) * HoWo;
-    for (int r = 0; r < rows; ++r) {
+    // output error: row by row, lanes past the group's slots load nothing (zeroed below)
+    // (packed rows exist only with one M tile, so row r of the tile is row r of D)
+    const float* dsrc = g.d_out + ((size_t)b0 * g.Cout + 16 * mt) * HoWo;  // row 0: channel 16 mt, shift 0
+    for (int r = 0, sh = 0; r < rows; ++r) {
+      if (r > 0) {  // next row: the next shift of the same channel, or the next channel
+        if (++sh == g.P) {
+          sh = 0;
+          dsrc += HoWo - (g.P - 1);
+        } else {
+          dsrc += 1;
+        }
+      }
 #pragma unroll
       for (int i = 0; i < DCH; ++i) {
         const int c = wave + WAVES * i;
-        if (c * CH < npx) {  // wave-uniform
-          if (c * CH + l * V < npx)
-            load_to_lds<VB>(dsrc + (size_t)r * HoWo + soff[i], lds + buf + L.dy + r * g.NPS + c * CH);
+        if (c * CHD < npx) {  // wave-uniform
+          if (c * CHD + l * VD < npx) load_to_lds<VBD>(dsrc + soff[i], lds + buf + L.dy + r * g.NPS + c * CHD);
         }
       }
     }
@@ -530,7 +547,7 @@ __global__ __launch_bounds__(THREADS) void wgrad_kernel(const WgradArgs g) {
   int cur = L.buf;
   if ((int)blockIdx.x < g.groups) issue(blockIdx.x, cur);
   for (int grp = blockIdx.x; grp < g.groups; grp += gridDim.x) {
-    const int nbk = (min(g.NB, g.B - grp * g.NB) * HoWo + 15) >> 4;
+    const int nbk = (min(g.NB, g.B - grp * g.NB) * SPI + 15) >> 4;
     __builtin_amdgcn_s_waitcnt(0);  // this wave's loads have landed in LDS
     lds_barrier();                  // ... and everybody's; the other buffer is no longer read
     const int nxt = cur == L.buf ? L.buf + L.buf_floats : L.buf;
@@ -606,42 +623,48 @@ __global__ __launch_bounds__(THREADS) void wgrad_kernel(const WgradArgs g) {
   }
 }
 
-// d_k[co][tap] = sum over the GP partial tiles, d_bias[co] = sum over the GB partial bias rows, each
-// in sixteen interleaved strands taken in ascending order and combined by a fixed tree.
-__global__ __launch_bounds__(THREADS) void wgrad_reduce_kernel(const float* __restrict__ part, int GP, int GB,
-                                                               int MT, int NT, int Cout, int K,
-                                                               float* __restrict__ d_k,
+// d_k[co][ci][u][v] = sum over the GP partial tiles and the P shifts of T[(co,sh)][(ci,u,v+sh)];
+// d_bias[co] = sum over the GP partial bias rows and the P shifts.  A workgroup takes REDUCE_EPW
+// outputs; REDUCE_STRANDS interleaved strands walk the partials in ascending order, eight loads in
+// flight (the walk is bound by load latency, so many short strands beat few long ones), and are
+// combined by a fixed tree.
+constexpr int REDUCE_EPW = 16, REDUCE_STRANDS = THREADS / REDUCE_EPW;
+__global__ __launch_bounds__(THREADS) void wgrad_reduce_kernel(const float* __restrict__ part, int GP, int MT,
+                                                               int NT, int Cout, int Cin, int KH, int KW,
+                                                               int P, float* __restrict__ d_k,
                                                                float* __restrict__ d_bias) {
   __shared__ float red[THREADS];
-  const int strand = threadIdx.x >> 4, el = blockIdx.x * 16 + (threadIdx.x & 15);
-  const int nk = Cout * K, total = nk + (d_bias ? Cout : 0);
+  const int strand = threadIdx.x / REDUCE_EPW, el = blockIdx.x * REDUCE_EPW + threadIdx.x % REDUCE_EPW;
+  const int KWP = KW + P - 1, nk = Cout * Cin * KH * KW, total = nk + (d_bias ? Cout : 0);
   float sum = 0.0f;
   if (el < total) {
-    const float* p;
-    size_t stride;
-    int G;
-    if (el < nk) {
-      const int co = el / K, col = el - co * K;
-      p = part + ((size_t)(co >> 4) * NT + (col >> 4)) * 256 + (co & 15) * 16 + (col & 15);
-      stride = (size_t)MT * NT * 256;
-      G = GP;
-    } else {
-      p = part + (size_t)GP * MT * NT * 256 + (el - nk);
-      stride = (size_t)MT * 16;
-      G = GB;
+    for (int sh = 0; sh < P; ++sh) {
+      const float* p;
+      size_t stride;
+      if (el < nk) {
+        const int v = el % KW, cu = (el / KW) % (Cin * KH), co = el / (KW * Cin * KH);
+        const int row = co * P + sh, col = cu * KWP + v + sh;
+        p = part + ((size_t)(row >> 4) * NT + (col >> 4)) * 256 + (row & 15) * 16 + (col & 15);
+        stride = (size_t)MT * NT * 256;
+      } else {
+        p = part + (size_t)GP * MT * NT * 256 + (size_t)(el - nk) * P + sh;
+        stride = (size_t)MT * 16;
+      }
+      int gi = strand;
+      for (; gi + 7 * REDUCE_STRANDS < GP; gi += 8 * REDUCE_STRANDS) {
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = p[(gi + REDUCE_STRANDS * k) * stride];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) sum += v[k];
+      }
+      for (; gi < GP; gi += REDUCE_STRANDS) sum += p[gi * stride];
     }
-    int gi = strand;
-    for (; gi + 48 < G; gi += 64) {
-      const float v0 = p[gi * stride], v1 = p[(gi + 16) * stride], v2 = p[(gi + 32) * stride],
-                  v3 = p[(gi + 48) * stride];
-      sum = (((sum + v0) + v1) + v2) + v3;
-    }
-    for (; gi < G; gi += 16) sum += p[gi * stride];
   }
   red[threadIdx.x] = sum;
   __syncthreads();
-  for (int s = 8; s > 0; s >>= 1) {
-    if (strand < s) red[threadIdx.x] += red[threadIdx.x + 16 * s];
+  for (int s = REDUCE_STRANDS / 2; s > 0; s >>= 1) {
+    if (strand < s) red[threadIdx.x] += red[threadIdx.x + REDUCE_EPW * s];
     __syncthreads();
   }
   if (strand == 0 && el < total) {

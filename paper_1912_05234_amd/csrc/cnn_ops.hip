@@ -315,32 +315,36 @@ struct WgradPlan {
   size_t lds_bytes = 0, workspace_bytes = 0;
 };
 
-WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
+WgradPlan plan_wgrad_packed(int B, int Cin, int H, int W, int Cout, int KH, int KW, int P) {
   WgradPlan p;
   igemm::WgradArgs& a = p.a;
   a.in = nullptr, a.d_out = nullptr, a.part = nullptr;
   a.B = B, a.Cin = Cin, a.H = H, a.W = W, a.Cout = Cout, a.KH = KH, a.KW = KW;
   a.Ho = H - KH + 1, a.Wo = W - KW + 1;
-  const long long K = (long long)Cin * KH * KW, HoWo = (long long)a.Ho * a.Wo, per_image = (long long)Cin * H * W;
-  if (2 * (per_image + 2 * HoWo) > LDS_LIMIT / 4 || K > (1 << 20)) return p;
-  a.K = (int)K, a.MT = (Cout + 15) / 16, a.NT = (int)((K + 15) / 16), a.NTG = (a.NT + 15) / 16;
+  a.P = P, a.MR = Cout * P, a.KWP = KW + P - 1, a.WOP = a.Wo / P;
+  const long long K = (long long)Cin * KH * a.KWP, HoWo = (long long)a.Ho * a.Wo, SPI = (long long)a.Ho * a.WOP;
+  const long long per_image = (long long)Cin * H * W;
+  if (2 * (per_image + 2 * SPI) > LDS_LIMIT / 4 || K > (1 << 20)) return p;
+  a.K = (int)K, a.MT = (a.MR + 15) / 16, a.NT = (int)((K + 15) / 16), a.NTG = (a.NT + 15) / 16;
   a.KS = a.NT >= 3 ? 1 : a.NT == 2 ? 2 : 4;
-  a.R = Cout < 16 ? Cout : 16;
-  a.vec = (per_image % 4 == 0 && HoWo % 4 == 0) ? 1 : 0;
-  const int chunk = a.vec ? 256 : 64;  // floats per staging load instruction
+  a.R = a.MR < 16 ? a.MR : 16;
+  a.vec_x = per_image % 4 == 0 ? 1 : 0;
+  a.vec_d = (P == 1 && HoWo % 4 == 0) ? 1 : 0;
+  const int chunk_x = a.vec_x ? 256 : 64, chunk_d = a.vec_d ? 256 : 64;  // floats per staging load instruction
   auto bytes = [&](int nb) {
     a.NB = nb;
-    a.NBK = (int)((nb * HoWo + 15) / 16);
+    a.NBK = (int)((nb * SPI + 15) / 16);
     a.NPS = igemm::error_row_stride(a.NBK);
-    a.XS = (int)((nb * per_image + chunk - 1) / chunk * chunk);
+    a.XS = (int)((nb * per_image + chunk_x - 1) / chunk_x * chunk_x);
     return (long long)igemm::wgrad_lds(a).total * 4;
   };
-  if (HoWo > 16LL * chunk || bytes(1) > LDS_LIMIT) return p;
+  if (SPI > 16LL * chunk_d || bytes(1) > LDS_LIMIT) return p;
   int nb = 1;
   const int nb_fill = (B + MAX_PARTIALS - 1) / MAX_PARTIALS;
   // more images per group while the partial sums stay at MAX_PARTIALS columns, the two buffers stay
   // within the LDS target and a row of the output error within sixteen load instructions
-  for (int c = 2; c <= MAX_GROUP && c <= B && c <= nb_fill && bytes(c) <= WGRAD_LDS_TARGET && c * HoWo <= 16LL * chunk; ++c)
+  for (int c = 2; c <= MAX_GROUP && c <= B && c <= nb_fill && bytes(c) <= WGRAD_LDS_TARGET && c * SPI <= 16LL * chunk_d;
+       ++c)
     nb = c;
   p.lds_bytes = (size_t)bytes(nb);
   a.groups = (B + nb - 1) / nb;
@@ -351,10 +355,31 @@ WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
   p.gx = gx;
   p.gy = (unsigned)(a.MT * a.NTG);
   p.workspace_bytes = ((size_t)gx * a.KS * a.MT * a.NT * 256 + (size_t)gx * a.KS * a.MT * 16) * sizeof(float);
-  a.inv_khkw = 1.0f / (float)(KH * KW), a.inv_kw = 1.0f / (float)KW;
-  a.inv_howo = 1.0f / (float)HoWo, a.inv_wo = 1.0f / (float)a.Wo;
+  a.inv_p = 1.0f / (float)P, a.inv_khkwp = 1.0f / (float)(KH * a.KWP), a.inv_kwp = 1.0f / (float)a.KWP;
+  a.inv_spi = 1.0f / (float)SPI, a.inv_wop = 1.0f / (float)a.WOP;
   p.fits = true;
   return p;
+}
+
+// The packing factor that needs the fewest matrix instructions per image (column tiles x blocks of
+// pixel slots) among the divisors P of Wo with Cout*P <= 16; 1 for kernels one column wide.
+WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
+  int best = 1;
+  if (KW > 1) {
+    const long long Ho = H - KH + 1, Wo = W - KW + 1;
+    long long best_cost = -1;
+    for (int P = 1; P * Cout <= 16; ++P) {
+      if (Wo % P) continue;
+      const long long cost = (((long long)Cin * KH * (KW + P - 1) + 15) / 16) * ((Ho * (Wo / P) + 15) / 16);
+      if (best_cost < 0 || cost < best_cost) best_cost = cost, best = P;
+    }
+  }
+  for (int P = best; P > 1; --P) {
+    if ((W - KW + 1) % P) continue;
+    const WgradPlan p = plan_wgrad_packed(B, Cin, H, W, Cout, KH, KW, P);
+    if (p.fits) return p;
+  }
+  return plan_wgrad_packed(B, Cin, H, W, Cout, KH, KW, 1);
 }
 
 inline bool conv_args_ok(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
@@ -406,13 +431,20 @@ int cnn_conv_bwd_weight(const float* in, const float* d_out, float* d_k, float* 
   WgradPlan p = plan_wgrad(B, Cin, H, W, Cout, KH, KW);
   if (p.fits && workspace && workspace_bytes >= p.workspace_bytes) {
     p.a.in = in, p.a.d_out = d_out, p.a.part = static_cast<float*>(workspace);
-    if (p.a.vec)
-      igemm::wgrad_kernel<16><<<dim3(p.gx, p.gy), igemm::THREADS, p.lds_bytes, (hipStream_t)hip_stream>>>(p.a);
+    const dim3 grid(p.gx, p.gy);
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (p.a.vec_x && p.a.vec_d)
+      igemm::wgrad_kernel<16, 16><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
+    else if (p.a.vec_x)
+      igemm::wgrad_kernel<16, 4><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
+    else if (p.a.vec_d)
+      igemm::wgrad_kernel<4, 16><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
     else
-      igemm::wgrad_kernel<4><<<dim3(p.gx, p.gy), igemm::THREADS, p.lds_bytes, (hipStream_t)hip_stream>>>(p.a);
-    const unsigned blocks = (unsigned)(((size_t)Cout * p.a.K + Cout + 15) / 16);
-    igemm::wgrad_reduce_kernel<<<blocks, igemm::THREADS, 0, (hipStream_t)hip_stream>>>(
-        p.a.part, (int)p.gx * p.a.KS, (int)p.gx * p.a.KS, p.a.MT, p.a.NT, Cout, p.a.K, d_k, d_bias);
+      igemm::wgrad_kernel<4, 4><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
+    const unsigned blocks =
+        (unsigned)(((size_t)Cout * Cin * KH * KW + Cout + igemm::REDUCE_EPW - 1) / igemm::REDUCE_EPW);
+    igemm::wgrad_reduce_kernel<<<blocks, igemm::THREADS, 0, st>>>(p.a.part, (int)p.gx * p.a.KS, p.a.MT, p.a.NT, Cout,
+                                                                 Cin, KH, KW, p.a.P, d_k, d_bias);
     return launched();
   }
   const unsigned blocks = (unsigned)(Cout * Cin * KH * KW + (d_bias ? Cout : 0));
