@@ -624,17 +624,17 @@ __global__ __launch_bounds__(THREADS) void wgrad_kernel(const WgradArgs g) {
 }
 
 // d_k[co][ci][u][v] = sum over the GP partial tiles and the P shifts of T[(co,sh)][(ci,u,v+sh)];
-// d_bias[co] = sum over the GP partial bias rows and the P shifts.  A workgroup takes REDUCE_EPW
-// outputs; REDUCE_STRANDS interleaved strands walk the partials in ascending order, eight loads in
-// flight (the walk is bound by load latency, so many short strands beat few long ones), and are
-// combined by a fixed tree.
-constexpr int REDUCE_EPW = 16, REDUCE_STRANDS = THREADS / REDUCE_EPW;
+// d_bias[co] = sum over the GP partial bias rows and the P shifts.  A workgroup takes `epw` outputs
+// (4, 8 or 16: few outputs are spread over more workgroups); THREADS / epw interleaved strands walk
+// the partials in ascending order, eight loads in flight (the walk is bound by load latency), and
+// are combined by a fixed tree.
 __global__ __launch_bounds__(THREADS) void wgrad_reduce_kernel(const float* __restrict__ part, int GP, int MT,
                                                                int NT, int Cout, int Cin, int KH, int KW,
-                                                               int P, float* __restrict__ d_k,
+                                                               int P, int epw, float* __restrict__ d_k,
                                                                float* __restrict__ d_bias) {
   __shared__ float red[THREADS];
-  const int strand = threadIdx.x / REDUCE_EPW, el = blockIdx.x * REDUCE_EPW + threadIdx.x % REDUCE_EPW;
+  const int strands = THREADS / epw;
+  const int strand = threadIdx.x / epw, el = blockIdx.x * epw + threadIdx.x % epw;
   const int KWP = KW + P - 1, nk = Cout * Cin * KH * KW, total = nk + (d_bias ? Cout : 0);
   float sum = 0.0f;
   if (el < total) {
@@ -651,20 +651,20 @@ __global__ __launch_bounds__(THREADS) void wgrad_reduce_kernel(const float* __re
         stride = (size_t)MT * 16;
       }
       int gi = strand;
-      for (; gi + 7 * REDUCE_STRANDS < GP; gi += 8 * REDUCE_STRANDS) {
+      for (; gi + 7 * strands < GP; gi += 8 * strands) {
         float v[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = p[(gi + REDUCE_STRANDS * k) * stride];
+        for (int k = 0; k < 8; ++k) v[k] = p[(gi + strands * k) * stride];
 #pragma unroll
         for (int k = 0; k < 8; ++k) sum += v[k];
       }
-      for (; gi < GP; gi += REDUCE_STRANDS) sum += p[gi * stride];
+      for (; gi < GP; gi += strands) sum += p[gi * stride];
     }
   }
   red[threadIdx.x] = sum;
   __syncthreads();
-  for (int s = REDUCE_STRANDS / 2; s > 0; s >>= 1) {
-    if (strand < s) red[threadIdx.x] += red[threadIdx.x + REDUCE_EPW * s];
+  for (int s = strands / 2; s > 0; s >>= 1) {
+    if (strand < s) red[threadIdx.x] += red[threadIdx.x + epw * s];
     __syncthreads();
   }
   if (strand == 0 && el < total) {

@@ -441,10 +441,10 @@ int cnn_conv_bwd_weight(const float* in, const float* d_out, float* d_k, float* 
       igemm::wgrad_kernel<4, 16><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
     else
       igemm::wgrad_kernel<4, 4><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
-    const unsigned blocks =
-        (unsigned)(((size_t)Cout * Cin * KH * KW + Cout + igemm::REDUCE_EPW - 1) / igemm::REDUCE_EPW);
-    igemm::wgrad_reduce_kernel<<<blocks, igemm::THREADS, 0, st>>>(p.a.part, (int)p.gx * p.a.KS, p.a.MT, p.a.NT, Cout,
-                                                                 Cin, KH, KW, p.a.P, d_k, d_bias);
+    const size_t outputs = (size_t)Cout * Cin * KH * KW + Cout;
+    const int epw = outputs >= 2048 ? 16 : outputs >= 512 ? 8 : 4;  // outputs per workgroup of the second kernel
+    igemm::wgrad_reduce_kernel<<<(unsigned)((outputs + epw - 1) / epw), igemm::THREADS, 0, st>>>(
+        p.a.part, (int)p.gx * p.a.KS, p.a.MT, p.a.NT, Cout, Cin, KH, KW, p.a.P, epw, d_k, d_bias);
     return launched();
   }
   const unsigned blocks = (unsigned)(Cout * Cin * KH * KW + (d_bias ? Cout : 0));
