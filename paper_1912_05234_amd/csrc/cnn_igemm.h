@@ -347,7 +347,25 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
       gemm_blocks<TP, 1>(acc, reinterpret_cast<const f4*>(wt + (size_t)arow * g.SP),
                       reinterpret_cast<const i4*>(koff + q * g.SP), reinterpret_cast<const char*>(x), po, 0, 1,
                       g.NBK, g.NBK - 1);
-      if (full) {  // wave-uniform: the common case carries no per-pixel predicates
+      if (full && (g.P & 3) == 0) {
+        // four (or a multiple of four) pixels per column: the lane's four result registers are
+        // horizontal neighbours of one channel, stored as one 16-byte item
+        if (nrow > 0) {
+#pragma unroll
+          for (int tt = 0; tt < TP; ++tt) *reinterpret_cast<f4*>(dst + (oo[tt] + ro[0])) = acc[tt];
+        }
+      } else if (full && (g.P & 1) == 0) {
+        // an even number of pixels per column: result registers (0, 1) and (2, 3) are horizontal
+        // neighbours of one channel, stored as 8-byte items (sixteen lanes fill 128 consecutive
+        // bytes when P = 2)
+#pragma unroll
+        for (int r = 0; r < 4; r += 2)
+          if (r < nrow) {
+#pragma unroll
+            for (int tt = 0; tt < TP; ++tt)
+              *reinterpret_cast<float2*>(dst + (oo[tt] + ro[r])) = float2{acc[tt][r], acc[tt][r + 1]};
+          }
+      } else if (full) {  // wave-uniform: the common case carries no per-pixel predicates
 #pragma unroll
         for (int r = 0; r < 4; ++r)
           if (r < nrow) {

@@ -30,7 +30,9 @@ CONV_CASES = [(3, 1, 28, 28, 6, 5, 5), (5, 6, 12, 12, 12, 5, 5), (2, 3, 9, 7, 4,
               (2, 3, 80, 80, 4, 3, 3), (1, 40, 20, 20, 2, 5, 5),
               # odd ones: one-row images, 17 and 33 output maps, a kernel as large as the image, packing by 7 and by 6
               (3, 2, 1, 300, 3, 1, 7), (2, 1, 40, 3, 17, 2, 3), (5, 7, 5, 9, 33, 5, 2), (1, 3, 16, 16, 1, 16, 16),
-              (9, 4, 10, 10, 2, 1, 4), (70, 1, 2, 2, 16, 2, 2)]
+              (9, 4, 10, 10, 2, 1, 4), (70, 1, 2, 2, 16, 2, 2),
+              # packing by 4 and by 8 (16-byte stores), by 6 (8-byte stores)
+              (40, 2, 6, 6, 3, 3, 3), (4, 2, 10, 12, 1, 3, 5)]
 
 
 def oracle_conv_fwd(x, k, b):
