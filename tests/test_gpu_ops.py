@@ -168,3 +168,35 @@ def test_training_gradient_assembled_from_per_op_calls(B):
     ref_loss = 0.5 * float(((host(y).astype(np.float64) - host(target)) ** 2).sum())
     assert abs(float(host(loss)[0]) - ref_loss) <= 1e-5 * ref_loss
 
+
+def _random_conv_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        KH, KW = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        H, W = KH + int(rng.integers(0, 14)), KW + int(rng.integers(0, 14))
+        cases.append((int(rng.integers(1, 80)), int(rng.integers(1, 9)), H, W, int(rng.integers(1, 20)), KH, KW))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_conv_cases(24, 20240527))
+def test_conv_random_shapes(case):
+    """Seeded random small shapes through all three convolution entry points (every launch plan the
+    shapes happen to select: packing factors, tile counts, K splits, ragged groups)."""
+    B, Cin, H, W, Cout, KH, KW = case
+    Ho, Wo = H - KH + 1, W - KW + 1
+    x, k, b = inputs.make_signed((B, Cin, H, W), 41), inputs.make_signed((Cout, Cin, KH, KW), 42), inputs.make_signed((Cout,), 43)
+    d = inputs.make_signed((B, Cout, Ho, Wo), 44)
+    x64, k64, d64 = x.astype(np.float64), k.astype(np.float64), d.astype(np.float64)
+    assert_close(host(binding.conv_fwd(dev(x), dev(k), dev(b))), oracle_conv_fwd(x, k, b), RTOL_ACT, "conv_fwd %r" % (case,))
+    ref_in = np.zeros((B, Cin, H, W))
+    ref_k = np.zeros((Cout, Cin, KH, KW))
+    for n in range(B):
+        for co in range(Cout):
+            ref_in[n] += oracle.backin(d64[n, co][None], k64[co], (Cin, H, W))
+            ref_k[co] += oracle.backweights(d64[n, co][None], x64[n])
+    assert_close(host(binding.conv_bwd_input(dev(d), dev(k), H, W)), ref_in, RTOL_ACT, "conv_bwd_input %r" % (case,))
+    d_k, d_b = binding.conv_bwd_weight(dev(x), dev(d))
+    assert_close(host(d_k), ref_k, RTOL_ACT, "conv_bwd_weight %r" % (case,))
+    assert_close(host(d_b), d64.sum(axis=(0, 2, 3)), RTOL_ACT, "conv_bwd_bias %r" % (case,))
+
