@@ -40,9 +40,10 @@ __device__ __forceinline__ f4 mfma16(float a, float b, f4 c) {
 
 constexpr int THREADS = 256;  // four waves per workgroup
 constexpr int WAVES = THREADS / 64;
-// Staged data of the next group of images travels through registers while the current group is
-// computed: up to PFV 16-byte items or PFS 4-byte items per thread (larger groups are copied
-// directly, without overlap).  Stage modes:
+// Forward and input-gradient kernel: staged data of the next group of images travels through
+// registers while the current group is computed, up to PFV 16-byte items or PFS 4-byte items per
+// thread (larger groups are copied directly, without overlap).  Stage modes (the weight-gradient
+// kernel stages with direct global-to-LDS loads instead):
 constexpr int PFV = 8, PFS = 16;  // the scalar items live in the first PFS / 4 vector registers
 constexpr int STAGE_DIRECT = 0, STAGE_VECTOR = 1, STAGE_SCALAR = 2;
 
