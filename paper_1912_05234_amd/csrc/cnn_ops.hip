@@ -115,26 +115,32 @@ __global__ __launch_bounds__(TPB) void conv_bwd_weight_kernel(const float* __res
   }
 }
 
+// One thread per output element.  With rows counted over all maps (r = map * Ho + p) the 2x2
+// window of output (r, q) is rows 2 r, 2 r + 1 and columns 2 q, 2 q + 1 of the input, so one division
+// per element suffices and the two columns move as one 8-byte item (W is even).
 __global__ __launch_bounds__(TPB) void avgpool_fwd_kernel(const float* __restrict__ in,
                                                           float* __restrict__ out, size_t total, int H,
                                                           int W) {
-  const int Ho = H / 2, Wo = W / 2;
+  const size_t Wo = (size_t)(W / 2);
   for (size_t o = blockIdx.x * (size_t)TPB + threadIdx.x; o < total; o += (size_t)gridDim.x * TPB) {
-    const int q = (int)(o % Wo), p = (int)((o / Wo) % Ho);
-    const size_t m = o / ((size_t)Wo * Ho);
-    const float* ip = in + (m * H + 2 * p) * (size_t)W + 2 * q;
-    out[o] = (ip[0] + ip[1] + ip[W] + ip[W + 1]) * 0.25f;
+    const size_t r = o / Wo, q = o - r * Wo;
+    const float2* ip = reinterpret_cast<const float2*>(in + 2 * r * W + 2 * q);
+    const float2 a = ip[0], b = ip[W / 2];
+    out[o] = (a.x + a.y + b.x + b.y) * 0.25f;
   }
 }
 
+// One thread per element of d_out: it writes the 2x2 block it spreads into (same row arithmetic).
 __global__ __launch_bounds__(TPB) void avgpool_bwd_kernel(const float* __restrict__ d_out,
                                                           float* __restrict__ d_in, size_t total, int Ho,
                                                           int Wo) {
-  const int H = 2 * Ho, W = 2 * Wo;
-  for (size_t o = blockIdx.x * (size_t)TPB + threadIdx.x; o < total; o += (size_t)gridDim.x * TPB) {
-    const int x = (int)(o % W), y = (int)((o / W) % H);
-    const size_t m = o / ((size_t)W * H);
-    d_in[o] = d_out[(m * Ho + y / 2) * (size_t)Wo + x / 2] * 0.25f;
+  const size_t W = 2 * (size_t)Wo;
+  for (size_t e = blockIdx.x * (size_t)TPB + threadIdx.x; e < total; e += (size_t)gridDim.x * TPB) {
+    const size_t r = e / Wo, q = e - r * Wo;
+    const float v = d_out[e] * 0.25f;
+    float2* op = reinterpret_cast<float2*>(d_in + 2 * r * W + 2 * q);
+    op[0] = float2{v, v};
+    op[Wo] = float2{v, v};
   }
 }
 
@@ -464,7 +470,7 @@ int cnn_avgpool_fwd(const float* in, float* out, int B, int C, int H, int W, voi
 int cnn_avgpool_bwd(const float* d_out, float* d_in, int B, int C, int Ho, int Wo, void* hip_stream) {
   if (!d_out || !d_in || B < 1 || C < 1 || Ho < 1 || Wo < 1) return CNN_EINVAL;
   if (!aligned16(d_out) || !aligned16(d_in)) return CNN_EINVAL;
-  const size_t total = (size_t)B * C * Ho * Wo * 4;
+  const size_t total = (size_t)B * C * Ho * Wo;
   avgpool_bwd_kernel<<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(d_out, d_in, total, Ho, Wo);
   return launched();
 }
