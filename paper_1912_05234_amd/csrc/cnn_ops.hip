@@ -192,16 +192,27 @@ __global__ __launch_bounds__(TPB) void fc_bwd_weight_kernel(const float* __restr
   }
 }
 
+// Four elements per thread as one 16-byte item; the last n % 4 elements one by one.
 __global__ __launch_bounds__(TPB) void logistic_fwd_kernel(const float* __restrict__ x,
                                                            float* __restrict__ y, size_t n) {
-  for (size_t e = blockIdx.x * (size_t)TPB + threadIdx.x; e < n; e += (size_t)gridDim.x * TPB)
-    y[e] = logistic(x[e]);
+  const size_t n4 = n / 4, stride = (size_t)gridDim.x * TPB, first = blockIdx.x * (size_t)TPB + threadIdx.x;
+  for (size_t e = first; e < n4; e += stride) {
+    const float4 v = reinterpret_cast<const float4*>(x)[e];
+    reinterpret_cast<float4*>(y)[e] = float4{logistic(v.x), logistic(v.y), logistic(v.z), logistic(v.w)};
+  }
+  for (size_t e = 4 * n4 + first; e < n; e += stride) y[e] = logistic(x[e]);
 }
 
 __global__ __launch_bounds__(TPB) void logistic_bwd_kernel(const float* __restrict__ y,
                                                            const float* __restrict__ d_y,
                                                            float* __restrict__ d_x, size_t n) {
-  for (size_t e = blockIdx.x * (size_t)TPB + threadIdx.x; e < n; e += (size_t)gridDim.x * TPB) {
+  const size_t n4 = n / 4, stride = (size_t)gridDim.x * TPB, first = blockIdx.x * (size_t)TPB + threadIdx.x;
+  for (size_t e = first; e < n4; e += stride) {
+    const float4 v = reinterpret_cast<const float4*>(y)[e], d = reinterpret_cast<const float4*>(d_y)[e];
+    reinterpret_cast<float4*>(d_x)[e] = float4{d.x * v.x * (1.0f - v.x), d.y * v.y * (1.0f - v.y),
+                                               d.z * v.z * (1.0f - v.z), d.w * v.w * (1.0f - v.w)};
+  }
+  for (size_t e = 4 * n4 + first; e < n; e += stride) {
     const float v = y[e];
     d_x[e] = d_y[e] * v * (1.0f - v);
   }
@@ -518,14 +529,14 @@ int cnn_fc_bwd_weight(const float* in, const float* d_out, float* d_w, float* d_
 
 int cnn_logistic_fwd(const float* x, float* y, size_t n, void* hip_stream) {
   if (!x || !y || n < 1 || !aligned16(x) || !aligned16(y)) return CNN_EINVAL;
-  logistic_fwd_kernel<<<grid_for(n), TPB, 0, (hipStream_t)hip_stream>>>(x, y, n);
+  logistic_fwd_kernel<<<grid_for((n + 3) / 4), TPB, 0, (hipStream_t)hip_stream>>>(x, y, n);
   return launched();
 }
 
 int cnn_logistic_bwd(const float* y, const float* d_y, float* d_x, size_t n, void* hip_stream) {
   if (!y || !d_y || !d_x || n < 1 || !aligned16(y) || !aligned16(d_y) || !aligned16(d_x))
     return CNN_EINVAL;
-  logistic_bwd_kernel<<<grid_for(n), TPB, 0, (hipStream_t)hip_stream>>>(y, d_y, d_x, n);
+  logistic_bwd_kernel<<<grid_for((n + 3) / 4), TPB, 0, (hipStream_t)hip_stream>>>(y, d_y, d_x, n);
   return launched();
 }
 
