@@ -119,8 +119,7 @@ __global__ __launch_bounds__(TPB) void conv_bwd_weight_kernel(const float* __res
 // window of output (r, q) is rows 2 r, 2 r + 1 and columns 2 q, 2 q + 1 of the input, so one division
 // per element suffices and the two columns move as one 8-byte item (W is even).
 __global__ __launch_bounds__(TPB) void avgpool_fwd_kernel(const float* __restrict__ in,
-                                                          float* __restrict__ out, size_t total, int H,
-                                                          int W) {
+                                                          float* __restrict__ out, size_t total, int W) {
   const size_t Wo = (size_t)(W / 2);
   for (size_t o = blockIdx.x * (size_t)TPB + threadIdx.x; o < total; o += (size_t)gridDim.x * TPB) {
     const size_t r = o / Wo, q = o - r * Wo;
@@ -132,8 +131,7 @@ __global__ __launch_bounds__(TPB) void avgpool_fwd_kernel(const float* __restric
 
 // One thread per element of d_out: it writes the 2x2 block it spreads into (same row arithmetic).
 __global__ __launch_bounds__(TPB) void avgpool_bwd_kernel(const float* __restrict__ d_out,
-                                                          float* __restrict__ d_in, size_t total, int Ho,
-                                                          int Wo) {
+                                                          float* __restrict__ d_in, size_t total, int Wo) {
   const size_t W = 2 * (size_t)Wo;
   for (size_t e = blockIdx.x * (size_t)TPB + threadIdx.x; e < total; e += (size_t)gridDim.x * TPB) {
     const size_t r = e / Wo, q = e - r * Wo;
@@ -229,7 +227,7 @@ constexpr int NUM_CU = 256;
 constexpr int MAX_GROUP = 64;               // images per group
 constexpr int MAX_PARTIALS = 1024;          // workgroup columns (partial sums) of the weight gradient
 
-// Workgroups that keep every compute unit as full as the LDS use allows (at most four each).
+// Workgroups that keep every compute unit as full as the LDS use allows (at most eight each).
 unsigned resident_workgroups(size_t lds_bytes) {
   size_t per_cu = CU_LDS / (lds_bytes + 512);
   if (per_cu > 8) per_cu = 8;
@@ -474,7 +472,7 @@ int cnn_avgpool_fwd(const float* in, float* out, int B, int C, int H, int W, voi
   if (!in || !out || B < 1 || C < 1 || H < 2 || W < 2 || (H & 1) || (W & 1)) return CNN_EINVAL;
   if (!aligned16(in) || !aligned16(out)) return CNN_EINVAL;
   const size_t total = (size_t)B * C * (H / 2) * (W / 2);
-  avgpool_fwd_kernel<<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(in, out, total, H, W);
+  avgpool_fwd_kernel<<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(in, out, total, W);
   return launched();
 }
 
@@ -482,7 +480,7 @@ int cnn_avgpool_bwd(const float* d_out, float* d_in, int B, int C, int Ho, int W
   if (!d_out || !d_in || B < 1 || C < 1 || Ho < 1 || Wo < 1) return CNN_EINVAL;
   if (!aligned16(d_out) || !aligned16(d_in)) return CNN_EINVAL;
   const size_t total = (size_t)B * C * Ho * Wo;
-  avgpool_bwd_kernel<<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(d_out, d_in, total, Ho, Wo);
+  avgpool_bwd_kernel<<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(d_out, d_in, total, Wo);
   return launched();
 }
 
