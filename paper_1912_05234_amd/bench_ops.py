@@ -5,7 +5,8 @@
 One JSON line per operation: the average duration of the call's kernels between two HIP events
 on the stream the binding launches on, the useful arithmetic (2 flops per multiply-add of the
 operation's definition; padding the kernels add is not counted) and its share of the fp32
-matrix-core peak.  Inputs are synthetic and resident in device memory.
+matrix-core peak; for the element-wise layers the bytes they must move and the share of the
+HBM peak.  Inputs are synthetic and resident in device memory.
 """
 import argparse
 import json
@@ -16,6 +17,7 @@ import torch
 from . import binding
 
 PEAK_TFLOPS = 157.3  # MI355X, fp32 matrix and vector alike
+PEAK_HBM_GBS = 8000.0
 
 # name: (Cin, H, W, Cout, KH, KW) -- the paper's C1 and C2 (Section 3, listing `forward`)
 CONVS = {"C1": (1, 28, 28, 6, 5, 5), "C2": (6, 12, 12, 12, 5, 5)}
@@ -55,6 +57,11 @@ def main(argv=None):
         line.update(extra or {})
         print(json.dumps(line), flush=True)
 
+    def report_bw(layer, op, us, nbytes):
+        gbs = nbytes / us / 1e3
+        print(json.dumps({"layer": layer, "op": op, "batch": B, "us": round(us, 2), "gb_per_s": round(gbs, 1),
+                          "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)}), flush=True)
+
     for name, (Cin, H, W, Cout, KH, KW) in CONVS.items():
         Ho, Wo = H - KH + 1, W - KW + 1
         x, k, b, d = rnd(B, Cin, H, W), rnd(Cout, Cin, KH, KW), rnd(Cout), rnd(B, Cout, Ho, Wo)
@@ -76,6 +83,19 @@ def main(argv=None):
         for op, fn in calls.items():
             assert fn() == 0, op
             report(name, op, time_call(fn, args.steps), flops)
+        # the element-wise layers that follow the convolution: sigmoid, pool, and their backward forms
+        act, pooled = torch.empty_like(out), torch.empty(B, Cout, Ho // 2, Wo // 2, device=dev)
+        d_act = torch.empty_like(out)
+        n = out.numel()
+        elementwise = {
+            "logistic_fwd": (lambda: L.cnn_logistic_fwd(p(out), p(act), n, s()), 8 * n),
+            "avgpool_fwd": (lambda: L.cnn_avgpool_fwd(p(act), p(pooled), B, Cout, Ho, Wo, s()), 5 * n),
+            "avgpool_bwd": (lambda: L.cnn_avgpool_bwd(p(pooled), p(d_act), B, Cout, Ho // 2, Wo // 2, s()), 5 * n),
+            "logistic_bwd": (lambda: L.cnn_logistic_bwd(p(act), p(d_act), p(d), n, s()), 12 * n),
+        }
+        for op, (fn, nbytes) in elementwise.items():
+            assert fn() == 0, op
+            report_bw(name, op, time_call(fn, args.steps), nbytes)
     I, O = FC
     x, w, b, d = rnd(B, I), rnd(O, I), rnd(O), rnd(B, O)
     out, d_in, d_w, d_b = torch.empty(B, O, device=dev), torch.empty(B, I, device=dev), torch.empty_like(w), torch.empty_like(b)
