@@ -33,6 +33,7 @@ namespace cnn {
 namespace igemm {
 
 using f4 = float __attribute__((ext_vector_type(4)));
+using f2 = float __attribute__((ext_vector_type(2)));
 using i4 = int __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ f4 mfma16(float a, float b, f4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
@@ -350,10 +351,13 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
                       g.NBK, g.NBK - 1);
       if (full && (g.P & 3) == 0) {
         // four (or a multiple of four) pixels per column: the lane's four result registers are
-        // horizontal neighbours of one channel, stored as one 16-byte item
+        // horizontal neighbours of one channel, stored as one 16-byte item (the wide stores carry
+        // the non-temporal hint: worth 5 % where the kernel is bound by its stores; the 4-byte
+        // stores below must not, they rely on the cache to merge them into lines)
         if (nrow > 0) {
 #pragma unroll
-          for (int tt = 0; tt < TP; ++tt) *reinterpret_cast<f4*>(dst + (oo[tt] + ro[0])) = acc[tt];
+          for (int tt = 0; tt < TP; ++tt)
+            __builtin_nontemporal_store(acc[tt], reinterpret_cast<f4*>(dst + (oo[tt] + ro[0])));
         }
       } else if (full && (g.P & 1) == 0) {
         // an even number of pixels per column: result registers (0, 1) and (2, 3) are horizontal
@@ -364,7 +368,8 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
           if (r < nrow) {
 #pragma unroll
             for (int tt = 0; tt < TP; ++tt)
-              *reinterpret_cast<float2*>(dst + (oo[tt] + ro[r])) = float2{acc[tt][r], acc[tt][r + 1]};
+              __builtin_nontemporal_store(f2{acc[tt][r], acc[tt][r + 1]},
+                                          reinterpret_cast<f2*>(dst + (oo[tt] + ro[r])));
           }
       } else if (full) {  // wave-uniform: the common case carries no per-pixel predicates
 #pragma unroll

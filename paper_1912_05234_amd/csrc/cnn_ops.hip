@@ -4,6 +4,8 @@
 // connected layers whose operands fit in LDS run as implicit GEMMs on the matrix
 // cores (cnn_igemm.h); the plain one-thread-per-output kernels below serve every
 // other shape.  The fused training step lives in cnn_fused.hip.
+#include <mutex>
+
 #include "cnn_common.h"
 #include "cnn_igemm.h"
 
@@ -18,6 +20,18 @@ inline unsigned grid_for(size_t n) {
   const size_t cap = 256 * 32;  // grid-stride beyond this
   return (unsigned)(g < cap ? (g ? g : 1) : cap);
 }
+
+// Streaming kernels: one item per thread (neighbouring workgroups then touch neighbouring memory,
+// which the memory system likes better than a few workgroups striding far: 6.2 against 5.0 TB/s for
+// a 566 MB copy), and outputs written with the non-temporal hint (+ 4 to 20 %): nothing here reads
+// its own output again.
+inline unsigned grid_stream(size_t n) {
+  size_t g = (n + TPB - 1) / TPB;
+  const size_t cap = 0x7fffffff;
+  return (unsigned)(g < cap ? (g ? g : 1) : cap);
+}
+typedef float vec2 __attribute__((ext_vector_type(2)));
+typedef float vec4 __attribute__((ext_vector_type(4)));
 
 // out[b,co,y,x] = bias[co] + sum_{ci,u,v} in[b,ci,y+u,x+v] * k[co,ci,u,v]
 __global__ __launch_bounds__(TPB) void conv_fwd_kernel(const float* __restrict__ in,
@@ -196,7 +210,8 @@ __global__ __launch_bounds__(TPB) void logistic_fwd_kernel(const float* __restri
   const size_t n4 = n / 4, stride = (size_t)gridDim.x * TPB, first = blockIdx.x * (size_t)TPB + threadIdx.x;
   for (size_t e = first; e < n4; e += stride) {
     const float4 v = reinterpret_cast<const float4*>(x)[e];
-    reinterpret_cast<float4*>(y)[e] = float4{logistic(v.x), logistic(v.y), logistic(v.z), logistic(v.w)};
+    __builtin_nontemporal_store(vec4{logistic(v.x), logistic(v.y), logistic(v.z), logistic(v.w)},
+                                reinterpret_cast<vec4*>(y) + e);
   }
   for (size_t e = 4 * n4 + first; e < n; e += stride) y[e] = logistic(x[e]);
 }
@@ -207,8 +222,9 @@ __global__ __launch_bounds__(TPB) void logistic_bwd_kernel(const float* __restri
   const size_t n4 = n / 4, stride = (size_t)gridDim.x * TPB, first = blockIdx.x * (size_t)TPB + threadIdx.x;
   for (size_t e = first; e < n4; e += stride) {
     const float4 v = reinterpret_cast<const float4*>(y)[e], d = reinterpret_cast<const float4*>(d_y)[e];
-    reinterpret_cast<float4*>(d_x)[e] = float4{d.x * v.x * (1.0f - v.x), d.y * v.y * (1.0f - v.y),
-                                               d.z * v.z * (1.0f - v.z), d.w * v.w * (1.0f - v.w)};
+    __builtin_nontemporal_store(vec4{d.x * v.x * (1.0f - v.x), d.y * v.y * (1.0f - v.y),
+                                     d.z * v.z * (1.0f - v.z), d.w * v.w * (1.0f - v.w)},
+                                reinterpret_cast<vec4*>(d_x) + e);
   }
   for (size_t e = 4 * n4 + first; e < n; e += stride) {
     const float v = y[e];
@@ -235,6 +251,69 @@ unsigned resident_workgroups(size_t lds_bytes) {
   return (unsigned)(NUM_CU * per_cu);
 }
 
+// LDS cycles of the gathered-operand reads of the first two column tiles over the first K steps, in
+// the usual model of the 32 four-byte banks: a wave's read is served in two halves of 32 lanes, and a
+// half takes as many cycles as the largest number of different words that fall into one bank.
+// Lane (q, j) of K step s reads word koff(4 s + q) + poff(16 tile + j).
+int gather_read_cost(int LW, int LP, int LI, int KH, int KWP, int K, int OWP, int COLS, int P) {
+  const int steps = (K + 3) / 4 < 16 ? (K + 3) / 4 : 16;
+  int cost = 0;
+  for (int tile = 0; tile < 2; ++tile)
+    for (int s = 0; s < steps; ++s)
+      for (int half = 0; half < 2; ++half) {
+        int word[32], worst = 0;
+        for (int l = 0; l < 32; ++l) {
+          const int kk = 4 * s + 2 * half + (l >> 4), n = 16 * tile + (l & 15);
+          const int c = kk / (KH * KWP), rem = kk % (KH * KWP), img = n / COLS, r = n % COLS;
+          word[l] = (kk < K ? c * LP + (rem / KWP) * LW + rem % KWP : 0) + img * LI + (r / OWP) * LW + P * (r % OWP);
+        }
+        for (int l = 0; l < 32; ++l) {  // different words in lane l's bank, counted at their first lane
+          int different = 0;
+          for (int m = 0; m < 32; ++m) {
+            if ((word[m] & 31) != (word[l] & 31)) continue;
+            bool first = true;
+            for (int e = 0; e < m; ++e) first = first && word[e] != word[m];
+            different += first;
+          }
+          if (different > worst) worst = different;
+        }
+        cost += worst;
+      }
+  return cost;
+}
+
+// Row stride (floats) of a bordered plane: the natural one or up to eight floats more, whichever the
+// model above likes best.  (C1's input error, 24 + 2*4 = 32 columns: every row starts in the same
+// bank and the read takes 14 cycles instead of 2; 36 columns make it conflict-free.)  Remembered per
+// shape, since a call should not pay for the search.
+int bordered_row_stride(int SC, int SH, int SW, int KH, int KW, int OH, int OW, int pady, int padx, int P) {
+  struct Entry {
+    int key[10], LW;
+  };
+  static Entry memo[16];
+  static int used = 0, next = 0;
+  static std::mutex guard;
+  const int key[10] = {SC, SH, SW, KH, KW, OH, OW, pady, padx, P};
+  std::lock_guard<std::mutex> lock(guard);
+  for (int i = 0; i < used; ++i) {
+    bool same = true;
+    for (int e = 0; e < 10; ++e) same = same && memo[i].key[e] == key[e];
+    if (same) return memo[i].LW;
+  }
+  const int base = SW + 2 * padx, rows = SH + 2 * pady, KWP = KW + P - 1, OWP = OW / P;
+  int best_lw = base, best_cost = -1;
+  for (int LW = base; LW <= base + 8; ++LW) {
+    const int LP = rows * LW, cost = gather_read_cost(LW, LP, SC * LP, KH, KWP, SC * KH * KWP, OWP, OH * OWP, P);
+    if (best_cost < 0 || cost < best_cost) best_cost = cost, best_lw = LW;
+  }
+  Entry& slot = memo[next];
+  next = (next + 1) % 16;
+  if (used < 16) ++used;
+  for (int e = 0; e < 10; ++e) slot.key[e] = key[e];
+  slot.LW = best_lw;
+  return best_lw;
+}
+
 struct ConvPlan {
   igemm::ConvArgs a;
   int tp = 0;  // pixel tiles per wave job; 0: the shape does not fit, use the plain kernel
@@ -244,16 +323,16 @@ struct ConvPlan {
 
 // dst[B][M][OH][OW] from src[B][SC][SH][SW] staged with a border of (pady, padx), P output pixels
 // per GEMM column.  tp = 0 when the operands do not fit in LDS.
-ConvPlan plan_conv_packed(const float* src, const float* w, const float* bias, float* dst, int B, int M,
+ConvPlan plan_conv_layout(const float* src, const float* w, const float* bias, float* dst, int B, int M,
                           int SC, int SH, int SW, int KH, int KW, int OH, int OW, int pady, int padx, int flip,
-                          int P) {
+                          int P, long long LW) {
   ConvPlan p;
   igemm::ConvArgs& a = p.a;
   a.src = src, a.w = w, a.bias = bias, a.dst = dst;
   a.B = B, a.M = M, a.SC = SC, a.SH = SH, a.SW = SW, a.KH = KH, a.KW = KW, a.OH = OH, a.OW = OW;
   a.pady = pady, a.padx = padx, a.flip = flip, a.zero_fill = (pady || padx) ? 1 : 0;
   a.P = P, a.MR = M * P, a.KWP = KW + P - 1, a.OWP = OW / P;
-  const long long K = (long long)SC * KH * a.KWP, LW = SW + 2LL * padx, LP = (SH + 2LL * pady) * LW, LI = SC * LP;
+  const long long K = (long long)SC * KH * a.KWP, LP = (SH + 2LL * pady) * LW, LI = SC * LP;
   const long long COLS = (long long)OH * a.OWP, MT = ((long long)a.MR + 15) / 16, NBK = (K + 15) / 16;
   const long long R = a.MR < 16 ? a.MR : 16;
   if ((MT * (R + 1) * 4 + 4) * (4 * NBK + 4) + 16 * MT + LI + 2 * COLS + 16 > LDS_LIMIT / 4) return p;  // not even one image
@@ -290,6 +369,8 @@ ConvPlan plan_conv_packed(const float* src, const float* w, const float* bias, f
   p.lds_bytes = (size_t)bytes(a.NB);
   const unsigned resident = resident_workgroups(p.lds_bytes);
   p.grid = (unsigned)a.groups < resident ? (unsigned)a.groups : resident;
+  // How a group reaches LDS: through registers that are loaded while the previous group is
+  // multiplied (16-byte or 4-byte items) when the group is small enough, else directly.
   const long long per_image = (long long)SC * SH * SW, per_group = a.NB * per_image;
   a.stage = (!a.zero_fill && per_image % 4 == 0 && per_group / 4 <= igemm::THREADS * igemm::PFV)
                 ? igemm::STAGE_VECTOR
@@ -299,6 +380,22 @@ ConvPlan plan_conv_packed(const float* src, const float* w, const float* bias, f
   a.inv_ohowp = 1.0f / (float)COLS, a.inv_owp = 1.0f / (float)a.OWP;
   a.inv_sw = 1.0f / (float)SW, a.inv_sh = 1.0f / (float)SH;
   return p;
+}
+
+// Bordered planes get the row stride the bank model prefers when the operands still fit with it.
+ConvPlan plan_conv_packed(const float* src, const float* w, const float* bias, float* dst, int B, int M,
+                          int SC, int SH, int SW, int KH, int KW, int OH, int OW, int pady, int padx, int flip,
+                          int P) {
+  const long long natural = SW + 2LL * padx, K = (long long)SC * KH * (KW + P - 1);
+  // the search works in int: only for planes that could fit in LDS at all
+  if ((pady || padx) && SC * (SH + 2LL * pady) * natural < LDS_LIMIT / 4 && K < (1 << 20)) {
+    const long long LW = bordered_row_stride(SC, SH, SW, KH, KW, OH, OW, pady, padx, P);
+    if (LW != natural) {
+      const ConvPlan p = plan_conv_layout(src, w, bias, dst, B, M, SC, SH, SW, KH, KW, OH, OW, pady, padx, flip, P, LW);
+      if (p.tp) return p;
+    }
+  }
+  return plan_conv_layout(src, w, bias, dst, B, M, SC, SH, SW, KH, KW, OH, OW, pady, padx, flip, P, natural);
 }
 
 // The packing factor: the largest divisor P of OW with M*P <= 16 whose operands fit in LDS (a wider
@@ -472,7 +569,7 @@ int cnn_avgpool_fwd(const float* in, float* out, int B, int C, int H, int W, voi
   if (!in || !out || B < 1 || C < 1 || H < 2 || W < 2 || (H & 1) || (W & 1)) return CNN_EINVAL;
   if (!aligned16(in) || !aligned16(out)) return CNN_EINVAL;
   const size_t total = (size_t)B * C * (H / 2) * (W / 2);
-  avgpool_fwd_kernel<<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(in, out, total, W);
+  avgpool_fwd_kernel<<<grid_stream(total), TPB, 0, (hipStream_t)hip_stream>>>(in, out, total, W);
   return launched();
 }
 
@@ -480,7 +577,7 @@ int cnn_avgpool_bwd(const float* d_out, float* d_in, int B, int C, int Ho, int W
   if (!d_out || !d_in || B < 1 || C < 1 || Ho < 1 || Wo < 1) return CNN_EINVAL;
   if (!aligned16(d_out) || !aligned16(d_in)) return CNN_EINVAL;
   const size_t total = (size_t)B * C * Ho * Wo;
-  avgpool_bwd_kernel<<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(d_out, d_in, total, Wo);
+  avgpool_bwd_kernel<<<grid_stream(total), TPB, 0, (hipStream_t)hip_stream>>>(d_out, d_in, total, Wo);
   return launched();
 }
 
@@ -527,14 +624,14 @@ int cnn_fc_bwd_weight(const float* in, const float* d_out, float* d_w, float* d_
 
 int cnn_logistic_fwd(const float* x, float* y, size_t n, void* hip_stream) {
   if (!x || !y || n < 1 || !aligned16(x) || !aligned16(y)) return CNN_EINVAL;
-  logistic_fwd_kernel<<<grid_for((n + 3) / 4), TPB, 0, (hipStream_t)hip_stream>>>(x, y, n);
+  logistic_fwd_kernel<<<grid_stream((n + 3) / 4), TPB, 0, (hipStream_t)hip_stream>>>(x, y, n);
   return launched();
 }
 
 int cnn_logistic_bwd(const float* y, const float* d_y, float* d_x, size_t n, void* hip_stream) {
   if (!y || !d_y || !d_x || n < 1 || !aligned16(y) || !aligned16(d_y) || !aligned16(d_x))
     return CNN_EINVAL;
-  logistic_bwd_kernel<<<grid_for((n + 3) / 4), TPB, 0, (hipStream_t)hip_stream>>>(y, d_y, d_x, n);
+  logistic_bwd_kernel<<<grid_stream((n + 3) / 4), TPB, 0, (hipStream_t)hip_stream>>>(y, d_y, d_x, n);
   return launched();
 }
 
