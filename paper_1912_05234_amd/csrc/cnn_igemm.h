@@ -398,9 +398,9 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
 // gridDim.x, ... for M tile mt = by / NTG and the tap tiles of group ntg = by % NTG.  With three or
 // more tap tiles in all, wave w owns tiles 16 ntg + w + 4 i (i < 4) and KS = 1; with two (one) tap
 // tiles the waves split the pixels as well: tile w % 2 (0), K slice w / 2 (w) of KS = 2 (4), a slice
-// taking every KS-th block.  Results go to part[bx*KS + slice][mt][nt][16][16]; the waves that own
-// tile 0 also sum their A operands, the bias gradient, into bpart[bx*KS + slice][16 mt + c] (bpart
-// follows part).
+// taking every KS-th block; the slices of a tile are added through LDS at the end.  Results go to
+// part[bx][mt][nt][16][16]; the waves that own tile 0 also sum their A operands, the bias gradient,
+// into bpart[bx][16 mt + c] (bpart follows part).
 //
 // With column packing (few output channels, P > 1) the rows are (co, sh), a pixel slot is the group
 // (y, X) of P adjacent pixels and the columns are the shifted taps (ci, u, v' < KW+P-1):
@@ -448,6 +448,8 @@ __host__ __device__ inline WgradLds wgrad_lds(const WgradArgs& a) {
   l.x = (a.R + 1) * a.NPS;   //   [XS] images of the group
   l.buf_floats = l.x + a.XS;
   l.total = l.buf + 2 * l.buf_floats;
+  const int handover = l.buf + WAVES * (256 + 16);  // the K slices' tiles and bias sums meet here at the end
+  if (l.total < handover) l.total = handover;
   return l;
 }
 
@@ -628,21 +630,44 @@ __global__ __launch_bounds__(THREADS) void wgrad_kernel(const WgradArgs g) {
     }
     cur = nxt;
   }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int nt = 16 * ntg + tile0 + 4 * i;
-    if (i < ntile) {
-      float* o = g.part + ((((size_t)blockIdx.x * g.KS + slice) * g.MT + mt) * g.NT + nt) * 256 + 64 * q + j;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) o[16 * r] = acc[i][r];
-    }
-  }
   if (sums_bias) {  // lane (j, q) summed channel j over its quarter of every block: add the four q
     asum += __shfl_xor(asum, 16, 64);
     asum += __shfl_xor(asum, 32, 64);
-    if (q == 0) {
-      float* bpart = g.part + (size_t)gridDim.x * g.KS * g.MT * g.NT * 256;
-      bpart[((size_t)blockIdx.x * g.KS + slice) * g.MT * 16 + 16 * mt + j] = asum;
+  }
+  if (g.KS > 1) {
+    // The K slices of a tile meet in LDS (the staging buffers are dead): slices 1.. hand their tile
+    // (one per wave when K is split) and bias sums to the wave of slice 0, which adds them in
+    // slice order, so the workgroup writes one partial per tile.
+    float* xch = lds + L.buf;
+    lds_barrier();  // every wave has left the buffers
+    if (slice > 0) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) xch[wave * 256 + 64 * r + l] = acc[0][r];
+      if (sums_bias && q == 0) xch[WAVES * 256 + wave * 16 + j] = asum;
+    }
+    lds_barrier();
+    if (slice == 0) {
+      for (int sl = 1; sl < g.KS; ++sl) {
+        const int other = g.KS == 2 ? wave + 2 * sl : sl;  // the wave that ran slice sl of this tile
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[0][r] += xch[other * 256 + 64 * r + l];
+        if (sums_bias && q == 0) asum += xch[WAVES * 256 + other * 16 + j];
+      }
+    }
+  }
+  if (slice == 0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int nt = 16 * ntg + tile0 + 4 * i;
+      if (i < ntile) {
+        float* o = g.part + (((size_t)blockIdx.x * g.MT + mt) * g.NT + nt) * 256 + 64 * q + j;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[16 * r] = acc[i][r];
+      }
+    }
+    if (sums_bias && q == 0) {
+      float* bpart = g.part + (size_t)gridDim.x * g.MT * g.NT * 256;
+      bpart[(size_t)blockIdx.x * g.MT * 16 + 16 * mt + j] = asum;
     }
   }
 }

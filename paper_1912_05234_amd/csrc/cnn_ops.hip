@@ -466,7 +466,7 @@ WgradPlan plan_wgrad_packed(int B, int Cin, int H, int W, int Cout, int KH, int 
   if (gx > (unsigned)a.groups) gx = (unsigned)a.groups;
   p.gx = gx;
   p.gy = (unsigned)(a.MT * a.NTG);
-  p.workspace_bytes = ((size_t)gx * a.KS * a.MT * a.NT * 256 + (size_t)gx * a.KS * a.MT * 16) * sizeof(float);
+  p.workspace_bytes = ((size_t)gx * a.MT * a.NT * 256 + (size_t)gx * a.MT * 16) * sizeof(float);
   a.inv_p = 1.0f / (float)P, a.inv_khkwp = 1.0f / (float)(KH * a.KWP), a.inv_kwp = 1.0f / (float)a.KWP;
   a.inv_spi = 1.0f / (float)SPI, a.inv_wop = 1.0f / (float)a.WOP;
   p.fits = true;
@@ -556,7 +556,7 @@ int cnn_conv_bwd_weight(const float* in, const float* d_out, float* d_k, float* 
     const size_t outputs = (size_t)Cout * Cin * KH * KW + Cout;
     const int epw = outputs >= 2048 ? 16 : outputs >= 512 ? 8 : 4;  // outputs per workgroup of the second kernel
     igemm::wgrad_reduce_kernel<<<(unsigned)((outputs + epw - 1) / epw), igemm::THREADS, 0, st>>>(
-        p.a.part, (int)p.gx * p.a.KS, p.a.MT, p.a.NT, Cout, Cin, KH, KW, p.a.P, epw, d_k, d_bias);
+        p.a.part, (int)p.gx, p.a.MT, p.a.NT, Cout, Cin, KH, KW, p.a.P, epw, d_k, d_bias);
     return launched();
   }
   const unsigned blocks = (unsigned)(Cout * Cin * KH * KW + (d_bias ? Cout : 0));
