@@ -43,10 +43,11 @@ constexpr int THREADS = 256;  // four waves per workgroup
 constexpr int WAVES = THREADS / 64;
 // Forward and input-gradient kernel: staged data of the next group of images travels through
 // registers while the current group is computed, up to PFV 16-byte items or PFS 4-byte items per
-// thread (larger groups are copied directly, without overlap).  Stage modes (the weight-gradient
-// kernel stages with direct global-to-LDS loads instead):
+// thread; what a larger group has beyond that follows in further rounds of the same size after the
+// group's turn has come, without overlap.  Stage modes (the weight-gradient kernel stages with
+// direct global-to-LDS loads instead):
 constexpr int PFV = 8, PFS = 16;  // the scalar items live in the first PFS / 4 vector registers
-constexpr int STAGE_DIRECT = 0, STAGE_VECTOR = 1, STAGE_SCALAR = 2;
+constexpr int STAGE_VECTOR = 1, STAGE_SCALAR = 2;
 
 // Workgroup barrier that orders LDS accesses only: global loads and stores stay in flight across it.
 __device__ __forceinline__ void lds_barrier() {
@@ -171,7 +172,7 @@ struct ConvArgs {
   int NBK, SP;         // blocks of four K steps; row stride of the two K-indexed tables (floats)
   int flip;            // 0: A[m][(c,u,v)] = w[m][c][u][v];  1: A[m][(c,u,v)] = w[c][m][KH-1-u][KW-1-v]
   int zero_fill;       // the planes have a border that must read as zero
-  int stage;           // STAGE_*: VECTOR needs SC*SH*SW % 4 == 0 and no border
+  int stage, rounds;   // STAGE_*: VECTOR needs SC*SH*SW % 4 == 0 and no border; register loads per group
   float inv_sp, inv_r1, inv_p, inv_khkwp, inv_kwp, inv_ohowp, inv_owp, inv_sw, inv_sh;
 };
 // LDS layout in floats, in this order.
@@ -286,44 +287,53 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
       ptgt[i] = e < g.NB * per_image ? target(e) : 0;
     }
   }
-  // Loads of group grp into registers (nothing for STAGE_DIRECT) ...
-  auto issue = [&](int grp) {
+  // Round r of group grp: loads into registers ...
+  auto issue = [&](int grp, int r) {
     const int b0 = grp * g.NB, count = min(g.NB, g.B - b0) * per_image;
     const float* src = g.src + (size_t)b0 * per_image;
     if (g.stage == STAGE_VECTOR) {
+      const int first = r * (THREADS * PFV) + t;
 #pragma unroll
       for (int i = 0; i < PFV; ++i)
-        if (t + THREADS * i < count >> 2) pv[i] = reinterpret_cast<const f4*>(src)[t + THREADS * i];
-    } else if (g.stage == STAGE_SCALAR) {
+        if (first + THREADS * i < count >> 2) pv[i] = reinterpret_cast<const f4*>(src)[first + THREADS * i];
+    } else {
+      const int first = r * (THREADS * PFS) + t;
 #pragma unroll
       for (int i = 0; i < PFS; ++i)
-        if (t + THREADS * i < count) pv[i >> 2][i & 3] = src[t + THREADS * i];
+        if (first + THREADS * i < count) pv[i >> 2][i & 3] = src[first + THREADS * i];
     }
   };
-  // ... and from there (or, STAGE_DIRECT, from memory) into LDS.
-  auto commit = [&](int grp) {
+  // ... and from there into LDS (the targets of round 0 are kept in registers).
+  auto commit = [&](int grp, int r) {
     const int b0 = grp * g.NB, count = min(g.NB, g.B - b0) * per_image;
     if (g.stage == STAGE_VECTOR) {
+      const int first = r * (THREADS * PFV) + t;
 #pragma unroll
       for (int i = 0; i < PFV; ++i)
-        if (t + THREADS * i < count >> 2) reinterpret_cast<f4*>(x)[t + THREADS * i] = pv[i];
-    } else if (g.stage == STAGE_SCALAR) {
+        if (first + THREADS * i < count >> 2) reinterpret_cast<f4*>(x)[first + THREADS * i] = pv[i];
+    } else if (r == 0) {
 #pragma unroll
       for (int i = 0; i < PFS; ++i)
         if (t + THREADS * i < count) x[ptgt[i]] = pv[i >> 2][i & 3];
     } else {
-      const float* src = g.src + (size_t)b0 * per_image;
-      for (int e = t; e < count; e += THREADS) x[target(e)] = src[e];
+      const int first = r * (THREADS * PFS) + t;
+#pragma unroll
+      for (int i = 0; i < PFS; ++i)
+        if (first + THREADS * i < count) x[target(first + THREADS * i)] = pv[i >> 2][i & 3];
     }
   };
 
-  if ((int)blockIdx.x < g.groups) issue(blockIdx.x);
+  if ((int)blockIdx.x < g.groups) issue(blockIdx.x, 0);
   for (int grp = blockIdx.x; grp < g.groups; grp += gridDim.x) {
     const int b0 = grp * g.NB, nb = min(g.NB, g.B - b0);
     lds_barrier();  // tables (first pass) / the previous group's reads are complete
-    commit(grp);
+    commit(grp, 0);
+    for (int r = 1; r < g.rounds; ++r) {  // what did not fit into the registers: no overlap
+      issue(grp, r);
+      commit(grp, r);
+    }
     lds_barrier();
-    if (grp + (int)gridDim.x < g.groups) issue(grp + gridDim.x);
+    if (grp + (int)gridDim.x < g.groups) issue(grp + gridDim.x, 0);
 
     const int N = nb * OHOWP, PT = (N + 15) >> 4, PG = (PT + TP - 1) / TP;
     char* dst = reinterpret_cast<char*>(g.dst + (size_t)b0 * g.M * OHOW);  // byte offsets below fit 32 bits
@@ -358,6 +368,13 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
 #pragma unroll
           for (int tt = 0; tt < TP; ++tt)
             __builtin_nontemporal_store(acc[tt], reinterpret_cast<f4*>(dst + (oo[tt] + ro[0])));
+        }
+      } else if (full && OHOW == 1 && (g.M & 3) == 0) {
+        // one pixel per image (the fully connected form): the lane's four result registers are
+        // four consecutive channels, which are neighbours in memory
+        if (nrow > 0) {
+#pragma unroll
+          for (int tt = 0; tt < TP; ++tt) *reinterpret_cast<f4*>(dst + (oo[tt] + ro[0])) = acc[tt];
         }
       } else if (full && (g.P & 1) == 0) {
         // an even number of pixels per column: result registers (0, 1) and (2, 3) are horizontal

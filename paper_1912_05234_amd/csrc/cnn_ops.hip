@@ -370,11 +370,15 @@ ConvPlan plan_conv_layout(const float* src, const float* w, const float* bias, f
   const unsigned resident = resident_workgroups(p.lds_bytes);
   p.grid = (unsigned)a.groups < resident ? (unsigned)a.groups : resident;
   // How a group reaches LDS: through registers that are loaded while the previous group is
-  // multiplied (16-byte or 4-byte items) when the group is small enough, else directly.
+  // multiplied, as 16-byte items when the images are borderless multiples of four floats.
   const long long per_image = (long long)SC * SH * SW, per_group = a.NB * per_image;
-  a.stage = (!a.zero_fill && per_image % 4 == 0 && per_group / 4 <= igemm::THREADS * igemm::PFV)
-                ? igemm::STAGE_VECTOR
-                : per_group <= igemm::THREADS * igemm::PFS ? igemm::STAGE_SCALAR : igemm::STAGE_DIRECT;
+  if (!a.zero_fill && per_image % 4 == 0) {
+    a.stage = igemm::STAGE_VECTOR;
+    a.rounds = (int)((per_group / 4 + igemm::THREADS * igemm::PFV - 1) / (igemm::THREADS * igemm::PFV));
+  } else {
+    a.stage = igemm::STAGE_SCALAR;
+    a.rounds = (int)((per_group + igemm::THREADS * igemm::PFS - 1) / (igemm::THREADS * igemm::PFS));
+  }
   a.inv_sp = 1.0f / (float)a.SP, a.inv_r1 = 1.0f / (float)(a.R + 1), a.inv_p = 1.0f / (float)P;
   a.inv_khkwp = 1.0f / (float)(KH * a.KWP), a.inv_kwp = 1.0f / (float)a.KWP;
   a.inv_ohowp = 1.0f / (float)COLS, a.inv_owp = 1.0f / (float)a.OWP;
