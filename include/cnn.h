@@ -129,6 +129,16 @@ int cnn_conv_fwd(const float* in, const float* k, const float* bias, float* out,
  * k[co,ci,u,v] * d_out[b,co,p-u,q-v]. */
 int cnn_conv_bwd_input(const float* d_out, const float* k, float* d_in, int B, int Cin, int H,
                        int W, int Cout, int KH, int KW, void* hip_stream);
+/* Reduced-precision forms of the two calls above, same arguments, same fp32 tensors: every operand
+ * (input or output error, and kernel) is rounded to bfloat16 (nearest, ties to even) as it is read,
+ * products are summed in fp32 on the bf16 matrix cores, bias and result stay fp32.  The paper
+ * computes in `float` (Section 3, listings `conv` and `backin`); these trade its 1e-5 agreement for
+ * matrix-core throughput: the result is the plain definition applied to the rounded operands, to
+ * fp32 summation accuracy.  Shapes that do not fit in LDS run a plain kernel with the same rounding. */
+int cnn_conv_fwd_bf16(const float* in, const float* k, const float* bias, float* out, int B, int Cin,
+                      int H, int W, int Cout, int KH, int KW, void* hip_stream);
+int cnn_conv_bwd_input_bf16(const float* d_out, const float* k, float* d_in, int B, int Cin, int H,
+                            int W, int Cout, int KH, int KW, void* hip_stream);
 /* `backweights` and `backbias`, summed over the batch:
  *   d_k[co,ci,u,v] = sum_{b,y,x} in[b,ci,y+u,x+v] * d_out[b,co,y,x];  d_bias[co] = sum d_out[:,co].
  * d_bias may be NULL.  `workspace` is device memory (16-byte aligned) for partial sums that the call

@@ -98,6 +98,14 @@ def mconv(I, k, b):
     return out
 
 
+def round_bf16(x):
+    """Nearest bfloat16 value of every element (ties to even), as float32."""
+    x = _c(x, np.float32)
+    out = np.empty_like(x)
+    _load().oracle_round_bf16(_p(x), ctypes.c_long(x.size), _p(out))
+    return out
+
+
 def sigmoid(x):
     x = _c(x)
     out = np.empty_like(x)

@@ -377,3 +377,24 @@ ORACLE_INSTANCE(f32, float, double)
 ORACLE_INSTANCE(f64, double, double)
 
 extern "C" int oracle_nparam(void) { return NPARAM; }
+
+// Nearest bfloat16 (1 sign, 8 exponent, 7 fraction bits: float's exponent range with an 8-bit
+// significand), ties to the even significand, returned as a float.  Written from the format's
+// definition with frexp / nearbyint (the default rounding mode is to nearest even); used to state
+// what the reduced-precision convolution computes: the plain definition applied to rounded operands.
+// Pins: hand-computed ties and neighbours, idempotence, an independent library conversion.
+extern "C" void oracle_round_bf16(const float* in, long n, float* out) {
+  for (long i = 0; i < n; ++i) {
+    const double x = in[i];
+    if (x == 0.0 || !std::isfinite(x)) {
+      out[i] = in[i];
+      continue;
+    }
+    int e;
+    std::frexp(x, &e);               // |x| = m * 2^e with m in [0.5, 1)
+    int q = e - 8;                    // spacing of 8-bit significands at this magnitude: 2^(e-8)
+    if (q < -133) q = -133;           // subnormals: fixed spacing 2^-126 * 2^-7
+    const double step = std::ldexp(1.0, q);
+    out[i] = (float)(std::nearbyint(x / step) * step);  // exact in double; may round up to infinity
+  }
+}

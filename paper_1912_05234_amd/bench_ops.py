@@ -80,6 +80,10 @@ def main(argv=None):
             "conv_bwd_weight": lambda: L.cnn_conv_bwd_weight(p(x), p(d), p(d_k), p(d_b), B, Cin, H, W, Cout, KH,
                                                              KW, p(ws), nbytes, s()),
         }
+        # reduced precision: operands rounded to bfloat16, fp32 sums (same tensors, same useful flops)
+        calls["conv_fwd_bf16"] = lambda: L.cnn_conv_fwd_bf16(p(x), p(k), p(b), p(out), B, Cin, H, W, Cout, KH, KW, s())
+        calls["conv_bwd_input_bf16"] = lambda: L.cnn_conv_bwd_input_bf16(p(d), p(k), p(d_in), B, Cin, H, W, Cout, KH,
+                                                                         KW, s())
         for op, fn in calls.items():
             assert fn() == 0, op
             report(name, op, time_call(fn, args.steps), flops)

@@ -8,6 +8,7 @@
 
 #include "cnn_common.h"
 #include "cnn_igemm.h"
+#include "cnn_igemm_bf16.h"
 
 namespace {
 
@@ -33,7 +34,14 @@ inline unsigned grid_stream(size_t n) {
 typedef float vec2 __attribute__((ext_vector_type(2)));
 typedef float vec4 __attribute__((ext_vector_type(4)));
 
+// An operand as the arithmetic sees it: itself, or rounded to bfloat16 (nearest even).
+template <bool BF16>
+__device__ __forceinline__ float operand(float v) {
+  return BF16 ? __uint_as_float((unsigned)igemm16::to_bf16(v) << 16) : v;
+}
+
 // out[b,co,y,x] = bias[co] + sum_{ci,u,v} in[b,ci,y+u,x+v] * k[co,ci,u,v]
+template <bool BF16>
 __global__ __launch_bounds__(TPB) void conv_fwd_kernel(const float* __restrict__ in,
                                                        const float* __restrict__ k,
                                                        const float* __restrict__ bias,
@@ -50,13 +58,14 @@ __global__ __launch_bounds__(TPB) void conv_fwd_kernel(const float* __restrict__
       const float* ip = in + ((b * Cin + ci) * H + y) * (size_t)W + x;
       const float* kp = k + ((size_t)co * Cin + ci) * KH * KW;
       for (int u = 0; u < KH; ++u)
-        for (int v = 0; v < KW; ++v) acc = fmaf(ip[u * W + v], kp[u * KW + v], acc);
+        for (int v = 0; v < KW; ++v) acc = fmaf(operand<BF16>(ip[u * W + v]), operand<BF16>(kp[u * KW + v]), acc);
     }
     out[o] = acc;
   }
 }
 
 // d_in[b,ci,p,q] = sum_co sum_{u,v valid} k[co,ci,u,v] * d_out[b,co,p-u,q-v]
+template <bool BF16>
 __global__ __launch_bounds__(TPB) void conv_bwd_input_kernel(const float* __restrict__ d_out,
                                                              const float* __restrict__ k,
                                                              float* __restrict__ d_in, size_t total,
@@ -76,7 +85,7 @@ __global__ __launch_bounds__(TPB) void conv_bwd_input_kernel(const float* __rest
       const float* kp = k + ((size_t)co * Cin + ci) * KH * KW;
       for (int u = u_lo; u <= u_hi; ++u)
         for (int v = v_lo; v <= v_hi; ++v)
-          acc = fmaf(kp[u * KW + v], dp[(p - u) * Wo + (q - v)], acc);
+          acc = fmaf(operand<BF16>(kp[u * KW + v]), operand<BF16>(dp[(p - u) * Wo + (q - v)]), acc);
     }
     d_in[o] = acc;
   }
@@ -498,6 +507,72 @@ WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
   return plan_wgrad_packed(B, Cin, H, W, Cout, KH, KW, 1);
 }
 
+// ---- reduced precision: the bf16 matrix-core kernel ------------------------------------------------
+struct Conv16Plan {
+  igemm16::Args a;
+  int tp = 0;  // pixel tiles per wave job; 0: the shape does not fit, use the plain kernel
+  unsigned grid = 0;
+  size_t lds_bytes = 0;
+};
+
+Conv16Plan plan_conv16(const float* src, const float* w, const float* bias, float* dst, int B, int M, int SC,
+                       int SH, int SW, int KH, int KW, int OH, int OW, int pady, int padx, int flip) {
+  Conv16Plan p;
+  igemm16::Args& a = p.a;
+  a.src = src, a.w = w, a.bias = bias, a.dst = dst;
+  a.B = B, a.M = M, a.SC = SC, a.SH = SH, a.SW = SW, a.KH = KH, a.KW = KW, a.OH = OH, a.OW = OW;
+  a.pady = pady, a.padx = padx, a.flip = flip;
+  const long long C8 = ((long long)SC + 7) & ~7LL, K = (long long)KH * KW * C8, NBK = (K + 31) / 32;
+  const long long LW = SW + 2LL * padx, LPIX = (SH + 2LL * pady) * LW, MT = ((long long)M + 15) / 16;
+  const long long COLS = (long long)OH * OW, per_image = (long long)SC * SH * SW;
+  // first in 64 bits: one image and the tables must fit before anything is narrowed to int
+  if (16 * MT * (64 * NBK + 16) + 16 * NBK + 64 * MT + 8 * COLS + 2 * LPIX * C8 + 64 > LDS_LIMIT) return p;
+  a.C8 = (int)C8, a.K = (int)K, a.NBK = (int)NBK, a.RS = (int)(64 * NBK + 16), a.LW = (int)LW, a.LPIX = (int)LPIX;
+  a.MT = (int)MT;
+  auto bytes = [&](int nb) {
+    a.NB = nb;
+    return (long long)igemm16::lds_layout(a).total;
+  };
+  if (bytes(1) > LDS_LIMIT) return p;
+  const int nb_tiles = (int)((64 + COLS - 1) / COLS);
+  int nb_want = (B + 2047) / 2048;
+  if (nb_want < nb_tiles) nb_want = nb_tiles;
+  if (nb_want > MAX_GROUP) nb_want = MAX_GROUP;
+  if (nb_want > B) nb_want = B;
+  double best = -1.0;
+  int best_nb = 1, best_tp = 1;
+  for (int nb = 1; nb <= nb_want; ++nb) {
+    const long long by = bytes(nb);
+    if (by > LDS_LIMIT || (by > LDS_TARGET && nb > nb_tiles)) break;
+    for (int tp = 1; tp <= 4; tp <<= 1) {
+      const long long PT = (nb * COLS + 15) / 16, jobs = ((PT + tp - 1) / tp) * MT;
+      const double used = (double)nb * COLS / 16.0 * MT, slots = (double)((jobs + 3) / 4) * 4 * tp;
+      const double score = used / slots * (1.0 + 0.005 * tp);
+      if (score >= best) best = score, best_nb = nb, best_tp = tp;
+    }
+  }
+  a.NB = best_nb;
+  p.tp = best_tp;
+  a.groups = (B + a.NB - 1) / a.NB;
+  p.lds_bytes = (size_t)bytes(a.NB);
+  const unsigned resident = resident_workgroups(p.lds_bytes);
+  p.grid = (unsigned)a.groups < resident ? (unsigned)a.groups : resident;
+  a.rounds = (int)((a.NB * per_image + igemm::THREADS * igemm16::PF - 1) / (igemm::THREADS * igemm16::PF));
+  a.inv_kp = 1.0f / (float)(32 * a.NBK), a.inv_c8 = 1.0f / (float)a.C8, a.inv_kw = 1.0f / (float)KW;
+  a.inv_ohow = 1.0f / (float)COLS, a.inv_ow = 1.0f / (float)OW, a.inv_pi = 1.0f / (float)per_image;
+  a.inv_hw = 1.0f / (float)(SH * SW), a.inv_sw = 1.0f / (float)SW;
+  return p;
+}
+
+int launch_conv16(const Conv16Plan& p, hipStream_t stream) {
+  switch (p.tp) {
+    case 4: igemm16::conv_kernel<4><<<p.grid, igemm::THREADS, p.lds_bytes, stream>>>(p.a); break;
+    case 2: igemm16::conv_kernel<2><<<p.grid, igemm::THREADS, p.lds_bytes, stream>>>(p.a); break;
+    default: igemm16::conv_kernel<1><<<p.grid, igemm::THREADS, p.lds_bytes, stream>>>(p.a); break;
+  }
+  return launched();
+}
+
 inline bool conv_args_ok(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
   return B >= 1 && Cin >= 1 && Cout >= 1 && KH >= 1 && KW >= 1 && H >= KH && W >= KW &&
          (size_t)Cout * Cin * KH * KW + (size_t)Cout < (size_t)1 << 30;
@@ -514,8 +589,8 @@ int cnn_conv_fwd(const float* in, const float* k, const float* bias, float* out,
   const ConvPlan p = plan_conv(in, k, bias, out, B, Cout, Cin, H, W, KH, KW, H - KH + 1, W - KW + 1, 0, 0, 0);
   if (p.tp) return launch_conv(p, (hipStream_t)hip_stream);
   const size_t total = (size_t)B * Cout * (H - KH + 1) * (W - KW + 1);
-  conv_fwd_kernel<<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(in, k, bias, out, total, Cin, H,
-                                                                         W, Cout, KH, KW);
+  conv_fwd_kernel<false><<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(in, k, bias, out, total, Cin,
+                                                                                H, W, Cout, KH, KW);
   return launched();
 }
 
@@ -527,8 +602,33 @@ int cnn_conv_bwd_input(const float* d_out, const float* k, float* d_in, int B, i
                                KH - 1, KW - 1, 1);
   if (p.tp) return launch_conv(p, (hipStream_t)hip_stream);
   const size_t total = (size_t)B * Cin * H * W;
-  conv_bwd_input_kernel<<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(d_out, k, d_in, total, Cin,
+  conv_bwd_input_kernel<false><<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(d_out, k, d_in, total,
+                                                                                      Cin, H, W, Cout, KH, KW);
+  return launched();
+}
+
+int cnn_conv_fwd_bf16(const float* in, const float* k, const float* bias, float* out, int B, int Cin, int H,
+                      int W, int Cout, int KH, int KW, void* hip_stream) {
+  if (!in || !k || !out || !conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;
+  if (!aligned16(in) || !aligned16(k) || !aligned16(out) || (bias && !aligned16(bias))) return CNN_EINVAL;
+  const Conv16Plan p = plan_conv16(in, k, bias, out, B, Cout, Cin, H, W, KH, KW, H - KH + 1, W - KW + 1, 0, 0, 0);
+  if (p.tp) return launch_conv16(p, (hipStream_t)hip_stream);
+  const size_t total = (size_t)B * Cout * (H - KH + 1) * (W - KW + 1);
+  conv_fwd_kernel<true><<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(in, k, bias, out, total, Cin,
                                                                                H, W, Cout, KH, KW);
+  return launched();
+}
+
+int cnn_conv_bwd_input_bf16(const float* d_out, const float* k, float* d_in, int B, int Cin, int H, int W,
+                            int Cout, int KH, int KW, void* hip_stream) {
+  if (!d_out || !k || !d_in || !conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;
+  if (!aligned16(d_out) || !aligned16(k) || !aligned16(d_in)) return CNN_EINVAL;
+  const Conv16Plan p = plan_conv16(d_out, k, nullptr, d_in, B, Cin, Cout, H - KH + 1, W - KW + 1, KH, KW, H, W,
+                                   KH - 1, KW - 1, 1);
+  if (p.tp) return launch_conv16(p, (hipStream_t)hip_stream);
+  const size_t total = (size_t)B * Cin * H * W;
+  conv_bwd_input_kernel<true><<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(d_out, k, d_in, total,
+                                                                                     Cin, H, W, Cout, KH, KW);
   return launched();
 }
 

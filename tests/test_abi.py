@@ -66,6 +66,9 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.cnn_conv_fwd(fake, fake, nul, fake, 1, 1, 2, 8, 1, 3, 3, nul) == EINVAL   # H < KH
     assert L.cnn_conv_fwd(fake, fake, nul, fake, 0, 1, 8, 8, 1, 3, 3, nul) == EINVAL   # B < 1
     assert L.cnn_conv_bwd_input(fake, nul, fake, 1, 1, 8, 8, 1, 3, 3, nul) == EINVAL
+    assert L.cnn_conv_fwd_bf16(fake, fake, nul, odd, 1, 1, 8, 8, 1, 3, 3, nul) == EINVAL
+    assert L.cnn_conv_fwd_bf16(fake, fake, nul, fake, 1, 1, 8, 2, 1, 3, 3, nul) == EINVAL   # W < KW
+    assert L.cnn_conv_bwd_input_bf16(fake, fake, nul, 1, 1, 8, 8, 1, 3, 3, nul) == EINVAL
     assert L.cnn_conv_bwd_weight(fake, fake, nul, nul, 1, 1, 8, 8, 1, 3, 3, nul, 0, nul) == EINVAL
     assert L.cnn_conv_bwd_weight(fake, fake, fake, nul, 1, 1, 8, 8, 1, 3, 3, odd, 1 << 20, nul) == EINVAL  # workspace alignment
     assert L.cnn_conv_bwd_weight_workspace_bytes(1, 1, 8, 8, 1, 9, 3) == 0               # kernel larger than input

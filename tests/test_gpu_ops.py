@@ -200,3 +200,47 @@ def test_conv_random_shapes(case):
     assert_close(host(d_k), ref_k, RTOL_ACT, "conv_bwd_weight %r" % (case,))
     assert_close(host(d_b), d64.sum(axis=(0, 2, 3)), RTOL_ACT, "conv_bwd_bias %r" % (case,))
 
+
+
+# ---- reduced precision: operands rounded to bfloat16, fp32 sums ----------------------------------------
+# Expected value: the oracle's plain definition applied to operands rounded by the oracle's own
+# rounding; what is left is fp32 summation order.  Bound: K products of magnitude <= 1, each exact in
+# fp32, summed in fp32: |error| <= K * 2^-24 * sum|terms| in the worst case, a few 1e-7 of the largest
+# result in practice; the tests allow 2e-5 of the largest result, as for the fp32 gradients.
+RTOL_BF16 = 2e-5
+BF16_CASES = [(5, 6, 12, 12, 12, 5, 5), (3, 1, 28, 28, 6, 5, 5), (2, 3, 9, 7, 4, 3, 2), (1, 2, 5, 5, 3, 1, 1),
+              (37, 2, 11, 13, 5, 4, 6), (3, 3, 8, 8, 20, 3, 3), (2, 30, 6, 6, 5, 3, 3), (1300, 6, 12, 12, 12, 5, 5),
+              (131, 1, 3, 3, 1, 2, 2), (2, 9, 7, 7, 33, 2, 3), (1, 3, 16, 16, 1, 16, 16), (2, 3, 80, 80, 4, 3, 3),
+              (4, 12, 4, 4, 10, 4, 4)]
+
+
+@pytest.mark.parametrize("case", BF16_CASES)
+def test_conv_fwd_bf16(case):
+    B, Cin, H, W, Cout, KH, KW = case
+    x = inputs.make_signed((B, Cin, H, W), 21)
+    k = inputs.make_signed((Cout, Cin, KH, KW), 22)
+    b = inputs.make_signed((Cout,), 23)
+    ref = oracle_conv_fwd(oracle.round_bf16(x), oracle.round_bf16(k), b)
+    got = host(binding.conv_fwd(dev(x), dev(k), dev(b), bf16=True))
+    assert_close(got, ref, RTOL_BF16, "conv_fwd_bf16")
+    # and it is the rounded problem that was solved, not the fp32 one: the two differ by far more
+    exact = oracle_conv_fwd(x, k, b)
+    if Cin * KH * KW >= 9:
+        assert np.abs(got - exact).max() > 20 * np.abs(got - ref).max()
+    assert_close(host(binding.conv_fwd(dev(x), dev(k), None, bf16=True)),
+                 oracle_conv_fwd(oracle.round_bf16(x), oracle.round_bf16(k), np.zeros(Cout, np.float32)), RTOL_BF16,
+                 "conv_fwd_bf16 no bias")
+
+
+@pytest.mark.parametrize("case", BF16_CASES)
+def test_conv_bwd_input_bf16(case):
+    B, Cin, H, W, Cout, KH, KW = case
+    Ho, Wo = H - KH + 1, W - KW + 1
+    d = inputs.make_signed((B, Cout, Ho, Wo), 24)
+    k = inputs.make_signed((Cout, Cin, KH, KW), 25)
+    d64, k64 = oracle.round_bf16(d).astype(np.float64), oracle.round_bf16(k).astype(np.float64)
+    ref = np.zeros((B, Cin, H, W), np.float64)
+    for n in range(B):
+        for co in range(Cout):
+            ref[n] += oracle.backin(d64[n, co][None], k64[co], (Cin, H, W))
+    assert_close(host(binding.conv_bwd_input(dev(d), dev(k), H, W, bf16=True)), ref, RTOL_BF16, "conv_bwd_input_bf16")

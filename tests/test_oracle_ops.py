@@ -244,3 +244,34 @@ def test_backin_inner_elements_see_every_weight():
     assert din[6, 6] == 25.0 and din[0, 0] == 1.0 and din[11, 11] == 1.0 and din[0, 11] == 1.0
     assert din[4, 0] == 5.0 and din[7, 11] == 5.0
     assert din.sum() == 64 * 25
+
+
+# ---- bfloat16 rounding (states what the reduced-precision convolution computes) ----------------------
+
+def test_round_bf16_hand_values():
+    """1 sign, 8 exponent, 7 fraction bits: the spacing in [1, 2) is 2^-7; ties go to the even significand."""
+    u = 2.0 ** -7
+    cases = [(1.0, 1.0), (1.0 + u, 1.0 + u), (1.0 + u / 2, 1.0),              # tie between 1 (even) and 1+u (odd)
+             (1.0 + 3 * u / 2, 1.0 + 2 * u),                                   # tie between 1+u (odd) and 1+2u (even)
+             (1.0 + u / 2 + 2.0 ** -23, 1.0 + u), (1.0 + u / 2 - 2.0 ** -23, 1.0),
+             (2.0 - u / 4, 2.0), (-1.0 - 3 * u / 2, -1.0 - 2 * u),
+             (0.0, 0.0), (2.0 ** -126, 2.0 ** -126), (2.0 ** -133, 2.0 ** -133), (2.0 ** -134, 0.0),
+             (3 * 2.0 ** -134, 2.0 ** -132), (0.1, 0.10009765625)]
+    got = oracle.round_bf16(np.array([a for a, _ in cases], np.float32))
+    np.testing.assert_array_equal(got, np.array([b for _, b in cases], np.float32))
+
+
+def test_round_bf16_against_library_and_properties():
+    import torch
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.uniform(-1, 1, 20000), rng.standard_normal(20000) * 1e-3,
+                        np.ldexp(rng.uniform(0.5, 1, 4000), rng.integers(-140, 120, 4000)) * rng.choice([-1, 1], 4000)])
+    x = x.astype(np.float32)
+    r = oracle.round_bf16(x)
+    lib = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()   # an independent conversion
+    np.testing.assert_array_equal(r, lib)
+    np.testing.assert_array_equal(oracle.round_bf16(r), r)                    # idempotent
+    assert np.all((r.view(np.uint32) & 0xFFFF) == 0)                          # low 16 bits of the float are clear
+    nz = x != 0
+    assert np.all(np.abs(r[nz].astype(np.float64) - x[nz]) <= np.abs(x[nz]).astype(np.float64) * 2.0 ** -8 + 2.0 ** -134)
+    assert np.all(np.sign(r) * np.sign(x) >= 0) and np.all(np.diff(oracle.round_bf16(np.sort(x))) >= 0)  # monotone
