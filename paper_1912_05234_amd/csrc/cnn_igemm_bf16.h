@@ -26,13 +26,19 @@ using igemm::divmod;
 using igemm::lds_barrier;
 using bf8 = __bf16 __attribute__((ext_vector_type(8)));
 
-constexpr int PF = 16;  // staged 4-byte items per thread and round
-
 // fp32 -> bf16 bits, round to nearest even (finite inputs)
 __device__ __forceinline__ unsigned short to_bf16(float f) {
   unsigned u = __float_as_uint(f);
   u += 0x7fffu + ((u >> 16) & 1u);
   return (unsigned short)(u >> 16);
+}
+// two at once: lo in bits 0..15, hi in bits 16..31 (the conversion of a float pair is one
+// instruction on gfx950, same rounding)
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+  using f2v = float __attribute__((ext_vector_type(2)));
+  using bf2v = __bf16 __attribute__((ext_vector_type(2)));
+  const bf2v r = __builtin_convertvector(f2v{lo, hi}, bf2v);
+  return __builtin_bit_cast(unsigned, r);
 }
 
 struct Args {
@@ -46,8 +52,8 @@ struct Args {
   int C8, K, NBK;     // channels padded to 8; reduction length KH*KW*C8; blocks of 32
   int RS;             // bytes of a row of the weight table
   int LW, LPIX;       // pixels of a staged row, of a staged image
-  int NB, groups, MT, rounds;
-  float inv_kp, inv_c8, inv_kw, inv_ohow, inv_ow, inv_pi, inv_hw, inv_sw;
+  int NB, groups, MT;
+  float inv_kp, inv_c8, inv_kw, inv_ohow, inv_ow, inv_chhw, inv_hw, inv_sw;
 };
 // LDS layout in bytes, in this order (every part a multiple of 16).
 struct Lds {
@@ -124,47 +130,49 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const Args g) {
   // borders and padding channels stay zero for the whole kernel
   for (int e = t; e < (g.NB * g.LPIX * g.C8) >> 3; e += THREADS) reinterpret_cast<f4*>(x)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
 
-  // byte offset in x of staged element e = (image, channel, row, column) of a group
-  auto target = [&](int e) {
-    int img, r, c, p, y, xx;
-    divmod(e, per_image, g.inv_pi, img, r);
-    divmod(r, HW, g.inv_hw, c, p);
-    divmod(p, g.SW, g.inv_sw, y, xx);
-    return 2 * ((img * g.LPIX + (y + g.pady) * g.LW + g.padx + xx) * g.C8 + c);
-  };
-  float pv[PF];
-  int ptgt[PF];
-#pragma unroll
-  for (int i = 0; i < PF; ++i) {
-    const int e = t + THREADS * i;
-    ptgt[i] = e < g.NB * per_image ? target(e) : 0;
-  }
-  auto issue = [&](int grp, int r) {
-    const int b0 = grp * g.NB, count = min(g.NB, g.B - b0) * per_image, first = r * (THREADS * PF) + t;
+  // Staging of a group: one item = one pixel's eight channels of a chunk, read from the eight
+  // channel planes (a wave reads 256 consecutive bytes of each), rounded, packed and written as one
+  // 16-byte LDS item; two items per thread in flight.  There is no hand-over through registers
+  // across the matrix work here: the workgroups are small, and the other resident ones cover the
+  // load latency.
+  const int CH = g.C8 >> 3;
+  auto stage = [&](int grp) {
+    const int b0 = grp * g.NB, items = min(g.NB, g.B - b0) * CH * HW;
     const float* src = g.src + (size_t)b0 * per_image;
+    for (int e0 = t; e0 < items; e0 += 2 * THREADS) {
+      float v[2][8];
+      int where[2];
 #pragma unroll
-    for (int i = 0; i < PF; ++i)
-      if (first + THREADS * i < count) pv[i] = src[first + THREADS * i];
-  };
-  auto commit = [&](int grp, int r) {
-    const int b0 = grp * g.NB, count = min(g.NB, g.B - b0) * per_image, first = r * (THREADS * PF) + t;
+      for (int k = 0; k < 2; ++k) {
+        const int e = e0 + k * THREADS;
+        where[k] = -1;
+        if (e < items) {
+          int img, r, chunk, p, y, xx;
+          divmod(e, CH * HW, g.inv_chhw, img, r);
+          divmod(r, HW, g.inv_hw, chunk, p);
+          divmod(p, g.SW, g.inv_sw, y, xx);
+          where[k] = 2 * ((img * g.LPIX + (y + g.pady) * g.LW + g.padx + xx) * g.C8 + 8 * chunk);
+          const float* sp = src + (size_t)img * per_image + (size_t)(8 * chunk) * HW + p;
 #pragma unroll
-    for (int i = 0; i < PF; ++i)
-      if (first + THREADS * i < count)
-        *reinterpret_cast<unsigned short*>(x + (r == 0 ? ptgt[i] : target(first + THREADS * i))) = to_bf16(pv[i]);
+          for (int cc = 0; cc < 8; ++cc) v[k][cc] = 8 * chunk + cc < g.SC ? sp[cc * HW] : 0.0f;
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 2; ++k)
+        if (where[k] >= 0) {
+          i4 packed;
+#pragma unroll
+          for (int h = 0; h < 4; ++h) packed[h] = (int)pack_bf16(v[k][2 * h], v[k][2 * h + 1]);
+          *reinterpret_cast<i4*>(x + where[k]) = packed;
+        }
+    }
   };
 
-  if ((int)blockIdx.x < g.groups) issue(blockIdx.x, 0);
   for (int grp = blockIdx.x; grp < g.groups; grp += gridDim.x) {
     const int b0 = grp * g.NB, nb = min(g.NB, g.B - b0);
     lds_barrier();  // tables and zeros (first pass) / the previous group's reads are complete
-    commit(grp, 0);
-    for (int r = 1; r < g.rounds; ++r) {
-      issue(grp, r);
-      commit(grp, r);
-    }
+    stage(grp);
     lds_barrier();
-    if (grp + (int)gridDim.x < g.groups) issue(grp + gridDim.x, 0);
 
     const int N = nb * OHOW, PT = (N + 15) >> 4, PG = (PT + TP - 1) / TP;
     float* dst = g.dst + (size_t)b0 * g.M * OHOW;
@@ -178,30 +186,45 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const Args g) {
         const int n = 16 * (pg * TP + tt) + j, nn = n < N ? n : N - 1;
         po[tt] = poff[nn];
         oo[tt] = ooff[nn];
-        acc[tt] = binit;
       }
       const char* arow = smem + L.wt + (16 * mt + j) * g.RS + 16 * q;
-      // two blocks per trip, the reads of the second under the MFMAs of the first
+      // Block 0 starts the sums from the bias; then two blocks per trip, the reads of one under the
+      // MFMAs of the other.  The byte offset of a block's K elements is fetched two blocks ahead, so
+      // that no read waits for another, and a trip has no branches: block numbers past the end are
+      // clamped to the last block, whose operands are then read again and not used.
+      const int last = g.NBK - 1;
+      const int* kq = koff + q;
       bf8 a0, a1, b0v[TP], b1v[TP];
-      auto load = [&](int b, bf8& a, bf8 (&bv)[TP]) {
-        a = *reinterpret_cast<const bf8*>(arow + 64 * b);
-        const int ko = koff[4 * b + q];
+      int k2 = kq[4 * min(2, last)], k3 = kq[4 * min(3, last)];
+      {
+        const int k0 = kq[0], k1 = kq[4 * min(1, last)];
+        a0 = *reinterpret_cast<const bf8*>(arow);
 #pragma unroll
-        for (int tt = 0; tt < TP; ++tt) bv[tt] = *reinterpret_cast<const bf8*>(x + po[tt] + ko);
-      };
-      load(0, a0, b0v);
-      int b = 0;
+        for (int tt = 0; tt < TP; ++tt) b0v[tt] = *reinterpret_cast<const bf8*>(x + po[tt] + k0);
+        a1 = *reinterpret_cast<const bf8*>(arow + 64 * min(1, last));
+#pragma unroll
+        for (int tt = 0; tt < TP; ++tt) b1v[tt] = *reinterpret_cast<const bf8*>(x + po[tt] + k1);
+#pragma unroll
+        for (int tt = 0; tt < TP; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b0v[tt], binit, 0, 0, 0);
+      }
+      int b = 1;  // block b is in a1, b1v
       for (; b + 1 < g.NBK; b += 2) {
-        load(b + 1, a1, b1v);
+        const int k4 = kq[4 * min(b + 3, last)], k5 = kq[4 * min(b + 4, last)];
+        a0 = *reinterpret_cast<const bf8*>(arow + 64 * (b + 1));
 #pragma unroll
-        for (int tt = 0; tt < TP; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b0v[tt], acc[tt], 0, 0, 0);
-        if (b + 2 < g.NBK) load(b + 2, a0, b0v);
+        for (int tt = 0; tt < TP; ++tt) b0v[tt] = *reinterpret_cast<const bf8*>(x + po[tt] + k2);
 #pragma unroll
         for (int tt = 0; tt < TP; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1v[tt], acc[tt], 0, 0, 0);
-      }
-      if (b < g.NBK) {  // an odd number of blocks: the last one is already in a0, b0v
+        a1 = *reinterpret_cast<const bf8*>(arow + 64 * min(b + 2, last));
+#pragma unroll
+        for (int tt = 0; tt < TP; ++tt) b1v[tt] = *reinterpret_cast<const bf8*>(x + po[tt] + k3);
 #pragma unroll
         for (int tt = 0; tt < TP; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b0v[tt], acc[tt], 0, 0, 0);
+        k2 = k4, k3 = k5;
+      }
+      if (b < g.NBK) {  // one block left: it is already in a1, b1v
+#pragma unroll
+        for (int tt = 0; tt < TP; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1v[tt], acc[tt], 0, 0, 0);
       }
       // lane (q, j) holds rows 16 mt + 4 q + r of column j
       const int m0 = 16 * mt + 4 * q;

@@ -547,7 +547,9 @@ Conv16Plan plan_conv16(const float* src, const float* w, const float* bias, floa
     for (int tp = 1; tp <= 4; tp <<= 1) {
       const long long PT = (nb * COLS + 15) / 16, jobs = ((PT + tp - 1) / tp) * MT;
       const double used = (double)nb * COLS / 16.0 * MT, slots = (double)((jobs + 3) / 4) * 4 * tp;
-      const double score = used / slots * (1.0 + 0.005 * tp);
+      // this kernel is bound by LDS reads, not by matrix slots: a job reads 1 KB of weights per
+      // block once for its tp tiles and 1 KB of pixels per tile
+      const double score = used / slots * tp / (tp + 1.0);
       if (score >= best) best = score, best_nb = nb, best_tp = tp;
     }
   }
@@ -557,9 +559,8 @@ Conv16Plan plan_conv16(const float* src, const float* w, const float* bias, floa
   p.lds_bytes = (size_t)bytes(a.NB);
   const unsigned resident = resident_workgroups(p.lds_bytes);
   p.grid = (unsigned)a.groups < resident ? (unsigned)a.groups : resident;
-  a.rounds = (int)((a.NB * per_image + igemm::THREADS * igemm16::PF - 1) / (igemm::THREADS * igemm16::PF));
   a.inv_kp = 1.0f / (float)(32 * a.NBK), a.inv_c8 = 1.0f / (float)a.C8, a.inv_kw = 1.0f / (float)KW;
-  a.inv_ohow = 1.0f / (float)COLS, a.inv_ow = 1.0f / (float)OW, a.inv_pi = 1.0f / (float)per_image;
+  a.inv_ohow = 1.0f / (float)COLS, a.inv_ow = 1.0f / (float)OW, a.inv_chhw = 1.0f / (float)(C8 / 8 * SH * SW);
   a.inv_hw = 1.0f / (float)(SH * SW), a.inv_sw = 1.0f / (float)SW;
   return p;
 }
