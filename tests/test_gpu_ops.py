@@ -244,3 +244,21 @@ def test_conv_bwd_input_bf16(case):
         for co in range(Cout):
             ref[n] += oracle.backin(d64[n, co][None], k64[co], (Cin, H, W))
     assert_close(host(binding.conv_bwd_input(dev(d), dev(k), H, W, bf16=True)), ref, RTOL_BF16, "conv_bwd_input_bf16")
+
+
+@pytest.mark.parametrize("case", _random_conv_cases(16, 20251127))
+def test_conv_bf16_random_shapes(case):
+    """Seeded random small shapes through the two reduced-precision entry points."""
+    B, Cin, H, W, Cout, KH, KW = case
+    Ho, Wo = H - KH + 1, W - KW + 1
+    x, k, b = inputs.make_signed((B, Cin, H, W), 51), inputs.make_signed((Cout, Cin, KH, KW), 52), inputs.make_signed((Cout,), 53)
+    d = inputs.make_signed((B, Cout, Ho, Wo), 54)
+    xr, kr, dr = oracle.round_bf16(x), oracle.round_bf16(k), oracle.round_bf16(d)
+    assert_close(host(binding.conv_fwd(dev(x), dev(k), dev(b), bf16=True)), oracle_conv_fwd(xr, kr, b), RTOL_BF16,
+                 "conv_fwd_bf16 %r" % (case,))
+    ref_in = np.zeros((B, Cin, H, W))
+    for n in range(B):
+        for co in range(Cout):
+            ref_in[n] += oracle.backin(dr[n, co][None].astype(np.float64), kr[co].astype(np.float64), (Cin, H, W))
+    assert_close(host(binding.conv_bwd_input(dev(d), dev(k), H, W, bf16=True)), ref_in, RTOL_BF16,
+                 "conv_bwd_input_bf16 %r" % (case,))
