@@ -524,7 +524,7 @@ Conv16Plan plan_conv16(const float* src, const float* w, const float* bias, floa
   a.pady = pady, a.padx = padx, a.flip = flip;
   const long long C8 = ((long long)SC + 7) & ~7LL, K = (long long)KH * KW * C8, NBK = (K + 31) / 32;
   const long long LW = SW + 2LL * padx, LPIX = (SH + 2LL * pady) * LW, MT = ((long long)M + 15) / 16;
-  const long long COLS = (long long)OH * OW, per_image = (long long)SC * SH * SW;
+  const long long COLS = (long long)OH * OW;
   // first in 64 bits: one image and the tables must fit before anything is narrowed to int
   if (16 * MT * (64 * NBK + 16) + 16 * NBK + 64 * MT + 8 * COLS + 2 * LPIX * C8 + 64 > LDS_LIMIT) return p;
   a.C8 = (int)C8, a.K = (int)K, a.NBK = (int)NBK, a.RS = (int)(64 * NBK + 16), a.LW = (int)LW, a.LPIX = (int)LPIX;
