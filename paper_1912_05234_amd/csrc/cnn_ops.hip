@@ -276,15 +276,11 @@ int gather_read_cost(int LW, int LP, int LI, int KH, int KWP, int K, int OWP, in
           const int c = kk / (KH * KWP), rem = kk % (KH * KWP), img = n / COLS, r = n % COLS;
           word[l] = (kk < K ? c * LP + (rem / KWP) * LW + rem % KWP : 0) + img * LI + (r / OWP) * LW + P * (r % OWP);
         }
-        for (int l = 0; l < 32; ++l) {  // different words in lane l's bank, counted at their first lane
-          int different = 0;
-          for (int m = 0; m < 32; ++m) {
-            if ((word[m] & 31) != (word[l] & 31)) continue;
-            bool first = true;
-            for (int e = 0; e < m; ++e) first = first && word[e] != word[m];
-            different += first;
-          }
-          if (different > worst) worst = different;
+        int per_bank[32] = {0};  // different words per bank: each word counted at its first lane
+        for (int l = 0; l < 32; ++l) {
+          bool first = true;
+          for (int e = 0; e < l; ++e) first = first && word[e] != word[l];
+          if (first && ++per_bank[word[l] & 31] > worst) worst = per_bank[word[l] & 31];
         }
         cost += worst;
       }
