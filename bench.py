@@ -12,7 +12,8 @@ per-batch calls inside the library.  Prints ONE JSON line.  Besides the contract
   roofline      the fused forward+backward kernel's algorithmic flop rate against MI355X's fp32
                 peak, from HIP events recorded around that kernel on its own stream;
   cpu_baseline  the single-threaded CPU oracle timed on this host on a bounded sample;
-  sweep         the same step at batch 1000 / 10000 / 60000 and the forward-only evaluation pass.
+  sweep         the same step at batch 1000 / 10000 / 60000, the forward-only evaluation pass, and the
+                stateless per-op calls (fp32 and bf16) at the layer shapes, microseconds per call.
 """
 import argparse
 import json
@@ -169,6 +170,11 @@ def main():
         sweep["evaluate_10000"] = {"images_per_s": N_EVAL / dt, "ms_per_pass": 1e3 * dt,
                                    "frac_fp32_peak": N_EVAL / dt * FLOP_PER_IMAGE_FWD / 1e12 / PEAK_FP32_TFLOPS}
         net.close()
+        # the stateless per-op calls at the layer shapes (10000 images): microseconds per call
+        from paper_1912_05234_amd import bench_ops
+        per_op = {}
+        bench_ops.run(10000, 20, lambda line: per_op.__setitem__("%s.%s" % (line["layer"], line["op"]), line["us"]))
+        sweep["per_op_us_batch_10000"] = per_op
         out["sweep"] = sweep
 
     if not args.no_cpu_baseline:

@@ -44,6 +44,12 @@ def main(argv=None):
     args = ap.parse_args(argv)
     if not torch.cuda.is_available():
         sys.exit("bench_ops needs a GPU")
+    run(args.batch, args.steps, lambda line: print(json.dumps(line), flush=True))
+
+
+def run(batch, steps, emit):
+    """Times every per-op call at `batch` images and hands each result (a dict) to `emit`."""
+    args = argparse.Namespace(batch=batch, steps=steps)
     dev, B = "cuda:0", args.batch
     gen = torch.Generator(device="cpu").manual_seed(7)
 
@@ -55,12 +61,12 @@ def main(argv=None):
         line = {"layer": layer, "op": op, "batch": B, "us": round(us, 2), "tflops": round(tf, 2),
                 "frac_of_fp32_peak": round(tf / PEAK_TFLOPS, 4)}
         line.update(extra or {})
-        print(json.dumps(line), flush=True)
+        emit(line)
 
     def report_bw(layer, op, us, nbytes):
         gbs = nbytes / us / 1e3
-        print(json.dumps({"layer": layer, "op": op, "batch": B, "us": round(us, 2), "gb_per_s": round(gbs, 1),
-                          "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)}), flush=True)
+        emit({"layer": layer, "op": op, "batch": B, "us": round(us, 2), "gb_per_s": round(gbs, 1),
+              "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)})
 
     for name, (Cin, H, W, Cout, KH, KW) in CONVS.items():
         Ho, Wo = H - KH + 1, W - KW + 1
