@@ -150,6 +150,13 @@ size_t cnn_conv_bwd_weight_workspace_bytes(int B, int Cin, int H, int W, int Cou
 int cnn_conv_bwd_weight(const float* in, const float* d_out, float* d_k, float* d_bias, int B,
                         int Cin, int H, int W, int Cout, int KH, int KW, void* workspace,
                         size_t workspace_bytes, void* hip_stream);
+/* Reduced-precision form of cnn_conv_bwd_weight, same arguments and workspace rules (its own size
+ * query): `in` and `d_out` are rounded to bfloat16 as they are read, products are summed in fp32 on
+ * the bf16 matrix cores; d_bias is the fp32 sum of the rounded d_out. */
+size_t cnn_conv_bwd_weight_bf16_workspace_bytes(int B, int Cin, int H, int W, int Cout, int KH, int KW);
+int cnn_conv_bwd_weight_bf16(const float* in, const float* d_out, float* d_k, float* d_bias, int B,
+                             int Cin, int H, int W, int Cout, int KH, int KW, void* workspace,
+                             size_t workspace_bytes, void* hip_stream);
 /* Listing `avgpool` over [B,C,H,W] (H, W even) -> [B,C,H/2,W/2]. */
 int cnn_avgpool_fwd(const float* in, float* out, int B, int C, int H, int W, void* hip_stream);
 /* Listing `backavgpool`: d_out[B,C,Ho,Wo] -> d_in[B,C,2Ho,2Wo] = d_out[..,y/2,x/2] / 4. */

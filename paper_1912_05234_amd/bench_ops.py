@@ -90,6 +90,10 @@ def run(batch, steps, emit):
         calls["conv_fwd_bf16"] = lambda: L.cnn_conv_fwd_bf16(p(x), p(k), p(b), p(out), B, Cin, H, W, Cout, KH, KW, s())
         calls["conv_bwd_input_bf16"] = lambda: L.cnn_conv_bwd_input_bf16(p(d), p(k), p(d_in), B, Cin, H, W, Cout, KH,
                                                                          KW, s())
+        nbytes16 = L.cnn_conv_bwd_weight_bf16_workspace_bytes(B, Cin, H, W, Cout, KH, KW)
+        ws16 = torch.empty(max(nbytes16, 16), dtype=torch.uint8, device=dev)
+        calls["conv_bwd_weight_bf16"] = lambda: L.cnn_conv_bwd_weight_bf16(p(x), p(d), p(d_k), p(d_b), B, Cin, H, W,
+                                                                           Cout, KH, KW, p(ws16), nbytes16, s())
         for op, fn in calls.items():
             assert fn() == 0, op
             report(name, op, time_call(fn, args.steps), flops)

@@ -39,6 +39,8 @@ SIGNATURES = {
     "cnn_conv_fwd_bf16": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp]),
     "cnn_conv_bwd_input_bf16": (_i, [_vp, _vp, _vp] + [_i] * 7 + [_vp]),
     "cnn_conv_bwd_weight_workspace_bytes": (_sz, [_i] * 7),
+    "cnn_conv_bwd_weight_bf16_workspace_bytes": (_sz, [_i] * 7),
+    "cnn_conv_bwd_weight_bf16": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp, _sz, _vp]),
     "cnn_conv_bwd_weight": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp, _sz, _vp]),
     "cnn_avgpool_fwd": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
     "cnn_avgpool_bwd": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
@@ -231,18 +233,20 @@ def _workspace(nbytes, device, use):
     return torch.empty((nbytes,), dtype=torch.uint8, device=device), nbytes
 
 
-def conv_bwd_weight(inp, d_out, want_bias=True, workspace=True):
+def conv_bwd_weight(inp, d_out, want_bias=True, workspace=True, bf16=False):
     """workspace=False passes none, which selects the kernel that needs no partial sums."""
+    suffix = "_bf16" if bf16 else ""
     inp, d_out = _dev(inp), _dev(d_out)
     B, Cin, H, W = inp.shape
     Cout, Ho, Wo = d_out.shape[1:]
     KH, KW = H - Ho + 1, W - Wo + 1
     d_k = torch.empty((Cout, Cin, KH, KW), dtype=torch.float32, device=inp.device)
     d_b = torch.empty((Cout,), dtype=torch.float32, device=inp.device) if want_bias else None
-    ws, nbytes = _workspace(lib().cnn_conv_bwd_weight_workspace_bytes(B, Cin, H, W, Cout, KH, KW), inp.device,
-                            workspace)
-    _check(lib().cnn_conv_bwd_weight(_ptr(inp), _ptr(d_out), _ptr(d_k), _ptr(d_b), B, Cin, H, W, Cout, KH,
-                                     KW, _ptr(ws), nbytes, _stream()), "cnn_conv_bwd_weight")
+    query = getattr(lib(), "cnn_conv_bwd_weight%s_workspace_bytes" % suffix)
+    ws, nbytes = _workspace(query(B, Cin, H, W, Cout, KH, KW), inp.device, workspace)
+    name = "cnn_conv_bwd_weight" + suffix
+    _check(getattr(lib(), name)(_ptr(inp), _ptr(d_out), _ptr(d_k), _ptr(d_b), B, Cin, H, W, Cout, KH, KW,
+                                _ptr(ws), nbytes, _stream()), name)
     return d_k, d_b
 
 

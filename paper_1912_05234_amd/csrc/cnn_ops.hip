@@ -106,6 +106,7 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 
 // One workgroup per weight (blocks [0, Cout*Cin*KH*KW)) or per bias (the next Cout
 // blocks): d_k[co,ci,u,v] = sum_{b,y,x} in[b,ci,y+u,x+v] * d_out[b,co,y,x].
+template <bool BF16>
 __global__ __launch_bounds__(TPB) void conv_bwd_weight_kernel(const float* __restrict__ in,
                                                               const float* __restrict__ d_out,
                                                               float* __restrict__ d_k,
@@ -122,8 +123,8 @@ __global__ __launch_bounds__(TPB) void conv_bwd_weight_kernel(const float* __res
     for (size_t e = threadIdx.x; e < dom; e += TPB) {
       const int x = (int)(e % Wo), y = (int)((e / Wo) % Ho);
       const size_t b = e / ((size_t)Wo * Ho);
-      acc = fmaf(in[((b * Cin + ci) * H + y + u) * (size_t)W + x + v],
-                 d_out[((b * Cout + co) * Ho + y) * (size_t)Wo + x], acc);
+      acc = fmaf(operand<BF16>(in[((b * Cin + ci) * H + y + u) * (size_t)W + x + v]),
+                 operand<BF16>(d_out[((b * Cout + co) * Ho + y) * (size_t)Wo + x]), acc);
     }
     acc = block_sum(acc, red);
     if (threadIdx.x == 0) d_k[id] = acc;
@@ -131,7 +132,7 @@ __global__ __launch_bounds__(TPB) void conv_bwd_weight_kernel(const float* __res
     const int co = id - nk;
     for (size_t e = threadIdx.x; e < dom; e += TPB) {
       const size_t b = e / ((size_t)Wo * Ho), r = e % ((size_t)Wo * Ho);
-      acc += d_out[(b * Cout + co) * (size_t)Ho * Wo + r];
+      acc += operand<BF16>(d_out[(b * Cout + co) * (size_t)Ho * Wo + r]);
     }
     acc = block_sum(acc, red);
     if (threadIdx.x == 0) d_bias[co] = acc;
@@ -570,6 +571,54 @@ int launch_conv16(const Conv16Plan& p, hipStream_t stream) {
   return launched();
 }
 
+struct Wgrad16Plan {
+  igemm16::WArgs a;
+  bool fits = false;
+  unsigned gx = 0, gy = 0;
+  size_t lds_bytes = 0, workspace_bytes = 0;
+};
+
+Wgrad16Plan plan_wgrad16(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
+  Wgrad16Plan p;
+  igemm16::WArgs& a = p.a;
+  a.in = nullptr, a.d_out = nullptr, a.part = nullptr;
+  a.B = B, a.Cin = Cin, a.H = H, a.W = W, a.Cout = Cout, a.KH = KH, a.KW = KW;
+  a.Ho = H - KH + 1, a.Wo = W - KW + 1;
+  const long long K = (long long)Cin * KH * KW, NT = (K + 15) / 16, MT = ((long long)Cout + 15) / 16;
+  const long long XG = (a.Wo + 7) / 8, WP = 8 * XG, RUNS = a.Ho * XG;
+  const long long WR = WP + 8 > (((long long)W + 7) & ~7LL) ? WP + 8 : (((long long)W + 7) & ~7LL), W4 = (W + 3) / 4;
+  if (KW > 8) return p;  // the shifted copies are made for at most eight kernel columns
+  // in 64 bits first: one image must fit
+  if (16 * (16 * ((RUNS + 3) / 4 * 4) + 16) + 2 * Cin * (long long)H * (KW * WP + WR) + 64 > LDS_LIMIT || NT > (1 << 20)) return p;
+  a.K = (int)K, a.NT = (int)NT, a.MT = (int)MT, a.NTG = (int)((NT + 15) / 16), a.XG = (int)XG, a.WP = (int)WP;
+  a.WR = (int)WR, a.W4 = (int)W4, a.DR = Cout < 16 ? Cout : 16;
+  auto bytes = [&](int nb) {
+    a.NB = nb;
+    a.NBK = (int)((nb * RUNS + 3) / 4);
+    a.RSD = 64 * a.NBK + 16;
+    return (long long)igemm16::wlds_layout(a).total;
+  };
+  if (bytes(1) > LDS_LIMIT) return p;
+  p.fits = true;
+  int nb = 1;
+  const int nb_fill = (B + MAX_PARTIALS - 1) / MAX_PARTIALS;
+  for (int c = 2; c <= MAX_GROUP && c <= B && c <= (nb_fill > 4 ? nb_fill : 4) && bytes(c) <= WGRAD_LDS_TARGET; ++c) nb = c;
+  p.lds_bytes = (size_t)bytes(nb);
+  a.groups = (B + nb - 1) / nb;
+  unsigned gx = resident_workgroups(p.lds_bytes) / (unsigned)(a.MT * a.NTG);
+  if (gx < 1) gx = 1;
+  if (gx > MAX_PARTIALS) gx = MAX_PARTIALS;
+  if (gx > (unsigned)a.groups) gx = (unsigned)a.groups;
+  p.gx = gx;
+  p.gy = (unsigned)(a.MT * a.NTG);
+  p.workspace_bytes = ((size_t)gx * a.MT * a.NT * 256 + (size_t)gx * a.MT * 16) * sizeof(float);
+  a.inv_khkw = 1.0f / (float)(KH * KW), a.inv_kw = 1.0f / (float)KW, a.inv_xg = 1.0f / (float)XG;
+  a.inv_hoxg = 1.0f / (float)RUNS, a.inv_hxg = 1.0f / (float)(H * XG);
+  a.inv_cinhxg = 1.0f / (float)(Cin * H * XG), a.inv_w4 = 1.0f / (float)W4, a.inv_hw4 = 1.0f / (float)(H * W4);
+  a.inv_cinhw4 = 1.0f / (float)(Cin * H * W4);
+  return p;
+}
+
 inline bool conv_args_ok(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
   return B >= 1 && Cin >= 1 && Cout >= 1 && KH >= 1 && KW >= 1 && H >= KH && W >= KW &&
          (size_t)Cout * Cin * KH * KW + (size_t)Cout < (size_t)1 << 30;
@@ -661,8 +710,37 @@ int cnn_conv_bwd_weight(const float* in, const float* d_out, float* d_k, float* 
     return launched();
   }
   const unsigned blocks = (unsigned)(Cout * Cin * KH * KW + (d_bias ? Cout : 0));
-  conv_bwd_weight_kernel<<<blocks, TPB, 0, (hipStream_t)hip_stream>>>(in, d_out, d_k, d_bias, B, Cin, H,
-                                                                      W, Cout, KH, KW);
+  conv_bwd_weight_kernel<false><<<blocks, TPB, 0, (hipStream_t)hip_stream>>>(in, d_out, d_k, d_bias, B, Cin,
+                                                                             H, W, Cout, KH, KW);
+  return launched();
+}
+
+size_t cnn_conv_bwd_weight_bf16_workspace_bytes(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
+  if (!conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return 0;
+  return plan_wgrad16(B, Cin, H, W, Cout, KH, KW).workspace_bytes;
+}
+
+int cnn_conv_bwd_weight_bf16(const float* in, const float* d_out, float* d_k, float* d_bias, int B, int Cin,
+                             int H, int W, int Cout, int KH, int KW, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+  if (!in || !d_out || !d_k || !conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;
+  if (!aligned16(in) || !aligned16(d_out) || !aligned16(d_k) || (d_bias && !aligned16(d_bias)))
+    return CNN_EINVAL;
+  if (workspace && !aligned16(workspace)) return CNN_EINVAL;
+  Wgrad16Plan p = plan_wgrad16(B, Cin, H, W, Cout, KH, KW);
+  if (p.fits && workspace && workspace_bytes >= p.workspace_bytes) {
+    p.a.in = in, p.a.d_out = d_out, p.a.part = static_cast<float*>(workspace);
+    hipStream_t st = (hipStream_t)hip_stream;
+    igemm16::wgrad_kernel<<<dim3(p.gx, p.gy), igemm::THREADS, p.lds_bytes, st>>>(p.a);
+    const size_t outputs = (size_t)Cout * Cin * KH * KW + Cout;
+    const int epw = outputs >= 2048 ? 16 : outputs >= 512 ? 8 : 4;
+    igemm::wgrad_reduce_kernel<<<(unsigned)((outputs + epw - 1) / epw), igemm::THREADS, 0, st>>>(
+        p.a.part, (int)p.gx, p.a.MT, p.a.NT, Cout, Cin, KH, KW, 1, epw, d_k, d_bias);
+    return launched();
+  }
+  const unsigned blocks = (unsigned)(Cout * Cin * KH * KW + (d_bias ? Cout : 0));
+  conv_bwd_weight_kernel<true><<<blocks, TPB, 0, (hipStream_t)hip_stream>>>(in, d_out, d_k, d_bias, B, Cin, H,
+                                                                            W, Cout, KH, KW);
   return launched();
 }
 

@@ -72,6 +72,10 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.cnn_conv_bwd_weight(fake, fake, nul, nul, 1, 1, 8, 8, 1, 3, 3, nul, 0, nul) == EINVAL
     assert L.cnn_conv_bwd_weight(fake, fake, fake, nul, 1, 1, 8, 8, 1, 3, 3, odd, 1 << 20, nul) == EINVAL  # workspace alignment
     assert L.cnn_conv_bwd_weight_workspace_bytes(1, 1, 8, 8, 1, 9, 3) == 0               # kernel larger than input
+    assert L.cnn_conv_bwd_weight_bf16(fake, fake, nul, nul, 1, 1, 8, 8, 1, 3, 3, nul, 0, nul) == EINVAL
+    assert L.cnn_conv_bwd_weight_bf16(fake, fake, fake, nul, 1, 1, 8, 8, 1, 3, 3, odd, 1 << 20, nul) == EINVAL
+    assert L.cnn_conv_bwd_weight_bf16_workspace_bytes(1, 1, 8, 8, 1, 9, 3) == 0
+    assert L.cnn_conv_bwd_weight_bf16_workspace_bytes(100, 6, 12, 12, 12, 5, 5) % ((10 * 256 + 16) * 4) == 0
     assert L.cnn_avgpool_fwd(fake, fake, 1, 1, 7, 8, nul) == EINVAL                     # odd extent
     assert L.cnn_avgpool_bwd(fake, nul, 1, 1, 4, 4, nul) == EINVAL
     assert L.cnn_fc_fwd(fake, fake, nul, fake, 1, 0, 10, nul) == EINVAL

@@ -262,3 +262,24 @@ def test_conv_bf16_random_shapes(case):
             ref_in[n] += oracle.backin(dr[n, co][None].astype(np.float64), kr[co].astype(np.float64), (Cin, H, W))
     assert_close(host(binding.conv_bwd_input(dev(d), dev(k), H, W, bf16=True)), ref_in, RTOL_BF16,
                  "conv_bwd_input_bf16 %r" % (case,))
+
+
+@pytest.mark.parametrize("case", BF16_CASES + [(70, 3, 9, 20, 5, 2, 4), (9, 2, 6, 40, 3, 3, 3)])
+def test_conv_bwd_weight_bf16(case):
+    B, Cin, H, W, Cout, KH, KW = case
+    Ho, Wo = H - KH + 1, W - KW + 1
+    x = inputs.make_signed((B, Cin, H, W), 26)
+    d = inputs.make_signed((B, Cout, Ho, Wo), 27)
+    x64, d64 = oracle.round_bf16(x).astype(np.float64), oracle.round_bf16(d).astype(np.float64)
+    ref_k = np.zeros((Cout, Cin, KH, KW), np.float64)
+    ref_b = np.zeros(Cout, np.float64)
+    for n in range(B):
+        for co in range(Cout):
+            ref_k[co] += oracle.backweights(d64[n, co][None], x64[n])
+            ref_b[co] += oracle.backbias(d64[n, co])
+    for workspace in (True, False):   # the matrix-core kernel, then the plain one with the same rounding
+        d_k, d_b = binding.conv_bwd_weight(dev(x), dev(d), workspace=workspace, bf16=True)
+        assert_close(host(d_k), ref_k, RTOL_BF16, "conv_bwd_weight_bf16")
+        assert_close(host(d_b), ref_b, RTOL_BF16, "conv_bwd_bias_bf16")
+    d_k2, none = binding.conv_bwd_weight(dev(x), dev(d), want_bias=False, bf16=True)
+    assert none is None and torch.equal(d_k2, binding.conv_bwd_weight(dev(x), dev(d), bf16=True)[0])
