@@ -248,7 +248,7 @@ def test_conv_bwd_input_bf16(case):
 
 @pytest.mark.parametrize("case", _random_conv_cases(16, 20251127))
 def test_conv_bf16_random_shapes(case):
-    """Seeded random small shapes through the two reduced-precision entry points."""
+    """Seeded random small shapes through the three reduced-precision entry points."""
     B, Cin, H, W, Cout, KH, KW = case
     Ho, Wo = H - KH + 1, W - KW + 1
     x, k, b = inputs.make_signed((B, Cin, H, W), 51), inputs.make_signed((Cout, Cin, KH, KW), 52), inputs.make_signed((Cout,), 53)
@@ -262,6 +262,13 @@ def test_conv_bf16_random_shapes(case):
             ref_in[n] += oracle.backin(dr[n, co][None].astype(np.float64), kr[co].astype(np.float64), (Cin, H, W))
     assert_close(host(binding.conv_bwd_input(dev(d), dev(k), H, W, bf16=True)), ref_in, RTOL_BF16,
                  "conv_bwd_input_bf16 %r" % (case,))
+    ref_k = np.zeros((Cout, Cin, KH, KW))
+    for n in range(B):
+        for co in range(Cout):
+            ref_k[co] += oracle.backweights(dr[n, co][None].astype(np.float64), xr[n].astype(np.float64))
+    d_k, d_b = binding.conv_bwd_weight(dev(x), dev(d), bf16=True)
+    assert_close(host(d_k), ref_k, RTOL_BF16, "conv_bwd_weight_bf16 %r" % (case,))
+    assert_close(host(d_b), dr.astype(np.float64).sum(axis=(0, 2, 3)), RTOL_BF16, "conv_bwd_bias_bf16 %r" % (case,))
 
 
 @pytest.mark.parametrize("case", BF16_CASES + [(70, 3, 9, 20, 5, 2, 4), (9, 2, 6, 40, 3, 3, 3)])
