@@ -607,7 +607,7 @@ Wgrad16Plan plan_wgrad16(int B, int Cin, int H, int W, int Cout, int KH, int KW)
   a.groups = (B + nb - 1) / nb;
   unsigned gx = resident_workgroups(p.lds_bytes) / (unsigned)(a.MT * a.NTG);
   if (gx < 1) gx = 1;
-  if (gx > MAX_PARTIALS) gx = MAX_PARTIALS;
+  if (gx > 2 * MAX_PARTIALS) gx = 2 * MAX_PARTIALS;  // every resident workgroup: this kernel lives on hidden latency
   if (gx > (unsigned)a.groups) gx = (unsigned)a.groups;
   p.gx = gx;
   p.gy = (unsigned)(a.MT * a.NTG);
