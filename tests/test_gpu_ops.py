@@ -169,6 +169,38 @@ def test_training_gradient_assembled_from_per_op_calls(B):
     assert abs(float(host(loss)[0]) - ref_loss) <= 1e-5 * ref_loss
 
 
+def test_training_gradient_with_bf16_c2_stays_close():
+    """The same chain with C2's three convolution calls in reduced precision: the gradient moves by
+    the bf16 rounding of C2's operands (relative 2^-9 each), far more than fp32 rounding and far less
+    than the gradient itself.  (Element by element the bf16 calls are checked against the oracle above.)"""
+    B = 64
+    w = inputs.make_weights()
+    images, labels = inputs.make_batch(B, 78)
+    net = binding.CNN(w, max_batch=B)
+    g_fused, _ = net.gradient(dev(images), dev(labels))
+    ref = inputs.unflatten(host(g_fused).astype(np.float64))
+    net.close()
+    x = dev(images).reshape(B, 1, 28, 28)
+    k1, b1, k2, b2, fc, b = (dev(w[n]) for n in ("k1", "b1", "k2", "b2", "fc", "b"))
+    k1 = k1.reshape(6, 1, 5, 5)
+    c1 = binding.logistic_fwd(binding.conv_fwd(x, k1, b1))
+    s1 = binding.avgpool_fwd(c1)
+    c2 = binding.logistic_fwd(binding.conv_fwd(s1, k2, b2, bf16=True))
+    s2f, fcw = binding.avgpool_fwd(c2).reshape(B, 192), fc.reshape(10, 192)
+    y = binding.logistic_fwd(binding.fc_fwd(s2f, fcw, b))
+    target = torch.zeros_like(y)
+    target[torch.arange(B), dev(labels).long()] = 1.0
+    d_pre = binding.logistic_bwd(y, y - target)
+    d_c2 = binding.logistic_bwd(c2, binding.avgpool_bwd(binding.fc_bwd_input(d_pre, fcw).reshape(B, 12, 4, 4)))
+    d_k2, d_b2 = binding.conv_bwd_weight(s1, d_c2, bf16=True)
+    d_c1 = binding.logistic_bwd(c1, binding.avgpool_bwd(binding.conv_bwd_input(d_c2, k2, 12, 12, bf16=True)))
+    d_k1, d_b1 = binding.conv_bwd_weight(x, d_c1)
+    for name, t in (("k2", d_k2), ("b2", d_b2), ("k1", d_k1), ("b1", d_b1)):
+        got, want = host(t).astype(np.float64).reshape(ref[name].shape), ref[name]
+        err = np.abs(got - want).max() / np.abs(want).max()
+        assert 2e-5 < err < 2e-2, (name, err)
+
+
 def _random_conv_cases(count, seed):
     rng = np.random.default_rng(seed)
     cases = []
