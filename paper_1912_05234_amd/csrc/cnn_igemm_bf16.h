@@ -49,11 +49,13 @@ struct Args {
   int B, M, SC, SH, SW, KH, KW, OH, OW;
   int pady, padx;     // border of zeros around a staged plane
   int flip;           // 0: A[m][(u,v,c)] = w[m][c][u][v];  1: A[m][(u,v,c)] = w[c][m][KH-1-u][KW-1-v]
-  int C8, K, NBK;     // channels padded to 8; reduction length KH*KW*C8; blocks of 32
+  int P, MR, KWP, OWP;  // column packing as in the fp32 kernel: P pixels per column, rows (m, sh) = M*P,
+                       // shifted taps v' < KW+P-1 with A[(m,sh)][(u,v',c)] = w[m][c][u][v'-sh], OW/P columns per row
+  int C8, K, NBK;     // channels padded to 8; reduction length KH*KWP*C8; blocks of 32
   int RS;             // bytes of a row of the weight table
   int LW, LPIX;       // pixels of a staged row, of a staged image
   int NB, groups, MT;
-  float inv_kp, inv_c8, inv_kw, inv_ohow, inv_ow, inv_chhw, inv_hw, inv_sw;
+  float inv_kp, inv_c8, inv_kwp, inv_cols, inv_owp, inv_chhw, inv_hw, inv_sw, inv_p;
 };
 // LDS layout in bytes, in this order (every part a multiple of 16).
 struct Lds {
@@ -65,9 +67,9 @@ __host__ __device__ inline Lds lds_layout(const Args& a) {
   l.wt = 0;                                     // bf16 [16 MT rows][RS / 2]
   l.koff = l.wt + 16 * a.MT * a.RS;             // int [NBK][4]: byte offset in x of K elements 32 b + 8 q ..
   l.bias = l.koff + 16 * a.NBK;                 // float [16 MT]
-  l.poff = l.bias + 64 * a.MT;                  // int [NB*OH*OW]: byte offset of the column's pixel in x
-  l.ooff = l.poff + up16(4 * a.NB * a.OH * a.OW);  // int [NB*OH*OW]: float offset of the column in dst
-  l.x = l.ooff + up16(4 * a.NB * a.OH * a.OW);  // bf16 [NB][LPIX][C8]
+  l.poff = l.bias + 64 * a.MT;                  // int [NB*OH*OWP]: byte offset of the column's first pixel in x
+  l.ooff = l.poff + up16(4 * a.NB * a.OH * a.OWP);  // int [NB*OH*OWP]: float offset of the column in dst (channel 0, sh 0)
+  l.x = l.ooff + up16(4 * a.NB * a.OH * a.OWP);  // bf16 [NB][LPIX][C8]
   l.total = l.x + up16(2 * a.NB * a.LPIX * a.C8);
   return l;
 }
@@ -94,12 +96,14 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const Args g) {
       const int e = e0 + i * THREADS;
       val[i] = 0.0f, where[i] = -1;
       if (e < 16 * g.MT * KP) {
-        int m, kk, tap, c, u, v;
-        divmod(e, KP, g.inv_kp, m, kk);
+        int mrow, kk, tap, c, u, vp, m, sh;
+        divmod(e, KP, g.inv_kp, mrow, kk);
         divmod(kk, g.C8, g.inv_c8, tap, c);
-        divmod(tap, g.KW, g.inv_kw, u, v);
-        where[i] = m * g.RS + 2 * kk;
-        if (m < g.M && kk < g.K && c < g.SC)
+        divmod(tap, g.KWP, g.inv_kwp, u, vp);
+        divmod(mrow, g.P, g.inv_p, m, sh);
+        const int v = vp - sh;
+        where[i] = mrow * g.RS + 2 * kk;
+        if (mrow < g.MR && kk < g.K && c < g.SC && v >= 0 && v < g.KW)
           val[i] = !g.flip ? g.w[((size_t)m * g.SC + c) * KHKW + u * g.KW + v]
                            : g.w[((size_t)c * g.M + m) * KHKW + (g.KH - 1 - u) * g.KW + (g.KW - 1 - v)];
       }
@@ -112,20 +116,33 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const Args g) {
     const int kk = 8 * e;  // 32 (e / 4) + 8 (e % 4)
     int off = 0;
     if (kk < g.K) {
-      int tap, c, u, v;
+      int tap, c, u, vp;
       divmod(kk, g.C8, g.inv_c8, tap, c);
-      divmod(tap, g.KW, g.inv_kw, u, v);
-      off = 2 * ((u * g.LW + v) * g.C8 + c);
+      divmod(tap, g.KWP, g.inv_kwp, u, vp);
+      off = 2 * ((u * g.LW + vp) * g.C8 + c);
     }
     koff[e] = off;
   }
-  for (int m = t; m < 16 * g.MT; m += THREADS) bl[m] = (g.bias && m < g.M) ? g.bias[m] : 0.0f;
-  for (int n = t; n < g.NB * OHOW; n += THREADS) {
+  for (int mrow = t; mrow < 16 * g.MT; mrow += THREADS) {
+    int m, sh;
+    divmod(mrow, g.P, g.inv_p, m, sh);
+    bl[mrow] = (g.bias && mrow < g.MR) ? g.bias[m] : 0.0f;
+  }
+  const int COLS = g.OH * g.OWP;
+  for (int n = t; n < g.NB * COLS; n += THREADS) {
     int img, r, y, xx;
-    divmod(n, OHOW, g.inv_ohow, img, r);
-    divmod(r, g.OW, g.inv_ow, y, xx);
-    poff[n] = 2 * (img * g.LPIX + y * g.LW + xx) * g.C8;
-    ooff[n] = img * g.M * OHOW + r;
+    divmod(n, COLS, g.inv_cols, img, r);
+    divmod(r, g.OWP, g.inv_owp, y, xx);
+    poff[n] = 2 * (img * g.LPIX + y * g.LW + g.P * xx) * g.C8;
+    ooff[n] = img * g.M * OHOW + y * g.OW + g.P * xx;
+  }
+  // float offset in dst of this lane's result register r in M tile 0 (packed forms have one M tile)
+  int ro0[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    int m, sh;
+    divmod(4 * q + r, g.P, g.inv_p, m, sh);
+    ro0[r] = m * OHOW + sh;
   }
   // borders and padding channels stay zero for the whole kernel
   for (int e = t; e < (g.NB * g.LPIX * g.C8) >> 3; e += THREADS) reinterpret_cast<f4*>(x)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
@@ -174,7 +191,7 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const Args g) {
     stage(grp);
     lds_barrier();
 
-    const int N = nb * OHOW, PT = (N + 15) >> 4, PG = (PT + TP - 1) / TP;
+    const int N = nb * COLS, PT = (N + 15) >> 4, PG = (PT + TP - 1) / TP;
     float* dst = g.dst + (size_t)b0 * g.M * OHOW;
     for (int job = wave; job < PG * g.MT; job += WAVES) {
       const int pg = job / g.MT, mt = job - pg * g.MT;
@@ -226,15 +243,23 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const Args g) {
 #pragma unroll
         for (int tt = 0; tt < TP; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1v[tt], acc[tt], 0, 0, 0);
       }
-      // lane (q, j) holds rows 16 mt + 4 q + r of column j
+      // lane (q, j) holds rows 16 mt + 4 q + r of column j; row (m, sh) is channel m, pixel P X + sh
       const int m0 = 16 * mt + 4 * q;
+      if ((g.P & 3) == 0 && 16 * (pg * TP + TP) <= N) {
+        // four (or a multiple of four) pixels per column: the four registers are neighbours in memory
+        if (m0 < g.MR) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-        if (m0 + r < g.M) {
-#pragma unroll
-          for (int tt = 0; tt < TP; ++tt)
-            if (16 * (pg * TP + tt) + j < N) dst[oo[tt] + (m0 + r) * OHOW] = acc[tt][r];
+          for (int tt = 0; tt < TP; ++tt) *reinterpret_cast<f4*>(dst + oo[tt] + ro0[0]) = acc[tt];
         }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (m0 + r < g.MR) {
+#pragma unroll
+            for (int tt = 0; tt < TP; ++tt)
+              if (16 * (pg * TP + tt) + j < N) dst[oo[tt] + ro0[r] + 16 * mt * OHOW] = acc[tt][r];
+          }
+      }
     }
   }
 }

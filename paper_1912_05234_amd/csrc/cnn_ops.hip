@@ -512,16 +512,17 @@ struct Conv16Plan {
   size_t lds_bytes = 0;
 };
 
-Conv16Plan plan_conv16(const float* src, const float* w, const float* bias, float* dst, int B, int M, int SC,
-                       int SH, int SW, int KH, int KW, int OH, int OW, int pady, int padx, int flip) {
+Conv16Plan plan_conv16_packed(const float* src, const float* w, const float* bias, float* dst, int B, int M, int SC,
+                              int SH, int SW, int KH, int KW, int OH, int OW, int pady, int padx, int flip, int P) {
   Conv16Plan p;
   igemm16::Args& a = p.a;
   a.src = src, a.w = w, a.bias = bias, a.dst = dst;
   a.B = B, a.M = M, a.SC = SC, a.SH = SH, a.SW = SW, a.KH = KH, a.KW = KW, a.OH = OH, a.OW = OW;
   a.pady = pady, a.padx = padx, a.flip = flip;
-  const long long C8 = ((long long)SC + 7) & ~7LL, K = (long long)KH * KW * C8, NBK = (K + 31) / 32;
-  const long long LW = SW + 2LL * padx, LPIX = (SH + 2LL * pady) * LW, MT = ((long long)M + 15) / 16;
-  const long long COLS = (long long)OH * OW;
+  a.P = P, a.MR = M * P, a.KWP = KW + P - 1, a.OWP = OW / P;
+  const long long C8 = ((long long)SC + 7) & ~7LL, K = (long long)KH * a.KWP * C8, NBK = (K + 31) / 32;
+  const long long LW = SW + 2LL * padx, LPIX = (SH + 2LL * pady) * LW, MT = ((long long)a.MR + 15) / 16;
+  const long long COLS = (long long)OH * a.OWP;
   // first in 64 bits: one image and the tables must fit before anything is narrowed to int
   if (16 * MT * (64 * NBK + 16) + 16 * NBK + 64 * MT + 8 * COLS + 2 * LPIX * C8 + 64 > LDS_LIMIT) return p;
   a.C8 = (int)C8, a.K = (int)K, a.NBK = (int)NBK, a.RS = (int)(64 * NBK + 16), a.LW = (int)LW, a.LPIX = (int)LPIX;
@@ -556,10 +557,26 @@ Conv16Plan plan_conv16(const float* src, const float* w, const float* bias, floa
   p.lds_bytes = (size_t)bytes(a.NB);
   const unsigned resident = resident_workgroups(p.lds_bytes);
   p.grid = (unsigned)a.groups < resident ? (unsigned)a.groups : resident;
-  a.inv_kp = 1.0f / (float)(32 * a.NBK), a.inv_c8 = 1.0f / (float)a.C8, a.inv_kw = 1.0f / (float)KW;
-  a.inv_ohow = 1.0f / (float)COLS, a.inv_ow = 1.0f / (float)OW, a.inv_chhw = 1.0f / (float)(C8 / 8 * SH * SW);
+  a.inv_kp = 1.0f / (float)(32 * a.NBK), a.inv_c8 = 1.0f / (float)a.C8, a.inv_kwp = 1.0f / (float)a.KWP;
+  a.inv_cols = 1.0f / (float)COLS, a.inv_owp = 1.0f / (float)a.OWP, a.inv_p = 1.0f / (float)P, a.inv_chhw = 1.0f / (float)(C8 / 8 * SH * SW);
   a.inv_hw = 1.0f / (float)(SH * SW), a.inv_sw = 1.0f / (float)SW;
   return p;
+}
+
+// Column packing as in the fp32 kernel (P pixels of a row per column, rows (m, sh)): among the
+// divisors P of OW with M*P <= 16 the one with the fewest 16-byte pixel reads per image, tiles x
+// K blocks; 1 for kernels one column wide.
+Conv16Plan plan_conv16(const float* src, const float* w, const float* bias, float* dst, int B, int M, int SC,
+                       int SH, int SW, int KH, int KW, int OH, int OW, int pady, int padx, int flip) {
+  Conv16Plan best = plan_conv16_packed(src, w, bias, dst, B, M, SC, SH, SW, KH, KW, OH, OW, pady, padx, flip, 1);
+  if (KW == 1) return best;
+  auto cost = [&](const Conv16Plan& p) { return (double)OH * p.a.OWP / 16.0 * p.a.NBK; };
+  for (int P = 2; P * M <= 16; ++P) {
+    if (OW % P) continue;
+    const Conv16Plan p = plan_conv16_packed(src, w, bias, dst, B, M, SC, SH, SW, KH, KW, OH, OW, pady, padx, flip, P);
+    if (p.tp && (!best.tp || cost(p) < cost(best))) best = p;
+  }
+  return best;
 }
 
 int launch_conv16(const Conv16Plan& p, hipStream_t stream) {
