@@ -142,3 +142,39 @@ def test_c2_layer_kernels_at_10000_images():
         acc_k += host(dk_c).astype(np.float64)
     assert_close(host(d_k), acc_k, RTOL_ACT, "conv_bwd_weight additivity over chunks")
     assert_close(host(d_b), d.astype(np.float64).sum(axis=(0, 2, 3)), RTOL_ACT, "bias gradient at 10000")
+
+
+def test_c2_layer_kernels_bf16_at_10000_images():
+    """The reduced-precision calls on the same C2 shape and batch: sampled images against the oracle's
+    definition applied to operands rounded by the oracle, and additivity of the weight gradient."""
+    B, rtol = 10000, 2e-5
+    x = inputs.make_signed((B, 6, 12, 12), 31)
+    k = inputs.make_signed((12, 6, 5, 5), 32)
+    bias = inputs.make_signed((12,), 33)
+    d = inputs.make_signed((B, 12, 8, 8), 34)
+    xd, kd, bd, dd = (torch.from_numpy(a).to(DEV) for a in (x, k, bias, d))
+    kr = oracle.round_bf16(k)
+    out = host(binding.conv_fwd(xd, kd, bd, bf16=True))
+    d_in = host(binding.conv_bwd_input(dd, kd, 12, 12, bf16=True))
+    for n in (0, 4097, B - 1):
+        ref = oracle.mconv(oracle.round_bf16(x[n]), kr, bias).reshape(12, 8, 8)
+        assert_close(out[n], ref, rtol, "conv_fwd_bf16[%d]" % n)
+        dr = oracle.round_bf16(d[n]).astype(np.float64)
+        ref_in = np.zeros((6, 12, 12))
+        for j in range(12):
+            ref_in += oracle.backin(dr[j][None], kr[j].astype(np.float64), (6, 12, 12))
+        assert_close(d_in[n], ref_in, rtol, "conv_bwd_input_bf16[%d]" % n)
+    d_k, d_b = binding.conv_bwd_weight(xd, dd, bf16=True)
+    acc_k = np.zeros((12, 6, 5, 5))
+    for c in range(0, B, 2500):
+        dk_c, _ = binding.conv_bwd_weight(xd[c:c + 2500].contiguous(), dd[c:c + 2500].contiguous(), bf16=True)
+        acc_k += host(dk_c).astype(np.float64)
+    assert_close(host(d_k), acc_k, rtol, "conv_bwd_weight_bf16 additivity over chunks")
+    assert_close(host(d_b), oracle.round_bf16(d).astype(np.float64).sum(axis=(0, 2, 3)), rtol, "bf16 bias gradient at 10000")
+    xr64, dr64 = oracle.round_bf16(x[:64]).astype(np.float64), oracle.round_bf16(d[:64]).astype(np.float64)
+    ref_k = np.zeros((12, 6, 5, 5))
+    for n in range(64):
+        for j in range(12):
+            ref_k[j] += oracle.backweights(dr64[n, j][None], xr64[n])
+    d_k64, _ = binding.conv_bwd_weight(xd[:64].contiguous(), dd[:64].contiguous(), bf16=True)
+    assert_close(host(d_k64), ref_k, rtol, "conv_bwd_weight_bf16 on 64 images")
