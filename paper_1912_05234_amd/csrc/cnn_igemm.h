@@ -43,7 +43,7 @@ constexpr int THREADS = 256;  // four waves per workgroup
 constexpr int WAVES = THREADS / 64;
 // Forward and input-gradient kernel: staged data of the next group of images travels through
 // registers while the current group is computed, up to PFV 16-byte items or PFS 4-byte items per
-// thread; what a larger group has beyond that follows in further rounds of the same size after the
+// thread; what a larger group has beyond that follows in further passes of the same size after the
 // group's turn has come, without overlap.  Stage modes (the weight-gradient kernel stages with
 // direct global-to-LDS loads instead):
 constexpr int PFV = 8, PFS = 16;  // the scalar items live in the first PFS / 4 vector registers
@@ -172,7 +172,7 @@ struct ConvArgs {
   int NBK, SP;         // blocks of four K steps; row stride of the two K-indexed tables (floats)
   int flip;            // 0: A[m][(c,u,v)] = w[m][c][u][v];  1: A[m][(c,u,v)] = w[c][m][KH-1-u][KW-1-v]
   int zero_fill;       // the planes have a border that must read as zero
-  int stage, rounds;   // STAGE_*: VECTOR needs SC*SH*SW % 4 == 0 and no border; register loads per group
+  int stage, passes;   // STAGE_*: VECTOR needs SC*SH*SW % 4 == 0 and no border; register loads per group
   float inv_sp, inv_r1, inv_p, inv_khkwp, inv_kwp, inv_ohowp, inv_owp, inv_sw, inv_sh;
 };
 // LDS layout in floats, in this order.
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
       ptgt[i] = e < g.NB * per_image ? target(e) : 0;
     }
   }
-  // Round r of group grp: loads into registers ...
+  // Pass r over group grp: loads into registers ...
   auto issue = [&](int grp, int r) {
     const int b0 = grp * g.NB, count = min(g.NB, g.B - b0) * per_image;
     const float* src = g.src + (size_t)b0 * per_image;
@@ -303,7 +303,7 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
         if (first + THREADS * i < count) pv[i >> 2][i & 3] = src[first + THREADS * i];
     }
   };
-  // ... and from there into LDS (the targets of round 0 are kept in registers).
+  // ... and from there into LDS (the targets of the first pass are kept in registers).
   auto commit = [&](int grp, int r) {
     const int b0 = grp * g.NB, count = min(g.NB, g.B - b0) * per_image;
     if (g.stage == STAGE_VECTOR) {
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(THREADS) void conv_kernel(const ConvArgs g) {
     const int b0 = grp * g.NB, nb = min(g.NB, g.B - b0);
     lds_barrier();  // tables (first pass) / the previous group's reads are complete
     commit(grp, 0);
-    for (int r = 1; r < g.rounds; ++r) {  // what did not fit into the registers: no overlap
+    for (int r = 1; r < g.passes; ++r) {  // what did not fit into the registers: no overlap
       issue(grp, r);
       commit(grp, r);
     }

@@ -380,10 +380,10 @@ ConvPlan plan_conv_layout(const float* src, const float* w, const float* bias, f
   const long long per_image = (long long)SC * SH * SW, per_group = a.NB * per_image;
   if (!a.zero_fill && per_image % 4 == 0) {
     a.stage = igemm::STAGE_VECTOR;
-    a.rounds = (int)((per_group / 4 + igemm::THREADS * igemm::PFV - 1) / (igemm::THREADS * igemm::PFV));
+    a.passes = (int)((per_group / 4 + igemm::THREADS * igemm::PFV - 1) / (igemm::THREADS * igemm::PFV));
   } else {
     a.stage = igemm::STAGE_SCALAR;
-    a.rounds = (int)((per_group + igemm::THREADS * igemm::PFS - 1) / (igemm::THREADS * igemm::PFS));
+    a.passes = (int)((per_group + igemm::THREADS * igemm::PFS - 1) / (igemm::THREADS * igemm::PFS));
   }
   a.inv_sp = 1.0f / (float)a.SP, a.inv_r1 = 1.0f / (float)(a.R + 1), a.inv_p = 1.0f / (float)P;
   a.inv_khkwp = 1.0f / (float)(KH * a.KWP), a.inv_kwp = 1.0f / (float)a.KWP;
