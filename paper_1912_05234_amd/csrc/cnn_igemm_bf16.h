@@ -2,7 +2,8 @@
 // (round to nearest, ties to even), products summed in fp32 on v_mfma_f32_16x16x32_bf16.
 // Tensors in memory stay fp32, NCHW; only the arithmetic changes, which is why these are separate
 // entry points with their own tolerance.  (The paper computes in `float` throughout, Section 3;
-// this is the reduced-precision matrix-core form of its `conv` / `backin`.)
+// this is the reduced-precision matrix-core form of its `conv` / `backin` and, further down, of
+// `backweights` / `backbias`.)
 //
 // The instruction takes, per lane, eight consecutive K elements of A's row (lane % 16) and of B's
 // column (lane % 16), K elements 8 (lane / 16) .. + 7 of a block of 32.  The K index is therefore
