@@ -243,7 +243,9 @@ RTOL_BF16 = 2e-5
 BF16_CASES = [(5, 6, 12, 12, 12, 5, 5), (3, 1, 28, 28, 6, 5, 5), (2, 3, 9, 7, 4, 3, 2), (1, 2, 5, 5, 3, 1, 1),
               (37, 2, 11, 13, 5, 4, 6), (3, 3, 8, 8, 20, 3, 3), (2, 30, 6, 6, 5, 3, 3), (1300, 6, 12, 12, 12, 5, 5),
               (131, 1, 3, 3, 1, 2, 2), (2, 9, 7, 7, 33, 2, 3), (1, 3, 16, 16, 1, 16, 16), (2, 3, 80, 80, 4, 3, 3),
-              (4, 12, 4, 4, 10, 4, 4)]
+              (4, 12, 4, 4, 10, 4, 4),
+              # the fully connected layer as a convolution with one pixel
+              (300, 192, 1, 1, 10, 1, 1)]
 
 
 @pytest.mark.parametrize("case", BF16_CASES)
