@@ -35,6 +35,7 @@ extern "C" {
 #define CNN_EINVAL (-1)     /* null / misaligned pointer, size out of range, odd pooling extent */
 #define CNN_EWORKSPACE (-2) /* workspace too small for max_batch */
 #define CNN_EHIP (-3)       /* a HIP call or kernel launch failed */
+#define CNN_ESCRATCH (-4)   /* the problem needs more than the library's built-in scratch buffer */
 
 #define CNN_NPARAM 3898     /* 150 + 6 + 1800 + 12 + 1920 + 10 */
 
@@ -150,6 +151,21 @@ size_t cnn_conv_bwd_weight_workspace_bytes(int B, int Cin, int H, int W, int Cou
 int cnn_conv_bwd_weight(const float* in, const float* d_out, float* d_k, float* d_bias, int B,
                         int Cin, int H, int W, int Cout, int KH, int KW, void* workspace,
                         size_t workspace_bytes, void* hip_stream);
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): cnn_conv_bwd_weight with the partial sums in
+ * a buffer of CNN_STATIC_SCRATCH_BYTES that is part of the loaded library (one copy per GPU, held
+ * until the process ends) instead of a caller workspace.  Same kernels, same summation order and
+ * therefore bitwise the same d_k / d_bias as cnn_conv_bwd_weight with a sufficient workspace.  The
+ * call allocates and frees nothing.  Returns CNN_ESCRATCH, with nothing enqueued, when the shape
+ * would need more partial sums than the buffer holds (cnn_conv_bwd_weight_workspace_bytes() tells:
+ * the network's layers need 2 MiB (C1) and 10.1 MiB (C2) at any batch size); shapes that only the
+ * slower kernel serves need no scratch and are accepted.  All calls on one GPU share that GPU's
+ * buffer: two calls whose kernels may overlap on one GPU (different streams, different threads)
+ * race, so serialise them.  The buffer's address on a device is looked up at the first call on
+ * that device (no allocation either). */
+#define CNN_STATIC_SCRATCH_BYTES (16u << 20)
+int cnn_conv_bwd_weight_static(const float* in, const float* d_out, float* d_k, float* d_bias, int B,
+                               int Cin, int H, int W, int Cout, int KH, int KW, void* hip_stream);
 /* Reduced-precision form of cnn_conv_bwd_weight, same arguments and workspace rules (its own size
  * query): `in` and `d_out` are rounded to bfloat16 as they are read, products are summed in fp32 on
  * the bf16 matrix cores; d_bias is the fp32 sum of the rounded d_out. */

@@ -42,6 +42,7 @@ SIGNATURES = {
     "cnn_conv_bwd_weight_bf16_workspace_bytes": (_sz, [_i] * 7),
     "cnn_conv_bwd_weight_bf16": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp, _sz, _vp]),
     "cnn_conv_bwd_weight": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp, _sz, _vp]),
+    "cnn_conv_bwd_weight_static": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp]),
     "cnn_avgpool_fwd": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
     "cnn_avgpool_bwd": (_i, [_vp, _vp, _i, _i, _i, _i, _vp]),
     "cnn_fc_fwd": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _vp]),
@@ -247,6 +248,17 @@ def conv_bwd_weight(inp, d_out, want_bias=True, workspace=True, bf16=False):
     name = "cnn_conv_bwd_weight" + suffix
     _check(getattr(lib(), name)(_ptr(inp), _ptr(d_out), _ptr(d_k), _ptr(d_b), B, Cin, H, W, Cout, KH, KW,
                                 _ptr(ws), nbytes, _stream()), name)
+    return d_k, d_b
+
+
+def conv_bwd_weight_static(inp, d_out, d_k, d_b=None):
+    """cnn_conv_bwd_weight_static into the caller's d_k / d_b (this wrapper allocates nothing either)."""
+    inp, d_out, d_k, d_b = _dev(inp), _dev(d_out), _dev(d_k), _dev(d_b)
+    B, Cin, H, W = inp.shape
+    Cout, Ho, Wo = d_out.shape[1:]
+    KH, KW = H - Ho + 1, W - Wo + 1
+    _check(lib().cnn_conv_bwd_weight_static(_ptr(inp), _ptr(d_out), _ptr(d_k), _ptr(d_b), B, Cin, H, W, Cout,
+                                            KH, KW, _stream()), "cnn_conv_bwd_weight_static")
     return d_k, d_b
 
 

@@ -350,6 +350,7 @@ const char* cnn_strerror(int code) {
     case CNN_EINVAL: return "invalid argument (null or misaligned pointer, size out of range)";
     case CNN_EWORKSPACE: return "workspace too small";
     case CNN_EHIP: return "HIP runtime call or kernel launch failed";
+    case CNN_ESCRATCH: return "the problem needs more than the library's built-in scratch buffer";
     default: return "unknown error code";
   }
 }

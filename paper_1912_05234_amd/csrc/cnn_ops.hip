@@ -641,6 +641,67 @@ inline bool conv_args_ok(int B, int Cin, int H, int W, int Cout, int KH, int KW)
          (size_t)Cout * Cin * KH * KW + (size_t)Cout < (size_t)1 << 30;
 }
 
+inline bool wgrad_args_ok(const float* in, const float* d_out, const float* d_k, const float* d_bias, int B, int Cin,
+                          int H, int W, int Cout, int KH, int KW) {
+  return in && d_out && d_k && conv_args_ok(B, Cin, H, W, Cout, KH, KW) && aligned16(in) && aligned16(d_out) &&
+         aligned16(d_k) && (!d_bias || aligned16(d_bias));
+}
+
+// The matrix-core weight gradient: partial tiles per workgroup column into `part`, then the
+// fixed-order sum of the columns.
+int launch_wgrad(WgradPlan& p, const float* in, const float* d_out, float* d_k, float* d_bias, float* part,
+                 hipStream_t st) {
+  p.a.in = in, p.a.d_out = d_out, p.a.part = part;
+  const dim3 grid(p.gx, p.gy);
+  if (p.a.vec_x && p.a.vec_d)
+    igemm::wgrad_kernel<16, 16><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
+  else if (p.a.vec_x)
+    igemm::wgrad_kernel<16, 4><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
+  else if (p.a.vec_d)
+    igemm::wgrad_kernel<4, 16><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
+  else
+    igemm::wgrad_kernel<4, 4><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
+  const igemm::WgradArgs& a = p.a;
+  const size_t outputs = (size_t)a.Cout * a.Cin * a.KH * a.KW + a.Cout;
+  const int epw = outputs >= 2048 ? 16 : outputs >= 512 ? 8 : 4;  // outputs per workgroup of the second kernel
+  igemm::wgrad_reduce_kernel<<<(unsigned)((outputs + epw - 1) / epw), igemm::THREADS, 0, st>>>(
+      a.part, (int)p.gx, a.MT, a.NT, a.Cout, a.Cin, a.KH, a.KW, a.P, epw, d_k, d_bias);
+  return launched();
+}
+
+int launch_wgrad_plain(const float* in, const float* d_out, float* d_k, float* d_bias, int B, int Cin, int H, int W,
+                       int Cout, int KH, int KW, hipStream_t st) {
+  const unsigned blocks = (unsigned)(Cout * Cin * KH * KW + (d_bias ? Cout : 0));
+  conv_bwd_weight_kernel<false><<<blocks, TPB, 0, st>>>(in, d_out, d_k, d_bias, B, Cin, H, W, Cout, KH, KW);
+  return launched();
+}
+
+// ---- built-in scratch for callers that cannot allocate ----------------------------------------------
+// Device memory that belongs to the loaded code object: every GPU the library runs on holds its own
+// copy at its own address until the process ends.  In host code the array's name is only a handle
+// for hipGetSymbolAddress; kernels get the address that call returned for the current device.
+constexpr size_t SCRATCH_FLOATS = CNN_STATIC_SCRATCH_BYTES / sizeof(float);
+static __device__ __align__(256) float scratch[SCRATCH_FLOATS];
+constexpr int SCRATCH_MAX_DEVICES = 64;
+
+// The current device's copy of `scratch`, looked up once per device.
+int scratch_of_current_device(float** out) {
+  static float* ptr[SCRATCH_MAX_DEVICES] = {};
+  static std::mutex guard;
+  int dev = -1;
+  CNN_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= SCRATCH_MAX_DEVICES) return CNN_EINVAL;
+  std::lock_guard<std::mutex> lock(guard);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    CNN_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return CNN_EHIP;
+    ptr[dev] = static_cast<float*>(p);
+  }
+  *out = ptr[dev];
+  return CNN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -703,33 +764,27 @@ size_t cnn_conv_bwd_weight_workspace_bytes(int B, int Cin, int H, int W, int Cou
 int cnn_conv_bwd_weight(const float* in, const float* d_out, float* d_k, float* d_bias, int B, int Cin,
                         int H, int W, int Cout, int KH, int KW, void* workspace, size_t workspace_bytes,
                         void* hip_stream) {
-  if (!in || !d_out || !d_k || !conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;
-  if (!aligned16(in) || !aligned16(d_out) || !aligned16(d_k) || (d_bias && !aligned16(d_bias)))
-    return CNN_EINVAL;
+  if (!wgrad_args_ok(in, d_out, d_k, d_bias, B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;
   if (workspace && !aligned16(workspace)) return CNN_EINVAL;
   WgradPlan p = plan_wgrad(B, Cin, H, W, Cout, KH, KW);
-  if (p.fits && workspace && workspace_bytes >= p.workspace_bytes) {
-    p.a.in = in, p.a.d_out = d_out, p.a.part = static_cast<float*>(workspace);
-    const dim3 grid(p.gx, p.gy);
-    hipStream_t st = (hipStream_t)hip_stream;
-    if (p.a.vec_x && p.a.vec_d)
-      igemm::wgrad_kernel<16, 16><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
-    else if (p.a.vec_x)
-      igemm::wgrad_kernel<16, 4><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
-    else if (p.a.vec_d)
-      igemm::wgrad_kernel<4, 16><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
-    else
-      igemm::wgrad_kernel<4, 4><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
-    const size_t outputs = (size_t)Cout * Cin * KH * KW + Cout;
-    const int epw = outputs >= 2048 ? 16 : outputs >= 512 ? 8 : 4;  // outputs per workgroup of the second kernel
-    igemm::wgrad_reduce_kernel<<<(unsigned)((outputs + epw - 1) / epw), igemm::THREADS, 0, st>>>(
-        p.a.part, (int)p.gx, p.a.MT, p.a.NT, Cout, Cin, KH, KW, p.a.P, epw, d_k, d_bias);
-    return launched();
-  }
-  const unsigned blocks = (unsigned)(Cout * Cin * KH * KW + (d_bias ? Cout : 0));
-  conv_bwd_weight_kernel<false><<<blocks, TPB, 0, (hipStream_t)hip_stream>>>(in, d_out, d_k, d_bias, B, Cin,
-                                                                             H, W, Cout, KH, KW);
-  return launched();
+  if (p.fits && workspace && workspace_bytes >= p.workspace_bytes)
+    return launch_wgrad(p, in, d_out, d_k, d_bias, static_cast<float*>(workspace), (hipStream_t)hip_stream);
+  return launch_wgrad_plain(in, d_out, d_k, d_bias, B, Cin, H, W, Cout, KH, KW, (hipStream_t)hip_stream);
+}
+
+int cnn_conv_bwd_weight_static(const float* in, const float* d_out, float* d_k, float* d_bias, int B, int Cin,
+                               int H, int W, int Cout, int KH, int KW, void* hip_stream) {
+  if (!wgrad_args_ok(in, d_out, d_k, d_bias, B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;
+  WgradPlan p = plan_wgrad(B, Cin, H, W, Cout, KH, KW);
+  if (!p.fits)  // only the kernel without partial sums serves this shape: it needs no scratch at all
+    return launch_wgrad_plain(in, d_out, d_k, d_bias, B, Cin, H, W, Cout, KH, KW, (hipStream_t)hip_stream);
+  if (p.workspace_bytes > sizeof(float) * SCRATCH_FLOATS) return CNN_ESCRATCH;
+  float* part = nullptr;
+  const int rc = scratch_of_current_device(&part);
+  if (rc != CNN_OK) return rc;
+  // every partial tile and bias row the second kernel reads is written by the first one in the same
+  // call, so nothing of the previous call's contents has to be cleared
+  return launch_wgrad(p, in, d_out, d_k, d_bias, part, (hipStream_t)hip_stream);
 }
 
 size_t cnn_conv_bwd_weight_bf16_workspace_bytes(int B, int Cin, int H, int W, int Cout, int KH, int KW) {

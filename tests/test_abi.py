@@ -32,7 +32,7 @@ def test_library_exports_every_declared_symbol():
 def test_error_strings_and_workspace_size():
     L = binding.lib()
     assert L.cnn_strerror(0) == b"ok"
-    for code in (-1, -2, -3, -99):
+    for code in (-1, -2, -3, -4, -99):
         assert len(L.cnn_strerror(code)) > 0
     assert L.cnn_workspace_bytes(0) == 0 and L.cnn_workspace_bytes(-5) == 0
     small, big = L.cnn_workspace_bytes(1), L.cnn_workspace_bytes(60000)
@@ -72,6 +72,11 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.cnn_conv_bwd_weight(fake, fake, nul, nul, 1, 1, 8, 8, 1, 3, 3, nul, 0, nul) == EINVAL
     assert L.cnn_conv_bwd_weight(fake, fake, fake, nul, 1, 1, 8, 8, 1, 3, 3, odd, 1 << 20, nul) == EINVAL  # workspace alignment
     assert L.cnn_conv_bwd_weight_workspace_bytes(1, 1, 8, 8, 1, 9, 3) == 0               # kernel larger than input
+    assert L.cnn_conv_bwd_weight_static(fake, fake, nul, nul, 1, 1, 8, 8, 1, 3, 3, nul) == EINVAL
+    assert L.cnn_conv_bwd_weight_static(fake, odd, fake, nul, 1, 1, 8, 8, 1, 3, 3, nul) == EINVAL
+    # more partial sums than the built-in buffer holds: refused before anything touches the device
+    assert L.cnn_conv_bwd_weight_workspace_bytes(8192, 8, 12, 12, 32, 5, 5) > 16 << 20
+    assert L.cnn_conv_bwd_weight_static(fake, fake, fake, nul, 8192, 8, 12, 12, 32, 5, 5, nul) == -4
     assert L.cnn_conv_bwd_weight_bf16(fake, fake, nul, nul, 1, 1, 8, 8, 1, 3, 3, nul, 0, nul) == EINVAL
     assert L.cnn_conv_bwd_weight_bf16(fake, fake, fake, nul, 1, 1, 8, 8, 1, 3, 3, odd, 1 << 20, nul) == EINVAL
     assert L.cnn_conv_bwd_weight_bf16_workspace_bytes(1, 1, 8, 8, 1, 9, 3) == 0
