@@ -21,7 +21,8 @@ namespace {
 
 using namespace cnn;
 
-constexpr int GCAP = 1024;      // most training waves (= gradient partials) per step: one per SIMD of 256 CUs
+constexpr int GCAP = 1024;      // waves of a full machine at one per SIMD (256 compute units)
+constexpr int TRAIN_BLOCKS = 256;  // most workgroups (= gradient partials) of the large-batch training kernel: one per compute unit
 constexpr int FWD_GCAP = 3072;  // most forward-only waves: three per SIMD
 // Batches up to this size give each image to a workgroup of eight waves (lower latency per image;
 // up to two such workgroups share a compute unit); larger ones give each image to a single wave
@@ -44,7 +45,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void forward_kernel(const float* __r
   WaveState<MODE> st;
   const size_t gw = (size_t)blockIdx.x * WAVES + wave, G = (size_t)gridDim.x * WAVES;
   Pixels px = load_pixels(images + (gw < (size_t)B ? gw : 0) * NI);  // in flight during the set-up
-  load_tables<MODE>(tab, tabg);
+  load_tables<TAB_FWD_ENTRIES, 64 * WAVES>(tab, tabg);
   wave_init(st, s);
   __syncthreads();  // the only workgroup-wide barrier: the operand table is complete
   st.bias2 = tab.bias[l & 15];
@@ -99,42 +100,57 @@ __global__ __launch_bounds__(64) void eval_reduce_kernel(const float* __restrict
   }
 }
 
-// Forward + backward over each wave's images.  The four waves of a workgroup then add their
-// gradient sums through LDS in a fixed order and the workgroup writes ONE partial row,
-// partial[blockIdx.x][PSTRIDE], with 16-byte stores (a wave without images contributes zeros).
-__global__ __launch_bounds__(64 * WAVES) void train_kernel(const float* __restrict__ images,
-                                                          const int32_t* __restrict__ labels, int B,
-                                                          const float* __restrict__ tabg,
-                                                          float* __restrict__ partial) {
-  __shared__ OperandTable<TAB_TRAIN_ENTRIES> tab;
-  __shared__ TrainLds lds[WAVES];
-  const int wave = threadIdx.x >> 6;
-  TrainLds& s = lds[wave];
+// Forward + backward over each wave's images: eight waves per workgroup, one workgroup per compute
+// unit, i.e. two waves per SIMD.  (One wave alone issues a vector instruction every 2.4 ns, two
+// together one every 1.4 ns, and the matrix instructions of one run under the LDS waits of the
+// other; the price is 256 registers and 15.25 KB of LDS per wave.)  Wave w of workgroup b walks
+// the images w * gridDim.x + b, + 8 * gridDim.x, ...: a batch that does not fill the machine leaves
+// the waves 4..7 of every workgroup idle rather than some compute units empty.  The eight waves
+// then add their gradient sums through LDS in a fixed order and the workgroup writes ONE partial
+// row, partial[blockIdx.x][PSTRIDE], with 16-byte stores (a wave without images contributes zeros).
+constexpr int TWAVES = 8;
+constexpr int FC_ACC_FLOATS = 30 * 64;  // per wave: the FC weight-gradient sums, [3 o + k][lane]
+__global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 2))) void train_kernel(
+    const float* __restrict__ images, const int32_t* __restrict__ labels, int B, const float* __restrict__ tabg,
+    float* __restrict__ partial, float* __restrict__ fc_acc) {
+  __shared__ OperandTable<TAB_WAVE_ENTRIES> tab;
+  __shared__ WaveTrainLds lds[TWAVES];
+  __shared__ WindowTable wt;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // in a scalar register: addresses built on it are wave-uniform
+  WaveTrainLds& s = lds[wave];
   WaveState<kTrain> st;
   CNN_KERNEL_MARK(0);
-  const size_t gw = (size_t)blockIdx.x * WAVES + wave, G = (size_t)gridDim.x * WAVES;
+  const size_t gw = (size_t)wave * gridDim.x + blockIdx.x, G = (size_t)gridDim.x * TWAVES;
   Pixels px = load_pixels(images + (gw < (size_t)B ? gw : 0) * NI);  // in flight during the set-up
-  load_tables<kTrain>(tab, tabg);
+  load_tables<TAB_WAVE_ENTRIES, 64 * TWAVES>(tab, tabg);
+  window_table_init(wt);
   wave_init(st, s);
-  __syncthreads();  // the only workgroup-wide barrier: the operand table is complete
+  // this wave's FC weight-gradient sums start at zero (global memory, see WaveState)
+  st.fc_acc = __builtin_amdgcn_make_buffer_rsrc(fc_acc + ((size_t)blockIdx.x * TWAVES + wave) * FC_ACC_FLOATS, 0,
+                                                sizeof(float) * FC_ACC_FLOATS, 0x00020000);
+#pragma unroll
+  for (int j = 0; j < 30; ++j) fc_acc_store(st.fc_acc, j, 0.0f, threadIdx.x & 63);
+  if (gw < (size_t)B) store_pixels(s.img, px);
+  __syncthreads();  // the operand and window tables are complete
   st.bias2 = tab.bias[threadIdx.x & 15];
   const DumpPtrs none = {nullptr, nullptr, nullptr, nullptr};
   CNN_KERNEL_MARK(1);
   for (size_t n = gw; n < (size_t)B; n += G) {
     float y[10];
     const size_t nn = n + G;
-    wave_image<kTrain>(st, s, tab, px, nn < (size_t)B ? images + nn * NI : nullptr, labels[n], y, none, n);
+    wave_image<kTrain>(st, s, tab, px, images + (nn < (size_t)B ? nn : n) * NI, labels[n], y, none, n, &wt);
   }
   CNN_KERNEL_MARK(2);
-  wave_flush(st, reinterpret_cast<float*>(&s), s.pool + FLUSH_PARK);
+  __syncthreads();  // every wave is done with the operand table: its storage parks the C1 GEMM results
+  wave_flush(st, reinterpret_cast<float*>(&s), tab.e + wave * C1G_PARK);
   __syncthreads();
   {
-    const f4* r0 = reinterpret_cast<const f4*>(&lds[0]);
-    const f4* r1 = reinterpret_cast<const f4*>(&lds[1]);
-    const f4* r2 = reinterpret_cast<const f4*>(&lds[2]);
-    const f4* r3 = reinterpret_cast<const f4*>(&lds[3]);
+    const f4* r = reinterpret_cast<const f4*>(&lds[0]);
+    constexpr int RF4 = PSTRIDE / 4;  // a wave's area is exactly one row
     f4* dst = reinterpret_cast<f4*>(partial + (size_t)blockIdx.x * PSTRIDE);
-    for (int i = threadIdx.x; i < PSTRIDE / 4; i += 64 * WAVES) dst[i] = (r0[i] + r1[i]) + (r2[i] + r3[i]);
+    for (int i = threadIdx.x; i < RF4; i += 64 * TWAVES)
+      dst[i] = ((r[i] + r[i + RF4]) + (r[i + 2 * RF4] + r[i + 3 * RF4])) +
+               ((r[i + 4 * RF4] + r[i + 5 * RF4]) + (r[i + 6 * RF4] + r[i + 7 * RF4]));
   }
   CNN_KERNEL_MARK(3);
   CNN_PHASE_FLUSH;
@@ -237,6 +253,7 @@ struct cnn_ctx {
   int32_t* dest;        // [PSTRIDE][TABLE_MAX_DEST]: slots of tabg that hold parameter p
   float* partial;       // [partial_rows_for(max_batch)][PSTRIDE]
   float* eval_partial;  // [gcap][2]
+  float* fc_acc;        // [TRAIN_BLOCKS * TWAVES][FC_ACC_FLOATS] when max_batch > GROUP_MAX_BATCH
   std::vector<hipEvent_t> ev;  // 2 per recorded step (before, after the fused kernel)
   int ev_used = 0;             // recorded steps
 };
@@ -252,13 +269,13 @@ inline int gcap_for(int max_batch, int cap = GCAP) {
 }
 
 struct Layout {
-  size_t w, tabg, dest, partial, eval_partial, total;
+  size_t w, tabg, dest, partial, eval_partial, fc_acc, total;
 };
 
 // Partial rows a step can write: one per workgroup, in the one-wave-per-image kernel (four waves
 // per workgroup) or in the small-batch kernel (one workgroup per image).
 inline int partial_rows_for(int max_batch) {
-  const int by_wave = gcap_for(max_batch) / WAVES;
+  const int by_wave = max_batch < TRAIN_BLOCKS ? max_batch : TRAIN_BLOCKS;
   const int by_group = max_batch < GROUP_MAX_BATCH ? max_batch : GROUP_MAX_BATCH;
   return by_wave > by_group ? by_wave : by_group;
 }
@@ -271,7 +288,10 @@ inline Layout layout_for(int max_batch) {
   l.dest = align_up(l.tabg + sizeof(float) * TABG_FLOATS, 256);
   l.partial = align_up(l.dest + sizeof(int32_t) * TABLE_MAX_DEST * PSTRIDE, 256);
   l.eval_partial = align_up(l.partial + sizeof(float) * PSTRIDE * g, 256);
-  l.total = align_up(l.eval_partial + sizeof(float) * 2 * (size_t)gcap_for(max_batch, FWD_GCAP), 256);
+  l.fc_acc = align_up(l.eval_partial + sizeof(float) * 2 * (size_t)gcap_for(max_batch, FWD_GCAP), 256);
+  // only the large-batch kernel keeps sums in global memory; it never launches more workgroups than images
+  const size_t train_waves = max_batch > GROUP_MAX_BATCH ? (size_t)TWAVES * (max_batch < TRAIN_BLOCKS ? max_batch : TRAIN_BLOCKS) : 0;
+  l.total = align_up(l.fc_acc + sizeof(float) * FC_ACC_FLOATS * train_waves, 256);
   return l;
 }
 
@@ -321,14 +341,15 @@ int run_forward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B,
 int run_backward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B, float scale,
                  float* grad_out, float* loss_sum) {
   const bool grouped = B <= GROUP_MAX_BATCH;
-  const int blocks = grouped ? B : blocks_for(ctx, B, false);  // small batches: one workgroup per image
+  // small batches: one workgroup per image; large ones: one workgroup of eight waves per compute unit
+  const int blocks = grouped ? B : (B < TRAIN_BLOCKS ? B : TRAIN_BLOCKS);
   const int G = blocks;  // one partial row per workgroup in both kernels
   const bool timed = (size_t)(2 * ctx->ev_used + 1) < ctx->ev.size();
   if (timed) CNN_HIP_TRY(hipEventRecord(ctx->ev[2 * ctx->ev_used], ctx->stream));
   if (grouped)
     train_group_kernel<<<blocks, 64 * GWAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, ctx->partial);
   else
-    train_kernel<<<blocks, 64 * WAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, ctx->partial);
+    train_kernel<<<blocks, 64 * TWAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, ctx->partial, ctx->fc_acc);
   if (hipGetLastError() != hipSuccess) return CNN_EHIP;
   if (timed) {
     CNN_HIP_TRY(hipEventRecord(ctx->ev[2 * ctx->ev_used + 1], ctx->stream));
@@ -399,6 +420,7 @@ int cnn_init(cnn_ctx** out, void* workspace, size_t workspace_bytes, int max_bat
   ctx->dest = reinterpret_cast<int32_t*>(base + l.dest);
   ctx->partial = reinterpret_cast<float*>(base + l.partial);
   ctx->eval_partial = reinterpret_cast<float*>(base + l.eval_partial);
+  ctx->fc_acc = reinterpret_cast<float*>(base + l.fc_acc);
   {
     // inverse of table_source: where each parameter sits in the expanded table
     static_assert(TABLE_MAX_DEST == 4 && table_max_multiplicity() <= TABLE_MAX_DEST,

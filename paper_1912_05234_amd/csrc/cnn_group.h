@@ -120,7 +120,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
 
   f4 px = reinterpret_cast<const f4*>(images + (size_t)(blockIdx.x < (unsigned)B ? blockIdx.x : 0) * NI)[pix];
   const int label = labels[blockIdx.x < (unsigned)B ? blockIdx.x : 0];  // in flight during the set-up too
-  TableLoad<kTrain, 64 * GWAVES> table;
+  TableLoad<TAB_TRAIN_ENTRIES, 64 * GWAVES> table;
   table.fetch(tabg);
   // every LDS cell that padded GEMM steps may read starts finite, and both col2im targets start at
   // zero (the image area is written below, before the first barrier, so it is left alone here)

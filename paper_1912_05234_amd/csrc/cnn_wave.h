@@ -58,10 +58,10 @@ struct __align__(16) FwdLds {
   float img[NI];
   float pool[NS1 + 288 + NS2];  // s1 at P_S1, s2 at P_S2
 };
-// Per-wave LDS of the training step.  d_s1 comes first: the col2im rows of the two padding maps
-// (c = 6, 7) add 0.0 at offsets up to 1152 floats past its start, which stays inside the struct.
-// `pool` holds, at the P_* offsets, the arrays that are dead by the time the C1 weight gradient
-// runs; that phase reuses the whole pool for the staged C1 error.
+// LDS of the small-batch training step (cnn_group.h; one image per workgroup).  d_s1 comes first:
+// the col2im rows of the two padding maps (c = 6, 7) add 0.0 at offsets up to 1152 floats past its
+// start, which stays inside the struct.  `pool` holds, at the P_* offsets, the arrays that are dead
+// by the time the C1 weight gradient runs; that phase reuses the whole pool for the staged C1 error.
 constexpr int P_S1 = 0;                 // s1[6][12][12] + 288 (padded K steps of the C2 forward read them)
 constexpr int P_S2 = P_S1 + NS1 + 288;  // s2[192]
 constexpr int P_DS2 = P_S2 + NS2;       // d_s2[192] + 64 (rows of the padding maps of the C2 tiles)
@@ -78,12 +78,35 @@ struct __align__(16) TrainLds {
   float img[NI];
   float pool[POOL_FLOATS];
 };
+// Per-wave LDS of the large-batch training step (one wave per image, two waves per SIMD): the same
+// arrays packed into exactly one partial row's worth of floats (15.25 KB), so that eight waves and
+// the operand table share a compute unit's 160 KB.  The padded K steps of the C2 forward read up
+// to 1152 floats past the start of s1: s2, d_s2 and d2, all finite.  d2 has no rows for the
+// padding maps.  The C1 error is staged in three chunks of eight image rows, d1c[6][8][24] with
+// the maps D1C_MAP apart (a stride of 192 would be a multiple of the 32 banks), over s1 .. d_s2,
+// which are dead by then.  The col2im rows of the padding maps add 0.0 to d_s1 offsets up to
+// 1152 + 144 + 100, i.e. inside img or the pool's first cells: re-written with their own values.
+constexpr int W_S1 = 0;                  // s1[6][12][12]
+constexpr int W_S2 = W_S1 + NS1;         // s2[192]
+constexpr int W_DS2 = W_S2 + NS2;        // d_s2[192] + 64
+constexpr int W_D2 = W_DS2 + NS2 + 64;   // d2[12][D2S]
+constexpr int W_END = W_D2 + 12 * D2S;
+constexpr int D1C_MAP = 8 * 24 + 4;
+constexpr int WPOOL_FLOATS = PSTRIDE - NS1 - NI;
+static_assert(WPOOL_FLOATS >= W_END && 6 * D1C_MAP <= W_D2, "pool holds the arrays; a d1 chunk ends before d2");
+struct __align__(16) WaveTrainLds {
+  float d_s1[NS1];
+  float img[NI];
+  float pool[WPOOL_FLOATS];
+};
+static_assert(sizeof(WaveTrainLds) == sizeof(float) * PSTRIDE, "a wave's LDS area holds one partial row");
 // Shared operand table, [entry][lane].
 constexpr int TAB_BF = 0;          // 38: C2 forward B operand, k2[j = n16][tap(s, q)]
 constexpr int TAB_FCW = 38;        // 30: fc[o][lane + 64 k] at entry 3 o + k
 constexpr int TAB_FWD_ENTRIES = 68;
 constexpr int TAB_AB = 68;         // 42: C2 input-error A operand, entry (cg*7 + tile)*3 + s
 constexpr int TAB_C1A = 110;       // 8: C1 forward A operand of the small-batch kernel, W[(m,sh) = n16][tap 4 ks + q]
+constexpr int TAB_WAVE_ENTRIES = TAB_C1A;  // what the one-wave-per-image training kernel reads
 constexpr int TAB_TRAIN_ENTRIES = 118;
 // After the [entry][lane] part: C1 weights by tap, k1t[tap][8] = k1[0..5][tap], 0, 0 for tap < 25 and
 // the biases b1 in row 25; every lane reads the same row (an LDS broadcast).
@@ -109,13 +132,14 @@ template <int MODE>
 struct LdsOf {
   typedef FwdLds type;
   static constexpr int entries = TAB_FWD_ENTRIES;
+  static constexpr int S1 = P_S1, S2 = P_S2;
 };
 template <>
 struct LdsOf<kTrain> {
-  typedef TrainLds type;
-  static constexpr int entries = TAB_TRAIN_ENTRIES;
+  typedef WaveTrainLds type;
+  static constexpr int entries = TAB_WAVE_ENTRIES;
+  static constexpr int S1 = W_S1, S2 = W_S2;
 };
-
 __device__ __forceinline__ float quad_xor1(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
 }
@@ -310,13 +334,14 @@ constexpr int table_max_multiplicity() {
 // kernel can do other set-up work while the loads are in flight: `fetch` issues all of a thread's
 // 16-byte loads, `commit` stores them to LDS.  All THREADS threads of the workgroup take part and
 // the caller follows the commit with a workgroup barrier.
-template <int MODE, int THREADS = 64 * WAVES>
+template <int ENTRIES, int THREADS>
 struct TableLoad {
-  static constexpr int PIECES = LdsOf<MODE>::entries * 16, ROUNDS = (PIECES + THREADS - 1) / THREADS;
+  static constexpr int PIECES = ENTRIES * 16, ROUNDS = (PIECES + THREADS - 1) / THREADS;
   static constexpr int TAIL = (K1T_FLOATS + TAB_BIAS_FLOATS) / 4;
-  typedef OperandTable<LdsOf<MODE>::entries> Table;
+  typedef OperandTable<ENTRIES> Table;
   static_assert(offsetof(Table, bias) == offsetof(Table, k1t) + sizeof(float) * K1T_FLOATS,
                 "k1t and bias are copied as one run");
+  static_assert(TAIL <= THREADS, "one thread per piece of the tail");
   f4 v[ROUNDS], tail;
   __device__ __forceinline__ void fetch(const float* __restrict__ tabg) {
     const int t = threadIdx.x;
@@ -338,10 +363,9 @@ struct TableLoad {
     if (t < TAIL) reinterpret_cast<f4*>(tab.k1t)[t] = tail;
   }
 };
-template <int MODE>
-__device__ __forceinline__ void load_tables(OperandTable<LdsOf<MODE>::entries>& tab,
-                                            const float* __restrict__ tabg) {
-  TableLoad<MODE> ld;
+template <int ENTRIES, int THREADS>
+__device__ __forceinline__ void load_tables(OperandTable<ENTRIES>& tab, const float* __restrict__ tabg) {
+  TableLoad<ENTRIES, THREADS> ld;
   ld.fetch(tabg);
   ld.commit(tab);
 }
@@ -361,10 +385,11 @@ constexpr int C1G_STEPS = 72;
 constexpr int C1G_PARK = 16 * 32;  // floats: T as [row i][column c]
 __host__ __device__ constexpr int c1g_imm_a(int kk) { return 24 * (kk / 3) + 8 * (kk % 3); }
 __host__ __device__ constexpr int c1g_imm_b(int kk) { return 28 * (kk / 3) + 8 * (kk % 3); }
-// Lane parts of the operand addresses (floats): d1 and the two image tiles.
-__device__ __forceinline__ void c1g_lane_offsets(int& a, int (&bt)[2]) {
-  const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
-  a = ((n16 >> 1) % 6) * D1_MAP + (n16 & 1) + 2 * q;
+// Lane parts of the operand addresses (floats): d1 (maps MAP floats apart) and the two image tiles.
+template <int MAP = D1_MAP>
+__device__ __forceinline__ void c1g_lane_offsets(int& a, int (&bt)[2], int l) {
+  const int q = l >> 4, n16 = l & 15;
+  a = ((n16 >> 1) % 6) * MAP + (n16 & 1) + 2 * q;
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const int c = 16 * nt + n16;
@@ -373,10 +398,10 @@ __device__ __forceinline__ void c1g_lane_offsets(int& a, int (&bt)[2]) {
 }
 // STEPS steps of the GEMM from the given origins of d1 and the image: operands of step kk + 2 are
 // read while the two MFMAs of step kk issue.
-template <int STEPS>
-__device__ __forceinline__ void c1g_accumulate(f4 (&acc)[2], const float* d1, const float* img) {
+template <int STEPS, int MAP = D1_MAP>
+__device__ __forceinline__ void c1g_accumulate(f4 (&acc)[2], const float* d1, const float* img, int lane) {
   int a, bt[2];
-  c1g_lane_offsets(a, bt);
+  c1g_lane_offsets<MAP>(a, bt, lane);
   const float* pa = d1 + a;
   const float* pb0 = img + bt[0];
   const float* pb1 = img + bt[1];
@@ -405,7 +430,7 @@ template <int NT>
 __device__ __forceinline__ void c1g_accumulate_tiles(f4 (&acc)[2], const float* const (&d1t)[3],
                                                      const float* const (&imgt)[3]) {
   int a, bt[2];
-  c1g_lane_offsets(a, bt);
+  c1g_lane_offsets(a, bt, threadIdx.x & 63);
   float oa[3], ob0[3], ob1[3];
   auto load_step = [&](int st, int slot) {
     const int k = st >> 2, row = st & 3;
@@ -438,17 +463,40 @@ __device__ __forceinline__ float c1g_combine(const float* park, int e) {
   return park[(2 * m) * 32 + 6 * u + v] + park[(2 * m + 1) * 32 + 6 * u + v + 1];
 }
 
+// Offsets of the origin of pooling window win = 12 wy + wx, shared by the waves of a training
+// workgroup and read per image (registers are what the training kernel is short of): .x inside the
+// 28 x 28 image, .y inside a 24 x 24 map.
+constexpr int NWIN = 144;
+struct WindowTable {
+  int2 o[NWIN];
+};
+__device__ __forceinline__ void window_table_init(WindowTable& w) {
+  for (int win = threadIdx.x; win < NWIN; win += blockDim.x)
+    w.o[win] = int2{56 * (win / 12) + 2 * (win % 12), 48 * (win / 12) + 2 * (win % 12)};
+}
+
+// Entry j (of 30) of a wave's FC sums in global memory: 256 bytes per entry, addressed as a scalar
+// base (the descriptor), a scalar 4 KB step and a 12-bit immediate, so that no vector register holds
+// an address.
+__device__ __forceinline__ float fc_acc_load(__amdgpu_buffer_rsrc_t r, int j, int l) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, 4 * l + 256 * (j & 15), 4096 * (j >> 4), 0));
+}
+__device__ __forceinline__ void fc_acc_store(__amdgpu_buffer_rsrc_t r, int j, float v, int l) {
+  __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, 4 * l + 256 * (j & 15), 4096 * (j >> 4), 0);
+}
+
 // Everything a wave keeps in registers across its images.
 template <int MODE>
 struct WaveState {
-  int pix0[9];    // LDS offset of the origin of this lane's pooling window in pixel group g
+  int pix0[9];    // forward only: LDS offset of the origin of this lane's pooling window in pixel group g
   float bias2;    // b2[n16]
   // training only
   f4 acc_k2[10];  // sum over images of d_c2 (x) s1 patches, D[j = 4q+r][tap = 16 nt + n16]
   f4 acc_k1[2];   // C1 weight gradient GEMM result T[(m,sh) = 4q+r][c = 16 nt + n16]
-  int d1off[9];   // offset of this lane's pixel of group g inside a 24x24 map
-  f4 acc_fc[3][3];  // FC weight gradient, D_r(lane) = g_fc[o = 4 mt + r][i = lane + 64 k]
-  float g_bq[3];    // FC bias gradient: lane l holds b[4 mt + l % 4] (the same in every quad)
+  __amdgpu_buffer_rsrc_t fc_acc;  // FC weight gradient sums of this wave in global memory, [30][64]:
+                                  // entry 3 o + k, lane l is g_fc[o][l + 64 k] (read, updated and written
+                                  // back once per image); a buffer descriptor in scalar registers
+  float g_b;      // FC bias gradient: lane o < 10 holds b[o]
   float g_b1[6], g_b2, loss;
 };
 
@@ -462,8 +510,7 @@ __device__ __forceinline__ void wave_init(WaveState<MODE>& st, typename LdsOf<MO
 #pragma unroll
   for (int g = 0; g < 9; ++g) {
     const int win = 16 * g + b;
-    st.pix0[g] = 2 * (win / 12) * 28 + 2 * (win % 12);
-    if (MODE == kTrain) st.d1off[g] = (2 * (win / 12) + ((l >> 1) & 1)) * 24 + 2 * (win % 12) + (l & 1);
+    st.pix0[g] = 2 * (win / 12) * 28 + 2 * (win % 12);  // unused when training (see WindowTable)
   }
   st.bias2 = 0.0f;  // read from the operand table once it is complete
   if (MODE == kTrain) {
@@ -474,12 +521,8 @@ __device__ __forceinline__ void wave_init(WaveState<MODE>& st, typename LdsOf<MO
     for (int i = 0; i < 6; ++i) st.g_b1[i] = 0.0f;
     st.g_b2 = 0.0f;
     st.loss = 0.0f;
-#pragma unroll
-    for (int mt = 0; mt < 3; ++mt) {
-      st.g_bq[mt] = 0.0f;
-#pragma unroll
-      for (int k = 0; k < 3; ++k) st.acc_fc[mt][k] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-    }
+    st.g_b = 0.0f;
+    // st.fc_acc is set by the kernel
   }
 }
 
@@ -504,44 +547,79 @@ __device__ __forceinline__ Pixels load_pixels(const float* __restrict__ image) {
   return px;
 }
 
-// One image through forward (and, when MODE == kTrain, backward).  `px` holds this image's pixels on
-// entry; if `next_image` is not null its pixels are loaded into `px` while this image is still being
-// worked on, so the HBM latency of the only per-image global read is hidden.  Returns yhat in y[10]
+// The lane index as a phase of the training step sees it: through a register the compiler cannot
+// see through, so that the address arithmetic built on it is redone in every phase of every image
+// instead of being computed once per kernel and held in (scarce) registers for its whole life.
+// The forward-only kernels have registers to spare and keep the hoisting.
+template <int MODE>
+__device__ __forceinline__ int phase_lane() {
+  int l = threadIdx.x & 63;
+  if (MODE == kTrain) asm volatile("" : "+v"(l));
+  return l;
+}
+#define CNN_PHASE_LANES                                              \
+  const int l = phase_lane<MODE>();                                  \
+  const int q = l >> 4, n16 = l & 15, b = l >> 2, sub = l & 3;       \
+  const int pp = 12 * ((n16 & 3) >> 1) + 2 * (n16 >> 2) + (n16 & 1); \
+  const float* tl = tab.e + l;                                       \
+  (void)q, (void)n16, (void)b, (void)sub, (void)pp, (void)tl
+
+__device__ __forceinline__ void store_pixels(float* img, const Pixels& px) {
+  const int l = threadIdx.x & 63;
+  f4* dst = reinterpret_cast<f4*>(img);
+  dst[l] = px.a;
+  dst[l + 64] = px.b;
+  dst[l + 128] = px.c;
+  if (l < 4) dst[l + 192] = px.d;
+}
+// Touches the 25 cache lines of an image so that they are on their way into the L2 cache; the value
+// is not used (the asm keeps the load alive and costs no instruction).
+__device__ __forceinline__ void touch_pixels(const float* __restrict__ image) {
+  const int l = threadIdx.x & 63;
+  float v = image[l < 25 ? 32 * l : 0];
+  asm volatile("" ::"v"(v));
+}
+
+// One image through forward (and, when MODE == kTrain, backward).  Forward only: `px` holds this
+// image's pixels on entry; if `next_image` is not null its pixels are loaded into `px` while this
+// image is still being worked on, so the HBM latency of the only per-image global read is hidden.
+// Training: the image is in s.img on entry and `next_image` (never null: the caller passes any
+// valid image when there is no next one) is in s.img on return; `px` is not used.  Returns yhat in y[10]
 // (wave-uniform).  `label` is only read when training.
 template <int MODE>
 __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<MODE>::type& s,
                                            const OperandTable<LdsOf<MODE>::entries>& tab, Pixels& px,
                                            const float* __restrict__ next_image, int label,
                                            float (&y)[10], const DumpPtrs& dump,
-                                           size_t n) {
+                                           size_t n, const WindowTable* wt = nullptr) {
+  constexpr int P_S1 = LdsOf<MODE>::S1, P_S2 = LdsOf<MODE>::S2;
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15, b = l >> 2, sub = l & 3;
   const int pp = 12 * ((n16 & 3) >> 1) + 2 * (n16 >> 2) + (n16 & 1);
   const float* tl = tab.e + l;  // this lane's column of the operand table
 
   CNN_PHASE_DECL;
   CNN_PHASE(0);
-  {
-    f4* dst = reinterpret_cast<f4*>(s.img);
-    dst[l] = px.a;
-    dst[l + 64] = px.b;
-    dst[l + 128] = px.c;
-    if (l < 4) dst[l + 192] = px.d;
+  if (MODE != kTrain) {
+    store_pixels(s.img, px);
+    wave_sync();
+    if (next_image) px = load_pixels(next_image);
   }
-  wave_sync();
-  if (MODE != kTrain && next_image) px = load_pixels(next_image);
+  // (training: the image is in LDS already, stored by the kernel or at the end of the previous image)
 
   CNN_PHASE(1);
   // ---- C1 = sigmoid(mconv(I, k1, b1)), S1 = avgpool(C1).  Tap-outer: the six weights of a tap are
   //      wave-uniform scalars, every lane holds its nine pixels' accumulators for all six maps. ----
   float c1[9][6];
   {
+    CNN_PHASE_LANES;
     const float* ip[9];
     {
       const f4 ba = *reinterpret_cast<const f4*>(&tab.k1t[25 * 8]);
       const float2 bb = *reinterpret_cast<const float2*>(&tab.k1t[25 * 8 + 4]);
+      // training: the window origins come from the shared table, re-read per image
 #pragma unroll
       for (int g = 0; g < 9; ++g) {
-        ip[g] = s.img + st.pix0[g] + (sub >> 1) * 28 + (sub & 1);
+        ip[g] = s.img + (MODE == kTrain ? wt->o[16 * g + b].x : st.pix0[g]) + (sub >> 1) * 28 + (sub & 1);
         c1[g][0] = ba[0]; c1[g][1] = ba[1]; c1[g][2] = ba[2]; c1[g][3] = ba[3];
         c1[g][4] = bb.x;  c1[g][5] = bb.y;
       }
@@ -552,18 +630,27 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
 #pragma unroll 1
     for (int u = 0; u < 5; ++u) {
       const float* ku = tab.k1t + u * 40;
-#pragma unroll
-      for (int v = 0; v < 5; ++v) {
+      // the reads of tap v + 1 are issued before the multiply-adds of tap v and no earlier (two
+      // sets of nine pixels and six weights in registers, not five)
+      float x[2][9], wt[2][6];
+      auto load_tap = [&](int v, float (&xx)[9], float (&ww)[6]) {
         const f4 wa = *reinterpret_cast<const f4*>(&ku[v * 8]);
         const float2 wb = *reinterpret_cast<const float2*>(&ku[v * 8 + 4]);
-        const float wt[6] = {wa[0], wa[1], wa[2], wa[3], wb.x, wb.y};
-        float x[9];
+        ww[0] = wa[0]; ww[1] = wa[1]; ww[2] = wa[2]; ww[3] = wa[3]; ww[4] = wb.x; ww[5] = wb.y;
 #pragma unroll
-        for (int g = 0; g < 9; ++g) x[g] = ip[g][u * 28 + v];
+        for (int g = 0; g < 9; ++g) xx[g] = ip[g][u * 28 + v];
+      };
+      load_tap(0, x[0], wt[0]);
+      __builtin_amdgcn_sched_group_barrier(0x100, 11, 0);
+#pragma unroll
+      for (int v = 0; v < 5; ++v) {
+        if (v < 4) load_tap(v + 1, x[(v + 1) & 1], wt[(v + 1) & 1]);
 #pragma unroll
         for (int i = 0; i < 6; ++i)
 #pragma unroll
-          for (int g = 0; g < 9; ++g) c1[g][i] = fmaf(wt[i], x[g], c1[g][i]);
+          for (int g = 0; g < 9; ++g) c1[g][i] = fmaf(wt[v & 1][i], x[v & 1][g], c1[g][i]);
+        if (v < 4) __builtin_amdgcn_sched_group_barrier(0x100, 11, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 54, 0);
       }
     }
     // sigmoid, then S1 = avgpool(C1): the four lanes of a quad are the four pixels of one window.
@@ -600,9 +687,11 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
     for (int e = l; e < NS1; e += 64) dump.s1[n * NS1 + e] = s.pool[P_S1 + e];
 
   CNN_PHASE(2);
+  if (MODE == kTrain) touch_pixels(next_image);
   // ---- C2 = sigmoid(mconv(S1, k2, b2)) as a 64 x 16 x 152 GEMM, S2 = avgpool(C2) ------------------
   f4 c2v[4];
   {
+    CNN_PHASE_LANES;
     const float* a12 = s.pool + P_S1 + pp + 12 * q;
     const float* a1 = s.pool + P_S1 + pp + q;
     const float* a144 = s.pool + P_S1 + pp + 144 * q;
@@ -645,14 +734,24 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
   CNN_PHASE(3);
   // ---- output = sigmoid(mconv(S2, fc, b)): lane owns inputs lane, lane+64, lane+128 ----------------
   float sv[3];
+  // training: this wave's FC weight-gradient sums come from global memory (they stay in the L2
+  // cache between images); the loads are in flight during the output layer
+  float fcv[MODE == kTrain ? 30 : 1];
+  {
+    CNN_PHASE_LANES;
 #pragma unroll
-  for (int k = 0; k < 3; ++k) sv[k] = s.pool[P_S2 + l + 64 * k];
+    for (int k = 0; k < 3; ++k) sv[k] = s.pool[P_S2 + l + 64 * k];
+    if constexpr (MODE == kTrain) {
 #pragma unroll
-  for (int o = 0; o < 10; ++o) {
-    float p = tl[(TAB_FCW + 3 * o) * 64] * sv[0];
-    p = fmaf(tl[(TAB_FCW + 3 * o + 1) * 64], sv[1], p);
-    p = fmaf(tl[(TAB_FCW + 3 * o + 2) * 64], sv[2], p);
-    y[o] = logistic(wave_sum(p) + tab.bias[TAB_BIAS_B + o]);
+      for (int j = 0; j < 30; ++j) fcv[j] = fc_acc_load(st.fc_acc, j, l);
+    }
+#pragma unroll
+    for (int o = 0; o < 10; ++o) {
+      float p = tl[(TAB_FCW + 3 * o) * 64] * sv[0];
+      p = fmaf(tl[(TAB_FCW + 3 * o + 1) * 64], sv[1], p);
+      p = fmaf(tl[(TAB_FCW + 3 * o + 2) * 64], sv[2], p);
+      y[o] = logistic(wave_sum(p) + tab.bias[TAB_BIAS_B + o]);
+    }
   }
   if constexpr (MODE == kTrain) {
     // ---- output error, FC backweights / backbias / backin ------------------------------------------
@@ -667,42 +766,48 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
       }
       st.loss = fmaf(0.5f, lsum, st.loss);
     }
-    // backweights as rank-1 updates on the 4x4 MFMA: A(lane) = delta[4 mt + lane%4] (delta is
-    // wave-uniform, so every quad holds the same four values), B(lane) = s2[lane + 64 k].
+    // backweights as rank-1 updates, g_fc[o][lane + 64 k] += delta[o] * s2[lane + 64 k] (delta is
+    // wave-uniform), on the sums fetched above; backbias: lane o keeps the sum of delta[o].
+    {
+      CNN_PHASE_LANES;
+      float mine = 0.0f;
 #pragma unroll
-    for (int mt = 0; mt < 3; ++mt) {
-      const float d0 = delta[4 * mt], d1 = delta[4 * mt + 1];
-      const float d2 = mt < 2 ? delta[4 * mt + 2] : 0.0f, d3 = mt < 2 ? delta[4 * mt + 3] : 0.0f;
-      const float aq = (sub & 2) ? ((sub & 1) ? d3 : d2) : ((sub & 1) ? d1 : d0);
-      st.g_bq[mt] += aq;  // backbias
+      for (int o = 0; o < 10; ++o) {
+        mine = l == o ? delta[o] : mine;
 #pragma unroll
-      for (int k = 0; k < 3; ++k) st.acc_fc[mt][k] = mfma4(aq, sv[k], st.acc_fc[mt][k]);
+        for (int k = 0; k < 3; ++k) fc_acc_store(st.fc_acc, 3 * o + k, fmaf(delta[o], sv[k], fcv[3 * o + k]), l);
+      }
+      st.g_b += mine;
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        float d = 0.0f;
+#pragma unroll
+        for (int o = 0; o < 10; ++o) d = fmaf(tl[(TAB_FCW + 3 * o + k) * 64], delta[o], d);
+        s.pool[W_DS2 + l + 64 * k] = d;
+      }
+      // clear the col2im target of the C2 input error
+      for (int e = l; e < NS1 / 4; e += 64) reinterpret_cast<f4*>(s.d_s1)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
     }
-#pragma unroll
-    for (int k = 0; k < 3; ++k) {
-      float d = 0.0f;
-#pragma unroll
-      for (int o = 0; o < 10; ++o) d = fmaf(tl[(TAB_FCW + 3 * o + k) * 64], delta[o], d);
-      s.pool[P_DS2 + l + 64 * k] = d;
-    }
-    // clear the col2im target of the C2 input error
-    for (int e = l; e < NS1 / 4; e += 64) reinterpret_cast<f4*>(s.d_s1)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
     wave_sync();
 
     CNN_PHASE(4);
     // ---- backavgpool through S2 and the derivative of C2's sigmoid; d_c2 stays in the MFMA result
-    //      layout, which is exactly the A-operand layout of the weight-gradient GEMM -------------------
+    //      layout, which is exactly the A-operand layout of the weight-gradient GEMM; the rows of the
+    //      twelve real maps also go to LDS as the B operand of the input-error GEMM ---------------------
     f4 d2v[4];
+    {
+    CNN_PHASE_LANES;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
-      const float up = s.pool[P_DS2 + n16 * 16 + 4 * mt + q] * 0.25f;  // rows n16 >= 12 read finite filler
+      const float up = s.pool[W_DS2 + n16 * 16 + 4 * mt + q] * 0.25f;  // rows n16 >= 12 read finite filler
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const float c = c2v[mt][r];
         d2v[mt][r] = up * c * (1.0f - c);
       }
-      *reinterpret_cast<f4*>(&s.pool[P_D2 + n16 * D2S + 16 * mt + 4 * q]) = d2v[mt];
+      if (n16 < 12) *reinterpret_cast<f4*>(&s.pool[W_D2 + n16 * D2S + 16 * mt + 4 * q]) = d2v[mt];
       st.g_b2 += (d2v[mt][0] + d2v[mt][1]) + (d2v[mt][2] + d2v[mt][3]);
+    }
     }
     wave_sync();
 
@@ -710,21 +815,32 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
     // ---- C2 backweights: G[j, tap] += sum_p d_c2[j, p] * s1[c, y(p)+u, x(p)+v];  K step = (S, r):
     //      the four pixels 16 S + 4 q + r of lane quarter q ------------------------------------------
     {
+      CNN_PHASE_LANES;
       const float* bsrc[10];  // s1 patch element of tap 16 nt + n16 for pixel quarter q
 #pragma unroll
       for (int nt = 0; nt < 10; ++nt) {
         const int tap = 16 * nt + n16;
         const int c = tap / 25, rem = tap - 25 * c, u = rem / 5, v = rem - 5 * u;
-        bsrc[nt] = s.pool + P_S1 + (tap < 150 ? c * 144 + u * 12 + v : 0) + 2 * q;
+        bsrc[nt] = s.pool + W_S1 + (tap < 150 ? c * 144 + u * 12 + v : 0) + 2 * q;
       }
+      // the ten s1 reads of step + 1 are issued under the ten MFMAs of a step and no earlier
+      float bv[2][10];
+      auto load_step = [&](int step, float (&o)[10]) {
+        const int S = step >> 2, r = step & 3, imm = 24 * S + 12 * (r >> 1) + (r & 1);
 #pragma unroll
-      for (int S = 0; S < 4; ++S)
+        for (int nt = 0; nt < 10; ++nt) o[nt] = bsrc[nt][imm];
+      };
+      load_step(0, bv[0]);
+      __builtin_amdgcn_sched_group_barrier(0x100, 10, 0);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int imm = 24 * S + 12 * (r >> 1) + (r & 1);
+      for (int step = 0; step < 16; ++step) {
+        if (step < 15) load_step(step + 1, bv[(step + 1) & 1]);
 #pragma unroll
-          for (int nt = 0; nt < 10; ++nt) st.acc_k2[nt] = mfma16(d2v[S][r], bsrc[nt][imm], st.acc_k2[nt]);
-        }
+        for (int nt = 0; nt < 10; ++nt)
+          st.acc_k2[nt] = mfma16(d2v[step >> 2][step & 3], bv[step & 1][nt], st.acc_k2[nt]);
+        if (step < 15) __builtin_amdgcn_sched_group_barrier(0x100, 10, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 10, 0);
+      }
     }
 
     CNN_PHASE(6);
@@ -735,40 +851,41 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
     //      same cells.  So for each v: terms of equal level are added in registers, then all even
     //      levels go to LDS in one round of read-add-write, then all odd levels.  Within a round no two
     //      lanes share an address (maps are 144 floats apart, levels 24, pixels of a tile distinct).
+    //      The two groups of four input maps (cg) are taken one after the other: half the registers.
     {
+      CNN_PHASE_LANES;
       float bd[3][4];
 #pragma unroll
       for (int sidx = 0; sidx < 3; ++sidx)
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) bd[sidx][nt] = s.pool[P_D2 + (4 * sidx + q) * D2S + 16 * nt + n16];
-      f4 t4[2][4];      // taps (4, v), v < 4, in register v
-      float t44[2][4];  // tap (4, 4)
+        for (int nt = 0; nt < 4; ++nt) bd[sidx][nt] = s.pool[W_D2 + (4 * sidx + q) * D2S + 16 * nt + n16];
 #pragma unroll
       for (int cg = 0; cg < 2; ++cg) {
-        float au[3], ac[3];
-#pragma unroll
-        for (int sidx = 0; sidx < 3; ++sidx) {
-          au[sidx] = tl[(TAB_AB + (cg * 7 + kTileU4) * 3 + sidx) * 64];
-          ac[sidx] = tl[(TAB_AB + (cg * 7 + kTileC) * 3 + sidx) * 64];
-        }
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-          f4 a = f4{0.0f, 0.0f, 0.0f, 0.0f}, c = a;
+        f4 t4[4];      // taps (4, v), v < 4, in register v
+        float t44[4];  // tap (4, 4)
+        {
+          float au[3], ac[3];
 #pragma unroll
           for (int sidx = 0; sidx < 3; ++sidx) {
-            a = mfma16(au[sidx], bd[sidx][nt], a);
-            c = mfma16(ac[sidx], bd[sidx][nt], c);
+            au[sidx] = tl[(TAB_AB + (cg * 7 + kTileU4) * 3 + sidx) * 64];
+            ac[sidx] = tl[(TAB_AB + (cg * 7 + kTileC) * 3 + sidx) * 64];
           }
-          t4[cg][nt] = a;
-          t44[cg][nt] = c[0];
-        }
-      }
-      float* tgt = s.d_s1 + 144 * q + pp;
-      // tile V(v+1) is issued before the rounds of V(v), so its MFMAs run under the LDS round trips
-      f4 tv[2][4], tn[2][4];  // taps (u, v), u < 4, in register u
-      auto v_tiles = [&](int v, f4 (&out)[2][4]) {
 #pragma unroll
-        for (int cg = 0; cg < 2; ++cg) {
+          for (int nt = 0; nt < 4; ++nt) {
+            f4 a = f4{0.0f, 0.0f, 0.0f, 0.0f}, c = a;
+#pragma unroll
+            for (int sidx = 0; sidx < 3; ++sidx) {
+              a = mfma16(au[sidx], bd[sidx][nt], a);
+              c = mfma16(ac[sidx], bd[sidx][nt], c);
+            }
+            t4[nt] = a;
+            t44[nt] = c[0];
+          }
+        }
+        float* tgt = s.d_s1 + 144 * q + pp + 576 * cg;
+        // tile V(v+1) is issued before the rounds of V(v), so its MFMAs run under the LDS round trips
+        f4 tv[4], tn[4];  // taps (u, v), u < 4, in register u
+        auto v_tiles = [&](int v, f4 (&out)[4]) {
           float av[3];
 #pragma unroll
           for (int sidx = 0; sidx < 3; ++sidx) av[sidx] = tl[(TAB_AB + (cg * 7 + kTileV0 + v) * 3 + sidx) * 64];
@@ -777,91 +894,102 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
             f4 a = f4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int sidx = 0; sidx < 3; ++sidx) a = mfma16(av[sidx], bd[sidx][nt], a);
-            out[cg][nt] = a;
+            out[nt] = a;
           }
-        }
-      };
-      v_tiles(0, tv);
+        };
+        v_tiles(0, tv);
 #pragma unroll
-      for (int v = 0; v < 5; ++v) {
-        if (v < 4) v_tiles(v + 1, tn);
-        // even levels 2m, m < 6: (nt = m, u = 0) + (m-1, 2) + (m-2, 4)
-        {
-          float e[2][6], old[2][6];
-#pragma unroll
-          for (int cg = 0; cg < 2; ++cg)
+        for (int v = 0; v < 5; ++v) {
+          if (v < 4) v_tiles(v + 1, tn);
+          // even levels 2m, m < 6: (nt = m, u = 0) + (m-1, 2) + (m-2, 4)
+          {
+            float e[6], old[6];
 #pragma unroll
             for (int m = 0; m < 6; ++m) {
               float acc = 0.0f;
-              if (m < 4) acc = tv[cg][m < 4 ? m : 0][0];
-              if (m >= 1 && m <= 4) acc += tv[cg][m >= 1 ? m - 1 : 0][2];
-              if (m >= 2) acc += v < 4 ? t4[cg][m >= 2 ? m - 2 : 0][v < 4 ? v : 0] : t44[cg][m >= 2 ? m - 2 : 0];
-              e[cg][m] = acc;
-              old[cg][m] = tgt[576 * cg + 24 * m + v];
+              if (m < 4) acc = tv[m < 4 ? m : 0][0];
+              if (m >= 1 && m <= 4) acc += tv[m >= 1 ? m - 1 : 0][2];
+              if (m >= 2) acc += v < 4 ? t4[m >= 2 ? m - 2 : 0][v < 4 ? v : 0] : t44[m >= 2 ? m - 2 : 0];
+              e[m] = acc;
+              old[m] = tgt[24 * m + v];
             }
 #pragma unroll
-          for (int cg = 0; cg < 2; ++cg)
-#pragma unroll
-            for (int m = 0; m < 6; ++m) tgt[576 * cg + 24 * m + v] = old[cg][m] + e[cg][m];
-        }
-        wave_sync();
-        // odd levels 2m+1, m < 5: (nt = m, u = 1) + (m-1, 3)
-        {
-          float e[2][5], old[2][5];
-#pragma unroll
-          for (int cg = 0; cg < 2; ++cg)
+            for (int m = 0; m < 6; ++m) tgt[24 * m + v] = old[m] + e[m];
+          }
+          wave_sync();
+          // odd levels 2m+1, m < 5: (nt = m, u = 1) + (m-1, 3)
+          {
+            float e[5], old[5];
 #pragma unroll
             for (int m = 0; m < 5; ++m) {
               float acc = 0.0f;
-              if (m < 4) acc = tv[cg][m < 4 ? m : 0][1];
-              if (m >= 1) acc += tv[cg][m >= 1 ? m - 1 : 0][3];
-              e[cg][m] = acc;
-              old[cg][m] = tgt[576 * cg + 24 * m + 12 + v];
+              if (m < 4) acc = tv[m < 4 ? m : 0][1];
+              if (m >= 1) acc += tv[m >= 1 ? m - 1 : 0][3];
+              e[m] = acc;
+              old[m] = tgt[24 * m + 12 + v];
             }
 #pragma unroll
-          for (int cg = 0; cg < 2; ++cg)
+            for (int m = 0; m < 5; ++m) tgt[24 * m + 12 + v] = old[m] + e[m];
+          }
+          wave_sync();
+          if (v < 4) {
 #pragma unroll
-            for (int m = 0; m < 5; ++m) tgt[576 * cg + 24 * m + 12 + v] = old[cg][m] + e[cg][m];
-        }
-        wave_sync();
-        if (v < 4) {
-#pragma unroll
-          for (int cg = 0; cg < 2; ++cg)
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt) tv[cg][nt] = tn[cg][nt];
+            for (int nt = 0; nt < 4; ++nt) tv[nt] = tn[nt];
+          }
         }
       }
     }
 
     CNN_PHASE(7);
-    if (next_image) px = load_pixels(next_image);
-    // ---- backavgpool through S1 and the derivative of C1's sigmoid for all nine pixel groups, staged
-    //      in LDS as d1[m][24][24] over the pool (s1, s2, d_s2, d2 are dead by now) ---------------------
+    // ---- backavgpool through S1 and the derivative of C1's sigmoid, then C1 backweights as a GEMM
+    //      over pixel pairs, in three chunks of eight image rows (pixel groups 3 gp .. 3 gp + 2): the
+    //      chunk's error is staged in LDS as d1c[m][8][24] over s1 .. d_s2 (dead by now) and the GEMM
+    //      runs the 24 K steps of those rows ---------------------------------------------------------
+    {
+      CNN_PHASE_LANES;
+      const int lane_d1 = (sub >> 1) * 24 + (sub & 1);
 #pragma unroll
-    for (int gp = 0; gp < 3; ++gp) {
-      float up[3][6];
+      for (int gp = 0; gp < 3; ++gp) {
+        float up[3][6];
+        int off[3];
 #pragma unroll
-      for (int k = 0; k < 3; ++k)
+        for (int k = 0; k < 3; ++k) {
+          off[k] = wt->o[16 * (3 * gp + k) + b].y - 192 * gp + lane_d1;
 #pragma unroll
-        for (int i = 0; i < 6; ++i) up[k][i] = s.d_s1[i * 144 + 16 * (3 * gp + k) + b];
+          for (int i = 0; i < 6; ++i) up[k][i] = s.d_s1[i * 144 + 16 * (3 * gp + k) + b];
+        }
 #pragma unroll
-      for (int k = 0; k < 3; ++k) {
-        const int g = 3 * gp + k;
-        float* dst = s.pool + st.d1off[g];
+        for (int k = 0; k < 3; ++k) {
+          const int g = 3 * gp + k;
+          float* dst = s.pool + off[k];
 #pragma unroll
-        for (int i = 0; i < 6; ++i) {
-          const float c = c1[g][i];
-          const float d1 = up[k][i] * 0.25f * c * (1.0f - c);
-          st.g_b1[i] += d1;
-          dst[i * D1_MAP] = d1;
+          for (int i = 0; i < 6; ++i) {
+            const float c = c1[g][i];
+            const float d1 = up[k][i] * 0.25f * c * (1.0f - c);
+            st.g_b1[i] += d1;
+            dst[i * D1C_MAP] = d1;
+          }
+        }
+        wave_sync();
+        CNN_PHASE(8);
+        // the next image's pixels (touched into the L2 cache long ago) are fetched under the last
+        // chunk's GEMM, when the fewest registers are in use, and take this image's place after it
+        // (through an offset the compiler cannot see before this point: it would otherwise start
+        // the loads, and occupy their sixteen registers, phases earlier)
+        Pixels nx;
+        if (gp == 2) {
+          int zero = 0;
+          asm volatile("" : "+v"(zero));
+          nx = load_pixels(next_image + zero);
+        }
+        c1g_accumulate<C1G_STEPS / 3, D1C_MAP>(st.acc_k1, s.pool, s.img + 8 * 28 * gp, phase_lane<MODE>());
+        wave_sync();
+        if (gp == 2) {
+          store_pixels(s.img, nx);
+          wave_sync();
         }
       }
     }
-    wave_sync();
-    CNN_PHASE(8);
-    // ---- C1 backweights: one GEMM over the image's 288 pixel pairs ------------------------------------
-    c1g_accumulate<C1G_STEPS>(st.acc_k1, s.pool, s.img);
-    wave_sync();
     CNN_PHASE(9);
   }
 }
@@ -869,23 +997,15 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
 // Writes the wave's gradient sums as one partial row (PSTRIDE floats in parameter order, the loss
 // in LOSS_SLOT, zeros after it) to `row`, every slot by exactly one lane.  `row` may be the start
 // of the wave's own LDS area (all of it is dead once the wave's images are done); `park` is
-// C1G_PARK floats of the same wave's LDS outside the row.
-constexpr int FLUSH_PARK = PSTRIDE - (NS1 + NI) + 48;  // offset into TrainLds::pool, past the row
-static_assert(sizeof(TrainLds) >= sizeof(float) * PSTRIDE, "a partial row fits a wave's LDS area");
-static_assert(FLUSH_PARK % 4 == 0 && FLUSH_PARK + C1G_PARK <= POOL_FLOATS, "park area inside the pool");
+// C1G_PARK floats of LDS outside the row that no other wave uses.
 __device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, float* row, float* park) {
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
 #pragma unroll
-  for (int mt = 0; mt < 3; ++mt) {
+  for (int o = 0; o < 10; ++o) {
 #pragma unroll
-    for (int k = 0; k < 3; ++k)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int o = 4 * mt + r;
-        if (o < 10) row[OFF_FC + o * NS2 + l + 64 * k] = st.acc_fc[mt][k][r];
-      }
-    if (l < 4 && 4 * mt + l < 10) row[OFF_B + 4 * mt + l] = st.g_bq[mt];
+    for (int k = 0; k < 3; ++k) row[OFF_FC + o * NS2 + l + 64 * k] = fc_acc_load(st.fc_acc, 3 * o + k, l);
   }
+  if (l < 10) row[OFF_B + l] = st.g_b;
   if (l < PSTRIDE - LOSS_SLOT) row[LOSS_SLOT + l] = l == 0 ? st.loss : 0.0f;
 #pragma unroll
   for (int nt = 0; nt < 10; ++nt)
