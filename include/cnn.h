@@ -36,6 +36,7 @@ extern "C" {
 #define CNN_EWORKSPACE (-2) /* workspace too small for max_batch */
 #define CNN_EHIP (-3)       /* a HIP call or kernel launch failed */
 #define CNN_ESCRATCH (-4)   /* the problem needs more than the library's built-in scratch buffer */
+#define CNN_ETIMEOUT (-5)   /* a bounded wait inside the device-side epoch loop was given up */
 
 #define CNN_NPARAM 3898     /* 150 + 6 + 1800 + 12 + 1920 + 10 */
 
@@ -98,6 +99,21 @@ int cnn_train_batch(cnn_ctx* ctx, const float* images, const int32_t* labels, in
  * result is bitwise the same as the equivalent sequence of cnn_train_batch calls. */
 int cnn_train_epoch(cnn_ctx* ctx, const float* images, const int32_t* labels, int N, int batch,
                     float lr, float* loss_sums);
+
+/* How cnn_train_epoch runs (the answer to the launch-orchestration problem of Section 4.3).
+ * device_loop = 0 (default): two kernels per step, enqueued back to back.  device_loop = 1: for
+ * batch <= 256 (and no more workgroups than the GPU holds at once) all floor(N / batch) whole steps
+ * run inside ONE kernel whose workgroups meet at two grid-wide barriers per step; a shorter last
+ * step, larger batches and every other call still use the two-kernel step.  Same arithmetic in the
+ * same order: the weights are bitwise those of the default mode.  The kernel needs the GPU to
+ * itself (all its workgroups resident): every wait at a barrier is bounded by wait_seconds (0 ..
+ * 3600); a workgroup that waits longer sets an error word and all leave, with the weights somewhere
+ * between two steps.  never_arrives != 0 makes every barrier wait for a workgroup that does not
+ * exist (a way to exercise the give-up path; the first barrier then fails before any update).
+ * cnn_epoch_status waits for the context's stream and returns CNN_OK, or CNN_ETIMEOUT once after a
+ * kernel gave up (it then re-arms the barrier state; set the weights again before training on). */
+int cnn_epoch_mode(cnn_ctx* ctx, int device_loop, double wait_seconds, int never_arrives);
+int cnn_epoch_status(cnn_ctx* ctx);
 
 /* Forward-only classification of N images (1 <= N <= max_batch): n_correct
  * (device int64) = number of images whose largest output (lowest index on ties)

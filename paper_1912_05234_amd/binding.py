@@ -31,6 +31,8 @@ SIGNATURES = {
     "cnn_gradient": (_i, [_vp, _vp, _vp, _i, _vp, _vp]),
     "cnn_train_batch": (_i, [_vp, _vp, _vp, _i, _f, _vp]),
     "cnn_train_epoch": (_i, [_vp, _vp, _vp, _i, _i, _f, _vp]),
+    "cnn_epoch_mode": (_i, [_vp, _i, ctypes.c_double, _i]),
+    "cnn_epoch_status": (_i, [_vp]),
     "cnn_evaluate": (_i, [_vp, _vp, _vp, _i, _vp, _vp]),
     "cnn_profile_begin": (_i, [_vp, _i]),
     "cnn_profile_read": (_i, [_vp, _vp, _i, ctypes.POINTER(_i)]),
@@ -184,6 +186,14 @@ class CNN:
         _check(lib().cnn_train_epoch(self._ctx, _ptr(images), _ptr(labels), images.shape[0], int(batch),
                                      float(lr), _ptr(_dev(loss_sums))), "cnn_train_epoch")
         return loss_sums
+
+    def epoch_mode(self, device_loop, wait_seconds=1.0, never_arrives=False):
+        _check(lib().cnn_epoch_mode(self._ctx, int(device_loop), float(wait_seconds), int(never_arrives)),
+               "cnn_epoch_mode")
+
+    def epoch_status(self):
+        """Waits for the stream; 0, or the (negative) code of a device-side loop that gave up."""
+        return lib().cnn_epoch_status(self._ctx)
 
     def evaluate(self, images, labels):
         images, labels = _dev(images), _dev(labels, torch.int32)

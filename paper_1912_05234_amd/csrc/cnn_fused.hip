@@ -29,6 +29,10 @@ constexpr int FWD_GCAP = 3072;  // most forward-only waves: three per SIMD
 // (more images in flight, no barriers).  Measured crossover: 21.7 against 27.9 us per step at batch
 // 512, 30.8 against 28.8 us at batch 768.
 constexpr int GROUP_MAX_BATCH = 640;
+// Device-side epoch loop: one barrier flag per workgroup (a batch of at most EPOCH_MAX_BATCH images:
+// thread t of a 512-thread workgroup polls flag t), one flag nobody sets, the error word.
+constexpr int EPOCH_MAX_BATCH = 256;
+constexpr int SYNC_PHANTOM = EPOCH_MAX_BATCH, SYNC_ERROR = EPOCH_MAX_BATCH + 1, SYNC_WORDS = EPOCH_MAX_BATCH + 2;
 
 // Forward-only: yhat[B,10], optional activation dump, optional (count, loss) per wave.
 // Wave gw = 4 * blockIdx.x + wave walks the images gw, gw + G, gw + 2G, ... (G = waves in the grid).
@@ -165,7 +169,8 @@ __global__ __launch_bounds__(64 * GWAVES) void train_group_kernel(const float* _
   __shared__ TrainLds s;
   __shared__ __align__(16) float d_s1b[D_S1B_FLOATS];
   __shared__ float ybuf[16];
-  group_train(images, labels, B, tabg, partial + (size_t)blockIdx.x * PSTRIDE, tab, s, d_s1b, ybuf);
+  group_train<false>(images + (size_t)blockIdx.x * NI, labels + blockIdx.x, tabg,
+                     partial + (size_t)blockIdx.x * PSTRIDE, tab, s, d_s1b, ybuf);
 }
 
 // Expanded operand table from the flat parameter vector: tabg[i] = w[table_source(i)] or 0.
@@ -180,41 +185,60 @@ __global__ __launch_bounds__(256) void expand_kernel(const float* __restrict__ w
 // Adds the G partial rows in a fixed order (sixteen interleaved strands, each summed in row
 // order, then a fixed tree over the strands) and either applies  w <- w - scale * g  (grad_out ==
 // nullptr) or stores g.  An updated parameter is also written to its slots of the expanded operand
-// table, dest[p][0..3] (-1 = none).  One workgroup per 64 parameters; the lanes of a wave read 64
-// consecutive floats of a row, and a strand keeps eight row reads in flight.
+// table, dest[p][0..3] (-1 = none).  One block of work per 64 parameters, `block` < PSTRIDE / 64; the
+// lanes of a wave read 64 consecutive floats of a row, and a strand keeps eight row reads in flight.
+// THREADS = 1024: one strand per wave; 512: every wave takes strands s and s + 8, one after the
+// other (same sums, same order).  COHERENT (device-side epoch loop: rows, weights and table are
+// written and read by different compute units within one kernel): agent-scope loads and stores.
 constexpr int RSTRANDS = 16;
-__global__ __launch_bounds__(64 * RSTRANDS) void reduce_update_kernel(const float* __restrict__ partial, int G,
-                                                                     float scale, float* __restrict__ w,
-                                                                     const int32_t* __restrict__ dest,
-                                                                     float* __restrict__ tabg,
-                                                                     float* __restrict__ grad_out,
-                                                                     float* __restrict__ loss_sum) {
-  __shared__ float red[RSTRANDS][64];
-  const int lane = threadIdx.x & 63, strand = threadIdx.x >> 6;
-  const int p = blockIdx.x * 64 + lane;
+template <bool COHERENT>
+__device__ __forceinline__ float ld_shared(const float* p) {
+  return COHERENT ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
+}
+template <bool COHERENT>
+__device__ __forceinline__ void st_shared(float* p, float v) {
+  if (COHERENT)
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else
+    *p = v;
+}
+template <int THREADS, bool COHERENT>
+__device__ __forceinline__ void reduce_update_block(int block, float (&red)[RSTRANDS][64],
+                                                    const float* __restrict__ partial, int G, float scale,
+                                                    float* __restrict__ w, const int32_t* __restrict__ dest,
+                                                    float* __restrict__ tabg, float* __restrict__ grad_out,
+                                                    float* __restrict__ loss_sum) {
+  static_assert(THREADS == 64 * RSTRANDS || THREADS == 32 * RSTRANDS, "one or two strands per wave");
+  constexpr int WAVES_HERE = THREADS / 64, PASSES = RSTRANDS / WAVES_HERE;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int p = block * 64 + lane;
   // what the update needs besides the sum is fetched first, so that it arrives during the reduction
   float w_old = 0.0f;
   int4 d = int4{-1, -1, -1, -1};
-  if (strand == 0 && !grad_out && p < NPARAM) {
-    w_old = w[p];
+  if (wave == 0 && !grad_out && p < NPARAM) {
+    w_old = ld_shared<COHERENT>(w + p);
     d = reinterpret_cast<const int4*>(dest)[p];
   }
   const float* src = partial + p;
-  // eight row reads in flight per strand; a row index past G reads nothing and adds 0.0
-  float a[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-  for (int g = strand; g < G; g += 8 * RSTRANDS) {
-    float r[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int row = g + k * RSTRANDS;
-      r[k] = row < G ? src[(size_t)row * PSTRIDE] : 0.0f;
+  for (int pass = 0; pass < PASSES; ++pass) {
+    const int strand = wave + WAVES_HERE * pass;
+    // eight row reads in flight per strand; a row index past G reads nothing and adds 0.0
+    float a[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    for (int g = strand; g < G; g += 8 * RSTRANDS) {
+      float r[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int row = g + k * RSTRANDS;
+        r[k] = row < G ? ld_shared<COHERENT>(src + (size_t)row * PSTRIDE) : 0.0f;
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) a[k] += r[k];
     }
-#pragma unroll
-    for (int k = 0; k < 8; ++k) a[k] += r[k];
+    red[strand][lane] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
   }
-  red[strand][lane] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
   __syncthreads();
-  if (strand == 0) {
+  if (wave == 0) {
     float t[RSTRANDS];
 #pragma unroll
     for (int k = 0; k < RSTRANDS; ++k) t[k] = red[k][lane];
@@ -228,15 +252,106 @@ __global__ __launch_bounds__(64 * RSTRANDS) void reduce_update_kernel(const floa
         grad_out[p] = total;
       } else {
         const float wn = fmaf(-scale, total, w_old);
-        w[p] = wn;
-        if (d.x >= 0) tabg[d.x] = wn;
-        if (d.y >= 0) tabg[d.y] = wn;
-        if (d.z >= 0) tabg[d.z] = wn;
-        if (d.w >= 0) tabg[d.w] = wn;
+        st_shared<COHERENT>(w + p, wn);
+        if (d.x >= 0) st_shared<COHERENT>(tabg + d.x, wn);
+        if (d.y >= 0) st_shared<COHERENT>(tabg + d.y, wn);
+        if (d.z >= 0) st_shared<COHERENT>(tabg + d.z, wn);
+        if (d.w >= 0) st_shared<COHERENT>(tabg + d.w, wn);
       }
     } else if (p == LOSS_SLOT && loss_sum) {
       *loss_sum = total;
     }
+  }
+}
+
+__global__ __launch_bounds__(64 * RSTRANDS) void reduce_update_kernel(const float* __restrict__ partial, int G,
+                                                                     float scale, float* __restrict__ w,
+                                                                     const int32_t* __restrict__ dest,
+                                                                     float* __restrict__ tabg,
+                                                                     float* __restrict__ grad_out,
+                                                                     float* __restrict__ loss_sum) {
+  __shared__ float red[RSTRANDS][64];
+  reduce_update_block<64 * RSTRANDS, false>(blockIdx.x, red, partial, G, scale, w, dest, tabg, grad_out, loss_sum);
+}
+
+// ---- device-side epoch loop ---------------------------------------------------------------------------
+// Every step of an epoch inside ONE kernel, for batches small enough that all workgroups (one per
+// image of a batch, eight waves each) are resident at once.  Per step: the fused forward + backward
+// of the workgroup's image (cnn_group.h) -> its partial row; grid barrier; the workgroups 0 ..
+// PSTRIDE/64 - 1 sum their 64 parameters over the rows in the order of reduce_update_kernel, update
+// them and the expanded operand table; grid barrier; next step (which re-reads the table).
+// Rows, weights and table travel between compute units (whose L2 caches are not coherent with each
+// other) as agent-scope loads and stores.
+//
+// Grid barrier: workgroup b publishes the number of the barrier in flags[b] once all its threads'
+// stores have completed; thread t < G of every workgroup polls flags[t].  No read-modify-write: a
+// central counter costs 3.2 us per barrier at 100 workgroups, this form 2.5 us.  Every wait is
+// bounded: after `limit` ticks of the 100 MHz wall clock (or when another workgroup has given up)
+// the workgroup sets the error word and leaves; so do, in turn, all others.  flags[phantom] with
+// phantom >= 0 is a flag nobody sets: the host's way to force the give-up path in a test.
+struct GridSync {
+  unsigned* flags;
+  unsigned* error;
+  unsigned G, epoch;
+  long long limit;
+  int phantom;
+};
+__device__ __forceinline__ bool grid_barrier(GridSync& gs, int* dead) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's agent-scope stores have been performed
+  __syncthreads();
+  ++gs.epoch;
+  const unsigned t = threadIdx.x;
+  if (t == 0) __hip_atomic_store(&gs.flags[blockIdx.x], gs.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (t < gs.G || (gs.phantom >= 0 && t == gs.G)) {
+    const unsigned* flag = &gs.flags[t < gs.G ? t : (unsigned)gs.phantom];
+    const long long t0 = wall_clock64();
+    unsigned polls = 0;
+    while ((int)(__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - gs.epoch) < 0) {
+      if ((++polls & 7) == 0 &&
+          (wall_clock64() - t0 > gs.limit ||
+           __hip_atomic_load(gs.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+        __hip_atomic_store(gs.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *dead = 1;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
+  }
+  __syncthreads();
+  return *dead == 0;
+}
+
+__global__ __launch_bounds__(64 * GWAVES) void train_epoch_kernel(const float* __restrict__ images,
+                                                              const int32_t* __restrict__ labels, int steps,
+                                                              float scale, float* __restrict__ w,
+                                                              const int32_t* __restrict__ dest,
+                                                              float* __restrict__ tabg,
+                                                              float* __restrict__ partial,
+                                                              float* __restrict__ loss_sums, unsigned* flags,
+                                                              unsigned* error, unsigned epoch_base,
+                                                              long long limit, int phantom) {
+  __shared__ OperandTable<TAB_TRAIN_ENTRIES> tab;
+  __shared__ TrainLds s;
+  __shared__ __align__(16) float d_s1b[D_S1B_FLOATS];
+  __shared__ float ybuf[16];
+  __shared__ float red[RSTRANDS][64];
+  __shared__ int dead;
+  if (threadIdx.x == 0) dead = 0;
+  GridSync gs{flags, error, gridDim.x, epoch_base, limit, phantom};
+  const int B = gridDim.x;  // images per step = workgroups
+  // a launch that follows one that gave up does nothing (the host resets the error word)
+  if (__hip_atomic_load(error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+  float* row = partial + (size_t)blockIdx.x * PSTRIDE;
+  for (int k = 0; k < steps; ++k) {
+    const size_t n = (size_t)k * B + blockIdx.x;
+    group_train<true>(images + n * NI, labels + n, tabg, row, tab, s, d_s1b, ybuf);
+    if (!grid_barrier(gs, &dead)) return;  // every row of the step is in memory
+    for (int j = blockIdx.x; j < PSTRIDE / 64; j += gridDim.x) {  // (a batch below 61 images: several blocks each)
+      reduce_update_block<64 * GWAVES, true>(j, red, partial, B, scale, w, dest, tabg, nullptr,
+                                            loss_sums ? loss_sums + k : nullptr);
+      __syncthreads();  // `red` is free again
+    }
+    if (!grid_barrier(gs, &dead)) return;  // weights and table of the next step are in memory
   }
 }
 
@@ -254,6 +369,12 @@ struct cnn_ctx {
   float* partial;       // [partial_rows_for(max_batch)][PSTRIDE]
   float* eval_partial;  // [gcap][2]
   float* fc_acc;        // [TRAIN_BLOCKS * TWAVES][FC_ACC_FLOATS] when max_batch > GROUP_MAX_BATCH
+  unsigned* sync;       // [SYNC_WORDS]: barrier flags of the device-side epoch loop, then its error word
+  int epoch_mode = 0;         // 1: cnn_train_epoch runs as one kernel where it can
+  long long wait_ticks = 0;   // longest wait at a grid barrier, in ticks of the 100 MHz wall clock
+  int phantom = -1;           // test hook: also wait for this flag, which nobody sets
+  unsigned barrier_count = 0; // barriers passed by every workgroup so far (flags hold such counts)
+  int resident_limit = -1;    // most workgroups of train_epoch_kernel resident at once (-1: not asked yet)
   std::vector<hipEvent_t> ev;  // 2 per recorded step (before, after the fused kernel)
   int ev_used = 0;             // recorded steps
 };
@@ -269,7 +390,7 @@ inline int gcap_for(int max_batch, int cap = GCAP) {
 }
 
 struct Layout {
-  size_t w, tabg, dest, partial, eval_partial, fc_acc, total;
+  size_t w, tabg, dest, partial, eval_partial, fc_acc, sync, total;
 };
 
 // Partial rows a step can write: one per workgroup, in the one-wave-per-image kernel (four waves
@@ -291,7 +412,8 @@ inline Layout layout_for(int max_batch) {
   l.fc_acc = align_up(l.eval_partial + sizeof(float) * 2 * (size_t)gcap_for(max_batch, FWD_GCAP), 256);
   // only the large-batch kernel keeps sums in global memory; it never launches more workgroups than images
   const size_t train_waves = max_batch > GROUP_MAX_BATCH ? (size_t)TWAVES * (max_batch < TRAIN_BLOCKS ? max_batch : TRAIN_BLOCKS) : 0;
-  l.total = align_up(l.fc_acc + sizeof(float) * FC_ACC_FLOATS * train_waves, 256);
+  l.sync = align_up(l.fc_acc + sizeof(float) * FC_ACC_FLOATS * train_waves, 256);
+  l.total = align_up(l.sync + sizeof(unsigned) * SYNC_WORDS, 256);
   return l;
 }
 
@@ -372,6 +494,7 @@ const char* cnn_strerror(int code) {
     case CNN_EWORKSPACE: return "workspace too small";
     case CNN_EHIP: return "HIP runtime call or kernel launch failed";
     case CNN_ESCRATCH: return "the problem needs more than the library's built-in scratch buffer";
+    case CNN_ETIMEOUT: return "a wait between workgroups of the device-side epoch loop was given up";
     default: return "unknown error code";
   }
 }
@@ -421,6 +544,8 @@ int cnn_init(cnn_ctx** out, void* workspace, size_t workspace_bytes, int max_bat
   ctx->partial = reinterpret_cast<float*>(base + l.partial);
   ctx->eval_partial = reinterpret_cast<float*>(base + l.eval_partial);
   ctx->fc_acc = reinterpret_cast<float*>(base + l.fc_acc);
+  ctx->sync = reinterpret_cast<unsigned*>(base + l.sync);
+  ctx->wait_ticks = 100000000ll;  // one second
   {
     // inverse of table_source: where each parameter sits in the expanded table
     static_assert(TABLE_MAX_DEST == 4 && table_max_multiplicity() <= TABLE_MAX_DEST,
@@ -435,7 +560,8 @@ int cnn_init(cnn_ctx** out, void* workspace, size_t workspace_bytes, int max_bat
     }
     // synchronous copy: the host vector may go away as soon as the call returns
     if (hipMemcpy(ctx->dest, dest.data(), sizeof(int32_t) * dest.size(), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemsetAsync(ctx->w, 0, sizeof(float) * PSTRIDE, ctx->stream) != hipSuccess) {
+        hipMemsetAsync(ctx->w, 0, sizeof(float) * PSTRIDE, ctx->stream) != hipSuccess ||
+        hipMemsetAsync(ctx->sync, 0, sizeof(unsigned) * SYNC_WORDS, ctx->stream) != hipSuccess) {
       (void)hipGetLastError();
       delete ctx;
       return CNN_EHIP;
@@ -525,13 +651,55 @@ int cnn_train_batch(cnn_ctx* ctx, const float* images, const int32_t* labels, in
 int cnn_train_epoch(cnn_ctx* ctx, const float* images, const int32_t* labels, int N, int batch, float lr,
                     float* loss_sums) {
   if (!ctx || N < 1 || !batch_ok(ctx, batch) || !images || !labels || !aligned16(images)) return CNN_EINVAL;
-  for (int k = 0, first = 0; first < N; ++k, first += batch) {
+  int first = 0, k = 0;
+  if (ctx->epoch_mode == 1 && batch <= EPOCH_MAX_BATCH && N >= batch) {
+    // the whole steps as ONE kernel, if all its workgroups can be resident at once
+    if (ctx->resident_limit < 0) {
+      int per_cu = 0, dev = 0, cus = 0;
+      CNN_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, train_epoch_kernel, 64 * GWAVES, 0));
+      CNN_HIP_TRY(hipGetDevice(&dev));
+      CNN_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+      ctx->resident_limit = per_cu * cus;
+    }
+    const int steps = N / batch;
+    if (batch <= ctx->resident_limit && ctx->barrier_count < 0x7f000000u - 2u * (unsigned)steps) {
+      train_epoch_kernel<<<batch, 64 * GWAVES, 0, ctx->stream>>>(
+          images, labels, steps, lr / (float)batch, ctx->w, ctx->dest, ctx->tabg, ctx->partial, loss_sums,
+          ctx->sync, ctx->sync + SYNC_ERROR, ctx->barrier_count, ctx->wait_ticks, ctx->phantom);
+      if (hipGetLastError() != hipSuccess) return CNN_EHIP;
+      ctx->barrier_count += 2u * (unsigned)steps;
+      first = steps * batch;
+      k = steps;
+    }
+  }
+  for (; first < N; ++k, first += batch) {
     const int B = N - first < batch ? N - first : batch;
     const int rc = run_backward(ctx, images + (size_t)first * NI, labels + first, B, lr / (float)B, nullptr,
                                 loss_sums ? loss_sums + k : nullptr);
     if (rc != CNN_OK) return rc;
   }
   return CNN_OK;
+}
+
+int cnn_epoch_mode(cnn_ctx* ctx, int device_loop, double wait_seconds, int never_arrives) {
+  if (!ctx || (device_loop != 0 && device_loop != 1) || !(wait_seconds >= 0.0) || wait_seconds > 3600.0)
+    return CNN_EINVAL;
+  ctx->epoch_mode = device_loop;
+  ctx->wait_ticks = (long long)(wait_seconds * 1e8);
+  ctx->phantom = never_arrives ? SYNC_PHANTOM : -1;
+  return CNN_OK;
+}
+
+int cnn_epoch_status(cnn_ctx* ctx) {
+  if (!ctx) return CNN_EINVAL;
+  unsigned err = 0;
+  CNN_HIP_TRY(hipMemcpyAsync(&err, ctx->sync + SYNC_ERROR, sizeof(err), hipMemcpyDeviceToHost, ctx->stream));
+  CNN_HIP_TRY(hipStreamSynchronize(ctx->stream));
+  if (err == 0) return CNN_OK;
+  // start over: the flags of a kernel that gave up hold different counts
+  CNN_HIP_TRY(hipMemsetAsync(ctx->sync, 0, sizeof(unsigned) * SYNC_WORDS, ctx->stream));
+  ctx->barrier_count = 0;
+  return CNN_ETIMEOUT;
 }
 
 }  // extern "C"

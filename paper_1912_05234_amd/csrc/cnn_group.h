@@ -104,11 +104,22 @@ __device__ __forceinline__ void group_k2_gradient(f4 (&acc)[3], const TrainLds& 
   }
 }
 
-// The whole step for the workgroup's image n = blockIdx.x (the grid is one workgroup per image); one
-// partial row per workgroup.  `d_s1b` is the second col2im target (D_S1B_FLOATS floats), `ybuf` 16
-// floats of LDS for the network output.
-__device__ __forceinline__ void group_train(const float* __restrict__ images,
-                                            const int32_t* __restrict__ labels, int B,
+// A value of the partial row.  COHERENT (the device-side epoch loop, where other compute units read
+// the row during the same kernel): an agent-scope store, written through to memory.
+template <bool COHERENT>
+__device__ __forceinline__ void put_row(float* p, float v) {
+  if (COHERENT)
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else
+    *p = v;
+}
+
+// The whole step for the workgroup's image (`image`, `label` point at it); one partial row, `out`.
+// `d_s1b` is the second col2im target (D_S1B_FLOATS floats), `ybuf` 16 floats of LDS for the network
+// output.  COHERENT: see put_row and TableLoad.
+template <bool COHERENT>
+__device__ __forceinline__ void group_train(const float* __restrict__ image,
+                                            const int32_t* __restrict__ label_ptr,
                                             const float* __restrict__ tabg, float* __restrict__ out,
                                             OperandTable<TAB_TRAIN_ENTRIES>& tab, TrainLds& s, float* d_s1b,
                                             float* ybuf) {
@@ -118,9 +129,9 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
   const int pix = t < NI / 4 ? t : 0;  // the 16-byte piece of the image this thread moves
   CNN_GROUP_MARK(0);
 
-  f4 px = reinterpret_cast<const f4*>(images + (size_t)(blockIdx.x < (unsigned)B ? blockIdx.x : 0) * NI)[pix];
-  const int label = labels[blockIdx.x < (unsigned)B ? blockIdx.x : 0];  // in flight during the set-up too
-  TableLoad<TAB_TRAIN_ENTRIES, 64 * GWAVES> table;
+  f4 px = reinterpret_cast<const f4*>(image)[pix];
+  const int label = *label_ptr;  // in flight during the set-up too
+  TableLoad<TAB_TRAIN_ENTRIES, 64 * GWAVES, COHERENT> table;
   table.fetch(tabg);
   // every LDS cell that padded GEMM steps may read starts finite, and both col2im targets start at
   // zero (the image area is written below, before the first barrier, so it is left alone here)
@@ -385,7 +396,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int j = 4 * q + r, tap = 16 * (first + k) + n16;
-        if (k < count && j < 12 && tap < 150) out[OFF_K2 + j * 150 + tap] = st.acc_k2[k][r];
+        if (k < count && j < 12 && tap < 150) put_row<COHERENT>(out + OFF_K2 + j * 150 + tap, st.acc_k2[k][r]);
       }
   }
   if (wave < 3) {
@@ -394,9 +405,9 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int o = 4 * wave + r;
-        if (o < 10) out[OFF_FC + o * NS2 + l + 64 * k] = st.acc_fc[k][r];
+        if (o < 10) put_row<COHERENT>(out + OFF_FC + o * NS2 + l + 64 * k, st.acc_fc[k][r]);
       }
-    if (l < 4 && 4 * wave + l < 10) out[OFF_B + 4 * wave + l] = st.g_bq;
+    if (l < 4 && 4 * wave + l < 10) put_row<COHERENT>(out + OFF_B + 4 * wave + l, st.g_bq);
   }
   CNN_GROUP_MARK(13);
   if (wave >= 6 || (wave == 3 && l >= 32)) {
@@ -407,7 +418,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
       float x[GWAVES];
 #pragma unroll
       for (int k = 0; k < GWAVES; ++k) x[k] = c1g_combine(k1s + k * C1G_PARK, e);
-      out[OFF_K1 + e] = ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
+      put_row<COHERENT>(out + OFF_K1 + e, ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7])));
     }
   }
   if (wave == 3) {
@@ -415,7 +426,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
       float x[GWAVES];
 #pragma unroll
       for (int k = 0; k < GWAVES; ++k) x[k] = b1s[k * 8 + l];
-      out[OFF_B1 + l] = ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
+      put_row<COHERENT>(out + OFF_B1 + l, ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7])));
     } else if (l >= 16 && l < 28) {  // C2 biases: 4 waves x 4 lane quarters
       const int j = l - 16;
       float x[16];
@@ -423,10 +434,10 @@ __device__ __forceinline__ void group_train(const float* __restrict__ images,
       for (int k = 0; k < 16; ++k) x[k] = b2s[k * 16 + j];
 #pragma unroll
       for (int k = 0; k < 16; k += 4) x[k] = (x[k] + x[k + 1]) + (x[k + 2] + x[k + 3]);
-      out[OFF_B2 + j] = (x[0] + x[4]) + (x[8] + x[12]);
+      put_row<COHERENT>(out + OFF_B2 + j, (x[0] + x[4]) + (x[8] + x[12]));
     }
   }
-  if (t == 0) out[LOSS_SLOT] = st.loss;
+  if (t == 0) put_row<COHERENT>(out + LOSS_SLOT, st.loss);
   CNN_GROUP_MARK(10);
 }
 

@@ -334,7 +334,10 @@ constexpr int table_max_multiplicity() {
 // kernel can do other set-up work while the loads are in flight: `fetch` issues all of a thread's
 // 16-byte loads, `commit` stores them to LDS.  All THREADS threads of the workgroup take part and
 // the caller follows the commit with a workgroup barrier.
-template <int ENTRIES, int THREADS>
+// COHERENT: the table was written by other compute units during this kernel (the device-side
+// epoch loop): its 16-byte pieces are fetched with agent-scope loads, which do not take stale lines
+// from this XCD's L2 cache.
+template <int ENTRIES, int THREADS, bool COHERENT = false>
 struct TableLoad {
   static constexpr int PIECES = ENTRIES * 16, ROUNDS = (PIECES + THREADS - 1) / THREADS;
   static constexpr int TAIL = (K1T_FLOATS + TAB_BIAS_FLOATS) / 4;
@@ -345,6 +348,19 @@ struct TableLoad {
   f4 v[ROUNDS], tail;
   __device__ __forceinline__ void fetch(const float* __restrict__ tabg) {
     const int t = threadIdx.x;
+    if (COHERENT) {
+      const __amdgpu_buffer_rsrc_t rs =
+          __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(tabg), 0, sizeof(float) * TABG_FLOATS, 0x00020000);
+      constexpr int AGENT_SCOPE = 16;  // the sc1 bit of the cache policy
+      typedef unsigned u4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+      for (int r = 0; r < ROUNDS; ++r) {
+        const int i = r * THREADS + t;
+        v[r] = __builtin_bit_cast(f4, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs, 16 * (i < PIECES ? i : 0), 0, AGENT_SCOPE));
+      }
+      tail = __builtin_bit_cast(f4, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs, 4 * TABG_K1T + 16 * (t < TAIL ? t : 0), 0, AGENT_SCOPE));
+      return;
+    }
     const f4* src = reinterpret_cast<const f4*>(tabg);
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {

@@ -32,7 +32,7 @@ def test_library_exports_every_declared_symbol():
 def test_error_strings_and_workspace_size():
     L = binding.lib()
     assert L.cnn_strerror(0) == b"ok"
-    for code in (-1, -2, -3, -4, -99):
+    for code in (-1, -2, -3, -4, -5, -99):
         assert len(L.cnn_strerror(code)) > 0
     assert L.cnn_workspace_bytes(0) == 0 and L.cnn_workspace_bytes(-5) == 0
     small, big = L.cnn_workspace_bytes(1), L.cnn_workspace_bytes(60000)
@@ -56,6 +56,8 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.cnn_forward(nul, fake, 1, fake) == EINVAL
     assert L.cnn_train_batch(nul, fake, fake, 1, 0.05, nul) == EINVAL
     assert L.cnn_train_epoch(nul, fake, fake, 10, 5, 0.05, nul) == EINVAL
+    assert L.cnn_epoch_mode(nul, 1, 1.0, 0) == EINVAL
+    assert L.cnn_epoch_status(nul) == EINVAL
     assert L.cnn_evaluate(nul, fake, fake, 1, fake, nul) == EINVAL
     assert L.cnn_gradient(nul, fake, fake, 1, fake, nul) == EINVAL
     assert L.cnn_get_weights(nul, nul, nul, nul, nul, nul, nul) == EINVAL
