@@ -128,13 +128,19 @@ __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 
   Pixels px = load_pixels(images + (gw < (size_t)B ? gw : 0) * NI);  // in flight during the set-up
   load_tables<TAB_WAVE_ENTRIES, 64 * TWAVES>(tab, tabg);
   window_table_init(wt);
-  wave_init(st, s);
-  // this wave's FC weight-gradient sums start at zero (global memory, see WaveState)
-  st.fc_acc = __builtin_amdgcn_make_buffer_rsrc(fc_acc + ((size_t)blockIdx.x * TWAVES + wave) * FC_ACC_FLOATS, 0,
-                                                sizeof(float) * FC_ACC_FLOATS, 0x00020000);
+  // waves without images (a batch below eight per workgroup leaves the highest ones idle) skip their
+  // set-up and their row; `active` = how many of this workgroup's waves have at least one image
+  const bool has_images = gw < (size_t)B;
+  const int active = (int)((((size_t)B > blockIdx.x ? (size_t)B - blockIdx.x : 0) + gridDim.x - 1) / gridDim.x);
+  if (has_images) {
+    wave_init(st, s);
+    // this wave's FC weight-gradient sums start at zero (global memory, see WaveState)
+    st.fc_acc = __builtin_amdgcn_make_buffer_rsrc(fc_acc + ((size_t)blockIdx.x * TWAVES + wave) * FC_ACC_FLOATS, 0,
+                                                  sizeof(float) * FC_ACC_FLOATS, 0x00020000);
 #pragma unroll
-  for (int j = 0; j < 30; ++j) fc_acc_store(st.fc_acc, j, 0.0f, threadIdx.x & 63);
-  if (gw < (size_t)B) store_pixels(s.img, px);
+    for (int j = 0; j < 30; ++j) fc_acc_store(st.fc_acc, j, 0.0f, threadIdx.x & 63);
+    store_pixels(s.img, px);
+  }
   __syncthreads();  // the operand and window tables are complete
   st.bias2 = tab.bias[threadIdx.x & 15];
   const DumpPtrs none = {nullptr, nullptr, nullptr, nullptr};
@@ -146,15 +152,20 @@ __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 
   }
   CNN_KERNEL_MARK(2);
   __syncthreads();  // every wave is done with the operand table: its storage parks the C1 GEMM results
-  wave_flush(st, reinterpret_cast<float*>(&s), tab.e + wave * C1G_PARK);
+  if (has_images) wave_flush(st, reinterpret_cast<float*>(&s), tab.e + wave * C1G_PARK);
   __syncthreads();
   {
+    // rows of the active waves in a fixed tree; an idle wave's row counts as zeros
     const f4* r = reinterpret_cast<const f4*>(&lds[0]);
     constexpr int RF4 = PSTRIDE / 4;  // a wave's area is exactly one row
     f4* dst = reinterpret_cast<f4*>(partial + (size_t)blockIdx.x * PSTRIDE);
-    for (int i = threadIdx.x; i < RF4; i += 64 * TWAVES)
-      dst[i] = ((r[i] + r[i + RF4]) + (r[i + 2 * RF4] + r[i + 3 * RF4])) +
-               ((r[i + 4 * RF4] + r[i + 5 * RF4]) + (r[i + 6 * RF4] + r[i + 7 * RF4]));
+    const f4 zero = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int i = threadIdx.x; i < RF4; i += 64 * TWAVES) {
+      f4 v[TWAVES];
+#pragma unroll
+      for (int k = 0; k < TWAVES; ++k) v[k] = k < active ? r[i + k * RF4] : zero;
+      dst[i] = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+    }
   }
   CNN_KERNEL_MARK(3);
   CNN_PHASE_FLUSH;
