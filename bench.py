@@ -5,15 +5,18 @@ one MI355X.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch 100]
 
 Workload: 60000 synthetic 28x28 fp32 images (uniform [0,1)) with uniform labels, resident in
-HBM before the timed region; one step = one cnn_train_batch over one batch of 100 consecutive
-images at rate 0.05 (the paper's batch size and rate, Section 4.2), batches taken round-robin
-over the 600 of an epoch; whole epochs are issued through cnn_train_epoch, which makes the same
-per-batch calls inside the library.  Prints ONE JSON line.  Besides the contract fields it carries
+HBM before the timed region; one step = forward, backward and SGD update over one batch of 100
+consecutive images at rate 0.05 (the paper's batch size and rate, Section 4.2), batches taken
+round-robin over the 600 of an epoch.  Every step is issued from C by cnn_train_epoch (whole epochs,
+then one call over the first n * batch images for the rest), so no per-step Python call sits in the
+timed region and the figure does not depend on --steps.  Prints ONE JSON line.  Besides the
+contract fields it carries
   roofline      the fused forward+backward kernel's algorithmic flop rate against MI355X's fp32
                 peak, from HIP events recorded around that kernel on its own stream;
   cpu_baseline  the single-threaded CPU oracle timed on this host on a bounded sample;
   sweep         the same step at batch 1000 / 10000 / 60000, the forward-only evaluation pass, and the
-                stateless per-op calls (fp32 and bf16) at the layer shapes, microseconds per call.
+                stateless per-op calls at the layer shapes (matrix cores, vector unit alone, bf16):
+                microseconds per call and the shares of the fp32 and HBM peaks.
 """
 import argparse
 import json
@@ -35,9 +38,10 @@ N_TRAIN, N_EVAL = 60000, 10000
 GROUP_MAX_BATCH = 640                 # batches up to this size run train_group_kernel, larger ones train_kernel
 # HBM bytes per launch of the fused kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same
 # command (profiles/train_group_kernel_batch100.md, profiles/train_kernel_batch60000.md), scaled by
-# what the counters read for a plain 256 MiB copy (FETCH x2.0, WRITE x1.0).  Only for the batch
-# sizes that were profiled; other sizes report null.
-MEASURED_TRAFFIC_BYTES = {100: 2376909, 60000: 194844672}
+# what the counters read for a plain 256 MiB copy (FETCH x2.0, WRITE x1.0).  Taken from profiles/,
+# not read in this run; only for the batch sizes that were profiled with the kernels as they are
+# now, null otherwise.
+MEASURED_TRAFFIC_BYTES = {100: 2376909}
 
 
 def main():
@@ -72,20 +76,16 @@ def main():
         """-> (images/s, ms per step, mean ms of the fused kernel) for `steps` timed steps."""
         net = binding.CNN(weights, max_batch=batch)
         loss = torch.zeros(1, dtype=torch.float32, device=dev)
-        # pre-slice outside the timed region so the host loop only makes library calls
         per_epoch = N_TRAIN // batch
-        views = [(images[b * batch:(b + 1) * batch], labels[b * batch:(b + 1) * batch])
-                 for b in range(per_epoch)]
-
         epoch_images, epoch_labels = images[:per_epoch * batch], labels[:per_epoch * batch]
 
         def go(n):
-            # whole epochs go through the library's epoch call, the remainder step by step
+            # whole epochs, then the first n % per_epoch batches: all through the library's epoch call
             for _ in range(n // per_epoch):
                 net.train_epoch(epoch_images, epoch_labels, batch, LR)
-            for s in range(n % per_epoch):
-                im, lb = views[s]
-                net.train_batch(im, lb, LR, loss)
+            rest = n % per_epoch
+            if rest:
+                net.train_epoch(epoch_images[:rest * batch], epoch_labels[:rest * batch], batch, LR)
 
         go(warmup)
         torch.cuda.synchronize()
@@ -99,7 +99,7 @@ def main():
         go(cap)
         ms = net.profile_read(cap)
         net.profile_begin(0)
-        net.train_batch(views[0][0], views[0][1], LR, loss)
+        net.train_batch(epoch_images[:batch], epoch_labels[:batch], LR, loss)
         assert bool(torch.isfinite(loss).item())
         net.close()
         return batch * steps / dt, 1e3 * dt / steps, float(np.mean(ms))
@@ -140,7 +140,7 @@ def main():
             "frac": achieved_tflops / PEAK_FP32_TFLOPS,
             "traffic": MEASURED_TRAFFIC_BYTES.get(args.batch),
             "traffic_unit": "HBM bytes per launch (algorithmic: %d image bytes + %d partial-row bytes)"
-                            % (args.batch * BYTES_PER_IMAGE, (args.batch if args.batch <= GROUP_MAX_BATCH else min((args.batch + 3) // 4, 256)) * 15616),
+                            % (args.batch * BYTES_PER_IMAGE, (args.batch if args.batch <= GROUP_MAX_BATCH else min(args.batch, 256)) * 15616),
             "kernel_ms": kernel_ms,
             "flop_per_launch": FLOP_PER_IMAGE_TRAIN * args.batch,
             "hbm_frac_whole_step": value * BYTES_PER_IMAGE / 1e9 / PEAK_HBM_GBS,
@@ -173,8 +173,10 @@ def main():
         # the stateless per-op calls at the layer shapes (10000 images): microseconds per call
         from paper_1912_05234_amd import bench_ops
         per_op = {}
-        bench_ops.run(10000, 20, lambda line: per_op.__setitem__("%s.%s" % (line["layer"], line["op"]), line["us"]))
-        sweep["per_op_us_batch_10000"] = per_op
+        keep = ("us", "frac_of_fp32_peak", "frac_of_hbm_peak", "binding_roof")
+        bench_ops.run(10000, 20, lambda line: per_op.__setitem__("%s.%s" % (line["layer"], line["op"]),
+                                                                  {k: line[k] for k in keep if k in line}))
+        sweep["per_op_batch_10000"] = per_op
         out["sweep"] = sweep
 
     if not args.no_cpu_baseline:

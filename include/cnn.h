@@ -61,7 +61,9 @@ int cnn_init(cnn_ctx** out, void* workspace, size_t workspace_bytes, int max_bat
 /* Frees the host-side context (not the workspace).  NULL is allowed. */
 void cnn_destroy(cnn_ctx* ctx);
 
-/* Copy the current parameters out to / in from device arrays; NULL skips an array. */
+/* Copy the current parameters out to / in from device arrays; NULL skips an array.  The arrays
+ * are those of listing `forward` (Section 3): k1[6,5,5], b1[6], k2[12,6,5,5], b2[12],
+ * fc[10,12,1,4,4], b[10].  The paper has no such calls; they stand in for checkpointing. */
 int cnn_get_weights(cnn_ctx* ctx, float* k1, float* b1, float* k2, float* b2, float* fc, float* b);
 int cnn_set_weights(cnn_ctx* ctx, const float* k1, const float* b1, const float* k2,
                     const float* b2, const float* fc, const float* b);
@@ -115,9 +117,10 @@ int cnn_train_epoch(cnn_ctx* ctx, const float* images, const int32_t* labels, in
 int cnn_epoch_mode(cnn_ctx* ctx, int device_loop, double wait_seconds, int never_arrives);
 int cnn_epoch_status(cnn_ctx* ctx);
 
-/* Forward-only classification of N images (1 <= N <= max_batch): n_correct
- * (device int64) = number of images whose largest output (lowest index on ties)
- * equals the label; loss_sum (nullable) = sum_n L_n. */
+/* Forward-only classification of N images (1 <= N <= max_batch), the pass over the test images
+ * that ends the paper's runs (Section 4.2): n_correct (device int64) = number of images whose
+ * largest output (lowest index on ties; the paper does not say) equals the label; loss_sum
+ * (nullable) = sum_n L_n.  The count is summed in integers: exact for any N. */
 int cnn_evaluate(cnn_ctx* ctx, const float* images, const int32_t* labels, int N,
                  int64_t* n_correct, float* loss_sum);
 
@@ -134,6 +137,9 @@ int cnn_profile_begin(cnn_ctx* ctx, int capacity);
 int cnn_profile_read(cnn_ctx* ctx, float* ms, int capacity, int* n_recorded);
 
 /* ---- Stateless per-operation entry points (batch axis first, NCHW). ----------
+ * No context, no device state: results depend on the arguments alone.  (The host keeps one small
+ * cache of launch parameters per tensor shape -- an LDS row stride chosen by a bank-conflict
+ * model, a pure function of the shape -- guarded by a mutex; calls from several threads are fine.)
  * conv = valid cross-correlation, no kernel flip (listing `conv`), over all Cin
  * input maps per output map plus bias (listing `mconv`), no activation:
  *   out[b,co,y,x] = bias[co] + sum_{ci,u,v} in[b,ci,y+u,x+v] * k[co,ci,u,v]
@@ -146,7 +152,17 @@ int cnn_conv_fwd(const float* in, const float* k, const float* bias, float* out,
  * k[co,ci,u,v] * d_out[b,co,p-u,q-v]. */
 int cnn_conv_bwd_input(const float* d_out, const float* k, float* d_in, int B, int Cin, int H,
                        int W, int Cout, int KH, int KW, void* hip_stream);
-/* Reduced-precision forms of the two calls above, same arguments, same fp32 tensors: every operand
+/* The two calls above on the fp32 vector unit alone (one thread per output element, plain
+ * multiply-adds in the order of the listings `conv` / `backin`, no matrix cores, no LDS): the
+ * comparison leg of the per-layer measurement (is the implicit-GEMM form on the matrix cores
+ * faster than the vector unit?), and the form to call when the data may hold NaN or infinity:
+ * it multiplies nothing by padding zeros.  Same arguments and results to rounding; any shape.
+ * (For the weight gradient the same role is played by cnn_conv_bwd_weight with a NULL workspace.) */
+int cnn_conv_fwd_valu(const float* in, const float* k, const float* bias, float* out, int B, int Cin,
+                      int H, int W, int Cout, int KH, int KW, void* hip_stream);
+int cnn_conv_bwd_input_valu(const float* d_out, const float* k, float* d_in, int B, int Cin, int H,
+                            int W, int Cout, int KH, int KW, void* hip_stream);
+/* Reduced-precision forms of cnn_conv_fwd and cnn_conv_bwd_input, same arguments, same fp32 tensors: every operand
  * (input or output error, and kernel) is rounded to bfloat16 (nearest, ties to even) as it is read,
  * products are summed in fp32 on the bf16 matrix cores, bias and result stay fp32.  The paper
  * computes in `float` (Section 3, listings `conv` and `backin`); these trade its 1e-5 agreement for
@@ -197,17 +213,22 @@ int cnn_avgpool_bwd(const float* d_out, float* d_in, int B, int C, int Ho, int W
  *   out[b,o] = bias[o] + sum_i in[b,i] * w[o,i];  bias may be NULL. */
 int cnn_fc_fwd(const float* in, const float* w, const float* bias, float* out, int B, int I, int O,
                void* hip_stream);
-/* d_in[b,i] = sum_o w[o,i] * d_out[b,o]. */
+/* Listing `backin` for that layer (kernel shape = input shape, so the error of an output is a
+ * single number and every product is valid), summed over the outputs:
+ *   d_in[b,i] = sum_o w[o,i] * d_out[b,o]. */
 int cnn_fc_bwd_input(const float* d_out, const float* w, float* d_in, int B, int I, int O,
                      void* hip_stream);
-/* d_w[o,i] = sum_b d_out[b,o] * in[b,i];  d_bias[o] = sum_b d_out[b,o] (nullable).  Workspace as
+/* Listings `backweights` (= conv(in, d_out) with a one-element d_out) and `backbias` for that
+ * layer, summed over the batch:
+ *   d_w[o,i] = sum_b d_out[b,o] * in[b,i];  d_bias[o] = sum_b d_out[b,o] (nullable).  Workspace as
  * for cnn_conv_bwd_weight. */
 size_t cnn_fc_bwd_weight_workspace_bytes(int B, int I, int O);
 int cnn_fc_bwd_weight(const float* in, const float* d_out, float* d_w, float* d_bias, int B, int I,
                       int O, void* workspace, size_t workspace_bytes, void* hip_stream);
 /* Listing `sigmoid`: y = 1 / (1 + exp(-x)), n elements. */
 int cnn_logistic_fwd(const float* x, float* y, size_t n, void* hip_stream);
-/* Its derivative through the stored output: d_x = d_y * y * (1 - y). */
+/* Its derivative through the stored output: d_x = d_y * y * (1 - y).  Not printed in the paper
+ * (the back-propagation driver is left to its repository); derived from the listing above. */
 int cnn_logistic_bwd(const float* y, const float* d_y, float* d_x, size_t n, void* hip_stream);
 
 #ifdef __cplusplus

@@ -4,9 +4,12 @@
 
 One JSON line per operation: the average duration of the call's kernels between two HIP events
 on the stream the binding launches on, the useful arithmetic (2 flops per multiply-add of the
-operation's definition; padding the kernels add is not counted) and its share of the fp32
-matrix-core peak; for the element-wise layers the bytes they must move and the share of the
-HBM peak.  Inputs are synthetic and resident in device memory.
+operation's definition; padding the kernels add is not counted) and its share of the fp32 peak,
+the bytes the operation must move (every input read once, every output written once) and their
+share of the HBM peak, and which of the two roofs binds (the larger share).  The convolutions are
+timed three ways: on the fp32 matrix cores (implicit GEMM), on the fp32 vector unit alone
+(`*_valu`, one thread per output; the weight gradient without workspace), and with operands rounded
+to bfloat16.  Inputs are synthetic (uniform [-1, 1), seeded) and resident in device memory.
 """
 import argparse
 import json
@@ -56,10 +59,12 @@ def run(batch, steps, emit):
     def rnd(*shape):
         return (torch.rand(*shape, generator=gen) * 2 - 1).to(dev)
 
-    def report(layer, op, us, flops, extra=None):
-        tf = flops / us / 1e6
+    def report(layer, op, us, flops, nbytes, extra=None):
+        tf, gbs = flops / us / 1e6, nbytes / us / 1e3
         line = {"layer": layer, "op": op, "batch": B, "us": round(us, 2), "tflops": round(tf, 2),
-                "frac_of_fp32_peak": round(tf / PEAK_TFLOPS, 4)}
+                "frac_of_fp32_peak": round(tf / PEAK_TFLOPS, 4), "gb_per_s": round(gbs, 1),
+                "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
+                "binding_roof": "hbm" if gbs / PEAK_HBM_GBS > tf / PEAK_TFLOPS else "fp32"}
         line.update(extra or {})
         emit(line)
 
@@ -85,7 +90,17 @@ def run(batch, steps, emit):
             "conv_bwd_input": lambda: L.cnn_conv_bwd_input(p(d), p(k), p(d_in), B, Cin, H, W, Cout, KH, KW, s()),
             "conv_bwd_weight": lambda: L.cnn_conv_bwd_weight(p(x), p(d), p(d_k), p(d_b), B, Cin, H, W, Cout, KH,
                                                              KW, p(ws), nbytes, s()),
+            # the fp32 vector unit alone
+            "conv_fwd_valu": lambda: L.cnn_conv_fwd_valu(p(x), p(k), p(b), p(out), B, Cin, H, W, Cout, KH, KW, s()),
+            "conv_bwd_input_valu": lambda: L.cnn_conv_bwd_input_valu(p(d), p(k), p(d_in), B, Cin, H, W, Cout, KH,
+                                                                     KW, s()),
+            "conv_bwd_weight_valu": lambda: L.cnn_conv_bwd_weight(p(x), p(d), p(d_k), p(d_b), B, Cin, H, W, Cout,
+                                                                  KH, KW, None, 0, s()),
         }
+        # bytes the operation must move: inputs read once, outputs written once
+        sz = {"x": 4 * x.numel(), "d": 4 * d.numel(), "k": 4 * (k.numel() + b.numel())}
+        must_move = {"conv_fwd": sz["x"] + sz["k"] + sz["d"], "conv_bwd_input": sz["d"] + sz["k"] + sz["x"],
+                     "conv_bwd_weight": sz["x"] + sz["d"] + sz["k"]}
         # reduced precision: operands rounded to bfloat16, fp32 sums (same tensors, same useful flops)
         calls["conv_fwd_bf16"] = lambda: L.cnn_conv_fwd_bf16(p(x), p(k), p(b), p(out), B, Cin, H, W, Cout, KH, KW, s())
         calls["conv_bwd_input_bf16"] = lambda: L.cnn_conv_bwd_input_bf16(p(d), p(k), p(d_in), B, Cin, H, W, Cout, KH,
@@ -96,7 +111,10 @@ def run(batch, steps, emit):
                                                                            Cout, KH, KW, p(ws16), nbytes16, s())
         for op, fn in calls.items():
             assert fn() == 0, op
-            report(name, op, time_call(fn, args.steps), flops)
+            slow = op.endswith("_valu")   # milliseconds each at 10000 images: fewer repeats
+            base = op.replace("_valu", "").replace("_bf16", "")
+            report(name, op, time_call(fn, max(3, args.steps // 10) if slow else args.steps, 1 if slow else 5), flops,
+                   must_move[base])
         # the element-wise layers that follow the convolution: sigmoid, pool, and their backward forms
         act, pooled = torch.empty_like(out), torch.empty(B, Cout, Ho // 2, Wo // 2, device=dev)
         d_act = torch.empty_like(out)
@@ -122,9 +140,12 @@ def run(batch, steps, emit):
         "fc_bwd_input": lambda: L.cnn_fc_bwd_input(p(d), p(w), p(d_in), B, I, O, s()),
         "fc_bwd_weight": lambda: L.cnn_fc_bwd_weight(p(x), p(d), p(d_w), p(d_b), B, I, O, p(ws), nbytes, s()),
     }
+    nb = {"fc_fwd": 4 * (x.numel() + w.numel() + b.numel() + out.numel()),
+          "fc_bwd_input": 4 * (d.numel() + w.numel() + d_in.numel()),
+          "fc_bwd_weight": 4 * (x.numel() + d.numel() + w.numel() + b.numel())}
     for op, fn in calls.items():
         assert fn() == 0, op
-        report("FC", op, time_call(fn, args.steps), 2.0 * B * I * O)
+        report("FC", op, time_call(fn, args.steps), 2.0 * B * I * O, nb[op])
 
 
 if __name__ == "__main__":

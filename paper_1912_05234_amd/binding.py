@@ -38,6 +38,8 @@ SIGNATURES = {
     "cnn_profile_read": (_i, [_vp, _vp, _i, ctypes.POINTER(_i)]),
     "cnn_conv_fwd": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp]),
     "cnn_conv_bwd_input": (_i, [_vp, _vp, _vp] + [_i] * 7 + [_vp]),
+    "cnn_conv_fwd_valu": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp]),
+    "cnn_conv_bwd_input_valu": (_i, [_vp, _vp, _vp] + [_i] * 7 + [_vp]),
     "cnn_conv_fwd_bf16": (_i, [_vp, _vp, _vp, _vp] + [_i] * 7 + [_vp]),
     "cnn_conv_bwd_input_bf16": (_i, [_vp, _vp, _vp] + [_i] * 7 + [_vp]),
     "cnn_conv_bwd_weight_workspace_bytes": (_sz, [_i] * 7),
@@ -217,23 +219,23 @@ class CNN:
 
 
 # ---- per-operation entry points -------------------------------------------------
-def conv_fwd(inp, k, bias=None, bf16=False):
+def conv_fwd(inp, k, bias=None, bf16=False, valu=False):
     inp, k, bias = _dev(inp), _dev(k), _dev(bias)
     B, Cin, H, W = inp.shape
     Cout, _, KH, KW = k.shape
     out = torch.empty((B, Cout, H - KH + 1, W - KW + 1), dtype=torch.float32, device=inp.device)
-    name = "cnn_conv_fwd_bf16" if bf16 else "cnn_conv_fwd"
+    name = "cnn_conv_fwd_bf16" if bf16 else "cnn_conv_fwd_valu" if valu else "cnn_conv_fwd"
     _check(getattr(lib(), name)(_ptr(inp), _ptr(k), _ptr(bias), _ptr(out), B, Cin, H, W, Cout, KH, KW,
                                 _stream()), name)
     return out
 
 
-def conv_bwd_input(d_out, k, H, W, bf16=False):
+def conv_bwd_input(d_out, k, H, W, bf16=False, valu=False):
     d_out, k = _dev(d_out), _dev(k)
     B = d_out.shape[0]
     Cout, Cin, KH, KW = k.shape
     d_in = torch.empty((B, Cin, H, W), dtype=torch.float32, device=d_out.device)
-    name = "cnn_conv_bwd_input_bf16" if bf16 else "cnn_conv_bwd_input"
+    name = "cnn_conv_bwd_input_bf16" if bf16 else "cnn_conv_bwd_input_valu" if valu else "cnn_conv_bwd_input"
     _check(getattr(lib(), name)(_ptr(d_out), _ptr(k), _ptr(d_in), B, Cin, H, W, Cout, KH, KW, _stream()), name)
     return d_in
 

@@ -87,19 +87,26 @@ __global__ __launch_bounds__(64 * WAVES, 2) void forward_kernel(const float* __r
   }
 }
 
-// Sums the G (count, loss) pairs: 64 interleaved strands, then a fixed butterfly.
+// Sums the G (count, loss) pairs: 64 interleaved strands, then a fixed order over the strands.  The
+// counts are whole numbers (each wave's is far below 2^24, so exact in its float) and are added as
+// 64-bit integers.
 __global__ __launch_bounds__(64) void eval_reduce_kernel(const float* __restrict__ eval_partial, int G,
                                                          int64_t* __restrict__ n_correct,
                                                          float* __restrict__ loss_sum) {
-  float ok = 0.0f, loss = 0.0f;
+  __shared__ long long counts[64];
+  long long ok = 0;
+  float loss = 0.0f;
   for (int g = threadIdx.x; g < G; g += 64) {
-    ok += eval_partial[2 * g];
+    ok += (long long)eval_partial[2 * g];
     loss += eval_partial[2 * g + 1];
   }
-  ok = wave_sum(ok);  // integers below 2^24: exact in fp32
+  counts[threadIdx.x] = ok;
   loss = wave_sum(loss);
+  __syncthreads();
   if (threadIdx.x == 0) {
-    if (n_correct) *n_correct = (int64_t)ok;
+    long long total = 0;
+    for (int k = 0; k < 64; ++k) total += counts[k];
+    if (n_correct) *n_correct = (int64_t)total;
     if (loss_sum) *loss_sum = loss;
   }
 }

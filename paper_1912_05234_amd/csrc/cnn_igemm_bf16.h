@@ -27,9 +27,11 @@ using igemm::divmod;
 using igemm::lds_barrier;
 using bf8 = __bf16 __attribute__((ext_vector_type(8)));
 
-// fp32 -> bf16 bits, round to nearest even (finite inputs)
+// fp32 -> bf16 bits, round to nearest even; a NaN stays a (quiet) NaN instead of having its
+// mantissa carried into the exponent
 __device__ __forceinline__ unsigned short to_bf16(float f) {
   unsigned u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);
   u += 0x7fffu + ((u >> 16) & 1u);
   return (unsigned short)(u >> 16);
 }

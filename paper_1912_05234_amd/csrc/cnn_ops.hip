@@ -731,6 +731,26 @@ int cnn_conv_bwd_input(const float* d_out, const float* k, float* d_in, int B, i
   return launched();
 }
 
+int cnn_conv_fwd_valu(const float* in, const float* k, const float* bias, float* out, int B, int Cin, int H,
+                      int W, int Cout, int KH, int KW, void* hip_stream) {
+  if (!in || !k || !out || !conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;
+  if (!aligned16(in) || !aligned16(k) || !aligned16(out) || (bias && !aligned16(bias))) return CNN_EINVAL;
+  const size_t total = (size_t)B * Cout * (H - KH + 1) * (W - KW + 1);
+  conv_fwd_kernel<false><<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(in, k, bias, out, total, Cin,
+                                                                                H, W, Cout, KH, KW);
+  return launched();
+}
+
+int cnn_conv_bwd_input_valu(const float* d_out, const float* k, float* d_in, int B, int Cin, int H, int W,
+                            int Cout, int KH, int KW, void* hip_stream) {
+  if (!d_out || !k || !d_in || !conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;
+  if (!aligned16(d_out) || !aligned16(k) || !aligned16(d_in)) return CNN_EINVAL;
+  const size_t total = (size_t)B * Cin * H * W;
+  conv_bwd_input_kernel<false><<<grid_for(total), TPB, 0, (hipStream_t)hip_stream>>>(d_out, k, d_in, total,
+                                                                                      Cin, H, W, Cout, KH, KW);
+  return launched();
+}
+
 int cnn_conv_fwd_bf16(const float* in, const float* k, const float* bias, float* out, int B, int Cin, int H,
                       int W, int Cout, int KH, int KW, void* hip_stream) {
   if (!in || !k || !out || !conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;

@@ -11,7 +11,7 @@ import torch
 
 import oracle
 from paper_1912_05234_amd import binding, inputs
-from parity import RTOL_ACT, RTOL_W, assert_close
+from parity import RTOL_GRAD, RTOL_ACT, RTOL_W, assert_close
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -45,7 +45,7 @@ def test_full_batch_step(B, golden, train_set):
     g_ref = golden["grad_%d" % B]
     g, r = inputs.unflatten(host(grad)), inputs.unflatten(g_ref)
     for name in g:
-        assert_close(g[name], r[name], 2e-5, "grad %s at B=%d" % (name, B))
+        assert_close(g[name], r[name], RTOL_GRAD, "grad %s at B=%d" % (name, B))
     assert abs(host(loss)[0] - float(golden["loss_%d" % B])) <= 2e-5 * float(golden["loss_%d" % B])
     # the step itself: w0 - (lr/B) * g, and bitwise the same when run twice
     net.train_batch(images[:B], labels[:B], LR)
@@ -84,6 +84,10 @@ def test_one_epoch_then_evaluation(golden, train_set):
     n_ok, loss = net.evaluate(ev_i, ev_l)
     yhat = host(net.forward(ev_i))
     assert_close(yhat[:64], golden["eval1_yhat_head"], RTOL_ACT, "yhat of the first 64 evaluation images")
+    # every one of the 10000 rows, against the oracle run now on the stored weights
+    ref_yhat, ref_ok, ref_loss = oracle.evaluate(ev_images, ev_labels, golden["w_epoch1"].astype(np.float32))
+    assert_close(yhat, ref_yhat, RTOL_ACT, "yhat of all 10000 evaluation images")
+    assert ref_ok == int(golden["eval1_correct"]) and abs(ref_loss - float(golden["eval1_loss"])) <= 1e-9 * ref_loss
     for n in (5000, 9999):   # sampled rows computed one by one
         ref = oracle.forward(ev_images[n], golden["w_epoch1"].astype(np.float32))["y"]
         assert_close(yhat[n], ref, RTOL_ACT, "yhat[%d]" % n)

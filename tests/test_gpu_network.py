@@ -7,7 +7,7 @@ import torch
 
 import oracle
 from paper_1912_05234_amd import binding, inputs
-from parity import RTOL_ACT, RTOL_W, assert_close, assert_close_elementwise
+from parity import RTOL_GRAD, RTOL_ACT, RTOL_W, assert_close, assert_close_elementwise
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -34,7 +34,10 @@ def oracle_grad(images, labels, wflat):
     return loss, g
 
 
-@pytest.mark.parametrize("B", [1, 7, 64])
+# 6149 = 2 * 3072 + 5: more images than the forward kernel has waves, so every wave walks several
+# images (the hand-over of the prefetched pixels, the activation dump of later images) and the last
+# round is ragged; every image is compared
+@pytest.mark.parametrize("B", [1, 7, 64, 6149])
 def test_forward_activations(B):
     images, _ = inputs.make_batch(B, 21)
     w = weights(biases=True)
@@ -61,10 +64,27 @@ def test_batch_gradient(B):
     g = inputs.unflatten(host(grad))
     r = inputs.unflatten(ref_g)
     for name in ("k1", "b1", "k2", "b2", "fc", "b"):
-        assert_close(g[name], r[name], 2e-5, "grad %s (B=%d)" % (name, B))
+        assert_close(g[name], r[name], RTOL_GRAD, "grad %s (B=%d)" % (name, B))
     assert abs(host(loss)[0] - ref_loss) <= 1e-5 * ref_loss
     # the weights were not touched
     np.testing.assert_array_equal(host(net.get_weights_flat()), inputs.flatten(w))
+
+
+@pytest.mark.parametrize("B", [640, 700])
+def test_gradient_of_a_repeated_image(B):
+    """B copies of ONE image: the batch gradient is B times that image's gradient, so every layer's
+    error array of the single image (the bias gradients are its sums per map) is checked against
+    the oracle's, in the small-batch kernel (640) and in the one-wave-per-image kernel (700)."""
+    image, label = inputs.make_batch(1, 27)
+    images, labels = np.repeat(image, B, axis=0), np.repeat(label, B)
+    w = weights(biases=True)
+    net = binding.CNN(w, max_batch=B)
+    grad, loss = net.gradient(dev(images), dev(labels))
+    ref_loss, ref_g = oracle_grad(image, label, inputs.flatten(w))
+    g, r = inputs.unflatten(host(grad) / B), inputs.unflatten(ref_g)
+    for name in ("b", "b2", "b1", "fc", "k2", "k1"):
+        assert_close(g[name], r[name], RTOL_GRAD, "single-image grad %s via %d copies" % (name, B))
+    assert abs(host(loss)[0] / B - ref_loss) <= 1e-5 * ref_loss
 
 
 def test_zero_weights_closed_form():
@@ -222,7 +242,7 @@ def test_ragged_batch_beyond_the_workgroup_cap():
         assert_close(yhat[n], oracle.forward(images[n], wflat)["y"], RTOL_ACT, "yhat[%d]" % n)
     grad, loss = net.gradient(dev(images), dev(labels))
     ref_loss, ref_g = oracle_grad(images, labels, wflat)
-    assert_close(host(grad), ref_g, 2e-5, "gradient")
+    assert_close(host(grad), ref_g, RTOL_GRAD, "gradient")
     assert abs(host(loss)[0] - ref_loss) <= 1e-5 * ref_loss
     n_ok, _ = net.evaluate(dev(images), dev(labels))
     assert int(host(n_ok)[0]) == int((yhat.argmax(1) == labels).sum())
@@ -242,7 +262,7 @@ def test_saturated_sigmoids_stay_finite(B):
     ref_y = np.stack([oracle.forward(images[n], wflat)["y"] for n in range(min(B, 16))])
     assert_close(yhat[:len(ref_y)], ref_y, RTOL_ACT, "saturated yhat")
     ref_loss, ref_g = oracle_grad(images, labels, wflat)
-    assert_close(host(grad), ref_g, 2e-5, "saturated gradient")
+    assert_close(host(grad), ref_g, RTOL_GRAD, "saturated gradient")
     assert abs(host(loss)[0] - ref_loss) <= 1e-5 * max(ref_loss, 1.0)
 
 

@@ -5,7 +5,7 @@ import torch
 
 import oracle
 from paper_1912_05234_amd import binding, inputs
-from parity import RTOL_ACT, assert_close, assert_close_elementwise
+from parity import RTOL_GRAD, RTOL_ACT, assert_close, assert_close_elementwise
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -48,6 +48,7 @@ def test_conv_fwd(case):
     b = inputs.make_signed((Cout,), 3)
     ref = oracle_conv_fwd(x, k, b)
     assert_close(host(binding.conv_fwd(dev(x), dev(k), dev(b))), ref, RTOL_ACT, "conv_fwd")
+    assert_close(host(binding.conv_fwd(dev(x), dev(k), dev(b), valu=True)), ref, RTOL_ACT, "conv_fwd_valu")
     ref0 = oracle_conv_fwd(x, k, np.zeros(Cout, np.float32))
     assert_close(host(binding.conv_fwd(dev(x), dev(k), None)), ref0, RTOL_ACT, "conv_fwd no bias")
 
@@ -63,6 +64,7 @@ def test_conv_bwd_input(case):
         for co in range(Cout):
             ref[n] += oracle.backin(d[n, co][None].astype(np.float64), k[co].astype(np.float64), (Cin, H, W))
     assert_close(host(binding.conv_bwd_input(dev(d), dev(k), H, W)), ref, RTOL_ACT, "conv_bwd_input")
+    assert_close(host(binding.conv_bwd_input(dev(d), dev(k), H, W, valu=True)), ref, RTOL_ACT, "conv_bwd_input_valu")
 
 
 @pytest.mark.parametrize("case", CONV_CASES)
@@ -85,6 +87,25 @@ def test_conv_bwd_weight(case):
         assert none is None and torch.equal(d_k2, d_k)   # deterministic order
 
 
+def test_vector_unit_convolutions_keep_non_finite_values_local():
+    """cnn_conv_fwd_valu / cnn_conv_bwd_input_valu multiply nothing by padding zeros: a NaN in the
+    data reaches exactly the outputs whose defining sums contain it."""
+    x = inputs.make_signed((2, 6, 12, 12), 61)
+    k = inputs.make_signed((12, 6, 5, 5), 62)
+    x[1, 3, 7, 2] = np.nan
+    out = host(binding.conv_fwd(dev(x), dev(k), None, valu=True))
+    hit = np.zeros(out.shape, bool)
+    hit[1, :, 3:8, 0:3] = True          # output (y, x) reads input rows y..y+4, columns x..x+4
+    assert np.array_equal(np.isnan(out), hit)
+    d = inputs.make_signed((2, 12, 8, 8), 63)
+    d[0, 5, 2, 6] = np.inf
+    g = host(binding.conv_bwd_input(dev(d), dev(k), 12, 12, valu=True))
+    bad = ~np.isfinite(g)
+    want = np.zeros(g.shape, bool)
+    want[0, :, 2:7, 6:11] = True        # d_out (y, x) spreads to input rows y..y+4, columns x..x+4
+    assert np.array_equal(bad, want)
+
+
 @pytest.mark.parametrize("shape", [(2, 6, 24, 24), (3, 12, 8, 8), (1, 1, 2, 2), (5, 3, 6, 10)])
 def test_avgpool_fwd_bwd(shape):
     x = inputs.make_signed(shape, 8)
@@ -95,21 +116,34 @@ def test_avgpool_fwd_bwd(shape):
     assert abs(up.astype(np.float64).sum() - d.astype(np.float64).sum()) <= 1e-6 * np.abs(d).sum()
 
 
-@pytest.mark.parametrize("B,I,O", [(7, 192, 10), (1, 1, 1), (300, 33, 5), (5000, 192, 10), (70, 20, 300)])
+@pytest.mark.parametrize("B,I,O", [(7, 192, 10), (1, 1, 1), (300, 33, 5), (2000, 192, 10), (70, 20, 300)])
 def test_fc(B, I, O):
     x, w, b = inputs.make_signed((B, I), 10), inputs.make_signed((O, I), 11), inputs.make_signed((O,), 12)
     d = inputs.make_signed((B, O), 13)
-    x64, w64, d64 = x.astype(np.float64), w.astype(np.float64), d.astype(np.float64)
-    # FC is mconv with kernel shape == input shape (Section 3): check one row through the oracle's mconv
-    np.testing.assert_allclose(oracle.mconv(x64[0], w64, b.astype(np.float64)).ravel(), x64[0] @ w64.T + b,
-                               rtol=0, atol=1e-12)
-    assert_close(host(binding.fc_fwd(dev(x), dev(w), dev(b))), x64 @ w64.T + b, RTOL_ACT, "fc_fwd")
-    assert_close(host(binding.fc_fwd(dev(x), dev(w), None)), x64 @ w64.T, RTOL_ACT, "fc_fwd no bias")
-    assert_close(host(binding.fc_bwd_input(dev(d), dev(w))), d64 @ w64, RTOL_ACT, "fc_bwd_input")
+    x64, w64, d64, b64 = x.astype(np.float64), w.astype(np.float64), d.astype(np.float64), b.astype(np.float64)
+    # expected values from the oracle's own functions: FC is mconv with kernel shape == input shape
+    # (Section 3), its backward forms are backin / backweights / backbias with a one-element error
+    ref_out = np.stack([oracle.mconv(x64[n], w64, b64).ravel() for n in range(B)])
+    ref_out0 = np.stack([oracle.mconv(x64[n], w64, np.zeros(O)).ravel() for n in range(B)])
+    ref_din = np.zeros((B, I))
+    ref_dw, ref_db = np.zeros((O, I)), np.zeros(O)
+    for n in range(B):
+        for o in range(O):
+            e = d64[n, o:o + 1]
+            ref_din[n] += oracle.backin(e, w64[o], (I,)).ravel()
+            ref_dw[o] += oracle.backweights(e, x64[n]).ravel()
+            ref_db[o] += oracle.backbias(e)
+    # (and the oracle agrees with the matrix products these reduce to)
+    np.testing.assert_allclose(ref_out, x64 @ w64.T + b64, rtol=0, atol=1e-11)
+    np.testing.assert_allclose(ref_din, d64 @ w64, rtol=0, atol=1e-11)
+    np.testing.assert_allclose(ref_dw, d64.T @ x64, rtol=0, atol=1e-9)
+    assert_close(host(binding.fc_fwd(dev(x), dev(w), dev(b))), ref_out, RTOL_ACT, "fc_fwd")
+    assert_close(host(binding.fc_fwd(dev(x), dev(w), None)), ref_out0, RTOL_ACT, "fc_fwd no bias")
+    assert_close(host(binding.fc_bwd_input(dev(d), dev(w))), ref_din, RTOL_ACT, "fc_bwd_input")
     for workspace in (True, False):
         d_w, d_b = binding.fc_bwd_weight(dev(x), dev(d), workspace=workspace)
-        assert_close(host(d_w), d64.T @ x64, RTOL_ACT, "fc_bwd_weight")
-        assert_close(host(d_b), d64.sum(0), RTOL_ACT, "fc_bwd_bias")
+        assert_close(host(d_w), ref_dw, RTOL_ACT, "fc_bwd_weight")
+        assert_close(host(d_b), ref_db, RTOL_ACT, "fc_bwd_bias")
 
 
 def test_logistic():
@@ -164,7 +198,7 @@ def test_training_gradient_assembled_from_per_op_calls(B):
     parts = dict(zip(("k1", "b1", "k2", "b2", "fc", "b"), (d_k1, d_b1, d_k2, d_b2, d_fc, d_b)))
     ref = inputs.unflatten(g_fused)
     for name, t in parts.items():
-        assert_close(host(t).reshape(ref[name].shape), ref[name], 2e-5, "gradient of %s from per-op calls" % name)
+        assert_close(host(t).reshape(ref[name].shape), ref[name], RTOL_GRAD, "gradient of %s from per-op calls" % name)
     ref_loss = 0.5 * float(((host(y).astype(np.float64) - host(target)) ** 2).sum())
     assert abs(float(host(loss)[0]) - ref_loss) <= 1e-5 * ref_loss
 
