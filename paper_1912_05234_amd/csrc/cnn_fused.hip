@@ -28,7 +28,10 @@ constexpr int FWD_GCAP = 3072;  // most forward-only waves: three per SIMD
 // up to two such workgroups share a compute unit); larger ones give each image to a single wave
 // (more images in flight, no barriers).  Measured crossover: 21.7 against 27.9 us per step at batch
 // 512, 30.8 against 28.8 us at batch 768.
-constexpr int GROUP_MAX_BATCH = 640;
+#ifndef GROUP_MAX
+#define GROUP_MAX 640
+#endif
+constexpr int GROUP_MAX_BATCH = GROUP_MAX;
 // Device-side epoch loop: one barrier flag per workgroup (a batch of at most EPOCH_MAX_BATCH images:
 // thread t of a 512-thread workgroup polls flag t), one flag nobody sets, the error word.
 constexpr int EPOCH_MAX_BATCH = 256;
@@ -114,13 +117,75 @@ __global__ __launch_bounds__(64) void eval_reduce_kernel(const float* __restrict
 // Forward + backward over each wave's images: eight waves per workgroup, one workgroup per compute
 // unit, i.e. two waves per SIMD.  (One wave alone issues a vector instruction every 2.4 ns, two
 // together one every 1.4 ns, and the matrix instructions of one run under the LDS waits of the
-// other; the price is 256 registers and 15.25 KB of LDS per wave.)  Wave w of workgroup b walks
-// the images w * gridDim.x + b, + 8 * gridDim.x, ...: a batch that does not fill the machine leaves
-// the waves 4..7 of every workgroup idle rather than some compute units empty.  The eight waves
-// then add their gradient sums through LDS in a fixed order and the workgroup writes ONE partial
-// row, partial[blockIdx.x][PSTRIDE], with 16-byte stores (a wave without images contributes zeros).
+// other; the price is 256 registers and 15.25 KB of LDS per wave.)  Workgroup b owns the images
+// b + gridDim.x * k, k < K; WaveShare says which of them each wave takes.  The eight waves then add
+// their gradient sums through LDS in a fixed order and the workgroup writes ONE partial row,
+// partial[blockIdx.x][PSTRIDE], with 16-byte stores (a wave without images contributes zeros).
 constexpr int TWAVES = 8;
 constexpr int FC_ACC_FLOATS = 30 * 64;  // per wave: the FC weight-gradient sums, [3 o + k][lane]
+// Which of a workgroup's K images each wave takes.  The images are dealt in rounds: a full round
+// gives one image to each of the eight waves, a half round one to each of waves 0..3 only; the
+// pattern of SHARE_ROUNDS rounds repeats every SHARE_PERIOD images.  A function of K and the wave
+// alone, so the grouping of the gradient sums (and with it every rounding) is the same in every run.
+// Why not full rounds only: the two waves of a SIMD do not advance at the same rate.  The one in
+// the lower slot wins the issue arbitration more often and needs about 64 thousand clocks per
+// image where its partner needs 88 (51 thousand for a wave that has the SIMD to itself), in every
+// workgroup alike, so an equal split leaves the SIMD to one wave for the last sixth of the kernel.
+// A batch that does not fill the machine (K < 8) still leaves waves 4..7 idle rather than two
+// waves on one SIMD and none on another: the first round is a full one.
+#ifndef SHARE_PATTERN_BITS
+#define SHARE_PATTERN_BITS 0xB  /* rounds F F H F (first round in bit 0): 4 images to 3 */
+#define SHARE_PATTERN_ROUNDS 4
+#endif
+constexpr int SHARE_ROUNDS = SHARE_PATTERN_ROUNDS;
+constexpr bool share_full(int r) { return (SHARE_PATTERN_BITS >> r) & 1; }
+constexpr int share_start(int r) {  // first image of round r inside a period
+  int at = 0;
+  for (int i = 0; i < r; ++i) at += share_full(i) ? 8 : 4;
+  return at;
+}
+constexpr int SHARE_PERIOD = share_start(SHARE_ROUNDS);
+constexpr int share_full_rounds() {
+  int n = 0;
+  for (int r = 0; r < SHARE_ROUNDS; ++r) n += share_full(r);
+  return n;
+}
+constexpr int SHARE_FULL = share_full_rounds();
+static_assert(share_full(0), "the first round deals to all eight waves");
+struct ShareSlots {  // start of the j-th round that deals to waves 0..3 (every round) / to waves 4..7 (full rounds)
+  int low[SHARE_ROUNDS], high[SHARE_ROUNDS];
+  constexpr ShareSlots() : low(), high() {
+    int nh = 0;
+    for (int r = 0; r < SHARE_ROUNDS; ++r) {
+      low[r] = share_start(r);
+      if (share_full(r)) high[nh++] = share_start(r);
+    }
+    for (; nh < SHARE_ROUNDS; ++nh) high[nh] = SHARE_PERIOD;  // never reached
+  }
+};
+__device__ constexpr ShareSlots SHARE_SLOTS = ShareSlots();
+// How many of K images wave w takes.
+__device__ __forceinline__ int share_count(int K, int w) {
+  const int per = w < 4 ? SHARE_ROUNDS : SHARE_FULL, rest = K % SHARE_PERIOD;
+  int n = per * (K / SHARE_PERIOD);
+#pragma unroll
+  for (int j = 0; j < SHARE_ROUNDS; ++j)
+    if (j < per && (w < 4 ? SHARE_SLOTS.low[j] : SHARE_SLOTS.high[j]) + w < rest) ++n;
+  return n;
+}
+// Walks wave w's images: k() is the current one, left how many remain including it.
+struct WaveShare {
+  int base, j, per, left, w;
+  __device__ __forceinline__ WaveShare(int K, int wave) : base(0), j(0), per(wave < 4 ? SHARE_ROUNDS : SHARE_FULL), left(share_count(K, wave)), w(wave) {}
+  __device__ __forceinline__ int k() const { return base + (w < 4 ? SHARE_SLOTS.low[j] : SHARE_SLOTS.high[j]) + w; }
+  __device__ __forceinline__ void advance() {
+    --left;
+    if (++j == per) {
+      j = 0;
+      base += SHARE_PERIOD;
+    }
+  }
+};
 __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 2))) void train_kernel(
     const float* __restrict__ images, const int32_t* __restrict__ labels, int B, const float* __restrict__ tabg,
     float* __restrict__ partial, float* __restrict__ fc_acc) {
@@ -131,14 +196,14 @@ __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 
   WaveTrainLds& s = lds[wave];
   WaveState<kTrain> st;
   CNN_KERNEL_MARK(0);
-  const size_t gw = (size_t)wave * gridDim.x + blockIdx.x, G = (size_t)gridDim.x * TWAVES;
-  Pixels px = load_pixels(images + (gw < (size_t)B ? gw : 0) * NI);  // in flight during the set-up
+  const int K = B > (int)blockIdx.x ? (B - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x : 0;
+  WaveShare mine(K, wave);
+  const bool has_images = mine.left > 0;
+  auto image_index = [&](int k) { return (size_t)blockIdx.x + (size_t)gridDim.x * (size_t)k; };
+  Pixels px = load_pixels(images + (has_images ? image_index(mine.k()) : 0) * NI);  // in flight during the set-up
   load_tables<TAB_WAVE_ENTRIES, 64 * TWAVES>(tab, tabg);
   window_table_init(wt);
-  // waves without images (a batch below eight per workgroup leaves the highest ones idle) skip their
-  // set-up and their row; `active` = how many of this workgroup's waves have at least one image
-  const bool has_images = gw < (size_t)B;
-  const int active = (int)((((size_t)B > blockIdx.x ? (size_t)B - blockIdx.x : 0) + gridDim.x - 1) / gridDim.x);
+  // waves without images skip their set-up and their row
   if (has_images) {
     wave_init(st, s);
     // this wave's FC weight-gradient sums start at zero (global memory, see WaveState)
@@ -152,17 +217,19 @@ __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 
   st.bias2 = tab.bias[threadIdx.x & 15];
   const DumpPtrs none = {nullptr, nullptr, nullptr, nullptr};
   CNN_KERNEL_MARK(1);
-  for (size_t n = gw; n < (size_t)B; n += G) {
+  while (mine.left > 0) {
     float y[10];
-    const size_t nn = n + G;
-    wave_image<kTrain>(st, s, tab, px, images + (nn < (size_t)B ? nn : n) * NI, labels[n], y, none, n, &wt);
+    const size_t n = image_index(mine.k());
+    mine.advance();
+    const size_t nn = mine.left > 0 ? image_index(mine.k()) : n;
+    wave_image<kTrain>(st, s, tab, px, images + nn * NI, labels[n], y, none, n, &wt);
   }
   CNN_KERNEL_MARK(2);
   __syncthreads();  // every wave is done with the operand table: its storage parks the C1 GEMM results
   if (has_images) wave_flush(st, reinterpret_cast<float*>(&s), tab.e + wave * C1G_PARK);
   __syncthreads();
   {
-    // rows of the active waves in a fixed tree; an idle wave's row counts as zeros
+    // rows of the waves that had images in a fixed tree; an idle wave's row counts as zeros
     const f4* r = reinterpret_cast<const f4*>(&lds[0]);
     constexpr int RF4 = PSTRIDE / 4;  // a wave's area is exactly one row
     f4* dst = reinterpret_cast<f4*>(partial + (size_t)blockIdx.x * PSTRIDE);
@@ -170,7 +237,7 @@ __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 
     for (int i = threadIdx.x; i < RF4; i += 64 * TWAVES) {
       f4 v[TWAVES];
 #pragma unroll
-      for (int k = 0; k < TWAVES; ++k) v[k] = k < active ? r[i + k * RF4] : zero;
+      for (int k = 0; k < TWAVES; ++k) v[k] = share_count(K, k) > 0 ? r[i + k * RF4] : zero;
       dst[i] = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
     }
   }
