@@ -36,9 +36,15 @@ constexpr int PSTRIDE = 3904;
 // hardware base-2 exponential and reciprocal (each about 1 ulp).  Finite for
 // every finite x: exp2 overflows to +inf and 1/inf = 0; it underflows to 0 and
 // 1/1 = 1.
+constexpr float NEG_LOG2E = -1.44269504088896340736f;
 __device__ __forceinline__ float logistic(float x) {
-  const float e = __builtin_amdgcn_exp2f(x * -1.44269504088896340736f);
+  const float e = __builtin_amdgcn_exp2f(x * NEG_LOG2E);
   return __builtin_amdgcn_rcpf(1.0f + e);
+}
+// The same function of z = -log2(e) * x: the convolution layers keep their weights and biases
+// multiplied by that constant in the expanded operand table, so their sums arrive already scaled.
+__device__ __forceinline__ float logistic_of_scaled(float z) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(z));
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

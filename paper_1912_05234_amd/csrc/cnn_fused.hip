@@ -258,12 +258,12 @@ __global__ __launch_bounds__(64 * GWAVES) void train_group_kernel(const float* _
                      partial + (size_t)blockIdx.x * PSTRIDE, tab, s, d_s1b, ybuf);
 }
 
-// Expanded operand table from the flat parameter vector: tabg[i] = w[table_source(i)] or 0.
+// Expanded operand table from the flat parameter vector: tabg[i] = table_scale(i) * w[table_source(i)] or 0.
 __global__ __launch_bounds__(256) void expand_kernel(const float* __restrict__ w, float* __restrict__ tabg) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < TABG_FLOATS) {
     const int p = table_source(i);
-    tabg[i] = p >= 0 ? w[p] : 0.0f;
+    tabg[i] = p >= 0 ? table_scale(i) * w[p] : 0.0f;
   }
 }
 
@@ -338,10 +338,10 @@ __device__ __forceinline__ void reduce_update_block(int block, float (&red)[RSTR
       } else {
         const float wn = fmaf(-scale, total, w_old);
         st_shared<COHERENT>(w + p, wn);
-        if (d.x >= 0) st_shared<COHERENT>(tabg + d.x, wn);
-        if (d.y >= 0) st_shared<COHERENT>(tabg + d.y, wn);
-        if (d.z >= 0) st_shared<COHERENT>(tabg + d.z, wn);
-        if (d.w >= 0) st_shared<COHERENT>(tabg + d.w, wn);
+        if (d.x >= 0) st_shared<COHERENT>(tabg + d.x, table_scale(d.x) * wn);
+        if (d.y >= 0) st_shared<COHERENT>(tabg + d.y, table_scale(d.y) * wn);
+        if (d.z >= 0) st_shared<COHERENT>(tabg + d.z, table_scale(d.z) * wn);
+        if (d.w >= 0) st_shared<COHERENT>(tabg + d.w, table_scale(d.w) * wn);
       }
     } else if (p == LOSS_SLOT && loss_sum) {
       *loss_sum = total;

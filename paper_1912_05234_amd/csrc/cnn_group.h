@@ -74,7 +74,8 @@ __device__ __forceinline__ void group_c1_error(GroupState& st, TrainLds& s, cons
 #pragma unroll
     for (int k = 0; k < NT; ++k) {
       const int T = wave + 8 * k, o = ln.s1 + c1f_tile_s1(T);
-      const float up0 = (s.d_s1[o] + d_s1b[o]) * 0.25f, up1 = (s.d_s1[o + 144] + d_s1b[o + 144]) * 0.25f;
+      // (the average pooling's 1/4 is in the col2im operand of the table)
+      const float up0 = s.d_s1[o] + d_s1b[o], up1 = s.d_s1[o + 144] + d_s1b[o + 144];
       const f4 c = c1[k];
       const float2 da = float2{up0 * c[0] * (1.0f - c[0]), up0 * c[1] * (1.0f - c[1])};
       const float2 db = float2{up1 * c[2] * (1.0f - c[2]), up1 * c[3] * (1.0f - c[3])};
@@ -191,7 +192,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ image,
         c2v = mfma16(opa[sidx % 3], opw[sidx % 3], c2v);
       }
 #pragma unroll
-      for (int r = 0; r < 4; ++r) c2v[r] = logistic(c2v[r]);
+      for (int r = 0; r < 4; ++r) c2v[r] = logistic_of_scaled(c2v[r]);
       if (n16 < 12) s.pool[P_S2 + n16 * 16 + 4 * wave + q] = 0.25f * ((c2v[0] + c2v[1]) + (c2v[2] + c2v[3]));
     }
     CNN_GROUP_MARK(4);

@@ -32,6 +32,8 @@
 //   4x4x1  : D_r(lane) += A(4*(lane/4)+r) * B(lane).
 #pragma once
 
+#include <type_traits>
+
 #include "cnn_common.h"
 
 // Hook for a cycle-counter probe at phase boundaries; empty in the library build.
@@ -316,6 +318,17 @@ __host__ __device__ constexpr int table_source(int i) {
   return k < 12 ? OFF_B2 + k
                 : k >= TAB_BIAS_B && k < TAB_BIAS_B + NY ? OFF_B + (k - TAB_BIAS_B)
                                                          : k >= TAB_BIAS_B1 ? OFF_B1 + (k - TAB_BIAS_B1) : -1;
+}
+// Factor a slot holds its parameter multiplied by: the forward weights and biases of both
+// convolution layers carry -log2(e) (see logistic_of_scaled); the C2 input-error operand carries the
+// 1/4 of the average pooling below it (backavgpool, Section 3), which the C1 error then does not apply.
+__host__ __device__ constexpr float table_scale(int i) {
+  if (i < TABG_K1T) {
+    const int e = i >> 6;
+    return e < TAB_FCW ? NEG_LOG2E : e >= TAB_AB && e < TAB_C1A ? 0.25f : 1.0f;
+  }
+  if (i < TABG_BIAS) return NEG_LOG2E;
+  return i - TABG_BIAS < 12 ? NEG_LOG2E : 1.0f;
 }
 // No parameter sits in more than four slots (a C1 weight: once by tap, twice as shifted GEMM operand):
 // the SGD kernel refreshes the expanded table by writing every updated parameter to its recorded places.
@@ -629,26 +642,22 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
   {
     CNN_PHASE_LANES;
     const float* ip[9];
-    {
-      const f4 ba = *reinterpret_cast<const f4*>(&tab.k1t[25 * 8]);
-      const float2 bb = *reinterpret_cast<const float2*>(&tab.k1t[25 * 8 + 4]);
-      // training: the window origins come from the shared table, re-read per image
+    // training: the window origins come from the shared table, re-read per image
 #pragma unroll
-      for (int g = 0; g < 9; ++g) {
-        ip[g] = s.img + (MODE == kTrain ? wt->o[16 * g + b].x : st.pix0[g]) + (sub >> 1) * 28 + (sub & 1);
-        c1[g][0] = ba[0]; c1[g][1] = ba[1]; c1[g][2] = ba[2]; c1[g][3] = ba[3];
-        c1[g][4] = bb.x;  c1[g][5] = bb.y;
-      }
-    }
-    // The loop over kernel rows is a real loop: its body holds 45 pixel reads, 10 broadcast weight
-    // reads and 270 multiply-adds, and the 54 accumulators are carried around it, which keeps the
-    // compiler from hoisting all 225 reads (and their registers) or serialising the sums.
-#pragma unroll 1
-    for (int u = 0; u < 5; ++u) {
+    for (int g = 0; g < 9; ++g)
+      ip[g] = s.img + (MODE == kTrain ? wt->o[16 * g + b].x : st.pix0[g]) + (sub >> 1) * 28 + (sub & 1);
+    // One kernel row u: 45 pixel reads, 10 broadcast weight reads and 270 multiply-adds.  The reads
+    // of tap v + 1 are issued before the multiply-adds of tap v and no earlier (two sets of nine
+    // pixels and six weights in registers, not five).  FIRST: the sums start here, at the biases.
+    auto kernel_row = [&](int u, auto first) {
+      constexpr bool FIRST = decltype(first)::value;
       const float* ku = tab.k1t + u * 40;
-      // the reads of tap v + 1 are issued before the multiply-adds of tap v and no earlier (two
-      // sets of nine pixels and six weights in registers, not five)
-      float x[2][9], wt[2][6];
+      float x[2][9], wt[2][6], bias[6];
+      if (FIRST) {
+        const f4 ba = *reinterpret_cast<const f4*>(&tab.k1t[25 * 8]);
+        const float2 bb = *reinterpret_cast<const float2*>(&tab.k1t[25 * 8 + 4]);
+        bias[0] = ba[0]; bias[1] = ba[1]; bias[2] = ba[2]; bias[3] = ba[3]; bias[4] = bb.x; bias[5] = bb.y;
+      }
       auto load_tap = [&](int v, float (&xx)[9], float (&ww)[6]) {
         const f4 wa = *reinterpret_cast<const f4*>(&ku[v * 8]);
         const float2 wb = *reinterpret_cast<const float2*>(&ku[v * 8 + 4]);
@@ -657,18 +666,23 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
         for (int g = 0; g < 9; ++g) xx[g] = ip[g][u * 28 + v];
       };
       load_tap(0, x[0], wt[0]);
-      __builtin_amdgcn_sched_group_barrier(0x100, 11, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, FIRST ? 13 : 11, 0);
 #pragma unroll
       for (int v = 0; v < 5; ++v) {
         if (v < 4) load_tap(v + 1, x[(v + 1) & 1], wt[(v + 1) & 1]);
 #pragma unroll
         for (int i = 0; i < 6; ++i)
 #pragma unroll
-          for (int g = 0; g < 9; ++g) c1[g][i] = fmaf(wt[v & 1][i], x[v & 1][g], c1[g][i]);
+          for (int g = 0; g < 9; ++g) c1[g][i] = fmaf(wt[v & 1][i], x[v & 1][g], FIRST && v == 0 ? bias[i] : c1[g][i]);
         if (v < 4) __builtin_amdgcn_sched_group_barrier(0x100, 11, 0);
         __builtin_amdgcn_sched_group_barrier(0x002, 54, 0);
       }
-    }
+    };
+    // Row 0 is written out; rows 1..4 are a real loop with the 54 sums carried around it, which keeps
+    // the compiler from hoisting all 225 reads (and their registers) or serialising the sums.
+    kernel_row(0, std::true_type());
+#pragma unroll 1
+    for (int u = 1; u < 5; ++u) kernel_row(u, std::false_type());
     // sigmoid, then S1 = avgpool(C1): the four lanes of a quad are the four pixels of one window.
     // A butterfly with selects leaves the window sum of map `sub` in lane `sub`, so one unmasked
     // store per group writes four maps (no divergent store, nothing for the scheduler to trip on).
@@ -677,7 +691,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
     for (int g = 0; g < 9; ++g) {
 #pragma unroll
       for (int i = 0; i < 6; ++i) {
-        c1[g][i] = logistic(c1[g][i]);
+        c1[g][i] = logistic_of_scaled(c1[g][i]);
         if (MODE == kForwardDump && dump.c1) {
           const int win = 16 * g + b;
           dump.c1[n * NC1 + i * 576 + (2 * (win / 12) + (sub >> 1)) * 24 + 2 * (win % 12) + (sub & 1)] = c1[g][i];
@@ -735,7 +749,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) c2v[mt][r] = logistic(c2v[mt][r]);
+      for (int r = 0; r < 4; ++r) c2v[mt][r] = logistic_of_scaled(c2v[mt][r]);
       if (n16 < 12) s.pool[P_S2 + n16 * 16 + 4 * mt + q] = 0.25f * ((c2v[mt][0] + c2v[mt][1]) + (c2v[mt][2] + c2v[mt][3]));
       if (MODE == kForwardDump && dump.c2 && n16 < 12)
 #pragma unroll
@@ -981,7 +995,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
 #pragma unroll
           for (int i = 0; i < 6; ++i) {
             const float c = c1[g][i];
-            const float d1 = up[k][i] * 0.25f * c * (1.0f - c);
+            const float d1 = up[k][i] * (c * (1.0f - c));  // the pooling's 1/4 is in the operand table
             st.g_b1[i] += d1;
             dst[i * D1C_MAP] = d1;
           }
