@@ -178,21 +178,32 @@ __device__ __forceinline__ void group_train(const float* __restrict__ image,
       const float* a12 = s.pool + P_S1 + pp + 12 * q + 24 * wave;
       const float* a1 = s.pool + P_S1 + pp + q + 24 * wave;
       const float* a144 = s.pool + P_S1 + pp + 144 * q + 24 * wave;
-      float opa[3], opw[3];
+      // operands of step s + AHEAD are read while step s issues: an LDS read takes longer than three
+      // matrix instructions, and with eight waves per image there are registers to spare
+      constexpr int AHEAD = 6, SLOTS = 8;
+      float opa[SLOTS], opw[SLOTS];
       auto load_step = [&](int sidx, float& oa, float& ow) {
         const float* base = sidx < 30 ? a12 : sidx < 36 ? a1 : a144;
         ow = tl[(TAB_BF + sidx) * 64];
         oa = base[fwd_imm(sidx)];
       };
-      load_step(0, opa[0], opw[0]);
-      load_step(1, opa[1], opw[1]);
+#pragma unroll
+      for (int sidx = 0; sidx < AHEAD; ++sidx) load_step(sidx, opa[sidx], opw[sidx]);
+      // even and odd K steps in two sums: a matrix instruction waits for the previous one of its own
+      // chain only
+      f4 odd = f4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
       for (int sidx = 0; sidx < 38; ++sidx) {
-        if (sidx + 2 < 38) load_step(sidx + 2, opa[(sidx + 2) % 3], opw[(sidx + 2) % 3]);
-        c2v = mfma16(opa[sidx % 3], opw[sidx % 3], c2v);
+        if (sidx + AHEAD < 38) load_step(sidx + AHEAD, opa[(sidx + AHEAD) % SLOTS], opw[(sidx + AHEAD) % SLOTS]);
+        if (sidx & 1)
+          odd = mfma16(opa[sidx % SLOTS], opw[sidx % SLOTS], odd);
+        else
+          c2v = mfma16(opa[sidx % SLOTS], opw[sidx % SLOTS], c2v);
+        if (sidx + AHEAD < 38) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       }
 #pragma unroll
-      for (int r = 0; r < 4; ++r) c2v[r] = logistic_of_scaled(c2v[r]);
+      for (int r = 0; r < 4; ++r) c2v[r] = logistic_of_scaled(c2v[r] + odd[r]);
       if (n16 < 12) s.pool[P_S2 + n16 * 16 + 4 * wave + q] = 0.25f * ((c2v[0] + c2v[1]) + (c2v[2] + c2v[3]));
     }
     CNN_GROUP_MARK(4);
