@@ -45,7 +45,9 @@ typedef struct cnn_ctx cnn_ctx; /* opaque, host memory owned by the library */
 const char* cnn_strerror(int code);
 
 /* Device bytes cnn_init needs for batches of up to max_batch images (weights, their copy laid out
- * as the kernels' matrix operands, per-workgroup gradient partials, reduction scratch).
+ * as the kernels' matrix operands, per-workgroup gradient partials, reduction scratch, and for
+ * max_batch above 640 one KiB per image: the pooled C2 output and the output error of every image of
+ * a batch, from which the fully connected layer's weight gradient is taken once per batch).
  * 0 if max_batch < 1. */
 size_t cnn_workspace_bytes(int max_batch);
 

@@ -122,7 +122,6 @@ __global__ __launch_bounds__(64) void eval_reduce_kernel(const float* __restrict
 // their gradient sums through LDS in a fixed order and the workgroup writes ONE partial row,
 // partial[blockIdx.x][PSTRIDE], with 16-byte stores (a wave without images contributes zeros).
 constexpr int TWAVES = 8;
-constexpr int FC_ACC_FLOATS = 30 * 64;  // per wave: the FC weight-gradient sums, [3 o + k][lane]
 // Which of a workgroup's K images each wave takes.  The images are dealt in rounds: a full round
 // gives one image to each of the eight waves, a half round one to each of waves 0..3 only; the
 // pattern of SHARE_ROUNDS rounds repeats every SHARE_PERIOD images.  A function of K and the wave
@@ -188,7 +187,7 @@ struct WaveShare {
 };
 __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 2))) void train_kernel(
     const float* __restrict__ images, const int32_t* __restrict__ labels, int B, const float* __restrict__ tabg,
-    float* __restrict__ partial, float* __restrict__ fc_acc) {
+    float* __restrict__ partial, float* fc_hist) {
   __shared__ OperandTable<TAB_WAVE_ENTRIES> tab;
   __shared__ WaveTrainLds lds[TWAVES];
   __shared__ WindowTable wt;
@@ -206,11 +205,6 @@ __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 
   // waves without images skip their set-up and their row
   if (has_images) {
     wave_init(st, s);
-    // this wave's FC weight-gradient sums start at zero (global memory, see WaveState)
-    st.fc_acc = __builtin_amdgcn_make_buffer_rsrc(fc_acc + ((size_t)blockIdx.x * TWAVES + wave) * FC_ACC_FLOATS, 0,
-                                                  sizeof(float) * FC_ACC_FLOATS, 0x00020000);
-#pragma unroll
-    for (int j = 0; j < 30; ++j) fc_acc_store(st.fc_acc, j, 0.0f, threadIdx.x & 63);
     store_pixels(s.img, px);
   }
   __syncthreads();  // the operand and window tables are complete
@@ -222,11 +216,37 @@ __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 
     const size_t n = image_index(mine.k());
     mine.advance();
     const size_t nn = mine.left > 0 ? image_index(mine.k()) : n;
-    wave_image<kTrain>(st, s, tab, px, images + nn * NI, labels[n], y, none, n, &wt);
+    wave_image<kTrain>(st, s, tab, px, images + nn * NI, labels[n], y, none, n, &wt, fc_hist + n * FC_HIST);
   }
   CNN_KERNEL_MARK(2);
+  // FC weight gradient: a second walk over this wave's images, four per K step (the history rows
+  // have left the L2 cache by now; a wave that is done early does this while the others still work)
+  f4 g_fc[12];
+  if (has_images) {
+#pragma unroll
+    for (int nt = 0; nt < 12; ++nt) g_fc[nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    // this wave's stores to its history rows are complete before it reads them back
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    WaveShare again(K, wave);
+    while (again.left > 0) {
+      const float* rows[4];
+      const float* row = nullptr;
+      const int count = again.left < 4 ? again.left : 4;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (again.left > 0) {
+          row = fc_hist + image_index(again.k()) * FC_HIST;
+          again.advance();
+        }
+        rows[k] = row;  // past the last image: the last one again (count masks its delta)
+      }
+      FcStepOperands op;
+      fc_step_load(op, rows, count);
+      fc_step_mfma(g_fc, op);
+    }
+  }
   __syncthreads();  // every wave is done with the operand table: its storage parks the C1 GEMM results
-  if (has_images) wave_flush(st, reinterpret_cast<float*>(&s), tab.e + wave * C1G_PARK);
+  if (has_images) wave_flush(st, g_fc, reinterpret_cast<float*>(&s), tab.e + wave * C1G_PARK);
   __syncthreads();
   {
     // rows of the waves that had images in a fixed tree; an idle wave's row counts as zeros
@@ -453,7 +473,7 @@ struct cnn_ctx {
   int32_t* dest;        // [PSTRIDE][TABLE_MAX_DEST]: slots of tabg that hold parameter p
   float* partial;       // [partial_rows_for(max_batch)][PSTRIDE]
   float* eval_partial;  // [gcap][2]
-  float* fc_acc;        // [TRAIN_BLOCKS * TWAVES][FC_ACC_FLOATS] when max_batch > GROUP_MAX_BATCH
+  float* fc_hist;       // [max_batch][FC_HIST] when max_batch > GROUP_MAX_BATCH: per image, what the FC weight gradient needs
   unsigned* sync;       // [SYNC_WORDS]: barrier flags of the device-side epoch loop, then its error word
   int epoch_mode = 0;         // 1: cnn_train_epoch runs as one kernel where it can
   long long wait_ticks = 0;   // longest wait at a grid barrier, in ticks of the 100 MHz wall clock
@@ -475,7 +495,7 @@ inline int gcap_for(int max_batch, int cap = GCAP) {
 }
 
 struct Layout {
-  size_t w, tabg, dest, partial, eval_partial, fc_acc, sync, total;
+  size_t w, tabg, dest, partial, eval_partial, fc_hist, sync, total;
 };
 
 // Partial rows a step can write: one per workgroup, in the one-wave-per-image kernel (four waves
@@ -494,10 +514,10 @@ inline Layout layout_for(int max_batch) {
   l.dest = align_up(l.tabg + sizeof(float) * TABG_FLOATS, 256);
   l.partial = align_up(l.dest + sizeof(int32_t) * TABLE_MAX_DEST * PSTRIDE, 256);
   l.eval_partial = align_up(l.partial + sizeof(float) * PSTRIDE * g, 256);
-  l.fc_acc = align_up(l.eval_partial + sizeof(float) * 2 * (size_t)gcap_for(max_batch, FWD_GCAP), 256);
+  l.fc_hist = align_up(l.eval_partial + sizeof(float) * 2 * (size_t)gcap_for(max_batch, FWD_GCAP), 256);
   // only the large-batch kernel keeps sums in global memory; it never launches more workgroups than images
-  const size_t train_waves = max_batch > GROUP_MAX_BATCH ? (size_t)TWAVES * (max_batch < TRAIN_BLOCKS ? max_batch : TRAIN_BLOCKS) : 0;
-  l.sync = align_up(l.fc_acc + sizeof(float) * FC_ACC_FLOATS * train_waves, 256);
+  const size_t hist_rows = max_batch > GROUP_MAX_BATCH ? (size_t)max_batch : 0;
+  l.sync = align_up(l.fc_hist + sizeof(float) * FC_HIST * hist_rows, 256);
   l.total = align_up(l.sync + sizeof(unsigned) * SYNC_WORDS, 256);
   return l;
 }
@@ -556,7 +576,7 @@ int run_backward(cnn_ctx* ctx, const float* images, const int32_t* labels, int B
   if (grouped)
     train_group_kernel<<<blocks, 64 * GWAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, ctx->partial);
   else
-    train_kernel<<<blocks, 64 * TWAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, ctx->partial, ctx->fc_acc);
+    train_kernel<<<blocks, 64 * TWAVES, 0, ctx->stream>>>(images, labels, B, ctx->tabg, ctx->partial, ctx->fc_hist);
   if (hipGetLastError() != hipSuccess) return CNN_EHIP;
   if (timed) {
     CNN_HIP_TRY(hipEventRecord(ctx->ev[2 * ctx->ev_used + 1], ctx->stream));
@@ -628,7 +648,7 @@ int cnn_init(cnn_ctx** out, void* workspace, size_t workspace_bytes, int max_bat
   ctx->dest = reinterpret_cast<int32_t*>(base + l.dest);
   ctx->partial = reinterpret_cast<float*>(base + l.partial);
   ctx->eval_partial = reinterpret_cast<float*>(base + l.eval_partial);
-  ctx->fc_acc = reinterpret_cast<float*>(base + l.fc_acc);
+  ctx->fc_hist = reinterpret_cast<float*>(base + l.fc_hist);
   ctx->sync = reinterpret_cast<unsigned*>(base + l.sync);
   ctx->wait_ticks = 100000000ll;  // one second
   {

@@ -504,16 +504,15 @@ __device__ __forceinline__ void window_table_init(WindowTable& w) {
     w.o[win] = int2{56 * (win / 12) + 2 * (win % 12), 48 * (win / 12) + 2 * (win % 12)};
 }
 
-// Entry j (of 30) of a wave's FC sums in global memory: 256 bytes per entry, addressed as a scalar
-// base (the descriptor), a scalar 4 KB step and a 12-bit immediate, so that no vector register holds
-// an address.
-__device__ __forceinline__ float fc_acc_load(__amdgpu_buffer_rsrc_t r, int j, int l) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, 4 * l + 256 * (j & 15), 4096 * (j >> 4), 0));
-}
-__device__ __forceinline__ void fc_acc_store(__amdgpu_buffer_rsrc_t r, int j, float v, int l) {
-  __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, 4 * l + 256 * (j & 15), 4096 * (j >> 4), 0);
-}
-
+// What the FC weight gradient needs of one image, kept in global memory until the wave has done all
+// its images: s2 (192 floats), then delta in [192, 202) and zeros up to 208; rows of 256 floats, so
+// that no two images share a cache line.  The gradient is then ONE GEMM per wave over its images,
+//   g_fc[o][i] = sum_n delta_n[o] * s2_n[i]                                   (backweights, Section 3)
+// with M = 10(16) outputs, N = 192 inputs in twelve tiles, K = the wave's images four at a time:
+// three matrix instructions per image instead of thirty multiply-adds on sums that no register or LDS
+// space is left for.
+constexpr int FC_HIST = 256;        // floats per image
+constexpr int FC_HIST_DELTA = 192;  // delta[0..9], then six zeros
 // Everything a wave keeps in registers across its images.
 template <int MODE>
 struct WaveState {
@@ -522,9 +521,6 @@ struct WaveState {
   // training only
   f4 acc_k2[10];  // sum over images of d_c2 (x) s1 patches, D[j = 4q+r][tap = 16 nt + n16]
   f4 acc_k1[2];   // C1 weight gradient GEMM result T[(m,sh) = 4q+r][c = 16 nt + n16]
-  __amdgpu_buffer_rsrc_t fc_acc;  // FC weight gradient sums of this wave in global memory, [30][64]:
-                                  // entry 3 o + k, lane l is g_fc[o][l + 64 k] (read, updated and written
-                                  // back once per image); a buffer descriptor in scalar registers
   float g_b;      // FC bias gradient: lane o < 10 holds b[o]
   float g_b1[6], g_b2, loss;
 };
@@ -551,7 +547,6 @@ __device__ __forceinline__ void wave_init(WaveState<MODE>& st, typename LdsOf<MO
     st.g_b2 = 0.0f;
     st.loss = 0.0f;
     st.g_b = 0.0f;
-    // st.fc_acc is set by the kernel
   }
 }
 
@@ -614,13 +609,14 @@ __device__ __forceinline__ void touch_pixels(const float* __restrict__ image) {
 // image is still being worked on, so the HBM latency of the only per-image global read is hidden.
 // Training: the image is in s.img on entry and `next_image` (never null: the caller passes any
 // valid image when there is no next one) is in s.img on return; `px` is not used.  Returns yhat in y[10]
-// (wave-uniform).  `label` is only read when training.
+// (wave-uniform).  `label` is only read when training; `hist` is the image's history row (FC_HIST
+// floats, training only).
 template <int MODE>
 __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<MODE>::type& s,
                                            const OperandTable<LdsOf<MODE>::entries>& tab, Pixels& px,
                                            const float* __restrict__ next_image, int label,
                                            float (&y)[10], const DumpPtrs& dump,
-                                           size_t n, const WindowTable* wt = nullptr) {
+                                           size_t n, const WindowTable* wt = nullptr, float* hist = nullptr) {
   constexpr int P_S1 = LdsOf<MODE>::S1, P_S2 = LdsOf<MODE>::S2;
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15, b = l >> 2, sub = l & 3;
   const int pp = 12 * ((n16 & 3) >> 1) + 2 * (n16 >> 2) + (n16 & 1);
@@ -764,17 +760,10 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
   CNN_PHASE(3);
   // ---- output = sigmoid(mconv(S2, fc, b)): lane owns inputs lane, lane+64, lane+128 ----------------
   float sv[3];
-  // training: this wave's FC weight-gradient sums come from global memory (they stay in the L2
-  // cache between images); the loads are in flight during the output layer
-  float fcv[MODE == kTrain ? 30 : 1];
   {
     CNN_PHASE_LANES;
 #pragma unroll
     for (int k = 0; k < 3; ++k) sv[k] = s.pool[P_S2 + l + 64 * k];
-    if constexpr (MODE == kTrain) {
-#pragma unroll
-      for (int j = 0; j < 30; ++j) fcv[j] = fc_acc_load(st.fc_acc, j, l);
-    }
 #pragma unroll
     for (int o = 0; o < 10; ++o) {
       float p = tl[(TAB_FCW + 3 * o) * 64] * sv[0];
@@ -796,18 +785,17 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
       }
       st.loss = fmaf(0.5f, lsum, st.loss);
     }
-    // backweights as rank-1 updates, g_fc[o][lane + 64 k] += delta[o] * s2[lane + 64 k] (delta is
-    // wave-uniform), on the sums fetched above; backbias: lane o keeps the sum of delta[o].
+    // backweights: s2 and delta go to the image's history row, the products are taken once per
+    // wave (wave_fc_gradient); backbias: lane o keeps the sum of delta[o].
     {
       CNN_PHASE_LANES;
       float mine = 0.0f;
 #pragma unroll
-      for (int o = 0; o < 10; ++o) {
-        mine = l == o ? delta[o] : mine;
-#pragma unroll
-        for (int k = 0; k < 3; ++k) fc_acc_store(st.fc_acc, 3 * o + k, fmaf(delta[o], sv[k], fcv[3 * o + k]), l);
-      }
+      for (int o = 0; o < 10; ++o) mine = l == o ? delta[o] : mine;
       st.g_b += mine;
+#pragma unroll
+      for (int k = 0; k < 3; ++k) hist[l + 64 * k] = sv[k];
+      if (l < 16) hist[FC_HIST_DELTA + l] = mine;  // zero in lanes 10..15
 #pragma unroll
       for (int k = 0; k < 3; ++k) {
         float d = 0.0f;
@@ -1024,17 +1012,39 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
   }
 }
 
+// FC weight gradient of a wave from the history rows of its images (see FC_HIST).  One K step of the
+// GEMM takes up to four images: lane (q, n16) supplies A[o = n16][k = q] = delta of the step's q-th
+// image and B[k = q][i = n16] = its s2[16 nt + n16] for the twelve tiles nt.  Result tile nt,
+// register r of lane (q, n16): g_fc[o = 4 q + r][i = 16 nt + n16].
+struct FcStepOperands {
+  float a, b[12];
+};
+// rows[k] points at the row of the step's k-th image, or at any valid row when the step has fewer
+// than four (`count` says how many are real: the others contribute delta = 0).
+__device__ __forceinline__ void fc_step_load(FcStepOperands& op, const float* const (&rows)[4], int count) {
+  const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
+  const float* mine = q == 0 ? rows[0] : q == 1 ? rows[1] : q == 2 ? rows[2] : rows[3];
+  op.a = mine[FC_HIST_DELTA + n16];
+  if (q >= count) op.a = 0.0f;
+#pragma unroll
+  for (int nt = 0; nt < 12; ++nt) op.b[nt] = mine[16 * nt + n16];
+}
+__device__ __forceinline__ void fc_step_mfma(f4 (&g_fc)[12], const FcStepOperands& op) {
+#pragma unroll
+  for (int nt = 0; nt < 12; ++nt) g_fc[nt] = mfma16(op.a, op.b[nt], g_fc[nt]);
+}
+
 // Writes the wave's gradient sums as one partial row (PSTRIDE floats in parameter order, the loss
 // in LOSS_SLOT, zeros after it) to `row`, every slot by exactly one lane.  `row` may be the start
 // of the wave's own LDS area (all of it is dead once the wave's images are done); `park` is
-// C1G_PARK floats of LDS outside the row that no other wave uses.
-__device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, float* row, float* park) {
+// C1G_PARK floats of LDS outside the row that no other wave uses; `g_fc` is wave_fc_gradient's result.
+__device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, const f4 (&g_fc)[12], float* row, float* park) {
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
 #pragma unroll
-  for (int o = 0; o < 10; ++o) {
+  for (int nt = 0; nt < 12; ++nt)
 #pragma unroll
-    for (int k = 0; k < 3; ++k) row[OFF_FC + o * NS2 + l + 64 * k] = fc_acc_load(st.fc_acc, 3 * o + k, l);
-  }
+    for (int r = 0; r < 4; ++r)
+      if (4 * q + r < 10) row[OFF_FC + (4 * q + r) * NS2 + 16 * nt + n16] = g_fc[nt][r];
   if (l < 10) row[OFF_B + l] = st.g_b;
   if (l < PSTRIDE - LOSS_SLOT) row[LOSS_SLOT + l] = l == 0 ? st.loss : 0.0f;
 #pragma unroll
