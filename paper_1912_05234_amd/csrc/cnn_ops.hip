@@ -262,9 +262,11 @@ unsigned resident_workgroups(size_t lds_bytes) {
 }
 
 // LDS cycles of the gathered-operand reads of the first two column tiles over the first K steps, in
-// the usual model of the 32 four-byte banks: a wave's read is served in two halves of 32 lanes, and a
-// half takes as many cycles as the largest number of different words that fall into one bank.
+// a model of the 64 four-byte banks (measured: a 64-lane read of every second word costs what a read of
+// consecutive words costs, every fourth word twice as much): a wave's read is served in two halves of
+// 32 lanes, and a half takes as many cycles as the largest number of different words that fall into one bank.
 // Lane (q, j) of K step s reads word koff(4 s + q) + poff(16 tile + j).
+constexpr int LDS_BANKS = 64;
 int gather_read_cost(int LW, int LP, int LI, int KH, int KWP, int K, int OWP, int COLS, int P) {
   const int steps = (K + 3) / 4 < 16 ? (K + 3) / 4 : 16;
   int cost = 0;
@@ -277,11 +279,11 @@ int gather_read_cost(int LW, int LP, int LI, int KH, int KWP, int K, int OWP, in
           const int c = kk / (KH * KWP), rem = kk % (KH * KWP), img = n / COLS, r = n % COLS;
           word[l] = (kk < K ? c * LP + (rem / KWP) * LW + rem % KWP : 0) + img * LI + (r / OWP) * LW + P * (r % OWP);
         }
-        int per_bank[32] = {0};  // different words per bank: each word counted at its first lane
+        int per_bank[LDS_BANKS] = {0};  // different words per bank: each word counted at its first lane
         for (int l = 0; l < 32; ++l) {
           bool first = true;
           for (int e = 0; e < l; ++e) first = first && word[e] != word[l];
-          if (first && ++per_bank[word[l] & 31] > worst) worst = per_bank[word[l] & 31];
+          if (first && ++per_bank[word[l] & (LDS_BANKS - 1)] > worst) worst = per_bank[word[l] & (LDS_BANKS - 1)];
         }
         cost += worst;
       }

@@ -1,5 +1,5 @@
 """Device-side epoch loop (cnn_epoch_mode(ctx, 1, ...)): bitwise the weights and losses of the
-two-kernel step, the oracle's to 1e-4, reproducible, and a give-up path that can be forced from the
+two-kernel step, the oracle's to parity.RTOL_W, reproducible, and a give-up path that can be forced from the
 host so that every kernel still exits normally."""
 import numpy as np
 import pytest

@@ -115,7 +115,7 @@ def run_training(net, images, labels, batch, lr):
 
 
 def test_small_training_configuration():
-    """1000 images, batch 100, rate 0.05, one epoch: every weight within 1e-4 of the oracle."""
+    """1000 images, batch 100, rate 0.05, one epoch: every weight within parity.RTOL_W (1e-5) of the oracle."""
     images, labels = inputs.make_batch(1000, 24)
     w = weights()
     net = binding.CNN(w, max_batch=100)
@@ -148,7 +148,7 @@ def test_small_training_configuration():
 
 
 def test_epoch_call_matches_the_oracle_and_the_per_batch_calls():
-    """cnn_train_epoch over 450 images in batches of 100 (last batch 50): weights within 1e-4 of the
+    """cnn_train_epoch over 450 images in batches of 100 (last batch 50): weights within parity.RTOL_W (1e-5) of the
     oracle's five steps, per-step losses, and bitwise equal to five cnn_train_batch calls."""
     images, labels = inputs.make_batch(450, 31)
     w = weights(biases=True)
