@@ -282,7 +282,7 @@ __device__ __forceinline__ void group_train(const float* __restrict__ image,
       for (int sidx = 0; sidx < 3; ++sidx)
 #pragma unroll
         for (int j = 0; j < 2; ++j) bd[sidx][j] = s.pool[P_D2 + (4 * sidx + q) * D2S + 16 * (2 * h + j) + n16];
-      const float* ta = tl + (TAB_AB + cg * 21) * 64;
+      const float* ta = tl + (cg ? TAB_AB1 : TAB_AB) * 64;
       f4 t4[2];
       float t44[2];
       {

@@ -93,6 +93,8 @@ constexpr int W_S2 = W_S1 + NS1;         // s2[192]
 constexpr int W_DS2 = W_S2 + NS2;        // d_s2[192] + 64
 constexpr int W_D2 = W_DS2 + NS2 + 64;   // d2[12][D2S]
 constexpr int W_END = W_D2 + 12 * D2S;
+constexpr int W_DS1_COPY = 304;          // second copy of d_s1's maps 4, 5 over d2: 2 x 144 + the reach of a padding column
+static_assert(W_DS1_COPY % 4 == 0 && W_DS1_COPY <= 12 * D2S, "the copy fits over d2");
 constexpr int D1C_MAP = 8 * 24 + 4;
 constexpr int WPOOL_FLOATS = PSTRIDE - NS1 - NI;
 static_assert(WPOOL_FLOATS >= W_END && 6 * D1C_MAP <= W_D2, "pool holds the arrays; a d1 chunk ends before d2");
@@ -106,10 +108,12 @@ static_assert(sizeof(WaveTrainLds) == sizeof(float) * PSTRIDE, "a wave's LDS are
 constexpr int TAB_BF = 0;          // 38: C2 forward B operand, k2[j = n16][tap(s, q)]
 constexpr int TAB_FCW = 38;        // 30: fc[o][lane + 64 k] at entry 3 o + k
 constexpr int TAB_FWD_ENTRIES = 68;
-constexpr int TAB_AB = 68;         // 42: C2 input-error A operand, entry (cg*7 + tile)*3 + s
-constexpr int TAB_C1A = 110;       // 8: C1 forward A operand of the small-batch kernel, W[(m,sh) = n16][tap 4 ks + q]
-constexpr int TAB_WAVE_ENTRIES = TAB_C1A;  // what the one-wave-per-image training kernel reads
-constexpr int TAB_TRAIN_ENTRIES = 118;
+constexpr int TAB_AB = 68;         // 21: C2 input-error A operand of input maps 0..3, entry tile*3 + s
+constexpr int TAB_PK = 89;         // 12: the same for input maps 4, 5 with two taps per tile (bwd_packed_tap), entry tile*3 + s
+constexpr int TAB_WAVE_ENTRIES = 101;  // what the one-wave-per-image training kernel reads
+constexpr int TAB_AB1 = 101;       // 21: input maps 4..7 in the plain form of TAB_AB (the small-batch kernel)
+constexpr int TAB_C1A = 122;       // 8: C1 forward A operand of the small-batch kernel, W[(m,sh) = n16][tap 4 ks + q]
+constexpr int TAB_TRAIN_ENTRIES = 130;
 // After the [entry][lane] part: C1 weights by tap, k1t[tap][8] = k1[0..5][tap], 0, 0 for tap < 25 and
 // the biases b1 in row 25; every lane reads the same row (an LDS broadcast).
 constexpr int K1T_FLOATS = 26 * 8;
@@ -202,6 +206,18 @@ __host__ __device__ constexpr int fwd_imm(int s) {
 enum BwdTile { kTileV0 = 0, kTileU4 = 5, kTileC = 6 };  // V(v) = kTileV0 + v
 __host__ __device__ constexpr int bwd_tap(int tile, int ri) {
   return tile < 5 ? 5 * ri + tile : tile == kTileU4 ? 20 + ri : (ri == 0 ? 24 : -1);
+}
+// Packed tiles for input maps 4 and 5 (a plain tile would leave the rows of maps 6, 7 empty): rows
+// qi = 0, 1 belong to map 4 + qi and the taps of columns v = 0, 1, 2; rows qi = 2, 3 to map 4 + (qi - 2)
+// again and the taps of columns v = 3, 4, whose terms are added into a second copy of the two maps
+// (lanes of both halves would otherwise meet in the same cells within a round).
+//   tile PV(s), s < 3 : qi < 2: (u = ri, v = s)       qi >= 2: (u = ri, v = 3 + s) for s < 2, nothing for s = 2
+//   tile PU           : qi < 2: (4, v = ri), ri < 3   qi >= 2: ri = 0: (4, 3), ri = 1: (4, 4)
+// so that in round s every lane finds "its" u = 4 term in result register s of PU.
+enum PackedTile { kTilePV0 = 0, kTilePU = 3 };
+__host__ __device__ constexpr int bwd_packed_tap(int tile, int qi, int ri) {
+  if (tile < 3) return qi < 2 ? 5 * ri + tile : (tile < 2 ? 5 * ri + 3 + tile : -1);
+  return qi < 2 ? (ri < 3 ? 20 + ri : -1) : (ri < 2 ? 23 + ri : -1);
 }
 // ---- C1 forward as a GEMM (16x16x4 MFMA) -----------------------------------------------------------
 // Output pixels are taken in horizontal pairs x = 2X + sh (sh = 0, 1).  With v' = v + sh the image
@@ -306,7 +322,12 @@ __host__ __device__ constexpr int table_source(int i) {
       return OFF_FC + o * NS2 + l + 64 * k;
     }
     if (e >= TAB_C1A) return c1f_weight(e - TAB_C1A, l);
-    const int t = e - TAB_AB, sidx = t % 3, tile = (t / 3) % 7, cg = t / 21;
+    if (e >= TAB_PK && e < TAB_AB1) {
+      const int t = e - TAB_PK, sidx = t % 3, tile = t / 3, qi = n16 >> 2;
+      const int c = 4 + (qi & 1), tap = bwd_packed_tap(tile, qi, n16 & 3);
+      return tap >= 0 ? OFF_K2 + (4 * sidx + q) * 150 + c * 25 + tap : -1;
+    }
+    const int cg = e >= TAB_AB1 ? 1 : 0, t = e - (cg ? TAB_AB1 : TAB_AB), sidx = t % 3, tile = t / 3;
     const int c = 4 * cg + (n16 >> 2), tap = bwd_tap(tile, n16 & 3);
     return c < 6 && tap >= 0 ? OFF_K2 + (4 * sidx + q) * 150 + c * 25 + tap : -1;
   }
@@ -877,80 +898,99 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
       for (int sidx = 0; sidx < 3; ++sidx)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) bd[sidx][nt] = s.pool[W_D2 + (4 * sidx + q) * D2S + 16 * nt + n16];
-#pragma unroll
-      for (int cg = 0; cg < 2; ++cg) {
-        f4 t4[4];      // taps (4, v), v < 4, in register v
-        float t44[4];  // tap (4, 4)
+      // the second copy of maps 4 and 5 (see bwd_packed_tap) lies over d2, which is in registers now
+      float* copy = s.pool + W_D2;
+      wave_sync();
+      for (int e = l; e < W_DS1_COPY / 4; e += 64) reinterpret_cast<f4*>(copy)[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+      wave_sync();
+      // One round pair (even levels, then odd levels) for the tiles tv of one tap column: `u4` is the
+      // u = 4 term per pixel tile, `dst` the lane's cell of level 0 for that column.
+      auto rounds = [&](const f4 (&tv)[4], const float (&u4)[4], float* dst) {
+        // even levels 2m, m < 6: (nt = m, u = 0) + (m-1, 2) + (m-2, 4)
         {
-          float au[3], ac[3];
+          float e[6], old[6];
 #pragma unroll
-          for (int sidx = 0; sidx < 3; ++sidx) {
-            au[sidx] = tl[(TAB_AB + (cg * 7 + kTileU4) * 3 + sidx) * 64];
-            ac[sidx] = tl[(TAB_AB + (cg * 7 + kTileC) * 3 + sidx) * 64];
+          for (int m = 0; m < 6; ++m) {
+            float acc = 0.0f;
+            if (m < 4) acc = tv[m < 4 ? m : 0][0];
+            if (m >= 1 && m <= 4) acc += tv[m >= 1 ? m - 1 : 0][2];
+            if (m >= 2) acc += u4[m >= 2 ? m - 2 : 0];
+            e[m] = acc;
+            old[m] = dst[24 * m];
           }
 #pragma unroll
-          for (int nt = 0; nt < 4; ++nt) {
-            f4 a = f4{0.0f, 0.0f, 0.0f, 0.0f}, c = a;
-#pragma unroll
-            for (int sidx = 0; sidx < 3; ++sidx) {
-              a = mfma16(au[sidx], bd[sidx][nt], a);
-              c = mfma16(ac[sidx], bd[sidx][nt], c);
-            }
-            t4[nt] = a;
-            t44[nt] = c[0];
-          }
+          for (int m = 0; m < 6; ++m) dst[24 * m] = old[m] + e[m];
         }
-        float* tgt = s.d_s1 + 144 * q + pp + 576 * cg;
+        wave_sync();
+        // odd levels 2m+1, m < 5: (nt = m, u = 1) + (m-1, 3)
+        {
+          float e[5], old[5];
+#pragma unroll
+          for (int m = 0; m < 5; ++m) {
+            float acc = 0.0f;
+            if (m < 4) acc = tv[m < 4 ? m : 0][1];
+            if (m >= 1) acc += tv[m >= 1 ? m - 1 : 0][3];
+            e[m] = acc;
+            old[m] = dst[24 * m + 12];
+          }
+#pragma unroll
+          for (int m = 0; m < 5; ++m) dst[24 * m + 12] = old[m] + e[m];
+        }
+        wave_sync();
+      };
+      // the four pixel tiles of one M tile: entry `first` + sidx of the table
+      auto tiles = [&](int first, f4 (&out)[4]) {
+        float av[3];
+#pragma unroll
+        for (int sidx = 0; sidx < 3; ++sidx) av[sidx] = tl[(first + sidx) * 64];
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+          f4 a = f4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+          for (int sidx = 0; sidx < 3; ++sidx) a = mfma16(av[sidx], bd[sidx][nt], a);
+          out[nt] = a;
+        }
+      };
+      // ---- input maps 0..3: lane quarter q owns map q; tiles V(0..4), U4, C ----
+      {
+        f4 t4[4], tc[4];  // taps (4, v), v < 4, in register v; tap (4, 4) in register 0
+        tiles(TAB_AB + kTileU4 * 3, t4);
+        tiles(TAB_AB + kTileC * 3, tc);
+        float* tgt = s.d_s1 + 144 * q + pp;
         // tile V(v+1) is issued before the rounds of V(v), so its MFMAs run under the LDS round trips
         f4 tv[4], tn[4];  // taps (u, v), u < 4, in register u
-        auto v_tiles = [&](int v, f4 (&out)[4]) {
-          float av[3];
-#pragma unroll
-          for (int sidx = 0; sidx < 3; ++sidx) av[sidx] = tl[(TAB_AB + (cg * 7 + kTileV0 + v) * 3 + sidx) * 64];
-#pragma unroll
-          for (int nt = 0; nt < 4; ++nt) {
-            f4 a = f4{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-            for (int sidx = 0; sidx < 3; ++sidx) a = mfma16(av[sidx], bd[sidx][nt], a);
-            out[nt] = a;
-          }
-        };
-        v_tiles(0, tv);
+        tiles(TAB_AB + kTileV0 * 3, tv);
 #pragma unroll
         for (int v = 0; v < 5; ++v) {
-          if (v < 4) v_tiles(v + 1, tn);
-          // even levels 2m, m < 6: (nt = m, u = 0) + (m-1, 2) + (m-2, 4)
-          {
-            float e[6], old[6];
+          if (v < 4) tiles(TAB_AB + (kTileV0 + v + 1) * 3, tn);
+          float u4[4];
 #pragma unroll
-            for (int m = 0; m < 6; ++m) {
-              float acc = 0.0f;
-              if (m < 4) acc = tv[m < 4 ? m : 0][0];
-              if (m >= 1 && m <= 4) acc += tv[m >= 1 ? m - 1 : 0][2];
-              if (m >= 2) acc += v < 4 ? t4[m >= 2 ? m - 2 : 0][v < 4 ? v : 0] : t44[m >= 2 ? m - 2 : 0];
-              e[m] = acc;
-              old[m] = tgt[24 * m + v];
-            }
-#pragma unroll
-            for (int m = 0; m < 6; ++m) tgt[24 * m + v] = old[m] + e[m];
-          }
-          wave_sync();
-          // odd levels 2m+1, m < 5: (nt = m, u = 1) + (m-1, 3)
-          {
-            float e[5], old[5];
-#pragma unroll
-            for (int m = 0; m < 5; ++m) {
-              float acc = 0.0f;
-              if (m < 4) acc = tv[m < 4 ? m : 0][1];
-              if (m >= 1) acc += tv[m >= 1 ? m - 1 : 0][3];
-              e[m] = acc;
-              old[m] = tgt[24 * m + 12 + v];
-            }
-#pragma unroll
-            for (int m = 0; m < 5; ++m) tgt[24 * m + 12 + v] = old[m] + e[m];
-          }
-          wave_sync();
+          for (int nt = 0; nt < 4; ++nt) u4[nt] = v < 4 ? t4[nt][v < 4 ? v : 0] : tc[nt][0];
+          rounds(tv, u4, tgt + v);
           if (v < 4) {
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) tv[nt] = tn[nt];
+          }
+        }
+      }
+      // ---- input maps 4, 5, packed: lane quarters 0, 1 own them for tap columns 0..2 and add into
+      //      d_s1, quarters 2, 3 own them again for columns 3, 4 and add into the copy; in round s a
+      //      lane's column is s or 3 + s (quarters 2, 3 have nothing in round 2: their tile rows are
+      //      zero and they re-write cells with their own values) ----
+      {
+        f4 tu[4];  // the u = 4 term of round s in register s
+        tiles(TAB_PK + kTilePU * 3, tu);
+        float* tgt = q < 2 ? s.d_s1 + 144 * (4 + q) + pp : copy + 144 * (q - 2) + pp + 3;
+        f4 tv[4], tn[4];
+        tiles(TAB_PK + kTilePV0 * 3, tv);
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+          if (r < 2) tiles(TAB_PK + (kTilePV0 + r + 1) * 3, tn);
+          float u4[4];
+#pragma unroll
+          for (int nt = 0; nt < 4; ++nt) u4[nt] = tu[nt][r];
+          rounds(tv, u4, tgt + r);
+          if (r < 2) {
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt) tv[nt] = tn[nt];
           }
@@ -975,6 +1015,9 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
           off[k] = wt->o[16 * (3 * gp + k) + b].y - 192 * gp + lane_d1;
 #pragma unroll
           for (int i = 0; i < 6; ++i) up[k][i] = s.d_s1[i * 144 + 16 * (3 * gp + k) + b];
+          // maps 4 and 5 were summed in two halves (the copy lies over d2, beyond the staged chunk)
+#pragma unroll
+          for (int i = 4; i < 6; ++i) up[k][i] += s.pool[W_D2 + (i - 4) * 144 + 16 * (3 * gp + k) + b];
         }
 #pragma unroll
         for (int k = 0; k < 3; ++k) {
