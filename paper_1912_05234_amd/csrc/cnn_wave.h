@@ -203,7 +203,7 @@ __host__ __device__ constexpr int fwd_imm(int s) {
 // c = 4 cg + qi (cg = 0, 1; maps 6, 7 are zero padding) and to the tap
 //   tile V(v), v < 5 : (u = ri, v)        tile U4 : (u = 4, v = ri)        tile C : (4, 4) in ri = 0 only.
 // A lane's result register r of tile (cg, .) therefore lands in d_s1[c = 4 cg + q] at row y+u, column x+v.
-enum BwdTile { kTileV0 = 0, kTileU4 = 5, kTileC = 6 };  // V(v) = kTileV0 + v
+enum BwdTile { kTileV0 = 0, kTileU4 = 5, kTileC = 6 };  // V(v) = kTileV0 + v; tile C is used by the small-batch kernel only
 __host__ __device__ constexpr int bwd_tap(int tile, int ri) {
   return tile < 5 ? 5 * ri + tile : tile == kTileU4 ? 20 + ri : (ri == 0 ? 24 : -1);
 }
@@ -213,11 +213,18 @@ __host__ __device__ constexpr int bwd_tap(int tile, int ri) {
 // (lanes of both halves would otherwise meet in the same cells within a round).
 //   tile PV(s), s < 3 : qi < 2: (u = ri, v = s)       qi >= 2: (u = ri, v = 3 + s) for s < 2, nothing for s = 2
 //   tile PU           : qi < 2: (4, v = ri), ri < 3   qi >= 2: ri = 0: (4, 3), ri = 1: (4, 4)
-// so that in round s every lane finds "its" u = 4 term in result register s of PU.
+// so that in round s every lane finds "its" u = 4 term in result register s of PU.  Register 3 of
+// PU is used by no round: its rows (qi, ri = 3) take tap (4, 4) of the maps 0..3, map qi, which puts
+// the term into the very lane that owns map qi when those maps are summed (the plain tile C of
+// those maps would use four rows of sixteen).
+// Returns 25 c + tap, or -1 for a zero row.
 enum PackedTile { kTilePV0 = 0, kTilePU = 3 };
-__host__ __device__ constexpr int bwd_packed_tap(int tile, int qi, int ri) {
-  if (tile < 3) return qi < 2 ? 5 * ri + tile : (tile < 2 ? 5 * ri + 3 + tile : -1);
-  return qi < 2 ? (ri < 3 ? 20 + ri : -1) : (ri < 2 ? 23 + ri : -1);
+__host__ __device__ constexpr int bwd_packed_source(int tile, int qi, int ri) {
+  const int c = 4 + (qi & 1);
+  if (tile < 3) return qi < 2 ? 25 * c + 5 * ri + tile : (tile < 2 ? 25 * c + 5 * ri + 3 + tile : -1);
+  if (ri == 3) return 25 * qi + 24;
+  if (qi < 2) return 25 * c + 20 + ri;
+  return ri < 2 ? 25 * c + 23 + ri : -1;
 }
 // ---- C1 forward as a GEMM (16x16x4 MFMA) -----------------------------------------------------------
 // Output pixels are taken in horizontal pairs x = 2X + sh (sh = 0, 1).  With v' = v + sh the image
@@ -323,9 +330,8 @@ __host__ __device__ constexpr int table_source(int i) {
     }
     if (e >= TAB_C1A) return c1f_weight(e - TAB_C1A, l);
     if (e >= TAB_PK && e < TAB_AB1) {
-      const int t = e - TAB_PK, sidx = t % 3, tile = t / 3, qi = n16 >> 2;
-      const int c = 4 + (qi & 1), tap = bwd_packed_tap(tile, qi, n16 & 3);
-      return tap >= 0 ? OFF_K2 + (4 * sidx + q) * 150 + c * 25 + tap : -1;
+      const int t = e - TAB_PK, sidx = t % 3, src = bwd_packed_source(t / 3, n16 >> 2, n16 & 3);
+      return src >= 0 ? OFF_K2 + (4 * sidx + q) * 150 + src : -1;
     }
     const int cg = e >= TAB_AB1 ? 1 : 0, t = e - (cg ? TAB_AB1 : TAB_AB), sidx = t % 3, tile = t / 3;
     const int c = 4 * cg + (n16 >> 2), tap = bwd_tap(tile, n16 & 3);
@@ -519,10 +525,19 @@ __device__ __forceinline__ float c1g_combine(const float* park, int e) {
 constexpr int NWIN = 144;
 struct WindowTable {
   int2 o[NWIN];
+  // C2 weight gradient: offset (floats, inside s1) of the s1 cell that lane l reads first for tap tile
+  // nt, i.e. of tap 16 nt + l % 16 = (c, u, v) at pixel quarter l / 16: c * 144 + u * 12 + v + 2 (l / 16)
+  // (0 + 2 (l / 16) for the padding taps 150..159)
+  int k2b[10][64];
 };
 __device__ __forceinline__ void window_table_init(WindowTable& w) {
   for (int win = threadIdx.x; win < NWIN; win += blockDim.x)
     w.o[win] = int2{56 * (win / 12) + 2 * (win % 12), 48 * (win / 12) + 2 * (win % 12)};
+  for (int e = threadIdx.x; e < 640; e += blockDim.x) {
+    const int nt = e >> 6, l = e & 63, tap = 16 * nt + (l & 15);
+    const int c = tap / 25, rem = tap - 25 * c, u = rem / 5, v = rem - 5 * u;
+    w.k2b[nt][l] = (tap < 150 ? c * 144 + u * 12 + v : 0) + 2 * (l >> 4);
+  }
 }
 
 // What the FC weight gradient needs of one image, kept in global memory until the wave has done all
@@ -802,7 +817,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
       for (int o = 0; o < 10; ++o) {
         const float e = y[o] - (o == label ? 1.0f : 0.0f);
         lsum = fmaf(e, e, lsum);
-        delta[o] = e * y[o] * (1.0f - y[o]);
+        delta[o] = e * fmaf(-y[o], y[o], y[o]);  // y (1 - y) as y - y^2: one instruction
       }
       st.loss = fmaf(0.5f, lsum, st.loss);
     }
@@ -842,7 +857,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const float c = c2v[mt][r];
-        d2v[mt][r] = up * c * (1.0f - c);
+        d2v[mt][r] = up * fmaf(-c, c, c);
       }
       if (n16 < 12) *reinterpret_cast<f4*>(&s.pool[W_D2 + n16 * D2S + 16 * mt + 4 * q]) = d2v[mt];
       st.g_b2 += (d2v[mt][0] + d2v[mt][1]) + (d2v[mt][2] + d2v[mt][3]);
@@ -857,11 +872,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
       CNN_PHASE_LANES;
       const float* bsrc[10];  // s1 patch element of tap 16 nt + n16 for pixel quarter q
 #pragma unroll
-      for (int nt = 0; nt < 10; ++nt) {
-        const int tap = 16 * nt + n16;
-        const int c = tap / 25, rem = tap - 25 * c, u = rem / 5, v = rem - 5 * u;
-        bsrc[nt] = s.pool + W_S1 + (tap < 150 ? c * 144 + u * 12 + v : 0) + 2 * q;
-      }
+      for (int nt = 0; nt < 10; ++nt) bsrc[nt] = s.pool + W_S1 + wt->k2b[nt][l];
       // the ten s1 reads of step + 1 are issued under the ten MFMAs of a step and no earlier
       float bv[2][10];
       auto load_step = [&](int step, float (&o)[10]) {
@@ -951,11 +962,13 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
           out[nt] = a;
         }
       };
-      // ---- input maps 0..3: lane quarter q owns map q; tiles V(0..4), U4, C ----
+      // ---- input maps 0..3: lane quarter q owns map q; tiles V(0..4) and U4; tap (4, 4) rides in
+      //      register 3 of the packed tile PU of the maps 4, 5 below ----
+      f4 tu[4];
+      tiles(TAB_PK + kTilePU * 3, tu);
       {
-        f4 t4[4], tc[4];  // taps (4, v), v < 4, in register v; tap (4, 4) in register 0
+        f4 t4[4];  // taps (4, v), v < 4, in register v
         tiles(TAB_AB + kTileU4 * 3, t4);
-        tiles(TAB_AB + kTileC * 3, tc);
         float* tgt = s.d_s1 + 144 * q + pp;
         // tile V(v+1) is issued before the rounds of V(v), so its MFMAs run under the LDS round trips
         f4 tv[4], tn[4];  // taps (u, v), u < 4, in register u
@@ -965,7 +978,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
           if (v < 4) tiles(TAB_AB + (kTileV0 + v + 1) * 3, tn);
           float u4[4];
 #pragma unroll
-          for (int nt = 0; nt < 4; ++nt) u4[nt] = v < 4 ? t4[nt][v < 4 ? v : 0] : tc[nt][0];
+          for (int nt = 0; nt < 4; ++nt) u4[nt] = v < 4 ? t4[nt][v < 4 ? v : 0] : tu[nt][3];
           rounds(tv, u4, tgt + v);
           if (v < 4) {
 #pragma unroll
@@ -978,8 +991,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
       //      lane's column is s or 3 + s (quarters 2, 3 have nothing in round 2: their tile rows are
       //      zero and they re-write cells with their own values) ----
       {
-        f4 tu[4];  // the u = 4 term of round s in register s
-        tiles(TAB_PK + kTilePU * 3, tu);
+        // (tu: the u = 4 term of round r in register r)
         float* tgt = q < 2 ? s.d_s1 + 144 * (4 + q) + pp : copy + 144 * (q - 2) + pp + 3;
         f4 tv[4], tn[4];
         tiles(TAB_PK + kTilePV0 * 3, tv);
@@ -1026,7 +1038,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
 #pragma unroll
           for (int i = 0; i < 6; ++i) {
             const float c = c1[g][i];
-            const float d1 = up[k][i] * (c * (1.0f - c));  // the pooling's 1/4 is in the operand table
+            const float d1 = up[k][i] * fmaf(-c, c, c);  // c (1 - c); the pooling's 1/4 is in the operand table
             st.g_b1[i] += d1;
             dst[i * D1C_MAP] = d1;
           }
