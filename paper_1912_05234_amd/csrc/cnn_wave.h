@@ -454,13 +454,20 @@ __device__ __forceinline__ void c1g_lane_offsets(int& a, int (&bt)[2], int l) {
 }
 // STEPS steps of the GEMM from the given origins of d1 and the image: operands of step kk + 2 are
 // read while the two MFMAs of step kk issue.
+// With `ones` (C1G_ONES floats of 1.0): the two padding columns 30, 31 read 1.0 instead of image
+// pixels, so that column 30 of the result is the sum of the A operand over all steps,
+//   T[(m,sh)][30] = sum_{y,X} d1[m][y][2X+sh],   g_b1[m] = T[(m,0)][30] + T[(m,1)][30]      (backbias, Section 3)
+// at no cost in instructions.
+constexpr int C1G_ONES = 224;  // the reach of a lane's B operand over eight image rows: 28 * 7 + 16 + 6 + 1
 template <int STEPS, int MAP = D1_MAP>
-__device__ __forceinline__ void c1g_accumulate(f4 (&acc)[2], const float* d1, const float* img, int lane) {
+__device__ __forceinline__ void c1g_accumulate(f4 (&acc)[2], const float* d1, const float* img, int lane,
+                                               const float* ones = nullptr) {
+  static_assert(28 * ((STEPS - 1) / 3) + 8 * 2 + 6 < C1G_ONES || STEPS > 24, "the ones cover a padding lane's reads");
   int a, bt[2];
   c1g_lane_offsets<MAP>(a, bt, lane);
   const float* pa = d1 + a;
   const float* pb0 = img + bt[0];
-  const float* pb1 = img + bt[1];
+  const float* pb1 = ones && (lane & 15) >= 14 ? ones + 2 * (lane >> 4) : img + bt[1];
   float oa[3], ob0[3], ob1[3];
   auto load_step = [&](int kk, int slot) {
     oa[slot] = pa[c1g_imm_a(kk)];
@@ -529,6 +536,7 @@ struct WindowTable {
   // nt, i.e. of tap 16 nt + l % 16 = (c, u, v) at pixel quarter l / 16: c * 144 + u * 12 + v + 2 (l / 16)
   // (0 + 2 (l / 16) for the padding taps 150..159)
   int k2b[10][64];
+  float ones[C1G_ONES];  // 1.0: B operand of the padding columns of the C1 weight-gradient GEMM (c1g_accumulate)
 };
 __device__ __forceinline__ void window_table_init(WindowTable& w) {
   for (int win = threadIdx.x; win < NWIN; win += blockDim.x)
@@ -538,6 +546,7 @@ __device__ __forceinline__ void window_table_init(WindowTable& w) {
     const int c = tap / 25, rem = tap - 25 * c, u = rem / 5, v = rem - 5 * u;
     w.k2b[nt][l] = (tap < 150 ? c * 144 + u * 12 + v : 0) + 2 * (l >> 4);
   }
+  for (int e = threadIdx.x; e < C1G_ONES; e += blockDim.x) w.ones[e] = 1.0f;
 }
 
 // What the FC weight gradient needs of one image, kept in global memory until the wave has done all
@@ -556,9 +565,9 @@ struct WaveState {
   float bias2;    // b2[n16]
   // training only
   f4 acc_k2[10];  // sum over images of d_c2 (x) s1 patches, D[j = 4q+r][tap = 16 nt + n16]
-  f4 acc_k1[2];   // C1 weight gradient GEMM result T[(m,sh) = 4q+r][c = 16 nt + n16]
+  f4 acc_k1[2];   // C1 weight gradient GEMM result T[(m,sh) = 4q+r][c = 16 nt + n16]; column 30: the C1 bias gradient
   float g_b;      // FC bias gradient: lane o < 10 holds b[o]
-  float g_b1[6], g_b2, loss;
+  float g_b2, loss;
 };
 
 template <int MODE>
@@ -578,8 +587,6 @@ __device__ __forceinline__ void wave_init(WaveState<MODE>& st, typename LdsOf<MO
 #pragma unroll
     for (int nt = 0; nt < 10; ++nt) st.acc_k2[nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
     st.acc_k1[0] = st.acc_k1[1] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-    for (int i = 0; i < 6; ++i) st.g_b1[i] = 0.0f;
     st.g_b2 = 0.0f;
     st.loss = 0.0f;
     st.g_b = 0.0f;
@@ -1038,9 +1045,9 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
 #pragma unroll
           for (int i = 0; i < 6; ++i) {
             const float c = c1[g][i];
-            const float d1 = up[k][i] * fmaf(-c, c, c);  // c (1 - c); the pooling's 1/4 is in the operand table
-            st.g_b1[i] += d1;
-            dst[i * D1C_MAP] = d1;
+            // c (1 - c); the pooling's 1/4 is in the operand table.  (backbias: the GEMM below sums d1
+            // in its padding column.)
+            dst[i * D1C_MAP] = up[k][i] * fmaf(-c, c, c);
           }
         }
         wave_sync();
@@ -1055,7 +1062,7 @@ __device__ __forceinline__ void wave_image(WaveState<MODE>& st, typename LdsOf<M
           asm volatile("" : "+v"(zero));
           nx = load_pixels(next_image + zero);
         }
-        c1g_accumulate<C1G_STEPS / 3, D1C_MAP>(st.acc_k1, s.pool, s.img + 8 * 28 * gp, phase_lane<MODE>());
+        c1g_accumulate<C1G_STEPS / 3, D1C_MAP>(st.acc_k1, s.pool, s.img + 8 * 28 * gp, phase_lane<MODE>(), wt->ones);
         wave_sync();
         if (gp == 2) {
           store_pixels(s.img, nx);
@@ -1123,11 +1130,8 @@ __device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, const f4 (&g_f
     const int e = l + 64 * round;
     if (e < 150) row[OFF_K1 + e] = c1g_combine(park, e);
   }
-#pragma unroll
-  for (int i = 0; i < 6; ++i) {
-    const float v = wave_sum(st.g_b1[i]);
-    if (l == 0) row[OFF_B1 + i] = v;
-  }
+  // C1 biases: column 30 of the same result holds the sums of d1 by (map, x parity)
+  if (l < 6) row[OFF_B1 + l] = park[(2 * l) * 32 + 30] + park[(2 * l + 1) * 32 + 30];
 }
 
 }  // namespace cnn
