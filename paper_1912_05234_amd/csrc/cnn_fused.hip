@@ -200,12 +200,30 @@ __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 
   const bool has_images = mine.left > 0;
   auto image_index = [&](int k) { return (size_t)blockIdx.x + (size_t)gridDim.x * (size_t)k; };
   Pixels px = load_pixels(images + (has_images ? image_index(mine.k()) : 0) * NI);  // in flight during the set-up
-  load_tables<TAB_WAVE_ENTRIES, 64 * TWAVES>(tab, tabg);
+  // every load of the set-up is issued before anything waits for one: the table proper (BF, FCW, AB,
+  // k1t, biases) in 16-byte pieces, and the packed entries, gathered one float at a time
+  TableLoad<TAB_WAVE_ENTRIES, 64 * TWAVES, false, TAB_PK> table;
+  table.fetch(tabg);
+  constexpr int PK_ROUNDS = (TAB_PK_COUNT * 64 + 64 * TWAVES - 1) / (64 * TWAVES);
+  float pk[PK_ROUNDS];
+#pragma unroll
+  for (int r = 0; r < PK_ROUNDS; ++r) {
+    const int i = r * 64 * TWAVES + threadIdx.x;
+    const int slot = i < TAB_PK_COUNT * 64 ? packed_table_slot(i >> 6, i & 63) : -1;
+    pk[r] = tabg[slot >= 0 ? slot : 0];
+    if (slot < 0) pk[r] = 0.0f;
+  }
   window_table_init(wt);
   // waves without images skip their set-up and their row
   if (has_images) {
     wave_init(st, s);
     store_pixels(s.img, px);
+  }
+  table.commit(tab);
+#pragma unroll
+  for (int r = 0; r < PK_ROUNDS; ++r) {
+    const int i = r * 64 * TWAVES + threadIdx.x;
+    if (i < TAB_PK_COUNT * 64) tab.e[TAB_PK * 64 + i] = pk[r];
   }
   __syncthreads();  // the operand and window tables are complete
   st.bias2 = tab.bias[threadIdx.x & 15];

@@ -109,11 +109,16 @@ constexpr int TAB_BF = 0;          // 38: C2 forward B operand, k2[j = n16][tap(
 constexpr int TAB_FCW = 38;        // 30: fc[o][lane + 64 k] at entry 3 o + k
 constexpr int TAB_FWD_ENTRIES = 68;
 constexpr int TAB_AB = 68;         // 21: C2 input-error A operand of input maps 0..3, entry tile*3 + s
-constexpr int TAB_PK = 89;         // 12: the same for input maps 4, 5 with two taps per tile (bwd_packed_tap), entry tile*3 + s
-constexpr int TAB_WAVE_ENTRIES = 101;  // what the one-wave-per-image training kernel reads
-constexpr int TAB_AB1 = 101;       // 21: input maps 4..7 in the plain form of TAB_AB (the small-batch kernel)
-constexpr int TAB_C1A = 122;       // 8: C1 forward A operand of the small-batch kernel, W[(m,sh) = n16][tap 4 ks + q]
-constexpr int TAB_TRAIN_ENTRIES = 130;
+constexpr int TAB_AB1 = 89;        // 21: the same for input maps 4..7 (the small-batch kernel)
+constexpr int TAB_C1A = 110;       // 8: C1 forward A operand of the small-batch kernel, W[(m,sh) = n16][tap 4 ks + q]
+constexpr int TAB_TRAIN_ENTRIES = 118;  // all of them; what the small-batch kernel reads
+// The one-wave-per-image training kernel reads BF, FCW and AB from the table and keeps, right after
+// them in its LDS copy, twelve entries that exist only there: input maps 4, 5 with two taps per tile
+// (bwd_packed_source), entry tile*3 + s, gathered from the AB / AB1 slots of global memory when the
+// kernel starts (packed_table_slot).
+constexpr int TAB_PK = TAB_AB1;
+constexpr int TAB_PK_COUNT = 12;
+constexpr int TAB_WAVE_ENTRIES = TAB_PK + TAB_PK_COUNT;
 // After the [entry][lane] part: C1 weights by tap, k1t[tap][8] = k1[0..5][tap], 0, 0 for tap < 25 and
 // the biases b1 in row 25; every lane reads the same row (an LDS broadcast).
 constexpr int K1T_FLOATS = 26 * 8;
@@ -226,6 +231,15 @@ __host__ __device__ constexpr int bwd_packed_source(int tile, int qi, int ri) {
   if (qi < 2) return 25 * c + 20 + ri;
   return ri < 2 ? 25 * c + 23 + ri : -1;
 }
+// Slot of the expanded table (float index) that holds what lane `lane` of packed entry e = tile*3 + s
+// needs, or -1 for a zero: the same weight sits in the plain tiles of AB (maps 0..3) or AB1 (maps 4..7).
+__host__ __device__ constexpr int packed_table_slot(int e, int lane) {
+  const int sidx = e % 3, q = lane >> 4, n16 = lane & 15, src = bwd_packed_source(e / 3, n16 >> 2, n16 & 3);
+  if (src < 0) return -1;
+  const int c = src / 25, tap = src % 25;
+  const int tile = tap < 20 ? tap % 5 : tap < 24 ? (int)kTileU4 : (int)kTileC, ri = tap < 20 ? tap / 5 : tap < 24 ? tap - 20 : 0;
+  return ((c < 4 ? TAB_AB : TAB_AB1) + tile * 3 + sidx) * 64 + q * 16 + (c & 3) * 4 + ri;
+}
 // ---- C1 forward as a GEMM (16x16x4 MFMA) -----------------------------------------------------------
 // Output pixels are taken in horizontal pairs x = 2X + sh (sh = 0, 1).  With v' = v + sh the image
 // factor img[y+u][2X+v'] does not depend on sh:
@@ -329,10 +343,6 @@ __host__ __device__ constexpr int table_source(int i) {
       return OFF_FC + o * NS2 + l + 64 * k;
     }
     if (e >= TAB_C1A) return c1f_weight(e - TAB_C1A, l);
-    if (e >= TAB_PK && e < TAB_AB1) {
-      const int t = e - TAB_PK, sidx = t % 3, src = bwd_packed_source(t / 3, n16 >> 2, n16 & 3);
-      return src >= 0 ? OFF_K2 + (4 * sidx + q) * 150 + src : -1;
-    }
     const int cg = e >= TAB_AB1 ? 1 : 0, t = e - (cg ? TAB_AB1 : TAB_AB), sidx = t % 3, tile = t / 3;
     const int c = 4 * cg + (n16 >> 2), tap = bwd_tap(tile, n16 & 3);
     return c < 6 && tap >= 0 ? OFF_K2 + (4 * sidx + q) * 150 + c * 25 + tap : -1;
@@ -377,15 +387,18 @@ constexpr int table_max_multiplicity() {
 // COHERENT: the table was written by other compute units during this kernel (the device-side
 // epoch loop): its 16-byte pieces are fetched with agent-scope loads, which do not take stale lines
 // from this XCD's L2 cache.
-template <int ENTRIES, int THREADS, bool COHERENT = false>
+// ENTRIES counts the entries of the LDS copy, of which the first LOADED come from global memory.
+template <int ENTRIES, int THREADS, bool COHERENT = false, int LOADED = ENTRIES>
 struct TableLoad {
-  static constexpr int PIECES = ENTRIES * 16, ROUNDS = (PIECES + THREADS - 1) / THREADS;
+  static constexpr int PIECES = LOADED * 16, ROUNDS = (PIECES + THREADS - 1) / THREADS;
   static constexpr int TAIL = (K1T_FLOATS + TAB_BIAS_FLOATS) / 4;
   typedef OperandTable<ENTRIES> Table;
   static_assert(offsetof(Table, bias) == offsetof(Table, k1t) + sizeof(float) * K1T_FLOATS,
                 "k1t and bias are copied as one run");
   static_assert(TAIL <= THREADS, "one thread per piece of the tail");
   f4 v[ROUNDS], tail;
+  // 16-byte piece of the table that this thread moves in round r (the same in global memory and in LDS)
+  static __device__ __forceinline__ int piece(int r) { return r * THREADS + (int)threadIdx.x; }
   __device__ __forceinline__ void fetch(const float* __restrict__ tabg) {
     const int t = threadIdx.x;
     if (COHERENT) {
@@ -395,7 +408,7 @@ struct TableLoad {
       typedef unsigned u4 __attribute__((ext_vector_type(4)));
 #pragma unroll
       for (int r = 0; r < ROUNDS; ++r) {
-        const int i = r * THREADS + t;
+        const int i = piece(r);
         v[r] = __builtin_bit_cast(f4, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs, 16 * (i < PIECES ? i : 0), 0, AGENT_SCOPE));
       }
       tail = __builtin_bit_cast(f4, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs, 4 * TABG_K1T + 16 * (t < TAIL ? t : 0), 0, AGENT_SCOPE));
@@ -404,7 +417,7 @@ struct TableLoad {
     const f4* src = reinterpret_cast<const f4*>(tabg);
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
-      const int i = r * THREADS + t;
+      const int i = piece(r);
       v[r] = src[i < PIECES ? i : 0];
     }
     tail = src[TABG_K1T / 4 + (t < TAIL ? t : 0)];
@@ -413,15 +426,15 @@ struct TableLoad {
     const int t = threadIdx.x;
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
-      const int i = r * THREADS + t;
+      const int i = piece(r);
       if (i < PIECES) reinterpret_cast<f4*>(tab.e)[i] = v[r];
     }
     if (t < TAIL) reinterpret_cast<f4*>(tab.k1t)[t] = tail;
   }
 };
-template <int ENTRIES, int THREADS>
+template <int ENTRIES, int THREADS, int LOADED = ENTRIES>
 __device__ __forceinline__ void load_tables(OperandTable<ENTRIES>& tab, const float* __restrict__ tabg) {
-  TableLoad<ENTRIES, THREADS> ld;
+  TableLoad<ENTRIES, THREADS, false, LOADED> ld;
   ld.fetch(tabg);
   ld.commit(tab);
 }
