@@ -246,9 +246,10 @@ __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 
     // this wave's stores to its history rows are complete before it reads them back
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     WaveShare again(K, wave);
-    while (again.left > 0) {
+    const float* row = fc_hist;  // overwritten before use: has_images
+    // operands of one K step (the next four images, fewer at the end)
+    auto load_step = [&](FcStepOperands& op) {
       const float* rows[4];
-      const float* row = nullptr;
       const int count = again.left < 4 ? again.left : 4;
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
@@ -258,10 +259,25 @@ __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 
         }
         rows[k] = row;  // past the last image: the last one again (count masks its delta)
       }
-      FcStepOperands op;
       fc_step_load(op, rows, count);
-      fc_step_mfma(g_fc, op);
-    }
+    };
+    // eight steps (32 images) at a time while there are that many, then four, two, one: the loads of
+    // a group are one memory round trip (the registers of the image loop are free by now)
+    auto steps = [&](auto group) {
+      constexpr int N = decltype(group)::value;
+      FcStepOperands ops[N];
+#pragma unroll
+      for (int g = 0; g < N; ++g) load_step(ops[g]);
+#pragma unroll
+      for (int g = 0; g < N; ++g) fc_step_mfma(g_fc, ops[g]);
+    };
+    while (again.left > 28) steps(std::integral_constant<int, 8>());
+    if (again.left > 12) steps(std::integral_constant<int, 4>());
+    if (again.left > 12) steps(std::integral_constant<int, 4>());
+    if (again.left > 4) steps(std::integral_constant<int, 2>());
+    if (again.left > 4) steps(std::integral_constant<int, 2>());
+    if (again.left > 0) steps(std::integral_constant<int, 1>());
+    if (again.left > 0) steps(std::integral_constant<int, 1>());
   }
   __syncthreads();  // every wave is done with the operand table: its storage parks the C1 GEMM results
   if (has_images) wave_flush(st, g_fc, reinterpret_cast<float*>(&s), tab.e + wave * C1G_PARK);
