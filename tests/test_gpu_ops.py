@@ -32,7 +32,10 @@ CONV_CASES = [(3, 1, 28, 28, 6, 5, 5), (5, 6, 12, 12, 12, 5, 5), (2, 3, 9, 7, 4,
               (3, 2, 1, 300, 3, 1, 7), (2, 1, 40, 3, 17, 2, 3), (5, 7, 5, 9, 33, 5, 2), (1, 3, 16, 16, 1, 16, 16),
               (9, 4, 10, 10, 2, 1, 4), (70, 1, 2, 2, 16, 2, 2),
               # packing by 4 and by 8 (16-byte stores), by 6 (8-byte stores)
-              (40, 2, 6, 6, 3, 3, 3), (4, 2, 10, 12, 1, 3, 5)]
+              (40, 2, 6, 6, 3, 3, 3), (4, 2, 10, 12, 1, 3, 5),
+              # the second convolution's shape with one image and with a ragged nine (its input gradient has a
+              # kernel of its own, one wave per image)
+              (1, 6, 12, 12, 12, 5, 5), (9, 6, 12, 12, 12, 5, 5)]
 
 
 def oracle_conv_fwd(x, k, b):
@@ -65,6 +68,25 @@ def test_conv_bwd_input(case):
             ref[n] += oracle.backin(d[n, co][None].astype(np.float64), k[co].astype(np.float64), (Cin, H, W))
     assert_close(host(binding.conv_bwd_input(dev(d), dev(k), H, W)), ref, RTOL_ACT, "conv_bwd_input")
     assert_close(host(binding.conv_bwd_input(dev(d), dev(k), H, W, valu=True)), ref, RTOL_ACT, "conv_bwd_input_valu")
+
+
+def test_conv_bwd_input_of_the_second_convolution_with_looping_waves():
+    """4101 images of C2's shape: more images than the col2im kernel has waves (512 workgroups of eight),
+    so waves take a second image (the hand-over of the prefetched error) and the last round is ragged;
+    sampled images against the oracle, and the bordered-convolution kernels' result for all of them."""
+    B, Cin, H, W, Cout, KH, KW = 4101, 6, 12, 12, 12, 5, 5
+    d = inputs.make_signed((B, Cout, 8, 8), 41)
+    k = inputs.make_signed((Cout, Cin, KH, KW), 42)
+    got = host(binding.conv_bwd_input(dev(d), dev(k), H, W))
+    sample = sorted(set(list(range(8)) + list(range(4090, 4101)) + list(range(0, B, 397))))
+    ref = np.zeros((len(sample), Cin, H, W), np.float64)
+    for i, n in enumerate(sample):
+        for co in range(Cout):
+            ref[i] += oracle.backin(d[n, co][None].astype(np.float64), k[co].astype(np.float64), (Cin, H, W))
+    assert_close(got[sample], ref, RTOL_ACT, "conv_bwd_input of C2, sampled images")
+    # the plain kernel computes the same sums in another order: every image
+    plain = host(binding.conv_bwd_input(dev(d), dev(k), H, W, valu=True))
+    assert_close(got, plain.astype(np.float64), RTOL_ACT, "conv_bwd_input of C2 against the plain kernel")
 
 
 @pytest.mark.parametrize("case", CONV_CASES)
