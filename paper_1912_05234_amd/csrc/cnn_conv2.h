@@ -1,0 +1,234 @@
+// Forward pass and weight gradient of a 5 x 5 convolution with six input and twelve output maps on
+// a 12 x 12 input (the shape of the network's second convolution), ONE WAVE PER IMAGE, in the GEMM
+// forms of the fused training step (arXiv 1912.05234, Section 3: listings conv / mconv,
+// backweights, backbias):
+//   forward          M = 64 output pixels in four tiles, N = 12(16) maps, K = 150(152) taps: 152
+//                    v_mfma_f32_16x16x4_f32 per image; the image's 864 inputs are staged in the
+//                    wave's LDS, the weights sit in LDS as the instruction's B operand
+//   weight gradient  M = 12(16) maps, N = 150(160) taps in ten tiles, K = 64 pixels: 160 per image;
+//                    the output error is the A operand straight from global memory, the sums stay
+//                    in registers over all of a wave's images; the eight waves of a workgroup are
+//                    added through LDS in a fixed order and the workgroup writes one set of partial
+//                    tiles in the layout of the general kernel (cnn_igemm.h), whose second kernel
+//                    adds the workgroups' partials.
+// Eight waves per workgroup, two workgroups per compute unit (four waves per SIMD): the matrix
+// instructions of three waves run under the LDS and memory waits of the fourth.  The general
+// kernels stage groups of images for four waves that then share them, which costs barriers and
+// staging time these shapes do not need: an image is small enough for one wave.  Pixel order and
+// operand layouts are those of cnn_wave.h (fwd_tap, fwd_imm); only such index helpers are shared.
+#pragma once
+
+#include "cnn_wave.h"
+
+namespace cnn {
+namespace conv2 {
+
+constexpr int WAVES_PER_GROUP = 8, THREADS = 64 * WAVES_PER_GROUP;
+constexpr int CIN = 6, COUT = 12, TAPS = CIN * 25, IN_FLOATS = NS1, OUT_FLOATS = COUT * 64;
+inline bool shape_fits(int Cin, int H, int W, int Cout, int KH, int KW) {
+  return Cin == CIN && Cout == COUT && KH == 5 && KW == 5 && H == 12 && W == 12;
+}
+
+// One image's input as 216 16-byte pieces in registers (the fourth only in lanes 0..23).
+struct Input {
+  f4 a, b, c, d;
+};
+__device__ __forceinline__ Input load_input(const float* __restrict__ in, size_t n) {
+  const f4* src = reinterpret_cast<const f4*>(in + n * IN_FLOATS);
+  const int l = threadIdx.x & 63;
+  Input x;
+  x.a = src[l];
+  x.b = src[l + 64];
+  x.c = src[l + 128];
+  x.d = src[l < 24 ? l + 192 : l];
+  return x;
+}
+__device__ __forceinline__ void store_input(float* lds, const Input& x) {
+  const int l = threadIdx.x & 63;
+  f4* dst = reinterpret_cast<f4*>(lds);
+  dst[l] = x.a;
+  dst[l + 64] = x.b;
+  dst[l + 128] = x.c;
+  if (l < 24) dst[l + 192] = x.d;
+}
+
+// ---- forward ---------------------------------------------------------------------------------------------
+constexpr int FWD_IN = IN_FLOATS + 288;  // the padded K steps read up to 1152 floats from the start (zero weights)
+struct __align__(16) FwdLds {
+  float tab[38 * 64];  // B operand, [K step][lane]: k[j = lane % 16][fwd_tap(step, lane / 16)]
+  float bias[16];
+  float in[WAVES_PER_GROUP][FWD_IN];
+};
+__global__ __launch_bounds__(THREADS) void forward_kernel(const float* __restrict__ in, const float* __restrict__ k,
+                                                          const float* __restrict__ bias, float* __restrict__ out,
+                                                          int B) {
+  __shared__ FwdLds lds;
+  const int t = threadIdx.x, wave = t >> 6, l = t & 63, q = l >> 4, n16 = l & 15;
+  for (int i = t; i < 38 * 64; i += THREADS) {
+    const int lane = i & 63, tap = fwd_tap(i >> 6, lane >> 4), j = lane & 15;
+    lds.tab[i] = j < COUT && tap >= 0 ? k[j * TAPS + tap] : 0.0f;
+  }
+  if (t < 16) lds.bias[t] = bias && t < COUT ? bias[t] : 0.0f;
+  float* x = lds.in[wave];
+  for (int e = IN_FLOATS + l; e < FWD_IN; e += 64) x[e] = 0.0f;  // finite filler behind the image
+  __syncthreads();
+  const float* tl = lds.tab + l;
+  const int pp = 12 * ((n16 & 3) >> 1) + 2 * (n16 >> 2) + (n16 & 1);
+  const float* a12 = x + pp + 12 * q;
+  const float* a1 = x + pp + q;
+  const float* a144 = x + pp + 144 * q;
+  const float b2 = lds.bias[n16];
+  const size_t G = (size_t)gridDim.x * WAVES_PER_GROUP, first = (size_t)blockIdx.x * WAVES_PER_GROUP + wave;
+  Input cur;
+  if (first < (size_t)B) cur = load_input(in, first);
+  for (size_t n = first; n < (size_t)B; n += G) {
+    store_input(x, cur);
+    wave_sync();
+    if (n + G < (size_t)B) cur = load_input(in, n + G);  // in flight during this image
+    f4 acc[4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) acc[mt] = f4{b2, b2, b2, b2};
+    float opa[3][4], opw[3];
+    auto load_step = [&](int s, float (&oa)[4], float& ow) {
+      const float* base = s < 30 ? a12 : s < 36 ? a1 : a144;
+      ow = tl[s * 64];
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) oa[mt] = base[fwd_imm(s) + 24 * mt];
+    };
+    load_step(0, opa[0], opw[0]);
+    load_step(1, opa[1], opw[1]);
+#pragma unroll
+    for (int s = 0; s < 38; ++s) {
+      if (s + 2 < 38) load_step(s + 2, opa[(s + 2) % 3], opw[(s + 2) % 3]);
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) acc[mt] = mfma16(opa[s % 3][mt], opw[s % 3], acc[mt]);
+      if (s + 2 < 38) __builtin_amdgcn_sched_group_barrier(0x100, 5, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    }
+    wave_sync();  // the reads of this image come before the next image's stores
+    // register r of tile mt is pixel (y, x) = (2 mt + r / 2, 2 q + r % 2) of map n16: two 8-byte stores per tile
+    if (n16 < COUT) {
+      float* dst = out + n * OUT_FLOATS + n16 * 64 + 2 * q;
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        *reinterpret_cast<float2*>(dst + 16 * mt) = float2{acc[mt][0], acc[mt][1]};
+        *reinterpret_cast<float2*>(dst + 16 * mt + 8) = float2{acc[mt][2], acc[mt][3]};
+      }
+    }
+  }
+}
+
+// ---- weight and bias gradient -------------------------------------------------------------------------------
+constexpr int ACC_FLOATS = 10 * 4 * 64;  // a wave's sums: [tile nt][register r][lane]
+struct __align__(16) WgradLds {
+  int k2b[10][64];                           // first s1 cell of tap 16 nt + lane % 16 for pixel quarter lane / 16
+  float x[WAVES_PER_GROUP][IN_FLOATS];
+  float comb[WAVES_PER_GROUP / 2][ACC_FLOATS];  // cross-wave sums
+  float bsum[WAVES_PER_GROUP][64];
+};
+// part: [gridDim.x][10 tiles][16 rows j][16 columns] then the bias rows [gridDim.x][16] (the layout
+// igemm::wgrad_reduce_kernel reads with MT = 1, NT = 10, P = 1).
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void bwd_weight_kernel(const float* __restrict__ in,
+                                                             const float* __restrict__ d_out,
+                                                             float* __restrict__ part, int B) {
+  __shared__ WgradLds lds;
+  const int t = threadIdx.x, wave = t >> 6, l = t & 63, q = l >> 4, n16 = l & 15;
+  for (int e = t; e < 640; e += THREADS) {
+    const int nt = e >> 6, lane = e & 63, tap = 16 * nt + (lane & 15);
+    const int c = tap / 25, rem = tap - 25 * c, u = rem / 5, v = rem - 5 * u;
+    lds.k2b[nt][lane] = (tap < TAPS ? c * 144 + u * 12 + v : 0) + 2 * (lane >> 4);
+  }
+  __syncthreads();
+  float* x = lds.x[wave];
+  const float* bsrc[10];
+#pragma unroll
+  for (int nt = 0; nt < 10; ++nt) bsrc[nt] = x + lds.k2b[nt][l];
+  // A operand: lane (q, n16) holds d_out[map n16][pixel 16 S + 4 q + r] = (y, x) = (2 S + r / 2, 2 q + r % 2);
+  // the lanes of the padding rows 12..15 read map 11 (their result rows are never stored)
+  const int lane_src = (n16 < COUT ? n16 : COUT - 1) * 64 + 2 * q;
+  auto load_error = [&](size_t n, f4 (&d)[4]) {
+    const float* src = d_out + n * OUT_FLOATS + lane_src;
+#pragma unroll
+    for (int S = 0; S < 4; ++S) {
+      const float2 lo = *reinterpret_cast<const float2*>(src + 16 * S), hi = *reinterpret_cast<const float2*>(src + 16 * S + 8);
+      d[S] = f4{lo.x, lo.y, hi.x, hi.y};
+    }
+  };
+  f4 acc[10];
+#pragma unroll
+  for (int nt = 0; nt < 10; ++nt) acc[nt] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+  float g_b = 0.0f;
+  const size_t G = (size_t)gridDim.x * WAVES_PER_GROUP, first = (size_t)blockIdx.x * WAVES_PER_GROUP + wave;
+  Input cur;
+  f4 d[4], dn[4];
+  if (first < (size_t)B) {
+    cur = load_input(in, first);
+    load_error(first, d);
+  }
+  for (size_t n = first; n < (size_t)B; n += G) {
+    store_input(x, cur);
+    wave_sync();
+    if (n + G < (size_t)B) {  // in flight during this image
+      cur = load_input(in, n + G);
+      load_error(n + G, dn);
+    }
+#pragma unroll
+    for (int S = 0; S < 4; ++S) g_b += (d[S][0] + d[S][1]) + (d[S][2] + d[S][3]);
+    float bv[2][10];
+    auto load_step = [&](int step, float (&o)[10]) {
+      const int S = step >> 2, r = step & 3, imm = 24 * S + 12 * (r >> 1) + (r & 1);
+#pragma unroll
+      for (int nt = 0; nt < 10; ++nt) o[nt] = bsrc[nt][imm];
+    };
+    load_step(0, bv[0]);
+#pragma unroll
+    for (int step = 0; step < 16; ++step) {
+      if (step < 15) load_step(step + 1, bv[(step + 1) & 1]);
+#pragma unroll
+      for (int nt = 0; nt < 10; ++nt) acc[nt] = mfma16(d[step >> 2][step & 3], bv[step & 1][nt], acc[nt]);
+      if (step < 15) __builtin_amdgcn_sched_group_barrier(0x100, 10, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 10, 0);
+    }
+    wave_sync();  // the reads of this image come before the next image's stores
+#pragma unroll
+    for (int S = 0; S < 4; ++S) d[S] = dn[S];
+  }
+  // ---- the eight waves' sums in a fixed order: (w, w + 4), then (w, w + 2), then (0, 1) ----
+  lds.bsum[wave][l] = g_b;
+#pragma unroll
+  for (int half = WAVES_PER_GROUP / 2; half >= 1; half >>= 1) {
+    __syncthreads();
+    if (wave >= half && wave < 2 * half) {
+      float* dst = lds.comb[wave - half];
+#pragma unroll
+      for (int nt = 0; nt < 10; ++nt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dst[(4 * nt + r) * 64 + l] = acc[nt][r];
+    }
+    __syncthreads();
+    if (wave < half) {
+      const float* src = lds.comb[wave];
+#pragma unroll
+      for (int nt = 0; nt < 10; ++nt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[nt][r] += src[(4 * nt + r) * 64 + l];
+    }
+  }
+  if (wave == 0) {
+    float* tile = part + (size_t)blockIdx.x * 10 * 256;
+#pragma unroll
+    for (int nt = 0; nt < 10; ++nt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) tile[nt * 256 + (4 * q + r) * 16 + n16] = acc[nt][r];  // row j = 4 q + r, column n16
+  } else if (wave == 1 && l < 16) {
+    // bias gradient of map l: the four lane quarters of the eight waves, in wave order
+    float s = 0.0f;
+    if (l < COUT)
+      for (int w = 0; w < WAVES_PER_GROUP; ++w) s += (lds.bsum[w][l] + lds.bsum[w][l + 16]) + (lds.bsum[w][l + 32] + lds.bsum[w][l + 48]);
+    part[(size_t)gridDim.x * 10 * 256 + (size_t)blockIdx.x * 16 + l] = s;
+  }
+}
+inline size_t bwd_weight_workspace_bytes(unsigned groups) { return sizeof(float) * (size_t)groups * (10 * 256 + 16); }
+
+}  // namespace conv2
+}  // namespace cnn

@@ -10,6 +10,7 @@
 #include "cnn_igemm.h"
 #include "cnn_igemm_bf16.h"
 #include "cnn_col2im.h"
+#include "cnn_conv2.h"
 
 namespace {
 
@@ -436,6 +437,7 @@ int launch_conv(const ConvPlan& p, hipStream_t stream) {
 struct WgradPlan {
   igemm::WgradArgs a;
   bool fits = false;
+  bool one_wave_per_image = false;  // the second convolution's shape: conv2::bwd_weight_kernel, gx workgroups
   unsigned gx = 0, gy = 0;
   size_t lds_bytes = 0, workspace_bytes = 0;
 };
@@ -489,6 +491,19 @@ WgradPlan plan_wgrad_packed(int B, int Cin, int H, int W, int Cout, int KH, int 
 // The packing factor that needs the fewest matrix instructions per image (column tiles x blocks of
 // pixel slots) among the divisors P of Wo with Cout*P <= 16; 1 for kernels one column wide.
 WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
+  if (conv2::shape_fits(Cin, H, W, Cout, KH, KW)) {
+    WgradPlan p;
+    igemm::WgradArgs& a = p.a;
+    a.in = nullptr, a.d_out = nullptr, a.part = nullptr;
+    a.B = B, a.Cin = Cin, a.H = H, a.W = W, a.Cout = Cout, a.KH = KH, a.KW = KW;
+    a.P = 1, a.MT = 1, a.NT = 10;  // what the second kernel needs to find the partial tiles
+    p.fits = p.one_wave_per_image = true;
+    const unsigned groups = (unsigned)((B + conv2::WAVES_PER_GROUP - 1) / conv2::WAVES_PER_GROUP);
+    p.gx = groups < 2u * NUM_CU ? groups : 2u * NUM_CU;  // two workgroups per compute unit are resident
+    p.gy = 1;
+    p.workspace_bytes = conv2::bwd_weight_workspace_bytes(p.gx);
+    return p;
+  }
   int best = 1;
   if (KW > 1) {
     const long long Ho = H - KH + 1, Wo = W - KW + 1;
@@ -656,7 +671,9 @@ int launch_wgrad(WgradPlan& p, const float* in, const float* d_out, float* d_k, 
                  hipStream_t st) {
   p.a.in = in, p.a.d_out = d_out, p.a.part = part;
   const dim3 grid(p.gx, p.gy);
-  if (p.a.vec_x && p.a.vec_d)
+  if (p.one_wave_per_image)
+    conv2::bwd_weight_kernel<<<p.gx, conv2::THREADS, 0, st>>>(in, d_out, part, p.a.B);
+  else if (p.a.vec_x && p.a.vec_d)
     igemm::wgrad_kernel<16, 16><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
   else if (p.a.vec_x)
     igemm::wgrad_kernel<16, 4><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
@@ -713,6 +730,13 @@ int cnn_conv_fwd(const float* in, const float* k, const float* bias, float* out,
                  int W, int Cout, int KH, int KW, void* hip_stream) {
   if (!in || !k || !out || !conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;
   if (!aligned16(in) || !aligned16(k) || !aligned16(out) || (bias && !aligned16(bias))) return CNN_EINVAL;
+  if (conv2::shape_fits(Cin, H, W, Cout, KH, KW)) {  // the network's second convolution: one wave per image
+    // (two workgroups per compute unit; one, three or four measured the same: the kernel is bound by its matrix instructions)
+    const int groups = (B + conv2::WAVES_PER_GROUP - 1) / conv2::WAVES_PER_GROUP, resident = 2 * NUM_CU;
+    conv2::forward_kernel<<<groups < resident ? groups : resident, conv2::THREADS, 0, (hipStream_t)hip_stream>>>(
+        in, k, bias, out, B);
+    return launched();
+  }
   const ConvPlan p = plan_conv(in, k, bias, out, B, Cout, Cin, H, W, KH, KW, H - KH + 1, W - KW + 1, 0, 0, 0);
   if (p.tp) return launch_conv(p, (hipStream_t)hip_stream);
   const size_t total = (size_t)B * Cout * (H - KH + 1) * (W - KW + 1);

@@ -89,6 +89,37 @@ def test_conv_bwd_input_of_the_second_convolution_with_looping_waves():
     assert_close(got, plain.astype(np.float64), RTOL_ACT, "conv_bwd_input of C2 against the plain kernel")
 
 
+def test_forward_and_weight_gradient_of_the_second_convolution_with_looping_waves():
+    """The same 4101 images through the one-wave-per-image forward and weight-gradient kernels of C2's
+    shape: sampled images of the forward pass against the oracle, every image against the plain
+    kernel; the weight and bias gradient (a sum over all images) against the plain kernel and, for
+    the last 37 images alone, against the oracle."""
+    B, Cin, H, W, Cout, KH, KW = 4101, 6, 12, 12, 12, 5, 5
+    x = inputs.make_signed((B, Cin, H, W), 43)
+    k = inputs.make_signed((Cout, Cin, KH, KW), 44)
+    b = inputs.make_signed((Cout,), 45)
+    d = inputs.make_signed((B, Cout, 8, 8), 46)
+    got = host(binding.conv_fwd(dev(x), dev(k), dev(b)))
+    sample = sorted(set(list(range(8)) + list(range(4090, 4101)) + list(range(0, B, 397))))
+    assert_close(got[sample], oracle_conv_fwd(x[sample], k, b), RTOL_ACT, "conv_fwd of C2, sampled images")
+    plain = host(binding.conv_fwd(dev(x), dev(k), dev(b), valu=True))
+    assert_close(got, plain.astype(np.float64), RTOL_ACT, "conv_fwd of C2 against the plain kernel")
+    gk, gb = binding.conv_bwd_weight(dev(x), dev(d))
+    pk, pb = binding.conv_bwd_weight(dev(x), dev(d), workspace=False)
+    assert_close(host(gk), host(pk).astype(np.float64), RTOL_GRAD, "conv_bwd_weight of C2 against the plain kernel")
+    assert_close(host(gb), host(pb).astype(np.float64), RTOL_GRAD, "conv_bwd_weight bias of C2 against the plain kernel")
+    tail = slice(B - 37, B)
+    gk, gb = binding.conv_bwd_weight(dev(x[tail]), dev(d[tail]))
+    rk = np.zeros((Cout, Cin, KH, KW), np.float64)
+    rb = np.zeros(Cout, np.float64)
+    for n in range(B - 37, B):
+        for co in range(Cout):
+            rk[co] += oracle.backweights(d[n, co][None].astype(np.float64), x[n].astype(np.float64)).reshape(Cin, KH, KW)
+            rb[co] += oracle.backbias(d[n, co].astype(np.float64))
+    assert_close(host(gk), rk, RTOL_GRAD, "conv_bwd_weight of C2, 37 images")
+    assert_close(host(gb), rb, RTOL_GRAD, "conv_bwd_weight bias of C2, 37 images")
+
+
 @pytest.mark.parametrize("case", CONV_CASES)
 def test_conv_bwd_weight(case):
     B, Cin, H, W, Cout, KH, KW = case
