@@ -231,4 +231,178 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(4, 4)))
 inline size_t bwd_weight_workspace_bytes(unsigned groups) { return sizeof(float) * (size_t)groups * (10 * 256 + 16); }
 
 }  // namespace conv2
+
+// ---- the first convolution's shape: one input map 28 x 28, six output maps, 5 x 5 kernel -----------------
+// Forward pass, one wave per image, as the GEMM over pixel pairs of cnn_wave.h (c1f_*: rows (map, x
+// parity), K = 30 shifted taps, 18 tiles of 16 pixel pairs): 144 matrix instructions per image.  The
+// operation moves 3.1 KB in and 13.8 KB out per image and is bound by those stores: the three tiles of
+// a band of four pixel rows are collected in LDS as out[6][4][24] and leave as six runs of 384
+// consecutive bytes in 16-byte items with the non-temporal hint (8-byte stores straight from the
+// result registers were 8 % slower than the general kernel once the output no longer fits the
+// last-level cache).
+namespace conv1 {
+
+constexpr int WAVES_PER_GROUP = 8, THREADS = 64 * WAVES_PER_GROUP;
+inline bool shape_fits(int Cin, int H, int W, int Cout, int KH, int KW) {
+  return Cin == 1 && Cout == 6 && KH == 5 && KW == 5 && H == 28 && W == 28;
+}
+constexpr int BAND = 6 * 4 * 24;  // one band of the output: six maps, four rows
+struct __align__(16) FwdLds {
+  float wa[C1F_KSTEPS * 64];  // A operand, [K step][lane]
+  float bias[8];
+  float img[WAVES_PER_GROUP][NI];
+  float band[WAVES_PER_GROUP][BAND];
+};
+__global__ __launch_bounds__(THREADS) void forward_kernel(const float* __restrict__ in, const float* __restrict__ k,
+                                                          const float* __restrict__ bias, float* __restrict__ out,
+                                                          int B) {
+  __shared__ FwdLds lds;
+  const int t = threadIdx.x, wave = t >> 6, l = t & 63, q = l >> 4, n16 = l & 15;
+  if (t < C1F_KSTEPS * 64) {
+    const int src = c1f_weight(t >> 6, t & 63);  // index into the flat parameter vector, k1 first
+    lds.wa[t] = src >= 0 ? k[src - OFF_K1] : 0.0f;
+  }
+  if (t < 8) lds.bias[t] = bias && t < 6 ? bias[t] : 0.0f;
+  __syncthreads();
+  float wa[C1F_KSTEPS];
+#pragma unroll
+  for (int ks = 0; ks < C1F_KSTEPS; ++ks) wa[ks] = lds.wa[ks * 64 + l];
+  f4 binit = f4{0.0f, 0.0f, 0.0f, 0.0f};
+  if (q < 3) binit = f4{lds.bias[2 * q], lds.bias[2 * q], lds.bias[2 * q + 1], lds.bias[2 * q + 1]};
+  const C1Lane ln = c1f_lane();
+  // maps 2 q and 2 q + 1 at the lane's pixel pair inside a band (lanes q = 3 hold padding rows)
+  const int lane_band = 2 * q * 96 + (((n16 >> 1) & 1) * 2 + (n16 & 1)) * 24 + 2 * (n16 >> 2);
+  float* img = lds.img[wave];
+  float* band = lds.band[wave];
+  const size_t G = (size_t)gridDim.x * WAVES_PER_GROUP, first = (size_t)blockIdx.x * WAVES_PER_GROUP + wave;
+  Pixels px;
+  if (first < (size_t)B) px = load_pixels(in + first * NI);
+  for (size_t n = first; n < (size_t)B; n += G) {
+    store_pixels(img, px);
+    wave_sync();
+    if (n + G < (size_t)B) px = load_pixels(in + (n + G) * NI);  // in flight during this image
+    float* dst = out + n * NC1;
+#pragma unroll
+    for (int ty = 0; ty < 6; ++ty) {
+      f4 d0, d1, d2;
+      c1f_gemm_pair(wa, ln, img + c1f_tile_img(3 * ty), img + c1f_tile_img(3 * ty + 1), binit, d0, d1);
+      c1f_gemm_one(wa, ln, img + c1f_tile_img(3 * ty + 2), binit, d2);
+      if (q < 3) {
+        float* p = band + lane_band;
+        *reinterpret_cast<float2*>(p) = float2{d0[0], d0[1]};
+        *reinterpret_cast<float2*>(p + 96) = float2{d0[2], d0[3]};
+        *reinterpret_cast<float2*>(p + 8) = float2{d1[0], d1[1]};
+        *reinterpret_cast<float2*>(p + 8 + 96) = float2{d1[2], d1[3]};
+        *reinterpret_cast<float2*>(p + 16) = float2{d2[0], d2[1]};
+        *reinterpret_cast<float2*>(p + 16 + 96) = float2{d2[2], d2[3]};
+      }
+      wave_sync();
+      // the band: map m's four rows are 96 consecutive floats of the output
+#pragma unroll
+      for (int i = 0; i < 3; ++i) {
+        const int e = l + 64 * i;  // 16-byte piece of the band
+        if (e < BAND / 4) {
+          const int m = e / 24, piece = e - 24 * m;
+          __builtin_nontemporal_store(reinterpret_cast<const f4*>(band)[e],
+                                      reinterpret_cast<f4*>(dst + m * 576 + ty * 96) + piece);
+        }
+      }
+      wave_sync();  // the band is read before the next one is written
+    }
+  }
+}
+
+// Weight and bias gradient of the same shape, one wave per image: the GEMM over pixel pairs of
+// cnn_wave.h (c1g_accumulate: rows (map, x parity), columns the 30 shifted taps, K = 288 pixel
+// pairs; the padding column 30 sums the error itself, i.e. the bias gradient): 144 matrix
+// instructions per image.  The output error (13.8 KB per image, the bulk of what the operation
+// reads) comes in three chunks of eight rows, d1c[6][8][24] with the maps D1C_MAP apart, the next
+// chunk in registers while the current one is multiplied.  The sums stay in registers over all of
+// a wave's images; the workgroup's eight waves are added in a fixed order and one set of partial
+// tiles goes to the workspace in the general kernel's layout for P = 2 (rows 2 m + sh, columns
+// 6 u + v'; bias rows 2 m + sh), which its second kernel joins and adds.
+constexpr int CHUNK_PIECES = 6 * 8 * 24 / 4;  // 16-byte pieces of an error chunk
+struct __align__(16) WgradLds {
+  float ones[C1G_ONES];
+  float img[WAVES_PER_GROUP][NI];
+  float d1c[WAVES_PER_GROUP][6 * D1C_MAP + 8];  // after the last image: the wave's sums, [8 registers][64 lanes]
+};
+static_assert(6 * D1C_MAP + 8 >= 8 * 64, "a wave's chunk area holds its sums");
+struct Chunk {
+  f4 v[5];  // pieces l, l + 64, .. (the fifth only in lanes 0..31)
+};
+__device__ __forceinline__ Chunk load_chunk(const float* __restrict__ d_out, size_t n, int gp) {
+  const int l = threadIdx.x & 63;
+  Chunk c;
+#pragma unroll
+  for (int i = 0; i < 5; ++i) {
+    const int e = l + 64 * i, ee = e < CHUNK_PIECES ? e : 0, m = ee / 48, piece = ee - 48 * m;
+    c.v[i] = reinterpret_cast<const f4*>(d_out + n * NC1 + m * 576 + gp * 192)[piece];
+  }
+  return c;
+}
+__device__ __forceinline__ void store_chunk(float* d1c, const Chunk& c) {
+  const int l = threadIdx.x & 63;
+#pragma unroll
+  for (int i = 0; i < 5; ++i) {
+    const int e = l + 64 * i, m = e / 48, piece = e - 48 * m;
+    if (e < CHUNK_PIECES) *reinterpret_cast<f4*>(d1c + m * D1C_MAP + 4 * piece) = c.v[i];
+  }
+}
+__global__ __launch_bounds__(THREADS) void bwd_weight_kernel(const float* __restrict__ in,
+                                                             const float* __restrict__ d_out,
+                                                             float* __restrict__ part, int B) {
+  __shared__ WgradLds lds;
+  const int t = threadIdx.x, wave = t >> 6, l = t & 63, q = l >> 4, n16 = l & 15;
+  for (int e = t; e < C1G_ONES; e += THREADS) lds.ones[e] = 1.0f;
+  __syncthreads();
+  float* img = lds.img[wave];
+  float* d1c = lds.d1c[wave];
+  f4 acc[2] = {f4{0.0f, 0.0f, 0.0f, 0.0f}, f4{0.0f, 0.0f, 0.0f, 0.0f}};
+  const size_t G = (size_t)gridDim.x * WAVES_PER_GROUP, first = (size_t)blockIdx.x * WAVES_PER_GROUP + wave;
+  Pixels px;
+  Chunk ch;
+  if (first < (size_t)B) {
+    px = load_pixels(in + first * NI);
+    ch = load_chunk(d_out, first, 0);
+  }
+  for (size_t n = first; n < (size_t)B; n += G) {
+    store_pixels(img, px);
+    const bool more = n + G < (size_t)B;
+    if (more) px = load_pixels(in + (n + G) * NI);  // in flight during this image
+#pragma unroll
+    for (int gp = 0; gp < 3; ++gp) {
+      store_chunk(d1c, ch);
+      wave_sync();
+      // the next chunk (of this image, or the first of the next image) is in flight during the GEMM
+      if (gp < 2)
+        ch = load_chunk(d_out, n, gp + 1);
+      else if (more)
+        ch = load_chunk(d_out, n + G, 0);
+      c1g_accumulate<C1G_STEPS / 3, D1C_MAP>(acc, d1c, img + 8 * 28 * gp, l, lds.ones);
+      wave_sync();  // the reads of this chunk come before the next chunk's (and image's) stores
+    }
+  }
+  // ---- the eight waves' sums in wave order; T[row i = 4 q + r][column 16 nt + n16] ----
+  float* mine = lds.d1c[wave];
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) mine[(4 * nt + r) * 64 + l] = acc[nt][r];
+  __syncthreads();
+  if (wave < 2) {  // wave nt adds and stores tile nt
+    float* tile = part + ((size_t)blockIdx.x * 2 + wave) * 256;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float sum = 0.0f;
+      for (int w = 0; w < WAVES_PER_GROUP; ++w) sum += lds.d1c[w][(4 * wave + r) * 64 + l];
+      tile[(4 * q + r) * 16 + n16] = sum;
+      // column 30 (tile 1, n16 = 14) holds the sums of the error by (map, x parity): the bias rows
+      if (wave == 1 && n16 == 14) part[(size_t)gridDim.x * 2 * 256 + (size_t)blockIdx.x * 16 + 4 * q + r] = sum;
+    }
+  }
+}
+inline size_t bwd_weight_workspace_bytes(unsigned groups) { return sizeof(float) * (size_t)groups * (2 * 256 + 16); }
+
+}  // namespace conv1
 }  // namespace cnn

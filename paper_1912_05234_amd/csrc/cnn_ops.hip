@@ -491,6 +491,19 @@ WgradPlan plan_wgrad_packed(int B, int Cin, int H, int W, int Cout, int KH, int 
 // The packing factor that needs the fewest matrix instructions per image (column tiles x blocks of
 // pixel slots) among the divisors P of Wo with Cout*P <= 16; 1 for kernels one column wide.
 WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
+  if (conv1::shape_fits(Cin, H, W, Cout, KH, KW)) {
+    WgradPlan p;
+    igemm::WgradArgs& a = p.a;
+    a.in = nullptr, a.d_out = nullptr, a.part = nullptr;
+    a.B = B, a.Cin = Cin, a.H = H, a.W = W, a.Cout = Cout, a.KH = KH, a.KW = KW;
+    a.P = 2, a.MT = 1, a.NT = 2;  // rows (map, x parity), columns the shifted taps: what the second kernel joins
+    p.fits = p.one_wave_per_image = true;
+    const unsigned groups = (unsigned)((B + conv1::WAVES_PER_GROUP - 1) / conv1::WAVES_PER_GROUP);
+    p.gx = groups < 2u * NUM_CU ? groups : 2u * NUM_CU;
+    p.gy = 1;
+    p.workspace_bytes = conv1::bwd_weight_workspace_bytes(p.gx);
+    return p;
+  }
   if (conv2::shape_fits(Cin, H, W, Cout, KH, KW)) {
     WgradPlan p;
     igemm::WgradArgs& a = p.a;
@@ -671,7 +684,9 @@ int launch_wgrad(WgradPlan& p, const float* in, const float* d_out, float* d_k, 
                  hipStream_t st) {
   p.a.in = in, p.a.d_out = d_out, p.a.part = part;
   const dim3 grid(p.gx, p.gy);
-  if (p.one_wave_per_image)
+  if (p.one_wave_per_image && p.a.Cin == 1)
+    conv1::bwd_weight_kernel<<<p.gx, conv1::THREADS, 0, st>>>(in, d_out, part, p.a.B);
+  else if (p.one_wave_per_image)
     conv2::bwd_weight_kernel<<<p.gx, conv2::THREADS, 0, st>>>(in, d_out, part, p.a.B);
   else if (p.a.vec_x && p.a.vec_d)
     igemm::wgrad_kernel<16, 16><<<grid, igemm::THREADS, p.lds_bytes, st>>>(p.a);
@@ -730,6 +745,12 @@ int cnn_conv_fwd(const float* in, const float* k, const float* bias, float* out,
                  int W, int Cout, int KH, int KW, void* hip_stream) {
   if (!in || !k || !out || !conv_args_ok(B, Cin, H, W, Cout, KH, KW)) return CNN_EINVAL;
   if (!aligned16(in) || !aligned16(k) || !aligned16(out) || (bias && !aligned16(bias))) return CNN_EINVAL;
+  if (conv1::shape_fits(Cin, H, W, Cout, KH, KW)) {  // the network's first convolution: one wave per image
+    const int groups = (B + conv1::WAVES_PER_GROUP - 1) / conv1::WAVES_PER_GROUP, resident = 2 * NUM_CU;
+    conv1::forward_kernel<<<groups < resident ? groups : resident, conv1::THREADS, 0, (hipStream_t)hip_stream>>>(
+        in, k, bias, out, B);
+    return launched();
+  }
   if (conv2::shape_fits(Cin, H, W, Cout, KH, KW)) {  // the network's second convolution: one wave per image
     // (two workgroups per compute unit; one, three or four measured the same: the kernel is bound by its matrix instructions)
     const int groups = (B + conv2::WAVES_PER_GROUP - 1) / conv2::WAVES_PER_GROUP, resident = 2 * NUM_CU;

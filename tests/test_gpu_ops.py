@@ -120,6 +120,37 @@ def test_forward_and_weight_gradient_of_the_second_convolution_with_looping_wave
     assert_close(host(gb), rb, RTOL_GRAD, "conv_bwd_weight bias of C2, 37 images")
 
 
+def test_forward_and_weight_gradient_of_the_first_convolution_with_looping_waves():
+    """4101 images of C1's shape through its one-wave-per-image forward and weight-gradient kernels (waves
+    take a second image, ragged last round): sampled images against the oracle, every image against the
+    plain kernel; without a bias; the gradient sums against the plain kernel and the oracle."""
+    B = 4101
+    x = inputs.make_signed((B, 1, 28, 28), 47)
+    k = inputs.make_signed((6, 1, 5, 5), 48)
+    b = inputs.make_signed((6,), 49)
+    got = host(binding.conv_fwd(dev(x), dev(k), dev(b)))
+    sample = sorted(set(list(range(8)) + list(range(4090, 4101)) + list(range(0, B, 397))))
+    assert_close(got[sample], oracle_conv_fwd(x[sample], k, b), RTOL_ACT, "conv_fwd of C1, sampled images")
+    plain = host(binding.conv_fwd(dev(x), dev(k), dev(b), valu=True))
+    assert_close(got, plain.astype(np.float64), RTOL_ACT, "conv_fwd of C1 against the plain kernel")
+    got0 = host(binding.conv_fwd(dev(x[:9]), dev(k), None))
+    assert_close(got0, oracle_conv_fwd(x[:9], k, np.zeros(6, np.float32)), RTOL_ACT, "conv_fwd of C1 without bias")
+    # weight and bias gradient over the same images: against the plain kernel, and the last 37 against the oracle
+    d = inputs.make_signed((B, 6, 24, 24), 50)
+    gk, gb = binding.conv_bwd_weight(dev(x), dev(d))
+    pk, pb = binding.conv_bwd_weight(dev(x), dev(d), workspace=False)
+    assert_close(host(gk), host(pk).astype(np.float64), RTOL_GRAD, "conv_bwd_weight of C1 against the plain kernel")
+    assert_close(host(gb), host(pb).astype(np.float64), RTOL_GRAD, "conv_bwd_weight bias of C1 against the plain kernel")
+    gk, gb = binding.conv_bwd_weight(dev(x[B - 37:]), dev(d[B - 37:]))
+    rk, rb = np.zeros((6, 1, 5, 5), np.float64), np.zeros(6, np.float64)
+    for n in range(B - 37, B):
+        for co in range(6):
+            rk[co] += oracle.backweights(d[n, co][None].astype(np.float64), x[n].astype(np.float64)).reshape(1, 5, 5)
+            rb[co] += oracle.backbias(d[n, co].astype(np.float64))
+    assert_close(host(gk), rk, RTOL_GRAD, "conv_bwd_weight of C1, 37 images")
+    assert_close(host(gb), rb, RTOL_GRAD, "conv_bwd_weight bias of C1, 37 images")
+
+
 @pytest.mark.parametrize("case", CONV_CASES)
 def test_conv_bwd_weight(case):
     B, Cin, H, W, Cout, KH, KW = case
