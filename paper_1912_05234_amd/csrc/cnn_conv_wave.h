@@ -1,7 +1,10 @@
-// Forward pass and weight gradient of a 5 x 5 convolution with six input and twelve output maps on
-// a 12 x 12 input (the shape of the network's second convolution), ONE WAVE PER IMAGE, in the GEMM
-// forms of the fused training step (arXiv 1912.05234, Section 3: listings conv / mconv,
-// backweights, backbias):
+// Convolution calls for the shapes of the network's own two convolution layers, ONE WAVE PER IMAGE,
+// in the GEMM forms of the fused training step (arXiv 1912.05234, Section 3: listings conv / mconv,
+// backweights, backbias).  An image of these layers is small enough for one wave to hold in its LDS,
+// which saves the barriers and the staging for shared groups of images that the general kernels
+// (cnn_igemm.h) pay; eight waves per workgroup, two workgroups per compute unit.
+//
+// namespace conv2: six input and twelve output maps, 5 x 5 kernel, 12 x 12 input
 //   forward          M = 64 output pixels in four tiles, N = 12(16) maps, K = 150(152) taps: 152
 //                    v_mfma_f32_16x16x4_f32 per image; the image's 864 inputs are staged in the
 //                    wave's LDS, the weights sit in LDS as the instruction's B operand
@@ -9,13 +12,13 @@
 //                    the output error is the A operand straight from global memory, the sums stay
 //                    in registers over all of a wave's images; the eight waves of a workgroup are
 //                    added through LDS in a fixed order and the workgroup writes one set of partial
-//                    tiles in the layout of the general kernel (cnn_igemm.h), whose second kernel
-//                    adds the workgroups' partials.
-// Eight waves per workgroup, two workgroups per compute unit (four waves per SIMD): the matrix
-// instructions of three waves run under the LDS and memory waits of the fourth.  The general
-// kernels stage groups of images for four waves that then share them, which costs barriers and
-// staging time these shapes do not need: an image is small enough for one wave.  Pixel order and
-// operand layouts are those of cnn_wave.h (fwd_tap, fwd_imm); only such index helpers are shared.
+//                    tiles in the layout of the general kernel, whose second kernel adds the
+//                    workgroups' partials
+//   (the input gradient of this shape is cnn_col2im.h)
+// namespace conv1: one input and six output maps, 5 x 5 kernel, 28 x 28 input: forward and weight
+//   gradient as GEMMs over pixel pairs, 144 per image each; see there.
+// Pixel order and operand layouts are those of cnn_wave.h (fwd_tap, fwd_imm, c1f_*, c1g_*); only such
+// index helpers and GEMM inner loops are shared with the fused step.
 #pragma once
 
 #include "cnn_wave.h"

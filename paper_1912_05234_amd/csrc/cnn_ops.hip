@@ -10,7 +10,7 @@
 #include "cnn_igemm.h"
 #include "cnn_igemm_bf16.h"
 #include "cnn_col2im.h"
-#include "cnn_conv2.h"
+#include "cnn_conv_wave.h"
 
 namespace {
 
