@@ -28,10 +28,7 @@ constexpr int FWD_GCAP = 3072;  // most forward-only waves: three per SIMD
 // up to two such workgroups share a compute unit); larger ones give each image to a single wave
 // (more images in flight, no barriers).  Measured crossover: 21.7 against 27.9 us per step at batch
 // 512, 30.8 against 28.8 us at batch 768.
-#ifndef GROUP_MAX
-#define GROUP_MAX 640
-#endif
-constexpr int GROUP_MAX_BATCH = GROUP_MAX;
+constexpr int GROUP_MAX_BATCH = 640;
 // Device-side epoch loop: one barrier flag per workgroup (a batch of at most EPOCH_MAX_BATCH images:
 // thread t of a 512-thread workgroup polls flag t), one flag nobody sets, the error word.
 constexpr int EPOCH_MAX_BATCH = 256;
@@ -132,12 +129,9 @@ constexpr int TWAVES = 8;
 // workgroup alike, so an equal split leaves the SIMD to one wave for the last sixth of the kernel.
 // A batch that does not fill the machine (K < 8) still leaves waves 4..7 idle rather than two
 // waves on one SIMD and none on another: the first round is a full one.
-#ifndef SHARE_PATTERN_BITS
-#define SHARE_PATTERN_BITS 0xB  /* rounds F F H F (first round in bit 0): 4 images to 3 */
-#define SHARE_PATTERN_ROUNDS 4
-#endif
-constexpr int SHARE_ROUNDS = SHARE_PATTERN_ROUNDS;
-constexpr bool share_full(int r) { return (SHARE_PATTERN_BITS >> r) & 1; }
+constexpr unsigned SHARE_PATTERN = 0xB;  // rounds F F H F (first round in bit 0): 4 images to 3
+constexpr int SHARE_ROUNDS = 4;
+constexpr bool share_full(int r) { return (SHARE_PATTERN >> r) & 1; }
 constexpr int share_start(int r) {  // first image of round r inside a period
   int at = 0;
   for (int i = 0; i < r; ++i) at += share_full(i) ? 8 : 4;
