@@ -87,27 +87,37 @@ __global__ __launch_bounds__(64 * WAVES, 2) void forward_kernel(const float* __r
   }
 }
 
-// Sums the G (count, loss) pairs: 64 interleaved strands, then a fixed order over the strands.  The
-// counts are whole numbers (each wave's is far below 2^24, so exact in its float) and are added as
-// 64-bit integers.
-__global__ __launch_bounds__(64) void eval_reduce_kernel(const float* __restrict__ eval_partial, int G,
-                                                         int64_t* __restrict__ n_correct,
-                                                         float* __restrict__ loss_sum) {
-  __shared__ long long counts[64];
+// Sums the G (count, loss) pairs: 1024 interleaved strands (at most three pairs each for the 3072
+// waves of the forward kernel, so the loads are one memory round trip), then a fixed tree over the
+// strands.  The counts are whole numbers (each wave's is far below 2^24, so exact in its float) and
+// are added as 64-bit integers.
+constexpr int EVAL_REDUCE_THREADS = 1024;
+__global__ __launch_bounds__(EVAL_REDUCE_THREADS) void eval_reduce_kernel(const float* __restrict__ eval_partial,
+                                                                          int G, int64_t* __restrict__ n_correct,
+                                                                          float* __restrict__ loss_sum) {
+  __shared__ long long counts[EVAL_REDUCE_THREADS];
+  __shared__ float losses[EVAL_REDUCE_THREADS];
+  const int t = threadIdx.x;
   long long ok = 0;
   float loss = 0.0f;
-  for (int g = threadIdx.x; g < G; g += 64) {
-    ok += (long long)eval_partial[2 * g];
-    loss += eval_partial[2 * g + 1];
+  for (int g = t; g < G; g += EVAL_REDUCE_THREADS) {
+    const float2 pair = reinterpret_cast<const float2*>(eval_partial)[g];
+    ok += (long long)pair.x;
+    loss += pair.y;
   }
-  counts[threadIdx.x] = ok;
-  loss = wave_sum(loss);
+  counts[t] = ok;
+  losses[t] = loss;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    long long total = 0;
-    for (int k = 0; k < 64; ++k) total += counts[k];
-    if (n_correct) *n_correct = (int64_t)total;
-    if (loss_sum) *loss_sum = loss;
+  for (int half = EVAL_REDUCE_THREADS / 2; half >= 1; half >>= 1) {
+    if (t < half) {
+      counts[t] += counts[t + half];
+      losses[t] += losses[t + half];
+    }
+    __syncthreads();
+  }
+  if (t == 0) {
+    if (n_correct) *n_correct = (int64_t)counts[0];
+    if (loss_sum) *loss_sum = losses[0];
   }
 }
 
@@ -764,7 +774,7 @@ int cnn_evaluate(cnn_ctx* ctx, const float* images, const int32_t* labels, int N
   if (!batch_ok(ctx, N) || !images || !labels || !n_correct || !aligned16(images)) return CNN_EINVAL;
   const int G = run_forward(ctx, images, labels, N, nullptr, nullptr, nullptr, nullptr, nullptr, true);
   if (G < 0) return G;
-  eval_reduce_kernel<<<1, 64, 0, ctx->stream>>>(ctx->eval_partial, G, n_correct, loss_sum);
+  eval_reduce_kernel<<<1, EVAL_REDUCE_THREADS, 0, ctx->stream>>>(ctx->eval_partial, G, n_correct, loss_sum);
   return hipGetLastError() == hipSuccess ? CNN_OK : CNN_EHIP;
 }
 
