@@ -212,12 +212,12 @@ __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 
   float pk[PK_ROUNDS];
 #pragma unroll
   for (int r = 0; r < PK_ROUNDS; ++r) {
-    const int i = r * 64 * TWAVES + threadIdx.x;
-    const int slot = i < TAB_PK_COUNT * 64 ? packed_table_slot(i >> 6, i & 63) : -1;
+    const int e = r * TWAVES + wave;  // a wave gathers one entry per round (wave-uniform: scalar arithmetic)
+    const int slot = e < TAB_PK_COUNT ? packed_table_slot(e, threadIdx.x & 63) : -1;
     pk[r] = tabg[slot >= 0 ? slot : 0];
     if (slot < 0) pk[r] = 0.0f;
   }
-  window_table_init(wt);
+  window_table_init<64 * TWAVES>(wt);
   // waves without images skip their set-up and their row
   if (has_images) {
     wave_init(st, s);
@@ -287,7 +287,8 @@ __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 
   if (has_images) wave_flush(st, g_fc, reinterpret_cast<float*>(&s), tab.e + wave * C1G_PARK);
   __syncthreads();
   {
-    // rows of the waves that had images in a fixed tree; an idle wave's row counts as zeros
+    // rows of the waves that had images in a fixed tree; an idle wave's row counts as zeros (the
+    // first round deals image k to wave k, so wave k has images exactly when K > k)
     const f4* r = reinterpret_cast<const f4*>(&lds[0]);
     constexpr int RF4 = PSTRIDE / 4;  // a wave's area is exactly one row
     f4* dst = reinterpret_cast<f4*>(partial + (size_t)blockIdx.x * PSTRIDE);
@@ -295,7 +296,7 @@ __global__ __launch_bounds__(64 * TWAVES) __attribute__((amdgpu_waves_per_eu(2, 
     for (int i = threadIdx.x; i < RF4; i += 64 * TWAVES) {
       f4 v[TWAVES];
 #pragma unroll
-      for (int k = 0; k < TWAVES; ++k) v[k] = share_count(K, k) > 0 ? r[i + k * RF4] : zero;
+      for (int k = 0; k < TWAVES; ++k) v[k] = K > k ? r[i + k * RF4] : zero;
       dst[i] = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
     }
   }

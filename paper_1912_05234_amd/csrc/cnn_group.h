@@ -401,24 +401,31 @@ __device__ __forceinline__ void group_train(const float* __restrict__ image,
   CNN_GROUP_MARK(9);
   __syncthreads();
   CNN_GROUP_MARK(12);
-  if (wave >= 4) {  // C2 weights: every wave stores the columns (tap tiles) it owns
+  // (stores grouped by the lanes that take part: one branch per group, not one per store)
+  if (wave >= 4) {  // C2 weights: every wave stores the columns (tap tiles) it owns; rows j = 4 q + r < 12
     const int first = k2_first(wave - 4), count = k2_count(wave - 4);
 #pragma unroll
-    for (int k = 0; k < 3; ++k)
+    for (int k = 0; k < 3; ++k) {
+      const int tap = 16 * (first + k) + n16;
+      if (k < count && q < 3 && tap < 150) {
+        float* dst = out + OFF_K2 + 4 * q * 150 + tap;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int j = 4 * q + r, tap = 16 * (first + k) + n16;
-        if (k < count && j < 12 && tap < 150) put_row<COHERENT>(out + OFF_K2 + j * 150 + tap, st.acc_k2[k][r]);
+        for (int r = 0; r < 4; ++r) put_row<COHERENT>(dst + r * 150, st.acc_k2[k][r]);
       }
+    }
   }
-  if (wave < 3) {
+  if (wave < 3) {  // FC rows o = 4 wave + r < 10: wave 2 has two
+    float* dst = out + OFF_FC + 4 * wave * NS2 + l;
 #pragma unroll
     for (int k = 0; k < 3; ++k)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int o = 4 * wave + r;
-        if (o < 10) put_row<COHERENT>(out + OFF_FC + o * NS2 + l + 64 * k, st.acc_fc[k][r]);
-      }
+      for (int r = 0; r < 2; ++r) put_row<COHERENT>(dst + r * NS2 + 64 * k, st.acc_fc[k][r]);
+    if (wave < 2) {
+#pragma unroll
+      for (int k = 0; k < 3; ++k)
+#pragma unroll
+        for (int r = 2; r < 4; ++r) put_row<COHERENT>(dst + r * NS2 + 64 * k, st.acc_fc[k][r]);
+    }
     if (l < 4 && 4 * wave + l < 10) put_row<COHERENT>(out + OFF_B + 4 * wave + l, st.g_bq);
   }
   CNN_GROUP_MARK(13);

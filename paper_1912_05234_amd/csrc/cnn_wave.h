@@ -551,15 +551,25 @@ struct WindowTable {
   int k2b[10][64];
   float ones[C1G_ONES];  // 1.0: B operand of the padding columns of the C1 weight-gradient GEMM (c1g_accumulate)
 };
+// Filled by all THREADS threads of the workgroup (the caller's barrier follows).
+template <int THREADS>
 __device__ __forceinline__ void window_table_init(WindowTable& w) {
-  for (int win = threadIdx.x; win < NWIN; win += blockDim.x)
-    w.o[win] = int2{56 * (win / 12) + 2 * (win % 12), 48 * (win / 12) + 2 * (win % 12)};
-  for (int e = threadIdx.x; e < 640; e += blockDim.x) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int r = 0; r < (NWIN + THREADS - 1) / THREADS; ++r) {
+    const int win = t + r * THREADS;
+    if (win < NWIN) w.o[win] = int2{56 * (win / 12) + 2 * (win % 12), 48 * (win / 12) + 2 * (win % 12)};
+  }
+#pragma unroll
+  for (int r = 0; r < (640 + THREADS - 1) / THREADS; ++r) {
+    const int e = t + r * THREADS;
     const int nt = e >> 6, l = e & 63, tap = 16 * nt + (l & 15);
     const int c = tap / 25, rem = tap - 25 * c, u = rem / 5, v = rem - 5 * u;
-    w.k2b[nt][l] = (tap < 150 ? c * 144 + u * 12 + v : 0) + 2 * (l >> 4);
+    if (e < 640) w.k2b[nt][l] = (tap < 150 ? c * 144 + u * 12 + v : 0) + 2 * (l >> 4);
   }
-  for (int e = threadIdx.x; e < C1G_ONES; e += blockDim.x) w.ones[e] = 1.0f;
+#pragma unroll
+  for (int r = 0; r < (C1G_ONES + THREADS - 1) / THREADS; ++r)
+    if (t + r * THREADS < C1G_ONES) w.ones[t + r * THREADS] = 1.0f;
 }
 
 // What the FC weight gradient needs of one image, kept in global memory until the wave has done all
@@ -1115,20 +1125,38 @@ __device__ __forceinline__ void fc_step_mfma(f4 (&g_fc)[12], const FcStepOperand
 // C1G_PARK floats of LDS outside the row that no other wave uses; `g_fc` is wave_fc_gradient's result.
 __device__ __forceinline__ void wave_flush(WaveState<kTrain>& st, const f4 (&g_fc)[12], float* row, float* park) {
   const int l = threadIdx.x & 63, q = l >> 4, n16 = l & 15;
+  // The stores are grouped by the lanes that take part (one branch per group, not one per store):
+  // FC rows o = 4 q + r < 10 are registers 0, 1 of the quarters 0..2 and registers 2, 3 of the quarters
+  // 0, 1; C2 rows j = 4 q + r < 12 are every register of the quarters 0..2, and of the last tap tile
+  // only the columns n16 < 6 are taps.
+  {
+    float* fc = row + OFF_FC + 4 * q * NS2 + n16;
+    if (q < 3) {
 #pragma unroll
-  for (int nt = 0; nt < 12; ++nt)
+      for (int nt = 0; nt < 12; ++nt)
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-      if (4 * q + r < 10) row[OFF_FC + (4 * q + r) * NS2 + 16 * nt + n16] = g_fc[nt][r];
+        for (int r = 0; r < 2; ++r) fc[r * NS2 + 16 * nt] = g_fc[nt][r];
+    }
+    if (q < 2) {
+#pragma unroll
+      for (int nt = 0; nt < 12; ++nt)
+#pragma unroll
+        for (int r = 2; r < 4; ++r) fc[r * NS2 + 16 * nt] = g_fc[nt][r];
+    }
+  }
   if (l < 10) row[OFF_B + l] = st.g_b;
   if (l < PSTRIDE - LOSS_SLOT) row[LOSS_SLOT + l] = l == 0 ? st.loss : 0.0f;
+  if (q < 3) {
+    float* k2 = row + OFF_K2 + 4 * q * 150 + n16;
 #pragma unroll
-  for (int nt = 0; nt < 10; ++nt)
+    for (int nt = 0; nt < 9; ++nt)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int j = 4 * q + r, tap = 16 * nt + n16;
-      if (j < 12 && tap < 150) row[OFF_K2 + j * 150 + tap] = st.acc_k2[nt][r];
+      for (int r = 0; r < 4; ++r) k2[r * 150 + 16 * nt] = st.acc_k2[nt][r];
+    if (n16 < 150 - 16 * 9) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) k2[r * 150 + 16 * 9] = st.acc_k2[9][r];
     }
+  }
   {
     float v = st.g_b2;  // lane (q, j): sum over the four lane quarters
     v += __shfl_xor(v, 16);
