@@ -147,9 +147,11 @@ int cnn_profile_read(cnn_ctx* ctx, float* ms, int capacity, int* n_recorded);
  *   out[b,co,y,x] = bias[co] + sum_{ci,u,v} in[b,ci,y+u,x+v] * k[co,ci,u,v]
  * with Ho = H-KH+1, Wo = W-KW+1 (both must be >= 1).  bias may be NULL.  All tensors are device
  * memory, 16-byte aligned, fp32, and finite: the matrix-core kernels multiply padding lanes by
- * zero, which a NaN or infinity in the input would turn into NaN.  (One shape, Cin = 6, Cout = 12,
- * KH = KW = 5, H = W = 12 -- the network's second convolution -- has kernels of its own for all three
- * convolution calls; same definitions, sums in another order.) */
+ * zero, which a NaN or infinity in the input would turn into NaN.  (The shapes of the network's own
+ * layers have kernels of their own: Cin = 6, Cout = 12, KH = KW = 5, H = W = 12, the second
+ * convolution, for all three convolution calls; Cin = 1, Cout = 6, KH = KW = 5, H = W = 28, the first,
+ * for the forward pass and the weight gradient; I = 192, O = 10 for the three cnn_fc_* calls.  Same
+ * definitions, sums in another order.) */
 int cnn_conv_fwd(const float* in, const float* k, const float* bias, float* out, int B, int Cin,
                  int H, int W, int Cout, int KH, int KW, void* hip_stream);
 /* `backin` summed over output maps: d_in[b,ci,p,q] = sum_co sum_{u,v : 0<=p-u<Ho, 0<=q-v<Wo}

@@ -11,6 +11,7 @@
 #include "cnn_igemm_bf16.h"
 #include "cnn_col2im.h"
 #include "cnn_conv_wave.h"
+#include "cnn_fc_wave.h"
 
 namespace {
 
@@ -437,7 +438,8 @@ int launch_conv(const ConvPlan& p, hipStream_t stream) {
 struct WgradPlan {
   igemm::WgradArgs a;
   bool fits = false;
-  bool one_wave_per_image = false;  // the second convolution's shape: conv2::bwd_weight_kernel, gx workgroups
+  bool one_wave_per_image = false;  // the shape of one of the network's convolutions: conv1:: / conv2::bwd_weight_kernel, gx workgroups
+  bool fc_rows = false;             // the shape of the network's fully connected layer: fc::bwd_weight_kernel, gx workgroups
   unsigned gx = 0, gy = 0;
   size_t lds_bytes = 0, workspace_bytes = 0;
 };
@@ -502,6 +504,21 @@ WgradPlan plan_wgrad(int B, int Cin, int H, int W, int Cout, int KH, int KW) {
     p.gx = groups < 2u * NUM_CU ? groups : 2u * NUM_CU;
     p.gy = 1;
     p.workspace_bytes = conv1::bwd_weight_workspace_bytes(p.gx);
+    return p;
+  }
+  if (H == 1 && W == 1 && KH == 1 && KW == 1 && fc::shape_fits(Cin, Cout)) {
+    WgradPlan p;
+    igemm::WgradArgs& a = p.a;
+    a.in = nullptr, a.d_out = nullptr, a.part = nullptr;
+    a.B = B, a.Cin = Cin, a.H = H, a.W = W, a.Cout = Cout, a.KH = KH, a.KW = KW;
+    a.P = 1, a.MT = 1, a.NT = fc::NT;  // what the second kernel needs to find the partial tiles
+    p.fits = p.fc_rows = true;
+    // a wave takes fc::AHEAD steps of four images per memory round trip
+    const int per_group = 4 * fc::AHEAD * fc::WGRAD_WAVES;
+    const unsigned groups = (unsigned)((B + per_group - 1) / per_group);
+    p.gx = groups < 2u * NUM_CU ? groups : 2u * NUM_CU;
+    p.gy = 1;
+    p.workspace_bytes = fc::bwd_weight_workspace_bytes(p.gx);
     return p;
   }
   if (conv2::shape_fits(Cin, H, W, Cout, KH, KW)) {
@@ -684,7 +701,9 @@ int launch_wgrad(WgradPlan& p, const float* in, const float* d_out, float* d_k, 
                  hipStream_t st) {
   p.a.in = in, p.a.d_out = d_out, p.a.part = part;
   const dim3 grid(p.gx, p.gy);
-  if (p.one_wave_per_image && p.a.Cin == 1)
+  if (p.fc_rows)
+    fc::bwd_weight_kernel<<<p.gx, fc::WGRAD_THREADS, 0, st>>>(in, d_out, part, p.a.B);
+  else if (p.one_wave_per_image && p.a.Cin == 1)
     conv1::bwd_weight_kernel<<<p.gx, conv1::THREADS, 0, st>>>(in, d_out, part, p.a.B);
   else if (p.one_wave_per_image)
     conv2::bwd_weight_kernel<<<p.gx, conv2::THREADS, 0, st>>>(in, d_out, part, p.a.B);
@@ -735,6 +754,14 @@ int scratch_of_current_device(float** out) {
   }
   *out = ptr[dev];
   return CNN_OK;
+}
+
+// Workgroups of the fully connected layer's row kernels: one tile of sixteen rows per wave while the
+// machine has room, then the waves loop.
+unsigned fc_groups(int B) {
+  const long long tiles = ((long long)B + fc::TILE - 1) / fc::TILE;
+  const long long groups = (tiles + fc::WAVES_PER_GROUP - 1) / fc::WAVES_PER_GROUP, resident = 4LL * NUM_CU;
+  return (unsigned)(groups < resident ? groups : resident);
 }
 
 }  // namespace
@@ -912,6 +939,11 @@ int cnn_fc_fwd(const float* in, const float* w, const float* bias, float* out, i
                void* hip_stream) {
   if (!in || !w || !out || B < 1 || I < 1 || O < 1) return CNN_EINVAL;
   if (!aligned16(in) || !aligned16(w) || !aligned16(out) || (bias && !aligned16(bias))) return CNN_EINVAL;
+  if (fc::shape_fits(I, O)) {
+    // the shape of the network's own layer: every wave takes tiles of sixteen rows straight from global memory
+    fc::forward_kernel<<<fc_groups(B), fc::THREADS, 0, (hipStream_t)hip_stream>>>(in, w, bias, out, B);
+    return launched();
+  }
   const ConvPlan p = plan_conv(in, w, bias, out, B, O, I, 1, 1, 1, 1, 1, 1, 0, 0, 0);
   if (p.tp) return launch_conv(p, (hipStream_t)hip_stream);
   const size_t total = (size_t)B * O;
@@ -923,6 +955,10 @@ int cnn_fc_bwd_input(const float* d_out, const float* w, float* d_in, int B, int
                      void* hip_stream) {
   if (!d_out || !w || !d_in || B < 1 || I < 1 || O < 1) return CNN_EINVAL;
   if (!aligned16(d_out) || !aligned16(w) || !aligned16(d_in)) return CNN_EINVAL;
+  if (fc::shape_fits(I, O)) {
+    fc::bwd_input_kernel<<<fc_groups(B), fc::THREADS, 0, (hipStream_t)hip_stream>>>(d_out, w, d_in, B);
+    return launched();
+  }
   const ConvPlan p = plan_conv(d_out, w, nullptr, d_in, B, I, O, 1, 1, 1, 1, 1, 1, 0, 0, 1);
   if (p.tp) return launch_conv(p, (hipStream_t)hip_stream);
   const size_t total = (size_t)B * I;

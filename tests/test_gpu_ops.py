@@ -200,7 +200,7 @@ def test_avgpool_fwd_bwd(shape):
     assert abs(up.astype(np.float64).sum() - d.astype(np.float64).sum()) <= 1e-6 * np.abs(d).sum()
 
 
-@pytest.mark.parametrize("B,I,O", [(7, 192, 10), (1, 1, 1), (300, 33, 5), (2000, 192, 10), (70, 20, 300)])
+@pytest.mark.parametrize("B,I,O", [(7, 192, 10), (1, 1, 1), (300, 33, 5), (2000, 192, 10), (4101, 192, 10), (70, 20, 300)])
 def test_fc(B, I, O):
     x, w, b = inputs.make_signed((B, I), 10), inputs.make_signed((O, I), 11), inputs.make_signed((O,), 12)
     d = inputs.make_signed((B, O), 13)
@@ -228,6 +228,30 @@ def test_fc(B, I, O):
         d_w, d_b = binding.fc_bwd_weight(dev(x), dev(d), workspace=workspace)
         assert_close(host(d_w), ref_dw, RTOL_ACT, "fc_bwd_weight")
         assert_close(host(d_b), ref_db, RTOL_ACT, "fc_bwd_bias")
+
+
+def test_fc_of_the_network_with_looping_waves():
+    """The network's own fully connected shape has kernels in which a wave takes sixteen rows (four for
+    the weight gradient) at a time; 70001 rows make their waves loop and leave a ragged last tile.  The
+    whole result is compared with the matrix products that test_fc pins the oracle's functions to, and
+    sampled rows with those functions themselves."""
+    B, I, O = 70001, 192, 10
+    x, w, b = inputs.make_signed((B, I), 20), inputs.make_signed((O, I), 21), inputs.make_signed((O,), 22)
+    d = inputs.make_signed((B, O), 23)
+    x64, w64, d64, b64 = x.astype(np.float64), w.astype(np.float64), d.astype(np.float64), b.astype(np.float64)
+    out = host(binding.fc_fwd(dev(x), dev(w), dev(b)))
+    d_in = host(binding.fc_bwd_input(dev(d), dev(w)))
+    assert_close(out, x64 @ w64.T + b64, RTOL_ACT, "fc_fwd")
+    assert_close(d_in, d64 @ w64, RTOL_ACT, "fc_bwd_input")
+    rows = np.unique(np.concatenate([np.arange(3), np.arange(B - 20, B), np.random.default_rng(5).integers(0, B, 40)]))
+    for n in rows:
+        assert_close(out[n], oracle.mconv(x64[n], w64, b64).ravel(), RTOL_ACT, "fc_fwd row %d" % n)
+        ref = sum(oracle.backin(d64[n, o:o + 1], w64[o], (I,)).ravel() for o in range(O))
+        assert_close(d_in[n], ref, RTOL_ACT, "fc_bwd_input row %d" % n)
+    for workspace in (True, False):
+        d_w, d_b = binding.fc_bwd_weight(dev(x), dev(d), workspace=workspace)
+        assert_close(host(d_w), d64.T @ x64, RTOL_ACT, "fc_bwd_weight")
+        assert_close(host(d_b), d64.sum(axis=0), RTOL_ACT, "fc_bwd_bias")
 
 
 def test_logistic():
