@@ -149,14 +149,14 @@ int cnn_profile_read(cnn_ctx* ctx, float* ms, int capacity, int* n_recorded);
  * memory, 16-byte aligned, fp32, and finite: the matrix-core kernels multiply padding lanes by
  * zero, which a NaN or infinity in the input would turn into NaN.  (The shapes of the network's own
  * layers have kernels of their own: Cin = 6, Cout = 12, KH = KW = 5, H = W = 12, the second
- * convolution, for all three convolution calls; Cin = 1, Cout = 6, KH = KW = 5, H = W = 28, the first,
- * for the forward pass and the weight gradient; I = 192, O = 10 for the three cnn_fc_* calls.  Same
+ * convolution, and Cin = 1, Cout = 6, KH = KW = 5, H = W = 28, the first, for all three convolution
+ * calls; I = 192, O = 10 for the three cnn_fc_* calls.  Same
  * definitions, sums in another order.) */
 int cnn_conv_fwd(const float* in, const float* k, const float* bias, float* out, int B, int Cin,
                  int H, int W, int Cout, int KH, int KW, void* hip_stream);
 /* `backin` summed over output maps: d_in[b,ci,p,q] = sum_co sum_{u,v : 0<=p-u<Ho, 0<=q-v<Wo}
- * k[co,ci,u,v] * d_out[b,co,p-u,q-v].  (One shape, Cin = 6, Cout = 12, KH = KW = 5, H = W = 12 -- the
- * network's second convolution -- has a kernel of its own; same definition, sums in another order.) */
+ * k[co,ci,u,v] * d_out[b,co,p-u,q-v].  (The shapes of the network's two convolutions have kernels of
+ * their own, see cnn_conv_fwd; same definition, sums in another order.) */
 int cnn_conv_bwd_input(const float* d_out, const float* k, float* d_in, int B, int Cin, int H,
                        int W, int Cout, int KH, int KW, void* hip_stream);
 /* The two calls above on the fp32 vector unit alone (one thread per output element, plain

@@ -16,7 +16,8 @@
 //                    workgroups' partials
 //   (the input gradient of this shape is cnn_col2im.h)
 // namespace conv1: one input and six output maps, 5 x 5 kernel, 28 x 28 input: forward and weight
-//   gradient as GEMMs over pixel pairs, 144 per image each; see there.
+//   gradient as GEMMs over pixel pairs, 144 per image each, and the input gradient on the vector
+//   unit; see there.
 // Pixel order and operand layouts are those of cnn_wave.h (fwd_tap, fwd_imm, c1f_*, c1g_*); only such
 // index helpers and GEMM inner loops are shared with the fused step.
 #pragma once
@@ -406,6 +407,123 @@ __global__ __launch_bounds__(THREADS) void bwd_weight_kernel(const float* __rest
   }
 }
 inline size_t bwd_weight_workspace_bytes(unsigned groups) { return sizeof(float) * (size_t)groups * (2 * 256 + 16); }
+
+// Input gradient of the same shape (listing `backin`, summed over the six maps of the output error):
+//   d_in[p][q] = sum_m sum_{u,v} k[m][u][v] * d_out[m][p-u][q-v]          (terms inside the 24 x 24 error only)
+// One output map and six input maps: a matrix tile has nothing to share between rows (the general
+// kernel packs fourteen pixels into a column to fill one and needs 476 matrix instructions per
+// image), so this runs on the fp32 vector unit, one wave per image.  A lane owns half a row of the
+// output, fourteen neighbouring pixels (56 lanes): for a map and a kernel row it reads the eighteen
+// error values its strip can reach, as nine 8-byte items, and does 70 multiply-adds, the 25 weights of
+// the map in registers (broadcast reads, once per map).  LDS reads are what bounds this kernel: a
+// 4-byte read of 64 lanes takes the LDS four cycles, an 8-byte read as well, hence strips whose
+// reads are 8-byte aligned.  The error lies in the wave's LDS in rows of 28 floats, four zeros and
+// the 24 values: the zeros of the next row are the right border, so no column is tested; a row
+// above or below the map is replaced by one row of zeros (chosen per lane and kernel row when the
+// kernel starts).
+constexpr int BI_STRIDE = 28, BI_MAP = 24 * BI_STRIDE, BI_ZERO = 6 * BI_MAP, BI_FLOATS = BI_ZERO + 32;
+constexpr int BI_KPAD = 28;                  // a map's 25 weights as seven 16-byte pieces
+constexpr int BI_PIECES = 6 * 24 * 24 / 4;  // 16-byte pieces of an image's error
+constexpr int BI_ROUNDS = (BI_PIECES + 63) / 64;
+struct __align__(16) BwdInputLds {
+  float k[6 * BI_KPAD];
+  float d[WAVES_PER_GROUP][BI_FLOATS];
+};
+__global__ __launch_bounds__(THREADS) void bwd_input_kernel(const float* __restrict__ d_out,
+                                                            const float* __restrict__ k, float* __restrict__ d_in,
+                                                            int B) {
+  __shared__ BwdInputLds lds;
+  const int t = threadIdx.x, wave = t >> 6, l = t & 63;
+  for (int e = t; e < 6 * BI_KPAD; e += THREADS) {
+    const int m = e / BI_KPAD, tap = e - BI_KPAD * m;
+    lds.k[e] = tap < 25 ? k[m * 25 + tap] : 0.0f;
+  }
+  float* d = lds.d[wave];
+  for (int e = l; e < BI_FLOATS; e += 64) d[e] = 0.0f;  // the borders stay zero, the values are replaced per image
+  __syncthreads();
+  // the lane's strip: row p, columns 14 hx .. 14 hx + 13; kernel row u reads error row p - u, whose first
+  // value for this strip is column 14 hx - 4, i.e. float 14 hx of the padded row
+  const bool live = l < 56;
+  const int p = live ? l >> 1 : 0, hx = l & 1, out_at = 28 * p + 14 * hx;
+  int off[5], step[5];
+#pragma unroll
+  for (int u = 0; u < 5; ++u) {
+    const int y = p - u;
+    const bool inside = y >= 0 && y < 24;
+    off[u] = (inside ? y * BI_STRIDE : BI_ZERO) + 14 * hx;
+    step[u] = inside ? BI_MAP : 0;
+  }
+  // where the lane's 16-byte pieces of the error go: piece e = (map, row, four columns)
+  int put[BI_ROUNDS];
+#pragma unroll
+  for (int j = 0; j < BI_ROUNDS; ++j) {
+    const int e = l + 64 * j, ee = e < BI_PIECES ? e : 0, m = ee / 144, rem = ee - 144 * m, y = rem / 6, x4 = rem - 6 * y;
+    put[j] = m * BI_MAP + y * BI_STRIDE + 4 + 4 * x4;
+  }
+  auto load_error = [&](size_t n, f4 (&v)[BI_ROUNDS]) {
+    const f4* src = reinterpret_cast<const f4*>(d_out + n * NC1);
+#pragma unroll
+    for (int j = 0; j < BI_ROUNDS; ++j) v[j] = src[l + 64 * j < BI_PIECES ? l + 64 * j : l];
+  };
+  const size_t G = (size_t)gridDim.x * WAVES_PER_GROUP, first = (size_t)blockIdx.x * WAVES_PER_GROUP + wave;
+  f4 cur[BI_ROUNDS];
+  if (first < (size_t)B) load_error(first, cur);
+  for (size_t n = first; n < (size_t)B; n += G) {
+#pragma unroll
+    for (int j = 0; j < BI_ROUNDS; ++j)
+      if (l + 64 * j < BI_PIECES) *reinterpret_cast<f4*>(d + put[j]) = cur[j];  // 16-byte aligned: rows of 28 floats
+    wave_sync();
+    if (n + G < (size_t)B) load_error(n + G, cur);  // in flight during this image
+    float acc[14];
+#pragma unroll
+    for (int i = 0; i < 14; ++i) acc[i] = 0.0f;
+    int at[5];
+#pragma unroll
+    for (int u = 0; u < 5; ++u) at[u] = off[u];
+#pragma unroll 1
+    for (int m = 0; m < 6; ++m) {
+      float w[BI_KPAD];  // the map's weights, every lane the same (broadcast reads)
+#pragma unroll
+      for (int i = 0; i < BI_KPAD / 4; ++i) {
+        const f4 piece = *reinterpret_cast<const f4*>(&lds.k[m * BI_KPAD + 4 * i]);
+        w[4 * i] = piece[0];
+        w[4 * i + 1] = piece[1];
+        w[4 * i + 2] = piece[2];
+        w[4 * i + 3] = piece[3];
+      }
+      // the eighteen values of kernel row u + 1 are read while the 70 multiply-adds of row u issue (the
+      // scheduling groups pin that order)
+      float x[2][18];
+      auto load_row = [&](int u, float (&o)[18]) {
+        const float2* src = reinterpret_cast<const float2*>(d + at[u]);
+#pragma unroll
+        for (int j = 0; j < 9; ++j) {
+          const float2 two = src[j];
+          o[2 * j] = two.x;
+          o[2 * j + 1] = two.y;
+        }
+        at[u] += step[u];
+      };
+      load_row(0, x[0]);
+#pragma unroll
+      for (int u = 0; u < 5; ++u) {
+        if (u < 4) load_row(u + 1, x[(u + 1) & 1]);
+#pragma unroll
+        for (int v = 0; v < 5; ++v)
+#pragma unroll
+          for (int i = 0; i < 14; ++i) acc[i] = fmaf(w[5 * u + v], x[u & 1][i - v + 4], acc[i]);
+        if (u < 4) __builtin_amdgcn_sched_group_barrier(0x100, 9, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 70, 0);
+      }
+    }
+    if (live) {
+      float2* dst = reinterpret_cast<float2*>(d_in + n * NI + out_at);
+#pragma unroll
+      for (int i = 0; i < 7; ++i) dst[i] = float2{acc[2 * i], acc[2 * i + 1]};
+    }
+    wave_sync();  // the reads of this image come before the next image's stores
+  }
+}
 
 }  // namespace conv1
 }  // namespace cnn

@@ -805,6 +805,13 @@ int cnn_conv_bwd_input(const float* d_out, const float* k, float* d_in, int B, i
                                     (hipStream_t)hip_stream>>>(d_out, k, d_in, B);
     return launched();
   }
+  if (conv1::shape_fits(Cin, H, W, Cout, KH, KW)) {
+    // the shape of the network's first convolution: one output map, nothing for a matrix tile to share
+    const int groups = (B + conv1::WAVES_PER_GROUP - 1) / conv1::WAVES_PER_GROUP;
+    conv1::bwd_input_kernel<<<groups < NUM_CU ? groups : NUM_CU, conv1::THREADS, 0, (hipStream_t)hip_stream>>>(
+        d_out, k, d_in, B);  // 128 KB of LDS: one workgroup per compute unit
+    return launched();
+  }
   const ConvPlan p = plan_conv(d_out, k, nullptr, d_in, B, Cin, Cout, H - KH + 1, W - KW + 1, KH, KW, H, W,
                                KH - 1, KW - 1, 1);
   if (p.tp) return launch_conv(p, (hipStream_t)hip_stream);

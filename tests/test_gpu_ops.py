@@ -120,8 +120,8 @@ def test_forward_and_weight_gradient_of_the_second_convolution_with_looping_wave
     assert_close(host(gb), rb, RTOL_GRAD, "conv_bwd_weight bias of C2, 37 images")
 
 
-def test_forward_and_weight_gradient_of_the_first_convolution_with_looping_waves():
-    """4101 images of C1's shape through its one-wave-per-image forward and weight-gradient kernels (waves
+def test_the_three_calls_of_the_first_convolution_with_looping_waves():
+    """4101 images of C1's shape through its one-wave-per-image forward, weight-gradient and input-gradient kernels (waves
     take a second image, ragged last round): sampled images against the oracle, every image against the
     plain kernel; without a bias; the gradient sums against the plain kernel and the oracle."""
     B = 4101
@@ -149,6 +149,16 @@ def test_forward_and_weight_gradient_of_the_first_convolution_with_looping_waves
             rb[co] += oracle.backbias(d[n, co].astype(np.float64))
     assert_close(host(gk), rk, RTOL_GRAD, "conv_bwd_weight of C1, 37 images")
     assert_close(host(gb), rb, RTOL_GRAD, "conv_bwd_weight bias of C1, 37 images")
+    # input gradient of the same error (a vector-unit kernel of its own for this shape): sampled images against
+    # the oracle, every image against the plain kernel
+    gi = host(binding.conv_bwd_input(dev(d), dev(k), 28, 28))
+    ref = np.zeros((len(sample), 1, 28, 28), np.float64)
+    for i, n in enumerate(sample):
+        for co in range(6):
+            ref[i] += oracle.backin(d[n, co][None].astype(np.float64), k[co].astype(np.float64), (1, 28, 28))
+    assert_close(gi[sample], ref, RTOL_ACT, "conv_bwd_input of C1, sampled images")
+    plain = host(binding.conv_bwd_input(dev(d), dev(k), 28, 28, valu=True))
+    assert_close(gi, plain.astype(np.float64), RTOL_ACT, "conv_bwd_input of C1 against the plain kernel")
 
 
 @pytest.mark.parametrize("case", CONV_CASES)
