@@ -132,7 +132,8 @@ __device__ __forceinline__ void group_train(const float* __restrict__ image,
 
   f4 px = reinterpret_cast<const f4*>(image)[pix];
   const int label = *label_ptr;  // in flight during the set-up too
-  TableLoad<TAB_TRAIN_ENTRIES, 64 * GWAVES, COHERENT> table;
+  // the C1 forward operands (the table's last entries) and the biases come first: see barrier (1)
+  TableLoad<TAB_TRAIN_ENTRIES, 64 * GWAVES, COHERENT, TAB_TRAIN_ENTRIES, TAB_C1A> table;
   table.fetch(tabg);
   // every LDS cell that padded GEMM steps may read starts finite, and both col2im targets start at
   // zero (the image area is written below, before the first barrier, so it is left alone here)
@@ -155,12 +156,14 @@ __device__ __forceinline__ void group_train(const float* __restrict__ image,
   CNN_GROUP_MARK(1);
   // The lane-invariant address arithmetic of the phases below is independent of the table, so the
   // compiler is free to run it while the table's loads are still in flight; barrier (1) publishes
-  // the table together with the image.
+  // the image together with what the C1 forward pass reads of the table (its own operands and the
+  // biases, fetched first); the rest of the table arrives during that pass and is published by
+  // barrier (2).
   {
-    table.commit(tab);
+    table.commit_first(tab);
     if (t < NI / 4) reinterpret_cast<f4*>(s.img)[t] = px;
     CNN_GROUP_MARK(2);
-    __syncthreads();  // (1) image and operand table in LDS
+    __syncthreads();  // (1) image, C1 forward operands and biases in LDS
     st.bias2 = tab.bias[n16];
 
     // ---- C1 forward + S1 for this wave's tiles ---------------------------------------------------------
@@ -169,8 +172,9 @@ __device__ __forceinline__ void group_train(const float* __restrict__ image,
       group_c1_forward<3>(s, tab, wave, ln, c1);
     else
       group_c1_forward<2>(s, tab, wave, ln, c1);
+    table.commit_rest(tab);
     CNN_GROUP_MARK(3);
-    __syncthreads();  // (2) S1 complete
+    __syncthreads();  // (2) S1 and the operand table complete
 
     // ---- C2 forward for pixel tile mt = wave, S2 (waves 0..3) -----------------------------------------
     f4 c2v = f4{st.bias2, st.bias2, st.bias2, st.bias2};
