@@ -388,7 +388,9 @@ constexpr int table_max_multiplicity() {
 // epoch loop): its 16-byte pieces are fetched with agent-scope loads, which do not take stale lines
 // from this XCD's L2 cache.
 // ENTRIES counts the entries of the LDS copy, of which the first LOADED come from global memory.
-template <int ENTRIES, int THREADS, bool COHERENT = false, int LOADED = ENTRIES>
+// FIRST: the entry whose pieces are fetched first; `commit_first` stores those (one round of loads)
+// and the tail, `commit_rest` the others, each followed by a barrier of the caller's.
+template <int ENTRIES, int THREADS, bool COHERENT = false, int LOADED = ENTRIES, int FIRST = 0>
 struct TableLoad {
   static constexpr int PIECES = LOADED * 16, ROUNDS = (PIECES + THREADS - 1) / THREADS;
   static constexpr int TAIL = (K1T_FLOATS + TAB_BIAS_FLOATS) / 4;
@@ -396,9 +398,17 @@ struct TableLoad {
   static_assert(offsetof(Table, bias) == offsetof(Table, k1t) + sizeof(float) * K1T_FLOATS,
                 "k1t and bias are copied as one run");
   static_assert(TAIL <= THREADS, "one thread per piece of the tail");
+  static_assert(FIRST >= 0 && FIRST < LOADED, "the entry fetched first is one of the loaded ones");
   f4 v[ROUNDS], tail;
-  // 16-byte piece of the table that this thread moves in round r (the same in global memory and in LDS)
-  static __device__ __forceinline__ int piece(int r) { return r * THREADS + (int)threadIdx.x; }
+  // 16-byte piece of the table that this thread moves in round r (the same in global memory and in
+  // LDS), or -1: the pieces are taken in the order FIRST * 16, .., PIECES - 1, 0, .., FIRST * 16 - 1, so
+  // that round 0 brings the entries from FIRST on (what the caller needs first) and loads return in
+  // the order they are issued
+  static __device__ __forceinline__ int piece(int r) {
+    const int i = r * THREADS + (int)threadIdx.x, at = i + FIRST * 16;
+    return i < PIECES ? (at < PIECES ? at : at - PIECES) : -1;
+  }
+  // Issue order: round 0, the tail (k1t, biases), the other rounds.
   __device__ __forceinline__ void fetch(const float* __restrict__ tabg) {
     const int t = threadIdx.x;
     if (COHERENT) {
@@ -406,30 +416,41 @@ struct TableLoad {
           __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(tabg), 0, sizeof(float) * TABG_FLOATS, 0x00020000);
       constexpr int AGENT_SCOPE = 16;  // the sc1 bit of the cache policy
       typedef unsigned u4 __attribute__((ext_vector_type(4)));
+      auto load = [&](int byte) { return __builtin_bit_cast(f4, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs, byte, 0, AGENT_SCOPE)); };
+      { const int i = piece(0); v[0] = load(16 * (i >= 0 ? i : 0)); }
+      tail = load(4 * TABG_K1T + 16 * (t < TAIL ? t : 0));
 #pragma unroll
-      for (int r = 0; r < ROUNDS; ++r) {
+      for (int r = 1; r < ROUNDS; ++r) {
         const int i = piece(r);
-        v[r] = __builtin_bit_cast(f4, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs, 16 * (i < PIECES ? i : 0), 0, AGENT_SCOPE));
+        v[r] = load(16 * (i >= 0 ? i : 0));
       }
-      tail = __builtin_bit_cast(f4, (u4)__builtin_amdgcn_raw_buffer_load_b128(rs, 4 * TABG_K1T + 16 * (t < TAIL ? t : 0), 0, AGENT_SCOPE));
       return;
     }
     const f4* src = reinterpret_cast<const f4*>(tabg);
-#pragma unroll
-    for (int r = 0; r < ROUNDS; ++r) {
-      const int i = piece(r);
-      v[r] = src[i < PIECES ? i : 0];
-    }
+    { const int i = piece(0); v[0] = src[i >= 0 ? i : 0]; }
     tail = src[TABG_K1T / 4 + (t < TAIL ? t : 0)];
+#pragma unroll
+    for (int r = 1; r < ROUNDS; ++r) {
+      const int i = piece(r);
+      v[r] = src[i >= 0 ? i : 0];
+    }
+  }
+  // Round 0 and the tail: the entries FIRST .. (and the first ones again, as far as a round reaches).
+  __device__ __forceinline__ void commit_first(Table& tab) const {
+    const int t = threadIdx.x, i = piece(0);
+    if (i >= 0) reinterpret_cast<f4*>(tab.e)[i] = v[0];
+    if (t < TAIL) reinterpret_cast<f4*>(tab.k1t)[t] = tail;
+  }
+  __device__ __forceinline__ void commit_rest(Table& tab) const {
+#pragma unroll
+    for (int r = 1; r < ROUNDS; ++r) {
+      const int i = piece(r);
+      if (i >= 0) reinterpret_cast<f4*>(tab.e)[i] = v[r];
+    }
   }
   __device__ __forceinline__ void commit(Table& tab) const {
-    const int t = threadIdx.x;
-#pragma unroll
-    for (int r = 0; r < ROUNDS; ++r) {
-      const int i = piece(r);
-      if (i < PIECES) reinterpret_cast<f4*>(tab.e)[i] = v[r];
-    }
-    if (t < TAIL) reinterpret_cast<f4*>(tab.k1t)[t] = tail;
+    commit_first(tab);
+    commit_rest(tab);
   }
 };
 template <int ENTRIES, int THREADS, int LOADED = ENTRIES>
